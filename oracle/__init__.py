@@ -1,0 +1,205 @@
+"""numpy front end of the CPU oracle (oracle/tweo_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+cpu_baseline leg of bench.py.  Nothing in the product package imports it and it
+imports nothing from the product package.  bf16 tensors travel as uint16 bit
+patterns, E4M3 tensors as uint8 codes.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tweo_oracle.c")
+_LIB = os.path.join(_HERE, "libtweo_oracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc (plain scalar C, OpenMP over independent rows)."""
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+        return _LIB
+    cmd = ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-std=c11",
+           "-Wall", "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _p(a, ct):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.orc_bf16_to_f32.restype = ctypes.c_float
+        L.orc_bf16_to_f32.argtypes = [ctypes.c_uint16]
+        L.orc_f32_to_bf16.restype = ctypes.c_uint16
+        L.orc_f32_to_bf16.argtypes = [ctypes.c_float]
+        L.orc_e4m3_decode.restype = ctypes.c_double
+        L.orc_e4m3_decode.argtypes = [ctypes.c_uint8]
+        L.orc_e4m3_encode.restype = ctypes.c_uint8
+        L.orc_e4m3_encode.argtypes = [ctypes.c_float]
+        L.orc_amax_bf16.restype = ctypes.c_float
+        L.orc_penalty_sum.restype = ctypes.c_double
+        L.orc_num_threads.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+_u8, _u16, _i8, _i32, _i64 = (ctypes.c_uint8, ctypes.c_uint16, ctypes.c_int8, ctypes.c_int32,
+                              ctypes.c_int64)
+_f32, _f64 = ctypes.c_float, ctypes.c_double
+
+
+def _c(a, dt):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == dt, (a.dtype, dt)
+    return a
+
+
+def num_threads():
+    return int(lib().orc_num_threads())
+
+
+def bf16_to_f32(h):
+    """uint16 patterns -> float32 (exact)."""
+    h = np.asarray(h, dtype=np.uint16)
+    if h.ndim == 0:
+        return np.float32(lib().orc_bf16_to_f32(int(h)))
+    return (h.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def f32_to_bf16_scalar(f):
+    return int(lib().orc_f32_to_bf16(ctypes.c_float(float(f))))
+
+
+def e4m3_decode(b):
+    return float(lib().orc_e4m3_decode(int(b)))
+
+
+def e4m3_encode(v):
+    return int(lib().orc_e4m3_encode(ctypes.c_float(float(v))))
+
+
+def amax_bf16(x):
+    x = _c(x, np.uint16)
+    return np.float32(lib().orc_amax_bf16(_p(x, _u16), _i64(x.size)))
+
+
+def scale_from_amax(amax):
+    s, si = _f32(), _f32()
+    lib().orc_scale_from_amax(_f32(float(amax)), ctypes.byref(s), ctypes.byref(si))
+    return np.float32(s.value), np.float32(si.value)
+
+
+def quantize_e4m3(x, scale, transpose=True):
+    x = _c(x, np.uint16)
+    assert x.ndim == 2
+    r, c = x.shape
+    q = np.empty((r, c), np.uint8)
+    qT = np.empty((c, r), np.uint8) if transpose else None
+    lib().orc_quantize_e4m3(_p(x, _u16), _i64(r), _i64(c), _f32(float(scale)), _p(q, _u8),
+                            _p(qT, _u8))
+    return q, qT
+
+
+def _rows(rows, limit):
+    if rows is None:
+        return None, 0
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    assert rows.ndim == 1 and (rows >= 0).all() and (rows < limit).all()
+    return rows, rows.size
+
+
+def fp8_linear_fwd(xq, wq, sx_inv, sw_inv, residual=None, rows=None, want_abs=True):
+    """Returns (y64, yabs, ybf16) for all rows m, or for the rows listed in `rows`."""
+    xq, wq = _c(xq, np.uint8), _c(wq, np.uint8)
+    M, K = xq.shape
+    N, K2 = wq.shape
+    assert K == K2
+    if residual is not None:
+        residual = _c(residual, np.uint16)
+        assert residual.shape == (M, N)
+    rows, nr = _rows(rows, M)
+    R = nr if rows is not None else M
+    y = np.empty((R, N), np.float64)
+    ya = np.empty((R, N), np.float64) if want_abs else None
+    yb = np.empty((R, N), np.uint16)
+    lib().orc_fp8_linear_fwd(_p(xq, _u8), _p(wq, _u8), _p(residual, _u16), _i64(M), _i64(N),
+                             _i64(K), _f32(float(sx_inv)), _f32(float(sw_inv)), _p(rows, _i64),
+                             _i64(nr), _p(y, _f64), _p(ya, _f64), _p(yb, _u16))
+    return y, ya, yb
+
+
+def fp8_linear_dgrad(dyq, wq, sdy_inv, sw_inv, rows=None, want_abs=True):
+    """dX rows (all m, or those in `rows`): (dx64, dxabs)."""
+    dyq, wq = _c(dyq, np.uint8), _c(wq, np.uint8)
+    M, N = dyq.shape
+    N2, K = wq.shape
+    assert N == N2
+    rows, nr = _rows(rows, M)
+    R = nr if rows is not None else M
+    dx = np.empty((R, K), np.float64)
+    da = np.empty((R, K), np.float64) if want_abs else None
+    lib().orc_fp8_linear_dgrad(_p(dyq, _u8), _p(wq, _u8), _i64(M), _i64(N), _i64(K),
+                               _f32(float(sdy_inv)), _f32(float(sw_inv)), _p(rows, _i64),
+                               _i64(nr), _p(dx, _f64), _p(da, _f64))
+    return dx, da
+
+
+def fp8_linear_wgrad(dyq, xq, sdy_inv, sx_inv, rows=None, want_abs=True):
+    """dW rows (all n, or those in `rows`): (dw64, dwabs)."""
+    dyq, xq = _c(dyq, np.uint8), _c(xq, np.uint8)
+    M, N = dyq.shape
+    M2, K = xq.shape
+    assert M == M2
+    rows, nr = _rows(rows, N)
+    R = nr if rows is not None else N
+    dw = np.empty((R, K), np.float64)
+    da = np.empty((R, K), np.float64) if want_abs else None
+    lib().orc_fp8_linear_wgrad(_p(dyq, _u8), _p(xq, _u8), _i64(M), _i64(N), _i64(K),
+                               _f32(float(sdy_inv)), _f32(float(sx_inv)), _p(rows, _i64),
+                               _i64(nr), _p(dw, _f64), _p(da, _f64))
+    return dw, da
+
+
+def penalty_sum(a_bf16, tau=3.0, eps=1e-6, p=4):
+    a = _c(a_bf16, np.uint16)
+    return float(lib().orc_penalty_sum(_p(a, _u16), _i64(a.size), _f64(tau), _f64(eps),
+                                       ctypes.c_int(p)))
+
+
+def penalty_grad(a_bf16, tau=3.0, eps=1e-6, p=4, g=1.0):
+    a = _c(a_bf16, np.uint16)
+    out = np.empty(a.shape, np.float64)
+    lib().orc_penalty_grad(_p(a, _u16), _i64(a.size), _f64(tau), _f64(eps), ctypes.c_int(p),
+                           _f64(g), _p(out, _f64))
+    return out
+
+
+def quantize_i8(x, inv_step):
+    x = _c(x, np.uint16)
+    q = np.empty(x.shape, np.int8)
+    lib().orc_quantize_i8(_p(x, _u16), _i64(x.size), _f32(float(inv_step)), _p(q, _i8))
+    return q
+
+
+def w8a8_linear(xq, wq, alpha, want_acc=False):
+    xq, wq = _c(xq, np.int8), _c(wq, np.int8)
+    M, K = xq.shape
+    N, K2 = wq.shape
+    assert K == K2
+    y = np.empty((M, N), np.uint16)
+    acc = np.empty((M, N), np.int32) if want_acc else None
+    if M < 64 and not want_acc:
+        lib().orc_w8a8_linear_small_m(_p(xq, _i8), _p(wq, _i8), _i64(M), _i64(N), _i64(K),
+                                      _f32(float(alpha)), _p(y, _u16))
+    else:
+        lib().orc_w8a8_linear(_p(xq, _i8), _p(wq, _i8), _i64(M), _i64(N), _i64(K),
+                              _f32(float(alpha)), _p(y, _u16), _p(acc, _i32))
+    return (y, acc) if want_acc else y

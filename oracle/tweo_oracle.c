@@ -1,0 +1,410 @@
+/*
+ * CPU oracle for the per-tensor FP8 linear layer with the TWEO penalty and for
+ * the W8A8 per-tensor static INT8 linear layer.
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is a slow, plain, scalar statement of
+ * what the GPU library must compute.  Only the tests, the smoke check and the
+ * cpu_baseline leg of the benchmark may call it; the product path never does.
+ * It shares no source, header, table or helper with the HIP kernels.
+ *
+ * Every function cites the passage of the TWEO paper (arXiv 2511.23225) that
+ * defines it, or says that the paper is silent and which reading is taken.
+ * Floating point is fp64 unless the method itself fixes a narrower type
+ * (bf16 storage, the fp32 scale multiply in front of the E4M3 rounding, the
+ * fp32 dequantisation multiply of the INT8 path).
+ *
+ * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math: the
+ * rounding steps rely on IEEE semantics and on the default round-to-nearest-
+ * even mode).
+ *
+ * Parity pins (tests/test_oracle_*.py): E4M3 range +-448 (Sec. 1), brute-force
+ * nearest-value search in exact rationals, a library cast for the in-range
+ * part, the printed penalty values 0.0625 / 1 / 10000 (Sec. 3.3), integer
+ * matmul by a library, adjoint identities between fwd/dgrad/wgrad, AbsMax
+ * end points +-Q_8 (Sec. 4.4).  No function here is "parity unpinned"; the
+ * conventions the paper leaves open (NaN handling, zero amax, rounding mode of
+ * "round") are listed where they are taken.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ bf16 */
+
+/* bf16 is the top half of an IEEE binary32; widening is exact. */
+float orc_bf16_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* binary32 -> bf16, round to nearest, ties to even; NaN stays a (quiet) NaN. */
+uint16_t orc_f32_to_bf16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    if (isnan(f))
+        return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t keep = u >> 16;
+    uint32_t rest = u & 0xFFFFu;
+    if (rest > 0x8000u || (rest == 0x8000u && (keep & 1u)))
+        keep += 1u; /* a carry out of the mantissa moves to the exponent; 0x7F7F+1 = inf */
+    return (uint16_t)keep;
+}
+
+/* ------------------------------------------------------------------ E4M3 */
+
+/*
+ * E4M3 as used for FP8 training: 1 sign, 4 exponent (bias 7), 3 mantissa
+ * bits, no infinities, one NaN code per sign (all ones), largest finite
+ * magnitude 448 (Sec. 1: "E4M3 ranges within +-448").
+ */
+double orc_e4m3_decode(uint8_t b)
+{
+    int s = b >> 7, e = (b >> 3) & 15, m = b & 7;
+    double mag;
+    if (e == 15 && m == 7)
+        return NAN;
+    if (e == 0)
+        mag = ldexp((double)m / 8.0, -6);
+    else
+        mag = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return s ? -mag : mag;
+}
+
+/*
+ * Round a binary32 to the nearest E4M3 value, ties to the even mantissa,
+ * saturating at +-448 (per-tensor FP8 casting never produces NaN from a finite
+ * input).  NaN maps to the NaN code.  The paper only names the format and its
+ * range; round-to-nearest-even with saturation is the reading taken here.
+ *
+ * The value grid inside the binade [2^E, 2^(E+1)) has spacing 2^(E-3); below
+ * the smallest normal 2^-6 the spacing stays 2^-9 (subnormals).  So divide by
+ * the spacing (exact in fp64: a power of two), round to an integer with the
+ * default IEEE mode (ties to even integer == ties to even mantissa), and the
+ * code is that integer offset by the binade's first code.
+ */
+uint8_t orc_e4m3_encode(float v)
+{
+    uint32_t u;
+    memcpy(&u, &v, sizeof u);
+    uint8_t sign = (u >> 31) ? 0x80 : 0x00;
+    if (isnan(v))
+        return sign | 0x7F;
+    double a = fabs((double)v);
+    if (a >= 448.0)
+        return sign | 0x7E;
+    if (a == 0.0)
+        return sign;
+    int ex;
+    (void)frexp(a, &ex); /* a = f * 2^ex with f in [0.5,1)  =>  floor(log2 a) = ex-1 */
+    int E = ex - 1;
+    if (E < -6)
+        E = -6;
+    double spacing = ldexp(1.0, E - 3);
+    double r = nearbyint(a / spacing); /* 0..8 in the subnormal band, 8..16 in a normal binade */
+    /* first code of binade E is ((E+7)<<3) and corresponds to r = 8 */
+    int code = ((E + 6) << 3) + (int)r;
+    return sign | (uint8_t)code;
+}
+
+/* ------------------------------------------------------------------ amax */
+
+/*
+ * Per-tensor amax = max_i |x_i| over the whole tensor (Sec. 4.3: one scaling
+ * factor for the entire tensor; Sec. 4.4 Eq. 4: max(|X|)).  bf16 magnitudes
+ * order like their 15-bit patterns, so the maximum is taken on patterns; this
+ * also fixes the open NaN/Inf case: Inf beats every finite value and a NaN
+ * beats Inf, i.e. a NaN in the tensor is reported, not hidden.
+ */
+float orc_amax_bf16(const uint16_t *x, int64_t n)
+{
+    uint16_t best = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        uint16_t mag = x[i] & 0x7FFF;
+        if (mag > best)
+            best = mag;
+    }
+    return orc_bf16_to_f32(best);
+}
+
+/*
+ * scale maps [-amax, amax] onto the E4M3 range: scale = 448 / amax, one fp32
+ * division; scale_inv = 1 / scale, one fp32 division.  The paper gives no
+ * formula, margin or guard; reading: margin 0, no power-of-two rounding,
+ * amax of 0 / Inf / NaN -> scale 1, an overflowing quotient -> FLT_MAX.
+ */
+void orc_scale_from_amax(float amax, float *scale, float *scale_inv)
+{
+    float s;
+    if (!(amax > 0.0f) || isinf(amax) || isnan(amax)) {
+        s = 1.0f;
+    } else {
+        s = 448.0f / amax;
+        if (isinf(s))
+            s = 3.402823466e+38f;
+    }
+    *scale = s;
+    *scale_inv = 1.0f / s;
+}
+
+/*
+ * q[r,c] = e4m3( fp32(x[r,c]) * scale ): one fp32 multiply, then the rounding
+ * above.  qT (optional) is the same bytes transposed, qT[c,r] = q[r,c].
+ */
+void orc_quantize_e4m3(const uint16_t *x, int64_t rows, int64_t cols, float scale,
+                       uint8_t *q, uint8_t *qT)
+{
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) {
+            volatile float prod = orc_bf16_to_f32(x[r * cols + c]) * scale;
+            uint8_t b = orc_e4m3_encode(prod);
+            q[r * cols + c] = b;
+            if (qT)
+                qT[c * rows + r] = b;
+        }
+}
+
+/* ------------------------------------------------------------- FP8 GEMMs */
+
+static void decode_table(double *t)
+{
+    for (int b = 0; b < 256; ++b)
+        t[b] = orc_e4m3_decode((uint8_t)b);
+}
+
+/*
+ * Forward: Y[m,n] = (sum_k dec(Xq[m,k]) dec(Wq[n,k])) * sx_inv * sw_inv (+ R[m,n]).
+ * A linear layer under per-tensor FP8 (Sec. 4.3); fp64 products of two E4M3
+ * values are exact, the fp64 sum is the reference.
+ * rows_idx (nullable) selects output rows m; row j of the outputs then holds
+ * row rows_idx[j].  y64: fp64 result.  yabs (nullable): sum_k |x w| * sx_inv *
+ * sw_inv (+|R|), the magnitude a rounding-error bound scales with.  ybf
+ * (nullable): bf16 rounding (via fp32) of the fp64 result.
+ */
+void orc_fp8_linear_fwd(const uint8_t *xq, const uint8_t *wq, const uint16_t *residual,
+                        int64_t M, int64_t N, int64_t K, float sx_inv, float sw_inv,
+                        const int64_t *rows_idx, int64_t n_rows,
+                        double *y64, double *yabs, uint16_t *ybf)
+{
+    double t[256];
+    decode_table(t);
+    int64_t R = rows_idx ? n_rows : M;
+    double alpha = (double)sx_inv * (double)sw_inv;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < R; ++j) {
+        int64_t m = rows_idx ? rows_idx[j] : j;
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0, aab = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                double p = t[xq[m * K + k]] * t[wq[n * K + k]];
+                acc += p;
+                aab += fabs(p);
+            }
+            double y = acc * alpha, ya = aab * alpha;
+            if (residual) {
+                double r = (double)orc_bf16_to_f32(residual[m * N + n]);
+                y += r;
+                ya += fabs(r);
+            }
+            y64[j * N + n] = y;
+            if (yabs)
+                yabs[j * N + n] = ya;
+            if (ybf)
+                ybf[j * N + n] = orc_f32_to_bf16((float)y);
+        }
+    }
+}
+
+/*
+ * Data gradient: dX[m,k] = (sum_n dec(dYq[m,n]) dec(Wq[n,k])) * sdy_inv * sw_inv.
+ * Operands are the untransposed tensors; rows_idx selects rows m.
+ */
+void orc_fp8_linear_dgrad(const uint8_t *dyq, const uint8_t *wq,
+                          int64_t M, int64_t N, int64_t K, float sdy_inv, float sw_inv,
+                          const int64_t *rows_idx, int64_t n_rows,
+                          double *dx64, double *dxabs)
+{
+    double t[256];
+    decode_table(t);
+    int64_t R = rows_idx ? n_rows : M;
+    double alpha = (double)sdy_inv * (double)sw_inv;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < R; ++j) {
+        int64_t m = rows_idx ? rows_idx[j] : j;
+        double *acc = dx64 + j * K;
+        double *aab = dxabs ? dxabs + j * K : NULL;
+        for (int64_t k = 0; k < K; ++k) {
+            acc[k] = 0.0;
+            if (aab)
+                aab[k] = 0.0;
+        }
+        for (int64_t n = 0; n < N; ++n) { /* n ascending for every (m,k) */
+            double g = t[dyq[m * N + n]];
+            for (int64_t k = 0; k < K; ++k) {
+                double p = g * t[wq[n * K + k]];
+                acc[k] += p;
+                if (aab)
+                    aab[k] += fabs(p);
+            }
+        }
+        for (int64_t k = 0; k < K; ++k) {
+            acc[k] *= alpha;
+            if (aab)
+                aab[k] *= alpha;
+        }
+    }
+}
+
+/*
+ * Weight gradient: dW[n,k] = (sum_m dec(dYq[m,n]) dec(Xq[m,k])) * sdy_inv * sx_inv.
+ * rows_idx selects rows n of dW.
+ */
+void orc_fp8_linear_wgrad(const uint8_t *dyq, const uint8_t *xq,
+                          int64_t M, int64_t N, int64_t K, float sdy_inv, float sx_inv,
+                          const int64_t *rows_idx, int64_t n_rows,
+                          double *dw64, double *dwabs)
+{
+    double t[256];
+    decode_table(t);
+    int64_t R = rows_idx ? n_rows : N;
+    double alpha = (double)sdy_inv * (double)sx_inv;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < R; ++j) {
+        int64_t n = rows_idx ? rows_idx[j] : j;
+        double *acc = dw64 + j * K;
+        double *aab = dwabs ? dwabs + j * K : NULL;
+        for (int64_t k = 0; k < K; ++k) {
+            acc[k] = 0.0;
+            if (aab)
+                aab[k] = 0.0;
+        }
+        for (int64_t m = 0; m < M; ++m) { /* m ascending for every (n,k) */
+            double g = t[dyq[m * N + n]];
+            for (int64_t k = 0; k < K; ++k) {
+                double p = g * t[xq[m * K + k]];
+                acc[k] += p;
+                if (aab)
+                    aab[k] += fabs(p);
+            }
+        }
+        for (int64_t k = 0; k < K; ++k) {
+            acc[k] *= alpha;
+            if (aab)
+                aab[k] *= alpha;
+        }
+    }
+}
+
+/* ---------------------------------------------------------- TWEO penalty */
+
+/*
+ * S = sum_i ( |a_i| / (tau + eps) )^p over a bf16 activation tensor
+ * (Sec. 3.3, the TWEO loss: the expectation is S divided by the element
+ * count; the 1/L layer average and lambda(t) of the total loss belong to the
+ * caller).  The paper leaves open whether the activation is taken before or
+ * after its bf16 rounding; the stored (rounded) tensor is what the model sees,
+ * so that is what is summed.
+ */
+double orc_penalty_sum(const uint16_t *a, int64_t n, double tau, double eps, int p)
+{
+    double denom = tau + eps, s = 0.0;
+    for (int64_t i = 0; i < n; ++i)
+        s += pow(fabs((double)orc_bf16_to_f32(a[i])) / denom, (double)p);
+    return s;
+}
+
+/*
+ * d/da of the summand above, times an outer factor g (the caller's
+ * lambda / (L * numel)): g * p * sign(a) |a|^(p-1) / (tau+eps)^p.  Not printed
+ * in the paper; it is the derivative of the loss of Sec. 3.3.
+ */
+void orc_penalty_grad(const uint16_t *a, int64_t n, double tau, double eps, int p, double g,
+                      double *out)
+{
+    double denom = tau + eps;
+    for (int64_t i = 0; i < n; ++i) {
+        double v = (double)orc_bf16_to_f32(a[i]);
+        double sgn = (v > 0) - (v < 0);
+        out[i] = g * p * sgn * pow(fabs(v) / denom, (double)(p - 1)) / denom;
+    }
+}
+
+/* ------------------------------------------------------------- INT8 W8A8 */
+
+/*
+ * Symmetric AbsMax quantisation with b = 8 (Sec. 4.4, Eq. 4): Q_8 = 127,
+ * X_q = round(X / s * Q_8).  Static per-tensor: inv_step = 127 / s is computed
+ * once by the caller.  Readings: "round" is round-to-nearest-even; the product
+ * is a single fp32 multiply by inv_step; a static scale can be exceeded at run
+ * time, so the result saturates to +-127 (-128 is never produced: the scheme
+ * is symmetric); NaN maps to 0.
+ */
+void orc_quantize_i8(const uint16_t *x, int64_t n, float inv_step, int8_t *q)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float prod = orc_bf16_to_f32(x[i]) * inv_step;
+        float r = nearbyintf(prod);
+        int v;
+        if (isnan(r))
+            v = 0;
+        else if (r > 127.0f)
+            v = 127;
+        else if (r < -127.0f)
+            v = -127;
+        else
+            v = (int)r;
+        q[i] = (int8_t)v;
+    }
+}
+
+/*
+ * W8A8 linear: acc[m,n] = sum_k xq[m,k] wq[n,k] in exact int32;
+ * y = bf16( fp32(acc) * alpha ), alpha = step_x * step_w (the X_deq factors of
+ * Eq. 4 for both operands, multiplied once by the caller).  fp32(acc) is the
+ * IEEE int->float conversion (rounds above 2^24), then one fp32 multiply, then
+ * bf16 round-to-nearest-even.  acc_out (nullable) receives the int32 sums.
+ */
+void orc_w8a8_linear(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N, int64_t K,
+                     float alpha, uint16_t *y, int32_t *acc_out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int32_t acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int32_t)xq[m * K + k] * (int32_t)wq[n * K + k];
+            volatile float prod = (float)acc * alpha;
+            y[m * N + n] = orc_f32_to_bf16(prod);
+            if (acc_out)
+                acc_out[m * N + n] = acc;
+        }
+}
+
+/* Column-parallel variant for tiny M (same arithmetic, threads split n). */
+void orc_w8a8_linear_small_m(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N, int64_t K,
+                             float alpha, uint16_t *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t m = 0; m < M; ++m) {
+            int32_t acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int32_t)xq[m * K + k] * (int32_t)wq[n * K + k];
+            volatile float prod = (float)acc * alpha;
+            y[m * N + n] = orc_f32_to_bf16(prod);
+        }
+}
+
+int orc_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    n = omp_get_max_threads();
+#endif
+    return n;
+}

@@ -1,0 +1,274 @@
+"""Pins for the oracle's FP8 GEMMs, TWEO penalty and INT8 W8A8 path (CPU only)."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_23225_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def e4m3_value(b):
+    """Exact rational value of a finite E4M3 code, from the format definition."""
+    s, e, m = b >> 7, (b >> 3) & 15, b & 7
+    assert not (e == 15 and m == 7)
+    v = Fraction(m, 8) * Fraction(1, 64) if e == 0 else (1 + Fraction(m, 8)) * Fraction(2) ** (e - 7)
+    return -v if s else v
+
+
+def rand_codes(rng, shape):
+    c = rng.integers(0, 256, shape).astype(np.uint8)
+    c[(c & 0x7F) == 0x7F] = 0x3A
+    return c
+
+
+# ------------------------------------------------------------------ GEMMs
+
+
+def test_gemms_brute_force_tiny_exact_rationals():
+    rng = np.random.default_rng(0)
+    M, K, N = 3, 5, 7
+    xq, wq, dyq = rand_codes(rng, (M, K)), rand_codes(rng, (N, K)), rand_codes(rng, (M, N))
+    sx, sw, sdy = np.float32(0.37), np.float32(2.25), np.float32(0.011)
+    res = synth.f32_to_bf16_bits(rng.standard_normal((M, N)).astype(np.float32))
+    X = [[e4m3_value(int(b)) for b in row] for row in xq]
+    W = [[e4m3_value(int(b)) for b in row] for row in wq]
+    G = [[e4m3_value(int(b)) for b in row] for row in dyq]
+    fx, fw, fdy = Fraction(float(sx)), Fraction(float(sw)), Fraction(float(sdy))
+    y, ya, yb = oracle.fp8_linear_fwd(xq, wq, sx, sw, residual=res)
+    y0, _, _ = oracle.fp8_linear_fwd(xq, wq, sx, sw)
+    dx, _ = oracle.fp8_linear_dgrad(dyq, wq, sdy, sw)
+    dw, _ = oracle.fp8_linear_wgrad(dyq, xq, sdy, sx)
+    R = synth.bf16_bits_to_f32(res)
+    for m in range(M):
+        for n in range(N):
+            exact = sum(X[m][k] * W[n][k] for k in range(K)) * fx * fw
+            assert abs(Fraction(y0[m, n]) - exact) <= abs(exact) * Fraction(1, 2 ** 49)
+            exact_r = exact + Fraction(float(R[m, n]))
+            assert abs(Fraction(y[m, n]) - exact_r) <= (abs(exact) + abs(exact_r)) * Fraction(1, 2 ** 49)
+            ab = sum(abs(X[m][k] * W[n][k]) for k in range(K)) * fx * fw + abs(Fraction(float(R[m, n])))
+            assert abs(Fraction(ya[m, n]) - ab) <= ab * Fraction(1, 2 ** 49)
+        for k in range(K):
+            exact = sum(G[m][n] * W[n][k] for n in range(N)) * fdy * fw
+            assert abs(Fraction(dx[m, k]) - exact) <= abs(exact) * Fraction(1, 2 ** 49) + Fraction(1, 2 ** 80)
+    for n in range(N):
+        for k in range(K):
+            exact = sum(G[m][n] * X[m][k] for m in range(M)) * fdy * fx
+            assert abs(Fraction(dw[n, k]) - exact) <= abs(exact) * Fraction(1, 2 ** 49) + Fraction(1, 2 ** 80)
+    # stored bf16 = round-to-nearest-even of the fp64 result (checked against a library cast)
+    import torch
+    lib_bits = torch.from_numpy(y.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy()
+    assert np.array_equal(yb.view(np.int16), lib_bits)
+
+
+def test_gemms_small_integer_operands_match_library_matmul():
+    # codes of small integers / powers of two: every product and sum is an exact integer
+    rng = np.random.default_rng(1)
+    ints = np.array([0, 1, 2, 3, 4, 6, 8, -1, -2, -3, -4, -6, -8], np.int64)
+    code_of = {int(v): oracle.e4m3_encode(float(v)) for v in ints}
+    M, K, N = 37, 96, 29
+    Xi, Wi, Gi = (rng.choice(ints, s) for s in ((M, K), (N, K), (M, N)))
+    enc = np.vectorize(lambda v: code_of[int(v)], otypes=[np.uint8])
+    xq, wq, dyq = enc(Xi), enc(Wi), enc(Gi)
+    y, _, _ = oracle.fp8_linear_fwd(xq, wq, 1.0, 1.0)
+    dx, _ = oracle.fp8_linear_dgrad(dyq, wq, 1.0, 1.0)
+    dw, _ = oracle.fp8_linear_wgrad(dyq, xq, 1.0, 1.0)
+    assert np.array_equal(y, (Xi @ Wi.T).astype(np.float64))
+    assert np.array_equal(dx, (Gi @ Wi).astype(np.float64))
+    assert np.array_equal(dw, (Gi.T @ Xi).astype(np.float64))
+    # row-sampled form returns exactly those rows
+    rows = np.array([5, 0, 36, 17])
+    assert np.array_equal(oracle.fp8_linear_fwd(xq, wq, 1.0, 1.0, rows=rows)[0], y[rows])
+    assert np.array_equal(oracle.fp8_linear_dgrad(dyq, wq, 1.0, 1.0, rows=rows)[0], dx[rows])
+    assert np.array_equal(oracle.fp8_linear_wgrad(dyq, xq, 1.0, 1.0, rows=rows[:3] % N)[0],
+                          dw[rows[:3] % N])
+
+
+def test_identity_weight_gives_known_magnitudes():
+    # W = I has amax 1 -> scale 448 -> codes {0x7E, 0}; Y = dec(Xq) * sx_inv * 448 * sw_inv
+    x, _, _ = synth.fp8_linear_inputs(0, 0, M=16, K=64, N=64)
+    sx, sxi = oracle.scale_from_amax(oracle.amax_bf16(x))
+    xq, _ = oracle.quantize_e4m3(x, sx)
+    w = synth.f32_to_bf16_bits(np.eye(64, dtype=np.float32))
+    sw, swi = oracle.scale_from_amax(oracle.amax_bf16(w))
+    assert sw == 448.0
+    wq, _ = oracle.quantize_e4m3(w, sw)
+    assert set(np.unique(wq).tolist()) == {0, 0x7E}
+    y, _, _ = oracle.fp8_linear_fwd(xq, wq, sxi, swi)
+    dec = np.array([[oracle.e4m3_decode(int(b)) for b in row] for row in xq])
+    expect = dec * 448.0 * float(sxi) * float(swi)
+    assert np.allclose(y, expect, rtol=1e-15, atol=0)
+
+
+def test_adjoint_identity_and_linearity():
+    rng = np.random.default_rng(2)
+    M, K, N = 24, 40, 56
+    xq, wq, dyq = rand_codes(rng, (M, K)), rand_codes(rng, (N, K)), rand_codes(rng, (M, N))
+    y, _, _ = oracle.fp8_linear_fwd(xq, wq, 1.0, 1.0)
+    dx, _ = oracle.fp8_linear_dgrad(dyq, wq, 1.0, 1.0)
+    dw, _ = oracle.fp8_linear_wgrad(dyq, xq, 1.0, 1.0)
+    dec = np.vectorize(lambda b: oracle.e4m3_decode(int(b)), otypes=[np.float64])
+    X, W, G = dec(xq), dec(wq), dec(dyq)
+    a, b, c = (G * y).sum(), (dx * X).sum(), (dw * W).sum()
+    scale = np.abs(G * y).sum()
+    assert abs(a - b) <= 1e-12 * scale and abs(a - c) <= 1e-12 * scale
+    # a transposed-operand mistake would break the shapes' asymmetric check below
+    assert np.allclose(y, X @ W.T, rtol=1e-13, atol=1e-9)
+    assert np.allclose(dx, G @ W, rtol=1e-13, atol=1e-9)
+    assert np.allclose(dw, G.T @ X, rtol=1e-13, atol=1e-9)
+    y2, _, _ = oracle.fp8_linear_fwd(xq, wq, 0.5, 4.0)
+    assert np.array_equal(y2, y * 2.0)
+
+
+# ---------------------------------------------------------------- penalty
+
+
+def printed_regimes():
+    rows = []
+    for line in open(os.path.join(GOLDEN, "penalty_regimes.txt")):
+        line = line.split("#")[0].split()
+        if len(line) == 2:
+            rows.append((float(line[0]), float(line[1])))
+    return rows
+
+
+def test_penalty_printed_values():
+    # Sec. 3.3: |A| = 0.5 tau, tau, 10 tau  ->  0.0625, 1, 10000 (p = 4); eps = 1e-6 shifts the
+    # values by the factor (tau/(tau+eps))^4 = 1 - 1.3e-6.
+    tau, n = 3.0, 4096
+    rows = printed_regimes()
+    assert [r[0] for r in rows] == [0.5, 1.0, 10.0]
+    for ratio, printed in rows:
+        a = synth.f32_to_bf16_bits(np.full(n, ratio * tau, np.float32))  # 1.5, 3, 30: exact in bf16
+        mean0 = oracle.penalty_sum(a, tau=tau, eps=0.0, p=4) / n
+        assert abs(mean0 - printed) <= 1e-12 * printed
+        mean = oracle.penalty_sum(a, tau=tau, eps=1e-6, p=4) / n
+        assert abs(mean / printed - (tau / (tau + 1e-6)) ** 4) < 1e-12
+
+
+def test_penalty_closed_forms_and_invariances():
+    tau, eps = 3.0, 1e-6
+    one = np.zeros(1000, np.float32)
+    one[123] = -96.0
+    assert np.isclose(oracle.penalty_sum(synth.f32_to_bf16_bits(one)), (96.0 / (tau + eps)) ** 4,
+                      rtol=1e-14)
+    rng = np.random.default_rng(4)
+    a = synth.f32_to_bf16_bits((rng.standard_normal(5000) * 3).astype(np.float32))
+    s = oracle.penalty_sum(a)
+    # textbook definition with a library power routine
+    ref = np.sum((np.abs(synth.bf16_bits_to_f32(a).astype(np.float64)) / (tau + eps)) ** 4)
+    assert np.isclose(s, ref, rtol=1e-13)
+    assert np.isclose(oracle.penalty_sum(a ^ np.uint16(0x8000)), s, rtol=1e-15)  # sign
+    assert np.isclose(oracle.penalty_sum(rng.permutation(a)), s, rtol=1e-12)  # order
+    a4 = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(a) * np.float32(4))  # exact in bf16
+    assert np.isclose(oracle.penalty_sum(a4), 256.0 * s, rtol=1e-13)  # homogeneity, degree p
+    for p, tau2 in ((2, 2.0), (6, 5.0)):
+        ref = np.sum((np.abs(synth.bf16_bits_to_f32(a).astype(np.float64)) / (tau2 + eps)) ** p)
+        assert np.isclose(oracle.penalty_sum(a, tau=tau2, p=p), ref, rtol=1e-13)
+
+
+def test_penalty_on_known_output_magnitudes():
+    # W = c*I: the layer output is c * X up to quantisation, so the penalty of the stored
+    # output is the closed form sum (|y|/(tau+eps))^4 over the decoded, rescaled X.
+    c = 2.0
+    x = synth.f32_to_bf16_bits(np.full((8, 32), 1.5, np.float32))
+    x[0, 0] = synth.f32_to_bf16_bits(np.array([30.0], np.float32))[0]
+    sx, sxi = oracle.scale_from_amax(oracle.amax_bf16(x))
+    xq, _ = oracle.quantize_e4m3(x, sx)
+    w = synth.f32_to_bf16_bits(c * np.eye(32, dtype=np.float32))
+    sw, swi = oracle.scale_from_amax(oracle.amax_bf16(w))
+    wq, _ = oracle.quantize_e4m3(w, sw)
+    _, _, yb = oracle.fp8_linear_fwd(xq, wq, sxi, swi)
+    y = synth.bf16_bits_to_f32(yb)
+    assert abs(y[0, 0] - 60.0) <= 60 * 2 ** -8 and np.all(np.abs(y[1:, :][np.eye(32, dtype=bool)[:7]] - 3.0) <= 0.25)
+    s = oracle.penalty_sum(yb)
+    approx = (60.0 / 3.0) ** 4 + (8 * 32 - 1 - 8 * 31) * 0 + 7 * 1.0  # diagonal terms only
+    diag_terms = (np.abs(y.astype(np.float64)) / (3.0 + 1e-6)) ** 4
+    assert np.isclose(s, diag_terms.sum(), rtol=1e-13)
+    assert abs(s - approx) / approx < 0.3
+
+
+def test_penalty_gradient_finite_differences():
+    rng = np.random.default_rng(6)
+    a = synth.f32_to_bf16_bits((rng.standard_normal(64) * 4).astype(np.float32))
+    g = oracle.penalty_grad(a, g=0.5)
+    v = synth.bf16_bits_to_f32(a).astype(np.float64)
+    f = lambda t: 0.5 * np.sum((np.abs(t) / (3.0 + 1e-6)) ** 4)
+    for i in range(0, 64, 5):
+        h = 1e-5
+        vp, vm = v.copy(), v.copy()
+        vp[i] += h
+        vm[i] -= h
+        assert np.isclose(g[i], (f(vp) - f(vm)) / (2 * h), rtol=1e-6, atol=1e-9)
+
+
+# ------------------------------------------------------------------- INT8
+
+
+def test_int8_quantize_pins():
+    x, w = synth.w8a8_inputs(0, 16, K=512, N=64)
+    amax = oracle.amax_bf16(x)
+    assert amax <= 20.0  # the outlier-free regime of TWEO-trained models (Table 2)
+    inv_step = np.float32(127.0) / amax
+    q = oracle.quantize_i8(x, inv_step)
+    f = synth.bf16_bits_to_f32(x)
+    top = np.abs(f) == amax
+    assert set(np.abs(q[top].astype(int)).tolist()) == {127}  # Q_8 = 127 end points (Sec. 4.4)
+    step = float(amax) / 127.0
+    assert np.all(np.abs(f.astype(np.float64) - q.astype(np.float64) * step) <= step / 2 * (1 + 1e-5))
+    assert q.min() >= -127
+    # library rounding (ties to even) on the same fp32 product
+    ref = np.clip(np.rint(f * inv_step), -127, 127).astype(np.int8)
+    assert np.array_equal(q, ref)
+    # ties: 0.5 -> 0, 1.5 -> 2, 2.5 -> 2 ; saturation beyond a static scale; NaN -> 0
+    t = synth.f32_to_bf16_bits(np.array([0.5, 1.5, 2.5, -0.5, -1.5, 300.0, -300.0, 127.5, np.inf],
+                                        np.float32))
+    assert oracle.quantize_i8(t, 1.0).tolist() == [0, 2, 2, 0, -2, 127, -127, 127, 127]
+    assert oracle.quantize_i8(np.array([0x7FC0], np.uint16), 1.0).tolist() == [0]
+
+
+def test_w8a8_matches_library_integer_matmul():
+    x, w = synth.w8a8_inputs(3, 16, K=1024, N=96)
+    sx, sw = float(oracle.amax_bf16(x)) / 127, float(oracle.amax_bf16(w)) / 127
+    xq = oracle.quantize_i8(x, np.float32(127.0) / oracle.amax_bf16(x))
+    wq = oracle.quantize_i8(w, np.float32(127.0) / oracle.amax_bf16(w))
+    alpha = np.float32(sx) * np.float32(sw)
+    y, acc = oracle.w8a8_linear(xq, wq, alpha, want_acc=True)
+    ref = xq.astype(np.int64) @ wq.astype(np.int64).T
+    assert np.array_equal(acc.astype(np.int64), ref)
+    import torch
+    yref = (torch.from_numpy(ref.astype(np.int32)).to(torch.float32) * float(alpha)).to(torch.bfloat16)
+    assert np.array_equal(y.view(np.int16), yref.view(torch.int16).numpy())
+    assert np.array_equal(oracle.w8a8_linear(xq, wq, alpha), y)  # small-M variant: same arithmetic
+    # alpha = 1: output is bf16(acc); large accumulators round in the int32 -> fp32 step
+    big_x = np.full((2, 11008), 127, np.int8)
+    big_w = np.full((3, 11008), -127, np.int8)
+    y1, acc1 = oracle.w8a8_linear(big_x, big_w, 1.0, want_acc=True)
+    assert acc1[0, 0] == -127 * 127 * 11008 and abs(int(acc1[0, 0])) > 2 ** 24
+    want = torch.tensor([float(np.float32(acc1[0, 0]))]).to(torch.bfloat16).view(torch.int16).item()
+    assert y1.view(np.int16)[0, 0] == want
+
+
+def test_w8a8_brute_force_tiny():
+    rng = np.random.default_rng(9)
+    xq = rng.integers(-127, 128, (2, 9)).astype(np.int8)
+    wq = rng.integers(-127, 128, (4, 9)).astype(np.int8)
+    _, acc = oracle.w8a8_linear(xq, wq, 1.0, want_acc=True)
+    for m in range(2):
+        for n in range(4):
+            assert acc[m, n] == sum(int(xq[m, k]) * int(wq[n, k]) for k in range(9))
+
+
+def test_dequantised_int8_linear_approximates_float_linear():
+    # Eq. 4's X_deq = X_q / Q_b * s : the W8A8 output approximates the float product
+    x, w = synth.w8a8_inputs(1, 64, K=2048, N=128)
+    ax, aw = oracle.amax_bf16(x), oracle.amax_bf16(w)
+    xq = oracle.quantize_i8(x, np.float32(127.0) / ax)
+    wq = oracle.quantize_i8(w, np.float32(127.0) / aw)
+    alpha = (ax / np.float32(127.0)) * (aw / np.float32(127.0))
+    y = synth.bf16_bits_to_f32(oracle.w8a8_linear(xq, wq, alpha)).astype(np.float64)
+    ref = synth.bf16_bits_to_f32(x).astype(np.float64) @ synth.bf16_bits_to_f32(w).astype(np.float64).T
+    assert np.linalg.norm(y - ref) / np.linalg.norm(ref) < 0.05
