@@ -1,0 +1,195 @@
+/*
+ * tweo.h - C ABI of the MI355X (gfx950) library for the per-tensor FP8 linear
+ * layer with the fused TWEO activation-outlier penalty, and for the W8A8
+ * per-tensor static INT8 linear layer (TWEO, arXiv 2511.23225).
+ *
+ * Conventions that hold for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library
+ *     never allocates, frees or synchronises.  Pointers are 16-byte aligned.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream).  Scalars that depend on device data (amax, scales,
+ *     penalty) stay on the device.
+ *   - Tensors are dense row-major, last index contiguous.  bf16 tensors are
+ *     passed as void* (2 bytes per element), E4M3 tensors as uint8_t codes
+ *     (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities,
+ *     largest finite value 448, code 0x7F/0xFF = NaN).
+ *   - Arguments are validated before anything is launched.  Errors come back
+ *     as a status code; nothing aborts or throws across the ABI.  After an
+ *     error the outputs are unspecified.
+ *   - Identical inputs give byte-identical outputs (no floating-point atomics,
+ *     fixed reduction orders).
+ */
+#ifndef TWEO_H
+#define TWEO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TWEO_OK = 0,
+    TWEO_ERR_INVALID_ARG = 1, /* NULL where not allowed, non-positive size, misaligned pointer */
+    TWEO_ERR_UNSUPPORTED = 2, /* shape or option outside what the kernels handle            */
+    TWEO_ERR_WORKSPACE = 3,   /* workspace NULL or smaller than tweo_workspace_bytes()      */
+    TWEO_ERR_HIP = 4          /* a launch failed (hipGetLastError() != hipSuccess)          */
+} tweo_status;
+
+/* Hyper-parameters of the TWEO loss (Sec. 3.3).  The paper uses tau = 3, p = 4
+ * in all experiments (Sec. 4.1) and eps = 1e-6.  p must be a positive even or
+ * odd integer <= 8; p = 4 is the fast path. */
+typedef struct {
+    float tau;
+    float eps;
+    int p;
+} tweo_penalty_cfg;
+
+/* Operations tweo_workspace_bytes() knows about. */
+enum {
+    TWEO_OP_FP8_LINEAR_FWD = 0,
+    TWEO_OP_FP8_LINEAR_BWD = 1,
+    TWEO_OP_W8A8_LINEAR = 2,
+    TWEO_OP_FP8_LINEAR_FWD_BF16 = 3,
+    TWEO_OP_FP8_LINEAR_BWD_BF16 = 4
+};
+
+/* Bytes of device workspace the given operation needs for these sizes (a
+ * multiple of 256; never 0).  The workspace needs no initialisation and may be
+ * reused by the next call on the same stream. */
+size_t tweo_workspace_bytes(int op, int64_t M, int64_t N, int64_t K);
+
+const char *tweo_status_string(tweo_status s);
+
+/*
+ * Per-tensor amax (Sec. 4.3: one scaling factor for the entire tensor;
+ * Sec. 4.4 Eq. 4: max(|X|)).
+ *   x_bf16   [n] bf16, n >= 1
+ *   amax_out one fp32 on the device; overwritten with max_i |x_i| (exact).  An
+ *            Inf in x gives Inf, a NaN gives NaN (the maximum is taken on the
+ *            15-bit magnitude patterns).
+ */
+tweo_status tweo_amax(const void *x_bf16, int64_t n, float *amax_out, void *stream);
+
+/*
+ * Per-tensor E4M3 quantize-cast (Sec. 4.3; E4M3 range +-448, Sec. 1).
+ *   scale = 448 / *amax (fp32 division; amax of 0, Inf or NaN gives scale 1; a
+ *   quotient that overflows gives FLT_MAX), scale_inv = 1 / scale.
+ *   q[r,c] = e4m3( fp32(x[r,c]) * scale ), round to nearest even, saturating at
+ *   +-448, NaN -> NaN code.
+ *   x_bf16 [rows, cols]; cols % 8 == 0.
+ *   amax   one fp32 on the device (e.g. from tweo_amax).
+ *   q      [rows, cols] codes.           qT  [cols, rows] codes or NULL.
+ *   scale_out, scale_inv_out: one fp32 each on the device, or NULL.
+ */
+tweo_status tweo_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
+                               uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
+                               void *stream);
+
+/*
+ * FP8 linear forward with the TWEO penalty fused into the epilogue
+ * (Sec. 4.3 for the per-tensor FP8 linear; Sec. 3.3 for the penalty).
+ *   acc[m,n] = sum_k dec(xq[m,k]) * dec(wq[n,k])            (fp32 accumulate)
+ *   y[m,n]   = bf16( acc[m,n] * (*sx_inv) * (*sw_inv) + residual[m,n] )
+ *   *penalty_sum = sum_{m,n} ( |y[m,n]| / (tau + eps) )^p   over the stored y
+ * The caller forms the mean (divide by M*N), the 1/L layer average and the
+ * lambda(t) weight of the total loss.  Passing the residual stream as
+ * `residual` on the block's last linear makes y the block output
+ * x + MLP(LN(x)) that the paper penalises.
+ *   xq [M,K], wq [N,K] codes, K % 16 == 0.   sx_inv, sw_inv: device fp32.
+ *   residual_bf16 [M,N] or NULL.             y_bf16 [M,N], N % 8 == 0.
+ *   pen NULL (or penalty_sum NULL) = no penalty.  penalty_sum: device fp64.
+ */
+tweo_status tweo_fp8_linear_fwd(const uint8_t *xq, const float *sx_inv, const uint8_t *wq,
+                                const float *sw_inv, const void *residual_bf16, int64_t M,
+                                int64_t N, int64_t K, void *y_bf16, const tweo_penalty_cfg *pen,
+                                double *penalty_sum, void *workspace, size_t workspace_bytes,
+                                void *stream);
+
+/*
+ * FP8 linear backward (autograd of the layer above under the same recipe).
+ *   dx[m,k] = bf16( (sum_n dec(dyq[m,n]) dec(wq[n,k])) * (*sdy_inv) * (*sw_inv) )
+ *   dw[n,k] = bf16( (sum_m dec(dyq[m,n]) dec(xq[m,k])) * (*sdy_inv) * (*sx_inv) )
+ * Operands are passed with the contraction index contiguous:
+ *   dyq [M,N], wqT [K,N]            for dx [M,K]   (N % 16 == 0, K % 8 == 0)
+ *   dyqT [N,M], xqT [K,M]           for dw [N,K]   (M % 16 == 0, K % 8 == 0)
+ * dx_bf16 or dw_bf16 may be NULL to skip that product (its operands may then
+ * be NULL too).
+ */
+tweo_status tweo_fp8_linear_bwd(const uint8_t *dyq, const uint8_t *dyqT, const float *sdy_inv,
+                                const uint8_t *wqT, const float *sw_inv, const uint8_t *xqT,
+                                const float *sx_inv, int64_t M, int64_t N, int64_t K,
+                                void *dx_bf16, void *dw_bf16, void *workspace,
+                                size_t workspace_bytes, void *stream);
+
+/*
+ * Static per-tensor INT8 quantisation (Sec. 4.4 Eq. 4 with b = 8, Q_8 = 127):
+ *   out[i] = clamp( rne( fp32(x[i]) * inv_step ), -127, 127 ),  inv_step = 127 / s
+ * computed once by the caller from the calibration amax.  NaN -> 0.
+ *   x_bf16 [n], n % 8 == 0.
+ */
+tweo_status tweo_quantize_i8(const void *x_bf16, int64_t n, float inv_step, int8_t *out,
+                             void *stream);
+
+/*
+ * W8A8 per-tensor static INT8 linear (Sec. 4.4): exact int32 accumulation,
+ *   y[m,n] = bf16( fp32( sum_k xq[m,k] wq[n,k] ) * alpha ),  alpha = step_x * step_w.
+ *   xq [M,K], wq [N,K] int8, K % 16 == 0; y_bf16 [M,N], N % 8 == 0.
+ * Bit-exact for every M (including the weight-streaming path used for small M).
+ */
+tweo_status tweo_w8a8_linear(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N, int64_t K,
+                             float alpha, void *y_bf16, void *workspace, size_t workspace_bytes,
+                             void *stream);
+
+/*
+ * State a forward pass leaves for the backward pass: the quantized operands,
+ * their transposes and the per-tensor scalars.  All members are device
+ * pointers to caller-owned buffers.
+ *   xq [M,K], xqT [K,M], wq [N,K], wqT [K,N]
+ *   scalars: 16 fp32: [0] amax_x [1] sx [2] sx_inv [3] amax_w [4] sw [5] sw_inv
+ *                     [6] amax_dy [7] sdy [8] sdy_inv, rest reserved.
+ */
+typedef struct {
+    uint8_t *xq;
+    uint8_t *xqT;
+    uint8_t *wq;
+    uint8_t *wqT;
+    float *scalars;
+} tweo_fp8_saved;
+
+/*
+ * Whole forward path from bf16 operands: amax(x), amax(w), both quantize-casts
+ * (with transposes, kept in `saved`), the FP8 GEMM and the fused penalty -
+ * i.e. every step of a per-tensor FP8 linear under current scaling (Sec. 4.3)
+ * plus Sec. 3.3's penalty.  M % 16 == 0, N % 16 == 0, K % 16 == 0.
+ */
+tweo_status tweo_fp8_linear_fwd_bf16(const void *x_bf16, const void *w_bf16,
+                                     const void *residual_bf16, int64_t M, int64_t N, int64_t K,
+                                     void *y_bf16, const tweo_penalty_cfg *pen,
+                                     double *penalty_sum, const tweo_fp8_saved *saved,
+                                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Whole backward path from a bf16 output gradient: amax(dy), quantize-cast of
+ * dy (and its transpose) into dyq [M,N] / dyqT [N,M], then dgrad and wgrad on
+ * the operands saved by the forward pass.
+ */
+tweo_status tweo_fp8_linear_bwd_bf16(const void *dy_bf16, const tweo_fp8_saved *saved, int64_t M,
+                                     int64_t N, int64_t K, uint8_t *dyq, uint8_t *dyqT,
+                                     void *dx_bf16, void *dw_bf16, void *workspace,
+                                     size_t workspace_bytes, void *stream);
+
+/*
+ * Tuning hook for benchmarks and tests: forces the GEMM workgroup tile
+ * (0 = choose from the shape, the default; 1 = 256x256, 2 = 256x128,
+ * 3 = 128x128, 4 = 64x64).  Process-wide, not thread safe.  Results are
+ * identical up to the fp32 summation order.  Returns TWEO_ERR_INVALID_ARG
+ * for an unknown variant.
+ */
+tweo_status tweo_set_gemm_tile(int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TWEO_H */

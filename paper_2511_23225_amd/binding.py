@@ -1,0 +1,178 @@
+"""ctypes binding of libtweo_hip.so: same names as include/tweo.h, argument marshalling only.
+
+Tensors are torch tensors on the GPU (torch provides device memory and streams,
+nothing else); bf16 tensors have dtype torch.bfloat16, E4M3 code tensors
+torch.uint8, INT8 tensors torch.int8.  Every call is enqueued on torch's current
+stream.  A non-zero status raises TweoError; a missing library raises at load
+time - there is no fallback path.
+"""
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libtweo_hip.so")
+
+TWEO_OK, TWEO_ERR_INVALID_ARG, TWEO_ERR_UNSUPPORTED, TWEO_ERR_WORKSPACE, TWEO_ERR_HIP = range(5)
+(TWEO_OP_FP8_LINEAR_FWD, TWEO_OP_FP8_LINEAR_BWD, TWEO_OP_W8A8_LINEAR, TWEO_OP_FP8_LINEAR_FWD_BF16,
+ TWEO_OP_FP8_LINEAR_BWD_BF16) = range(5)
+
+EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quantize_e4m3",
+           "tweo_fp8_linear_fwd", "tweo_fp8_linear_bwd", "tweo_quantize_i8", "tweo_w8a8_linear",
+           "tweo_fp8_linear_fwd_bf16", "tweo_fp8_linear_bwd_bf16", "tweo_set_gemm_tile")
+
+
+class TweoError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: status %d (%s)" % (where, status, status_string(status)))
+
+
+class PenaltyCfg(ctypes.Structure):
+    _fields_ = [("tau", ctypes.c_float), ("eps", ctypes.c_float), ("p", ctypes.c_int)]
+
+
+class Fp8Saved(ctypes.Structure):
+    _fields_ = [("xq", ctypes.c_void_p), ("xqT", ctypes.c_void_p), ("wq", ctypes.c_void_p),
+                ("wqT", ctypes.c_void_p), ("scalars", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def load():
+    """Loads the HIP library (after torch, so that both share one HIP runtime)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    import torch  # noqa: F401  (loads libamdhip64 first)
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("%s is missing: run `python -m paper_2511_23225_amd.build` "
+                          "(or __graft_entry__.build()) first" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    L.tweo_workspace_bytes.restype = sz
+    L.tweo_workspace_bytes.argtypes = [ctypes.c_int, i64, i64, i64]
+    L.tweo_status_string.restype = ctypes.c_char_p
+    L.tweo_status_string.argtypes = [ctypes.c_int]
+    L.tweo_amax.argtypes = [vp, i64, vp, vp]
+    L.tweo_quantize_e4m3.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp]
+    L.tweo_fp8_linear_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp,
+                                      ctypes.POINTER(PenaltyCfg), vp, vp, sz, vp]
+    L.tweo_fp8_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
+    L.tweo_quantize_i8.argtypes = [vp, i64, f32, vp, vp]
+    L.tweo_w8a8_linear.argtypes = [vp, vp, i64, i64, i64, f32, vp, vp, sz, vp]
+    L.tweo_fp8_linear_fwd_bf16.argtypes = [vp, vp, vp, i64, i64, i64, vp, ctypes.POINTER(PenaltyCfg),
+                                           vp, ctypes.POINTER(Fp8Saved), vp, sz, vp]
+    L.tweo_fp8_linear_bwd_bf16.argtypes = [vp, ctypes.POINTER(Fp8Saved), i64, i64, i64, vp, vp, vp,
+                                           vp, vp, sz, vp]
+    L.tweo_set_gemm_tile.argtypes = [ctypes.c_int]
+    for name in EXPORTS:
+        if name not in ("tweo_workspace_bytes", "tweo_status_string"):
+            getattr(L, name).restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def status_string(status):
+    return load().tweo_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status, where):
+    if status != TWEO_OK:
+        raise TweoError(status, where)
+
+
+def _pen(pen):
+    if pen is None:
+        return None
+    tau, eps, p = pen
+    return ctypes.byref(PenaltyCfg(float(tau), float(eps), int(p)))
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return _ptr(workspace), workspace.numel() * workspace.element_size()
+
+
+def tweo_workspace_bytes(op, M, N, K):
+    return int(load().tweo_workspace_bytes(int(op), int(M), int(N), int(K)))
+
+
+def tweo_set_gemm_tile(variant):
+    _check(load().tweo_set_gemm_tile(int(variant)), "tweo_set_gemm_tile")
+
+
+def tweo_amax(x_bf16, amax_out):
+    _check(load().tweo_amax(_ptr(x_bf16), x_bf16.numel(), _ptr(amax_out), _stream()), "tweo_amax")
+
+
+def tweo_quantize_e4m3(x_bf16, amax, q, qT=None, scale_out=None, scale_inv_out=None):
+    rows, cols = x_bf16.shape
+    _check(load().tweo_quantize_e4m3(_ptr(x_bf16), rows, cols, _ptr(amax), _ptr(q), _ptr(qT),
+                                     _ptr(scale_out), _ptr(scale_inv_out), _stream()),
+           "tweo_quantize_e4m3")
+
+
+def tweo_fp8_linear_fwd(xq, sx_inv, wq, sw_inv, y_bf16, residual_bf16=None, pen=None,
+                        penalty_sum=None, workspace=None):
+    M, K = xq.shape
+    N = wq.shape[0]
+    wp, wb = _ws(workspace)
+    _check(load().tweo_fp8_linear_fwd(_ptr(xq), _ptr(sx_inv), _ptr(wq), _ptr(sw_inv),
+                                      _ptr(residual_bf16), M, N, K, _ptr(y_bf16), _pen(pen),
+                                      _ptr(penalty_sum), wp, wb, _stream()), "tweo_fp8_linear_fwd")
+
+
+def tweo_fp8_linear_bwd(dyq, dyqT, sdy_inv, wqT, sw_inv, xqT, sx_inv, M, N, K, dx_bf16=None,
+                        dw_bf16=None, workspace=None):
+    wp, wb = _ws(workspace)
+    _check(load().tweo_fp8_linear_bwd(_ptr(dyq), _ptr(dyqT), _ptr(sdy_inv), _ptr(wqT), _ptr(sw_inv),
+                                      _ptr(xqT), _ptr(sx_inv), M, N, K, _ptr(dx_bf16), _ptr(dw_bf16),
+                                      wp, wb, _stream()), "tweo_fp8_linear_bwd")
+
+
+def tweo_quantize_i8(x_bf16, inv_step, out):
+    _check(load().tweo_quantize_i8(_ptr(x_bf16), x_bf16.numel(), float(inv_step), _ptr(out),
+                                   _stream()), "tweo_quantize_i8")
+
+
+def tweo_w8a8_linear(xq, wq, alpha, y_bf16, workspace=None):
+    M, K = xq.shape
+    N = wq.shape[0]
+    wp, wb = _ws(workspace)
+    _check(load().tweo_w8a8_linear(_ptr(xq), _ptr(wq), M, N, K, float(alpha), _ptr(y_bf16), wp, wb,
+                                   _stream()), "tweo_w8a8_linear")
+
+
+def make_saved(xq, xqT, wq, wqT, scalars):
+    return Fp8Saved(xq.data_ptr(), xqT.data_ptr(), wq.data_ptr(), wqT.data_ptr(), scalars.data_ptr())
+
+
+def tweo_fp8_linear_fwd_bf16(x_bf16, w_bf16, y_bf16, saved, residual_bf16=None, pen=None,
+                             penalty_sum=None, workspace=None):
+    M, K = x_bf16.shape
+    N = w_bf16.shape[0]
+    wp, wb = _ws(workspace)
+    _check(load().tweo_fp8_linear_fwd_bf16(_ptr(x_bf16), _ptr(w_bf16), _ptr(residual_bf16), M, N, K,
+                                           _ptr(y_bf16), _pen(pen), _ptr(penalty_sum),
+                                           ctypes.byref(saved), wp, wb, _stream()),
+           "tweo_fp8_linear_fwd_bf16")
+
+
+def tweo_fp8_linear_bwd_bf16(dy_bf16, saved, K, dyq, dyqT, dx_bf16=None, dw_bf16=None,
+                             workspace=None):
+    M, N = dy_bf16.shape
+    wp, wb = _ws(workspace)
+    _check(load().tweo_fp8_linear_bwd_bf16(_ptr(dy_bf16), ctypes.byref(saved), M, N, K, _ptr(dyq),
+                                           _ptr(dyqT), _ptr(dx_bf16), _ptr(dw_bf16), wp, wb,
+                                           _stream()), "tweo_fp8_linear_bwd_bf16")

@@ -1,0 +1,286 @@
+// C ABI of the library (include/tweo.h): argument validation and dispatch.
+// Nothing here allocates, frees or synchronises; everything is enqueued on the
+// caller's stream.
+#include "../../include/tweo.h"
+#include "kernels.h"
+
+using namespace tweo;
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t b) { return b == 0 ? 256 : (b + 255) / 256 * 256; }
+inline tweo_status hip_status(hipError_t e) { return e == hipSuccess ? TWEO_OK : TWEO_ERR_HIP; }
+constexpr int64_t kMaxDim = (int64_t)1 << 30;
+
+inline bool dims_ok(int64_t M, int64_t N, int64_t K)
+{
+    return M > 0 && N > 0 && K > 0 && M <= kMaxDim && N <= kMaxDim && K <= ((int64_t)1 << 24) &&
+           M * N < ((int64_t)1 << 40);
+}
+
+// upper bound on the number of GEMM workgroups for any tile shape
+inline size_t partial_slots(int64_t M, int64_t N) { return (size_t)(((M + 63) / 64) * ((N + 63) / 64)); }
+
+tweo_status check_penalty(const tweo_penalty_cfg *pen, double *penalty_sum, float &inv_tau, int &p)
+{
+    p = 0;
+    inv_tau = 0.0f;
+    if (!pen || !penalty_sum)
+        return TWEO_OK;
+    if (!(pen->tau > 0.0f) || !(pen->eps >= 0.0f))
+        return TWEO_ERR_INVALID_ARG;
+    if (pen->p < 1 || pen->p > 8)
+        return TWEO_ERR_UNSUPPORTED;
+    inv_tau = (float)(1.0 / ((double)pen->tau + (double)pen->eps));
+    p = pen->p;
+    return TWEO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *tweo_status_string(tweo_status s)
+{
+    switch (s) {
+    case TWEO_OK: return "ok";
+    case TWEO_ERR_INVALID_ARG: return "invalid argument";
+    case TWEO_ERR_UNSUPPORTED: return "unsupported shape or option";
+    case TWEO_ERR_WORKSPACE: return "workspace missing or too small";
+    case TWEO_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+tweo_status tweo_set_gemm_tile(int variant)
+{
+    if (variant < 0 || variant > 4)
+        return TWEO_ERR_INVALID_ARG;
+    set_gemm_tile_override(variant);
+    return TWEO_OK;
+}
+
+size_t tweo_workspace_bytes(int op, int64_t M, int64_t N, int64_t K)
+{
+    (void)K;
+    if (M <= 0 || N <= 0)
+        return 256;
+    switch (op) {
+    case TWEO_OP_FP8_LINEAR_FWD:
+    case TWEO_OP_FP8_LINEAR_FWD_BF16:
+        return round256(partial_slots(M, N) * sizeof(float));
+    default:
+        return 256;
+    }
+}
+
+tweo_status tweo_amax(const void *x_bf16, int64_t n, float *amax_out, void *stream)
+{
+    if (!x_bf16 || !amax_out || n <= 0 || !aligned16(x_bf16))
+        return TWEO_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = launch_fill_u32((uint32_t *)amax_out, 1, 0u, s);
+    if (e != hipSuccess)
+        return TWEO_ERR_HIP;
+    return hip_status(launch_amax(x_bf16, n, amax_out, s));
+}
+
+tweo_status tweo_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
+                               uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
+                               void *stream)
+{
+    if (!x_bf16 || !amax || !q || rows <= 0 || cols <= 0 || !aligned16(x_bf16) || !aligned16(q) ||
+        (qT && !aligned16(qT)))
+        return TWEO_ERR_INVALID_ARG;
+    if (cols % 8 != 0 || rows > kMaxDim || cols > kMaxDim)
+        return TWEO_ERR_UNSUPPORTED;
+    return hip_status(launch_quantize_e4m3(x_bf16, rows, cols, amax, q, qT, scale_out,
+                                           scale_inv_out, (hipStream_t)stream));
+}
+
+tweo_status tweo_fp8_linear_fwd(const uint8_t *xq, const float *sx_inv, const uint8_t *wq,
+                                const float *sw_inv, const void *residual_bf16, int64_t M,
+                                int64_t N, int64_t K, void *y_bf16, const tweo_penalty_cfg *pen,
+                                double *penalty_sum, void *workspace, size_t workspace_bytes,
+                                void *stream)
+{
+    if (!xq || !sx_inv || !wq || !sw_inv || !y_bf16 || M <= 0 || N <= 0 || K <= 0 ||
+        !aligned16(xq) || !aligned16(wq) || !aligned16(y_bf16) ||
+        (residual_bf16 && !aligned16(residual_bf16)))
+        return TWEO_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || K % 16 != 0 || N % 8 != 0)
+        return TWEO_ERR_UNSUPPORTED;
+    float inv_tau;
+    int p;
+    tweo_status st = check_penalty(pen, penalty_sum, inv_tau, p);
+    if (st != TWEO_OK)
+        return st;
+    if (p != 0 && (!workspace || workspace_bytes < tweo_workspace_bytes(TWEO_OP_FP8_LINEAR_FWD, M, N, K) ||
+                   !aligned16(workspace)))
+        return TWEO_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    GemmArgs a{};
+    a.A = xq;
+    a.B = wq;
+    a.M = M;
+    a.N = N;
+    a.K = K;
+    a.s0 = sx_inv;
+    a.s1 = sw_inv;
+    a.residual = residual_bf16;
+    a.out = y_bf16;
+    a.inv_tau = inv_tau;
+    a.p = p;
+    a.partials = (float *)workspace;
+    hipError_t e = launch_fp8_gemm(a, s);
+    if (e != hipSuccess)
+        return TWEO_ERR_HIP;
+    if (p != 0)
+        e = launch_penalty_finish((const float *)workspace, fp8_gemm_workgroups(M, N, K),
+                                  penalty_sum, s);
+    return hip_status(e);
+}
+
+tweo_status tweo_fp8_linear_bwd(const uint8_t *dyq, const uint8_t *dyqT, const float *sdy_inv,
+                                const uint8_t *wqT, const float *sw_inv, const uint8_t *xqT,
+                                const float *sx_inv, int64_t M, int64_t N, int64_t K,
+                                void *dx_bf16, void *dw_bf16, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    if (M <= 0 || N <= 0 || K <= 0 || !sdy_inv || (!dx_bf16 && !dw_bf16))
+        return TWEO_ERR_INVALID_ARG;
+    if (dx_bf16 && (!dyq || !wqT || !sw_inv || !aligned16(dyq) || !aligned16(wqT) || !aligned16(dx_bf16)))
+        return TWEO_ERR_INVALID_ARG;
+    if (dw_bf16 && (!dyqT || !xqT || !sx_inv || !aligned16(dyqT) || !aligned16(xqT) || !aligned16(dw_bf16)))
+        return TWEO_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || K % 8 != 0 || (dx_bf16 && N % 16 != 0) || (dw_bf16 && M % 16 != 0) ||
+        M > ((int64_t)1 << 24) || N > ((int64_t)1 << 24))
+        return TWEO_ERR_UNSUPPORTED;
+    hipStream_t s = (hipStream_t)stream;
+    if (dx_bf16) {  // dX[M,K] = dYq[M,N] * WqT[K,N]^T   (contraction over N)
+        GemmArgs a{};
+        a.A = dyq;
+        a.B = wqT;
+        a.M = M;
+        a.N = K;
+        a.K = N;
+        a.s0 = sdy_inv;
+        a.s1 = sw_inv;
+        a.out = dx_bf16;
+        hipError_t e = launch_fp8_gemm(a, s);
+        if (e != hipSuccess)
+            return TWEO_ERR_HIP;
+    }
+    if (dw_bf16) {  // dW[N,K] = dYqT[N,M] * XqT[K,M]^T  (contraction over M)
+        GemmArgs a{};
+        a.A = dyqT;
+        a.B = xqT;
+        a.M = N;
+        a.N = K;
+        a.K = M;
+        a.s0 = sdy_inv;
+        a.s1 = sx_inv;
+        a.out = dw_bf16;
+        hipError_t e = launch_fp8_gemm(a, s);
+        if (e != hipSuccess)
+            return TWEO_ERR_HIP;
+    }
+    return TWEO_OK;
+}
+
+tweo_status tweo_quantize_i8(const void *x_bf16, int64_t n, float inv_step, int8_t *out,
+                             void *stream)
+{
+    if (!x_bf16 || !out || n <= 0 || !aligned16(x_bf16) || !aligned16(out) || !(inv_step == inv_step))
+        return TWEO_ERR_INVALID_ARG;
+    if (n % 8 != 0)
+        return TWEO_ERR_UNSUPPORTED;
+    return hip_status(launch_quantize_i8(x_bf16, n, inv_step, out, (hipStream_t)stream));
+}
+
+tweo_status tweo_w8a8_linear(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N, int64_t K,
+                             float alpha, void *y_bf16, void *workspace, size_t workspace_bytes,
+                             void *stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!xq || !wq || !y_bf16 || M <= 0 || N <= 0 || K <= 0 || !aligned16(xq) || !aligned16(wq) ||
+        !aligned16(y_bf16))
+        return TWEO_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || K % 16 != 0 || N % 8 != 0)
+        return TWEO_ERR_UNSUPPORTED;
+    GemmArgs a{};
+    a.A = (const uint8_t *)xq;
+    a.B = (const uint8_t *)wq;
+    a.M = M;
+    a.N = N;
+    a.K = K;
+    a.alpha = alpha;
+    a.out = y_bf16;
+    return hip_status(launch_i8_gemm(a, (hipStream_t)stream));
+}
+
+tweo_status tweo_fp8_linear_fwd_bf16(const void *x_bf16, const void *w_bf16,
+                                     const void *residual_bf16, int64_t M, int64_t N, int64_t K,
+                                     void *y_bf16, const tweo_penalty_cfg *pen,
+                                     double *penalty_sum, const tweo_fp8_saved *saved,
+                                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x_bf16 || !w_bf16 || !y_bf16 || !saved || !saved->xq || !saved->xqT || !saved->wq ||
+        !saved->wqT || !saved->scalars || M <= 0 || N <= 0 || K <= 0 || !aligned16(x_bf16) ||
+        !aligned16(w_bf16) || !aligned16(saved->xq) || !aligned16(saved->xqT) ||
+        !aligned16(saved->wq) || !aligned16(saved->wqT) || !aligned16(saved->scalars))
+        return TWEO_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || M % 16 != 0 || N % 16 != 0 || K % 16 != 0)
+        return TWEO_ERR_UNSUPPORTED;
+    float inv_tau;
+    int p;
+    tweo_status st = check_penalty(pen, penalty_sum, inv_tau, p);
+    if (st != TWEO_OK)
+        return st;
+    if (p != 0 && (!workspace || workspace_bytes < tweo_workspace_bytes(TWEO_OP_FP8_LINEAR_FWD_BF16, M, N, K)))
+        return TWEO_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    float *sc = saved->scalars;
+    hipError_t e = launch_fill_u32((uint32_t *)sc, 6, 0u, s);
+    if (e == hipSuccess)
+        e = launch_amax(x_bf16, M * K, sc + 0, s);
+    if (e == hipSuccess)
+        e = launch_amax(w_bf16, N * K, sc + 3, s);
+    if (e == hipSuccess)
+        e = launch_quantize_e4m3(x_bf16, M, K, sc + 0, saved->xq, saved->xqT, sc + 1, sc + 2, s);
+    if (e == hipSuccess)
+        e = launch_quantize_e4m3(w_bf16, N, K, sc + 3, saved->wq, saved->wqT, sc + 4, sc + 5, s);
+    if (e != hipSuccess)
+        return TWEO_ERR_HIP;
+    return tweo_fp8_linear_fwd(saved->xq, sc + 2, saved->wq, sc + 5, residual_bf16, M, N, K, y_bf16,
+                               pen, penalty_sum, workspace, workspace_bytes, stream);
+}
+
+tweo_status tweo_fp8_linear_bwd_bf16(const void *dy_bf16, const tweo_fp8_saved *saved, int64_t M,
+                                     int64_t N, int64_t K, uint8_t *dyq, uint8_t *dyqT,
+                                     void *dx_bf16, void *dw_bf16, void *workspace,
+                                     size_t workspace_bytes, void *stream)
+{
+    if (!dy_bf16 || !saved || !saved->xqT || !saved->wqT || !saved->scalars || !dyq || !dyqT ||
+        M <= 0 || N <= 0 || K <= 0 || !aligned16(dy_bf16) || !aligned16(dyq) || !aligned16(dyqT))
+        return TWEO_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || M % 16 != 0 || N % 16 != 0 || K % 16 != 0)
+        return TWEO_ERR_UNSUPPORTED;
+    hipStream_t s = (hipStream_t)stream;
+    float *sc = saved->scalars;
+    hipError_t e = launch_fill_u32((uint32_t *)(sc + 6), 3, 0u, s);
+    if (e == hipSuccess)
+        e = launch_amax(dy_bf16, M * N, sc + 6, s);
+    if (e == hipSuccess)
+        e = launch_quantize_e4m3(dy_bf16, M, N, sc + 6, dyq, dyqT, sc + 7, sc + 8, s);
+    if (e != hipSuccess)
+        return TWEO_ERR_HIP;
+    return tweo_fp8_linear_bwd(dyq, dyqT, sc + 8, saved->wqT, sc + 5, saved->xqT, sc + 2, M, N, K,
+                               dx_bf16, dw_bf16, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

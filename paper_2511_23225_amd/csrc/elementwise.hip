@@ -1,0 +1,287 @@
+// HBM-bound passes of the per-tensor FP8 / INT8 recipes: amax reduction, E4M3
+// quantize-cast (with a transposed copy), static INT8 quantize, and the small
+// fill / finish kernels around them.  gfx950 only.
+#include "kernels.h"
+#include "device_utils.h"
+
+namespace tweo {
+
+// ---------------------------------------------------------------------------
+// fill: clears device scalars without a memset node (safe under graph capture).
+__global__ void fill_u32_kernel(uint32_t *p, int n, uint32_t v)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        p[i] = v;
+}
+
+hipError_t launch_fill_u32(uint32_t *p, int n, uint32_t v, hipStream_t s)
+{
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((n + 63) / 64), dim3(64), 0, s, p, n, v);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// amax (Sec. 4.3 / Eq. 4): max over the whole tensor of the 15-bit magnitude
+// patterns.  2 B/element of HBM reads, nothing else: 16-byte loads, four in
+// flight per lane, packed 16-bit max, wave shuffle + LDS tree, then one integer
+// atomicMax per workgroup on the fp32 bit pattern (positive floats order like
+// unsigned integers, so the result is exact and order independent).
+constexpr int kAmaxThreads = 256;
+
+__device__ __forceinline__ uint32_t pk_absmax(uint32_t m, uint32_t d)
+{
+    u16x2 a = __builtin_bit_cast(u16x2, m);
+    u16x2 b = __builtin_bit_cast(u16x2, d & 0x7FFF7FFFu);
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(a, b));
+}
+
+__device__ __forceinline__ uint32_t pk_absmax4(uint32_t m, uint4 v)
+{
+    m = pk_absmax(m, v.x);
+    m = pk_absmax(m, v.y);
+    m = pk_absmax(m, v.z);
+    return pk_absmax(m, v.w);
+}
+
+__global__ __launch_bounds__(kAmaxThreads) void amax_kernel(const uint4 *__restrict__ x,
+                                                            int64_t n_vec,
+                                                            const uint16_t *__restrict__ tail,
+                                                            int n_tail, uint32_t *out)
+{
+    __shared__ uint32_t red[kAmaxThreads / kWave];
+    const int64_t stride = (int64_t)gridDim.x * kAmaxThreads;
+    int64_t i = (int64_t)blockIdx.x * kAmaxThreads + threadIdx.x;
+    uint32_t m = 0;
+    for (; i + 3 * stride < n_vec; i += 4 * stride) {
+        uint4 v0 = x[i], v1 = x[i + stride], v2 = x[i + 2 * stride], v3 = x[i + 3 * stride];
+        m = pk_absmax4(m, v0);
+        m = pk_absmax4(m, v1);
+        m = pk_absmax4(m, v2);
+        m = pk_absmax4(m, v3);
+    }
+    for (; i < n_vec; i += stride)
+        m = pk_absmax4(m, x[i]);
+    if (blockIdx.x == 0 && (int)threadIdx.x < n_tail)
+        m = pk_absmax(m, tail[threadIdx.x]);
+    uint32_t r = (m & 0xFFFFu) > (m >> 16) ? (m & 0xFFFFu) : (m >> 16);
+    r = wave_reduce_max_u32(r);
+    if ((threadIdx.x & (kWave - 1)) == 0)
+        red[threadIdx.x / kWave] = r;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kAmaxThreads / kWave; ++w)
+            r = red[w] > r ? red[w] : r;
+        atomicMax(out, r << 16);  // bf16 magnitude widened to the fp32 pattern
+    }
+}
+
+hipError_t launch_amax(const void *x_bf16, int64_t n, float *amax_zeroed, hipStream_t s)
+{
+    int64_t n_vec = n / 8;
+    int n_tail = (int)(n % 8);
+    int64_t blocks = (n_vec + kAmaxThreads * 4 - 1) / (kAmaxThreads * 4);
+    if (blocks < 1)
+        blocks = 1;
+    if (blocks > 256 * 8)
+        blocks = 256 * 8;
+    hipLaunchKernelGGL(amax_kernel, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, s,
+                       (const uint4 *)x_bf16, n_vec, (const uint16_t *)x_bf16 + n_vec * 8, n_tail,
+                       (uint32_t *)amax_zeroed);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// E4M3 quantize-cast (Sec. 4.3): q = e4m3(fp32(x) * scale), scale = 448/amax
+// derived on the device from the amax scalar.  Rounding is the hardware's
+// round-to-nearest-even conversion; saturation at +-448 (Sec. 1) is applied in
+// front of it so that the result does not depend on the conversion's overflow
+// behaviour, and NaN is routed around the clamp.
+//
+// Each lane owns an 8x8 block of elements: eight 16-byte loads (one per row),
+// eight 8-byte stores of q, and - after an in-register 8x8 byte transpose with
+// v_perm_b32 - eight 8-byte stores of qT.  A wave is 8x8 lanes = 64x64
+// elements, so loads are 128 B contiguous per row and both outputs are written
+// in 64 B contiguous pieces.  No LDS, no barriers.
+// 3 B/element of HBM traffic without qT, 4 B/element with it.
+constexpr int kQuantThreads = 256;
+constexpr int kQuantTileRows = 64;
+constexpr int kQuantTileCols = 256;
+
+__device__ __forceinline__ float sat_e4m3(float v)
+{
+    float c = __builtin_amdgcn_fmed3f(v, -448.0f, 448.0f);
+    return v != v ? v : c;
+}
+
+__device__ __forceinline__ uint32_t cvt4_e4m3(float a, float b, float c, float d)
+{
+    int r = __builtin_amdgcn_cvt_pk_fp8_f32(sat_e4m3(a), sat_e4m3(b), 0, false);
+    r = __builtin_amdgcn_cvt_pk_fp8_f32(sat_e4m3(c), sat_e4m3(d), r, true);
+    return (uint32_t)r;
+}
+
+// rows a,b,c,d (one dword = 4 bytes each) -> columns t0..t3 of the 4x4 byte matrix
+__device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d,
+                                                   uint32_t &t0, uint32_t &t1, uint32_t &t2,
+                                                   uint32_t &t3)
+{
+    uint32_t p0 = __builtin_amdgcn_perm(b, a, 0x05010400u);  // a0 b0 a1 b1
+    uint32_t p1 = __builtin_amdgcn_perm(b, a, 0x07030602u);  // a2 b2 a3 b3
+    uint32_t p2 = __builtin_amdgcn_perm(d, c, 0x05010400u);  // c0 d0 c1 d1
+    uint32_t p3 = __builtin_amdgcn_perm(d, c, 0x07030602u);  // c2 d2 c3 d3
+    t0 = __builtin_amdgcn_perm(p2, p0, 0x05040100u);         // a0 b0 c0 d0
+    t1 = __builtin_amdgcn_perm(p2, p0, 0x07060302u);         // a1 b1 c1 d1
+    t2 = __builtin_amdgcn_perm(p3, p1, 0x05040100u);         // a2 b2 c2 d2
+    t3 = __builtin_amdgcn_perm(p3, p1, 0x07060302u);         // a3 b3 c3 d3
+}
+
+template <bool WITH_T>
+__global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
+    const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
+    const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
+    float *scale_out, float *scale_inv_out)
+{
+    const float scale = scale_from_amax(*amax);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (scale_out)
+            *scale_out = scale;
+        if (scale_inv_out)
+            *scale_inv_out = 1.0f / scale;
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int64_t by = blockIdx.x / tiles_x, bx = blockIdx.x % tiles_x;
+    const int64_t r0 = by * kQuantTileRows + (lane >> 3) * 8;
+    const int64_t c0 = bx * kQuantTileCols + wave * 64 + (lane & 7) * 8;
+    if (c0 >= cols || r0 >= rows)
+        return;
+
+    uint4 in[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        in[i] = make_uint4(0, 0, 0, 0);
+        if (r0 + i < rows)
+            in[i] = *(const uint4 *)(x + (r0 + i) * cols + c0);
+    }
+    uint32_t lo[8], hi[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        lo[i] = cvt4_e4m3(bf16lo_to_f32(in[i].x) * scale, bf16hi_to_f32(in[i].x) * scale,
+                          bf16lo_to_f32(in[i].y) * scale, bf16hi_to_f32(in[i].y) * scale);
+        hi[i] = cvt4_e4m3(bf16lo_to_f32(in[i].z) * scale, bf16hi_to_f32(in[i].z) * scale,
+                          bf16lo_to_f32(in[i].w) * scale, bf16hi_to_f32(in[i].w) * scale);
+        if (r0 + i < rows)
+            *(uint2 *)(q + (r0 + i) * cols + c0) = make_uint2(lo[i], hi[i]);
+    }
+    if (WITH_T) {
+        // T[j] = column j of the 8x8 block = bytes (row0..row7)
+        uint32_t ta[8], tb[8];  // ta: rows 0-3, tb: rows 4-7
+        transpose4x4_bytes(lo[0], lo[1], lo[2], lo[3], ta[0], ta[1], ta[2], ta[3]);
+        transpose4x4_bytes(hi[0], hi[1], hi[2], hi[3], ta[4], ta[5], ta[6], ta[7]);
+        transpose4x4_bytes(lo[4], lo[5], lo[6], lo[7], tb[0], tb[1], tb[2], tb[3]);
+        transpose4x4_bytes(hi[4], hi[5], hi[6], hi[7], tb[4], tb[5], tb[6], tb[7]);
+        const bool full = (r0 + 8 <= rows) && ((rows & 7) == 0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint8_t *dst = qT + (c0 + j) * rows + r0;
+            if (full) {
+                *(uint2 *)dst = make_uint2(ta[j], tb[j]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (r0 + i < rows)
+                        dst[i] = (uint8_t)((i < 4 ? ta[j] >> (8 * i) : tb[j] >> (8 * (i - 4))) & 0xFF);
+            }
+        }
+    }
+}
+
+hipError_t launch_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
+                                uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
+                                hipStream_t s)
+{
+    int64_t tiles_x = (cols + kQuantTileCols - 1) / kQuantTileCols;
+    int64_t tiles_y = (rows + kQuantTileRows - 1) / kQuantTileRows;
+    dim3 grid((unsigned)(tiles_x * tiles_y)), block(kQuantThreads);
+    if (qT)
+        hipLaunchKernelGGL(quantize_e4m3_kernel<true>, grid, block, 0, s, (const uint16_t *)x_bf16,
+                           rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out);
+    else
+        hipLaunchKernelGGL(quantize_e4m3_kernel<false>, grid, block, 0, s, (const uint16_t *)x_bf16,
+                           rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Static INT8 quantize (Sec. 4.4 Eq. 4, Q_8 = 127): q = clamp(rne(x*inv_step), +-127).
+// 16 elements per lane: two 16-byte loads, one 16-byte store.  3 B/element.
+constexpr int kQi8Threads = 256;
+
+__device__ __forceinline__ uint32_t q_i8(float v, float inv_step)
+{
+    float prod = v * inv_step;
+    float r = __builtin_rintf(prod);  // v_rndne_f32: ties to even
+    r = __builtin_amdgcn_fmed3f(r, -127.0f, 127.0f);
+    r = (prod != prod) ? 0.0f : r;  // NaN -> 0
+    return (uint32_t)(int)r & 0xFFu;
+}
+
+__device__ __forceinline__ uint32_t q_i8x4(uint32_t d0, uint32_t d1, float s)
+{
+    return q_i8(bf16lo_to_f32(d0), s) | (q_i8(bf16hi_to_f32(d0), s) << 8) |
+           (q_i8(bf16lo_to_f32(d1), s) << 16) | (q_i8(bf16hi_to_f32(d1), s) << 24);
+}
+
+__global__ __launch_bounds__(kQi8Threads) void quantize_i8_kernel(const uint4 *__restrict__ x,
+                                                                  int64_t n_vec, float inv_step,
+                                                                  uint2 *__restrict__ out)
+{
+    const int64_t stride = (int64_t)gridDim.x * kQi8Threads;
+    for (int64_t i = (int64_t)blockIdx.x * kQi8Threads + threadIdx.x; i < n_vec; i += stride) {
+        uint4 v = x[i];
+        out[i] = make_uint2(q_i8x4(v.x, v.y, inv_step), q_i8x4(v.z, v.w, inv_step));
+    }
+}
+
+hipError_t launch_quantize_i8(const void *x_bf16, int64_t n, float inv_step, int8_t *out,
+                              hipStream_t s)
+{
+    int64_t n_vec = n / 8;
+    int64_t blocks = (n_vec + kQi8Threads - 1) / kQi8Threads;
+    if (blocks > 256 * 16)
+        blocks = 256 * 16;
+    hipLaunchKernelGGL(quantize_i8_kernel, dim3((unsigned)blocks), dim3(kQi8Threads), 0, s,
+                       (const uint4 *)x_bf16, n_vec, inv_step, (uint2 *)out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Penalty finish: sums the per-workgroup fp32 partials in a fixed order in fp64.
+constexpr int kFinishThreads = 256;
+
+__global__ __launch_bounds__(kFinishThreads) void penalty_finish_kernel(
+    const float *__restrict__ partials, int n, double *out)
+{
+    __shared__ double red[kFinishThreads];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += kFinishThreads)
+        s += (double)partials[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = kFinishThreads / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w)
+            red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0)
+        *out = red[0];
+}
+
+hipError_t launch_penalty_finish(const float *partials, int n, double *out, hipStream_t s)
+{
+    hipLaunchKernelGGL(penalty_finish_kernel, dim3(1), dim3(kFinishThreads), 0, s, partials, n, out);
+    return hipGetLastError();
+}
+
+}  // namespace tweo

@@ -1,0 +1,43 @@
+// Host-side launchers of the HIP kernels (internal to the library; the public
+// surface is include/tweo.h).  Every launcher enqueues on `s` and returns
+// hipGetLastError().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace tweo {
+
+hipError_t launch_fill_u32(uint32_t *p, int n, uint32_t v, hipStream_t s);
+hipError_t launch_amax(const void *x_bf16, int64_t n, float *amax_zeroed, hipStream_t s);
+hipError_t launch_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
+                                uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
+                                hipStream_t s);
+hipError_t launch_quantize_i8(const void *x_bf16, int64_t n, float inv_step, int8_t *out,
+                              hipStream_t s);
+hipError_t launch_penalty_finish(const float *partials, int n, double *out, hipStream_t s);
+
+// C[M,N] = A[M,K] * B[N,K]^T on 8-bit operands, both K-contiguous.
+struct GemmArgs {
+    const uint8_t *A;
+    const uint8_t *B;
+    int64_t M, N, K;
+    const float *s0;        // FP8: alpha = (*s0) * (*s1), device scalars
+    const float *s1;
+    float alpha;            // INT8: host scalar
+    const void *residual;   // bf16 [M,N] or nullptr (FP8 only)
+    void *out;              // bf16 [M,N]
+    float inv_tau;          // 1 / (tau + eps)
+    int p;                  // penalty power; 0 = no penalty
+    float *partials;        // one fp32 per workgroup when p != 0
+};
+
+// Number of workgroups (= penalty partials) the FP8 GEMM uses for this shape.
+int fp8_gemm_workgroups(int64_t M, int64_t N, int64_t K);
+hipError_t launch_fp8_gemm(const GemmArgs &a, hipStream_t s);
+hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s);
+
+// Tile-shape override for benchmarking sweeps: 0 = heuristic.
+void set_gemm_tile_override(int variant);
+
+}  // namespace tweo

@@ -1,0 +1,62 @@
+"""Helpers shared by the GPU parity tests: host<->device marshalling and tolerance checks."""
+import numpy as np
+import torch
+
+import paper_2511_23225_amd as tw
+
+DEV = "cuda:0"
+PEN = (3.0, 1e-6, 4)  # tau, eps, p used in all of the paper's experiments (Sec. 4.1)
+
+
+def to_dev_bf16(bits_u16):
+    return torch.from_numpy(np.ascontiguousarray(bits_u16).view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def bf16_bits(t):
+    return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def to_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def scalar_f32(v=0.0):
+    return torch.full((4,), float(v), dtype=torch.float32, device=DEV)  # 16-byte slot
+
+
+def gpu_amax(x_dev):
+    out = scalar_f32(-1.0)
+    tw.tweo_amax(x_dev, out)
+    return out
+
+
+def gpu_quantize(x_dev, amax_dev, transpose=True):
+    r, c = x_dev.shape
+    q = torch.empty((r, c), dtype=torch.uint8, device=DEV)
+    qT = torch.empty((c, r), dtype=torch.uint8, device=DEV) if transpose else None
+    s, si = scalar_f32(), scalar_f32()
+    tw.tweo_quantize_e4m3(x_dev, amax_dev, q, qT, s, si)
+    return q, qT, s, si
+
+
+def workspace(op, M, N, K):
+    return torch.empty(tw.tweo_workspace_bytes(op, M, N, K), dtype=torch.uint8, device=DEV)
+
+
+def check_gemm(got_bits, ref64, refabs, K, what):
+    """Contract (rel 1e-2 with an rms floor) and the tighter bound a correct kernel earns:
+    bf16 output rounding (2^-8 relative) + fp32 accumulation of K terms."""
+    got = (got_bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    diff = np.abs(got - ref64)
+    rms = np.sqrt(np.mean(ref64 ** 2))
+    contract = 1e-2 * np.abs(ref64) + 1e-2 * rms
+    bad = diff > contract
+    assert not bad.any(), "%s: %d elements outside the 1e-2 contract, worst %g" % (
+        what, bad.sum(), (diff / (np.abs(ref64) + rms)).max())
+    earned = 2.0 ** -8 * np.abs(ref64) + 8.0 * np.sqrt(K) * 2.0 ** -24 * refabs + 1e-30
+    bad = diff > earned
+    assert not bad.any(), "%s: %d elements outside the earned bound, worst ratio %g" % (
+        what, bad.sum(), (diff / earned).max())
+    nrm = np.linalg.norm(diff) / max(np.linalg.norm(ref64), 1e-300)
+    assert nrm < 4e-3, "%s: normwise error %g" % (what, nrm)
+    return nrm

@@ -1,0 +1,196 @@
+"""GPU parity of the FP8 linear forward (+ fused TWEO penalty) and backward, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2511_23225_amd as tw
+from paper_2511_23225_amd import synth
+from gpu_util import (DEV, PEN, to_dev_bf16, to_dev, bf16_bits, scalar_f32, gpu_amax, gpu_quantize,
+                      workspace, check_gemm)
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def oracle_quantized(x):
+    amax = oracle.amax_bf16(x)
+    s, si = oracle.scale_from_amax(amax)
+    q, qT = oracle.quantize_e4m3(x, s)
+    return q, qT, si
+
+
+def run_fwd(xq, wq, sxi, swi, M, N, K, residual=None, pen=PEN):
+    y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    S = torch.zeros(2, dtype=torch.float64, device=DEV)
+    ws = workspace(tw.TWEO_OP_FP8_LINEAR_FWD, M, N, K)
+    tw.tweo_fp8_linear_fwd(to_dev(xq), scalar_f32(sxi), to_dev(wq), scalar_f32(swi), y,
+                           residual_bf16=None if residual is None else to_dev_bf16(residual),
+                           pen=pen, penalty_sum=S if pen else None, workspace=ws)
+    torch.cuda.synchronize()
+    return bf16_bits(y), float(S.cpu()[0])
+
+
+CASES = [  # (cfg, gemm, M, K, N): several tiles and ragged tails in M and N
+    (0, 0, 256, 512, 512),
+    (0, 0, 200, 384, 136),
+    (1, 0, 515, 768, 264),
+    (2, 0, 333, 256, 1000),
+    (3, 4, 130, 1408, 72),
+    (0, 0, 16, 16, 8),
+]
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("case", CASES)
+def test_fwd_with_penalty(case, tile):
+    cfg, gi, M, K, N = case
+    say("fwd cfg=%d gemm=%d M=%d K=%d N=%d tile=%d" % (cfg, gi, M, K, N, tile))
+    x, w, _ = synth.fp8_linear_inputs(cfg, gi, M=M, K=K, N=N)
+    xq, _, sxi = oracle_quantized(x)
+    wq, _, swi = oracle_quantized(w)
+    ref, refabs, refbf = oracle.fp8_linear_fwd(xq, wq, sxi, swi)
+    tw.tweo_set_gemm_tile(tile)
+    try:
+        got, S = run_fwd(xq, wq, sxi, swi, M, N, K)
+    finally:
+        tw.tweo_set_gemm_tile(0)
+    check_gemm(got, ref, refabs, K, "fwd")
+    Sref = oracle.penalty_sum(refbf, *PEN)
+    assert abs(S - Sref) <= 1e-4 * Sref, (S, Sref)
+
+
+def test_fwd_residual_is_block_output():
+    # y = x + f(x): the penalised tensor is the block output (Sec. 3.3)
+    cfg, gi, M, K, N = 1, 3, 384, 1024, 256
+    say("fwd residual M=%d K=%d N=%d" % (M, K, N))
+    x, w, _ = synth.fp8_linear_inputs(cfg, gi, M=M, K=K, N=N)
+    res = synth.residual_input(cfg, gi, M, N)
+    xq, _, sxi = oracle_quantized(x)
+    wq, _, swi = oracle_quantized(w)
+    ref, refabs, refbf = oracle.fp8_linear_fwd(xq, wq, sxi, swi, residual=res)
+    got, S = run_fwd(xq, wq, sxi, swi, M, N, K, residual=res)
+    check_gemm(got, ref, refabs, K, "fwd+residual")
+    Sref = oracle.penalty_sum(refbf, *PEN)
+    assert abs(S - Sref) <= 1e-4 * Sref
+    got2, _ = run_fwd(xq, wq, sxi, swi, M, N, K, residual=res, pen=None)
+    assert np.array_equal(got, got2)  # the penalty does not change the stored output
+
+
+@pytest.mark.parametrize("pen", [(3.0, 1e-6, 4), (2.0, 1e-6, 4), (5.0, 0.0, 2), (3.0, 1e-6, 3), (4.0, 1e-6, 6)])
+def test_penalty_hyperparameters(pen):
+    M, K, N = 256, 512, 512
+    say("penalty", pen)
+    x, w, _ = synth.fp8_linear_inputs(0, 0)
+    xq, _, sxi = oracle_quantized(x)
+    wq, _, swi = oracle_quantized(w)
+    _, _, refbf = oracle.fp8_linear_fwd(xq, wq, sxi, swi, want_abs=False)
+    _, S = run_fwd(xq, wq, sxi, swi, M, N, K, pen=pen)
+    Sref = oracle.penalty_sum(refbf, *pen)
+    assert abs(S - Sref) <= 1e-4 * Sref, (S, Sref)
+
+
+def test_penalty_printed_regimes_through_the_gemm():
+    # W = c*I makes every output magnitude known: |y| = 0.5 tau, tau, 10 tau -> mean 0.0625, 1, 1e4
+    M = N = K = 128
+    for ratio, printed in ((0.5, 0.0625), (1.0, 1.0), (10.0, 10000.0)):
+        say("penalty regime", ratio)
+        # decoded operands: x = 1.5 everywhere on the diagonal selector, w = diag
+        xq = np.full((M, K), oracle.e4m3_encode(1.5), np.uint8)
+        wq = np.zeros((N, K), np.uint8)
+        wq[np.arange(N), np.arange(N)] = oracle.e4m3_encode(2.0)
+        # y = 1.5 * 2 * sxi * swi = 3 * ratio  with sxi*swi = ratio (powers of two / exact)
+        got, S = run_fwd(xq, wq, np.float32(ratio), np.float32(1.0), M, N, K, pen=(3.0, 0.0, 4))
+        y = synth.bf16_bits_to_f32(got)
+        assert np.all(y == np.float32(3.0 * ratio))
+        assert abs(S / (M * N) - printed) <= 1e-6 * printed
+
+
+@pytest.mark.parametrize("tile", [0, 1, 3, 4])
+@pytest.mark.parametrize("case", [(0, 0, 256, 512, 512), (1, 1, 208, 256, 136), (3, 0, 144, 640, 392)])
+def test_bwd(case, tile):
+    cfg, gi, M, K, N = case
+    say("bwd cfg=%d M=%d K=%d N=%d tile=%d" % (cfg, M, K, N, tile))
+    x, w, dy = synth.fp8_linear_inputs(cfg, gi, M=M, K=K, N=N)
+    xq, xqT, sxi = oracle_quantized(x)
+    wq, wqT, swi = oracle_quantized(w)
+    dyq, dyqT, sdyi = oracle_quantized(dy)
+    dx_ref, dx_abs = oracle.fp8_linear_dgrad(dyq, wq, sdyi, swi)
+    dw_ref, dw_abs = oracle.fp8_linear_wgrad(dyq, xq, sdyi, sxi)
+    dx = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
+    dw = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+    tw.tweo_set_gemm_tile(tile)
+    try:
+        tw.tweo_fp8_linear_bwd(to_dev(dyq), to_dev(dyqT), scalar_f32(sdyi), to_dev(wqT),
+                               scalar_f32(swi), to_dev(xqT), scalar_f32(sxi), M, N, K, dx, dw,
+                               workspace(tw.TWEO_OP_FP8_LINEAR_BWD, M, N, K))
+        torch.cuda.synchronize()
+    finally:
+        tw.tweo_set_gemm_tile(0)
+    check_gemm(bf16_bits(dx), dx_ref, dx_abs, N, "dgrad")
+    check_gemm(bf16_bits(dw), dw_ref, dw_abs, M, "wgrad")
+
+
+def test_whole_path_from_bf16_and_determinism():
+    cfg, gi, M, K, N = 0, 0, 256, 512, 512
+    say("bf16 path M=%d K=%d N=%d" % (M, K, N))
+    x, w, dy = synth.fp8_linear_inputs(cfg, gi)
+    xd, wd, dyd = to_dev_bf16(x), to_dev_bf16(w), to_dev_bf16(dy)
+    u8 = lambda *s: torch.empty(s, dtype=torch.uint8, device=DEV)
+    outs = []
+    for rep in range(2):
+        xq, xqT, wq, wqT = u8(M, K), u8(K, M), u8(N, K), u8(K, N)
+        dyq, dyqT = u8(M, N), u8(N, M)
+        sc = torch.full((16,), -3.0, dtype=torch.float32, device=DEV)
+        saved = tw.make_saved(xq, xqT, wq, wqT, sc)
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+        dx = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
+        dw = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+        S = torch.zeros(2, dtype=torch.float64, device=DEV)
+        ws = workspace(tw.TWEO_OP_FP8_LINEAR_FWD_BF16, M, N, K)
+        tw.tweo_fp8_linear_fwd_bf16(xd, wd, y, saved, pen=PEN, penalty_sum=S, workspace=ws)
+        tw.tweo_fp8_linear_bwd_bf16(dyd, saved, K, dyq, dyqT, dx, dw, ws)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy().copy() for t in (xq, xqT, wq, wqT, dyq, dyqT)] +
+                    [bf16_bits(y), bf16_bits(dx), bf16_bits(dw), S.cpu().numpy().copy(),
+                     sc.cpu().numpy().copy()])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)  # run-to-run identical, penalty included
+    gxq, gxqT, gwq, gwqT, gdyq, gdyqT, gy, gdx, gdw, gS, gsc = outs[0]
+    oxq, oxqT, sxi = oracle_quantized(x)
+    owq, owqT, swi = oracle_quantized(w)
+    odyq, odyqT, sdyi = oracle_quantized(dy)
+    for g, o in ((gxq, oxq), (gxqT, oxqT), (gwq, owq), (gwqT, owqT), (gdyq, odyq), (gdyqT, odyqT)):
+        assert np.array_equal(g, o)
+    want_sc = [oracle.amax_bf16(x), *oracle.scale_from_amax(oracle.amax_bf16(x)),
+               oracle.amax_bf16(w), *oracle.scale_from_amax(oracle.amax_bf16(w)),
+               oracle.amax_bf16(dy), *oracle.scale_from_amax(oracle.amax_bf16(dy))]
+    assert np.array_equal(gsc[:9], np.array(want_sc, np.float32))
+    ref, refabs, refbf = oracle.fp8_linear_fwd(oxq, owq, sxi, swi)
+    check_gemm(gy, ref, refabs, K, "fwd")
+    Sref = oracle.penalty_sum(refbf, *PEN)
+    assert abs(gS[0] - Sref) <= 1e-4 * Sref
+    dx_ref, dx_abs = oracle.fp8_linear_dgrad(odyq, owq, sdyi, swi)
+    dw_ref, dw_abs = oracle.fp8_linear_wgrad(odyq, oxq, sdyi, sxi)
+    check_gemm(gdx, dx_ref, dx_abs, N, "dgrad")
+    check_gemm(gdw, dw_ref, dw_abs, M, "wgrad")
+
+
+def test_error_paths_need_no_launch():
+    y = torch.empty((16, 16), dtype=torch.bfloat16, device=DEV)
+    q = torch.zeros((16, 16), dtype=torch.uint8, device=DEV)
+    s = scalar_f32(1.0)
+    S = torch.zeros(2, dtype=torch.float64, device=DEV)
+    with pytest.raises(tw.TweoError) as e:
+        tw.tweo_fp8_linear_fwd(q, s, q, s, y, pen=PEN, penalty_sum=S, workspace=None)
+    assert e.value.status == tw.TWEO_ERR_WORKSPACE
+    with pytest.raises(tw.TweoError) as e:
+        tw.tweo_fp8_linear_fwd(q, s, q, s, y, pen=(3.0, 1e-6, 9), penalty_sum=S,
+                               workspace=workspace(0, 16, 16, 16))
+    assert e.value.status == tw.TWEO_ERR_UNSUPPORTED
+    with pytest.raises(tw.TweoError) as e:
+        tw.tweo_fp8_linear_fwd(q[:, :8].contiguous(), s, q[:, :8].contiguous(), s, y)
+    assert e.value.status == tw.TWEO_ERR_UNSUPPORTED  # K % 16 != 0
