@@ -1,0 +1,271 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-tensor FP8 linear hot path (fwd + bwd, fused TWEO penalty) on one MI355X.
+
+A step = one pass over every linear layer of the workload's Transformer block, each from its
+bf16 operands: amax(X), amax(W), E4M3 casts (+ transposes), FP8 forward GEMM with the penalty
+epilogue, amax(dY), cast of dY, dgrad GEMM, wgrad GEMM.  Inputs are synthetic (seeded), resident
+in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama|gpt2|vit|single]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+WORKLOADS = {"single": 0, "gpt2": 1, "vit": 2, "llama": 3}
+FP8_PEAK_TFLOPS = 5000.0   # MI355X dense FP8 MFMA
+INT8_PEAK_TOPS = 5000.0
+HBM_PEAK_GBS = 8000.0
+PEN = (3.0, 1e-6, 4)       # tau, eps, p of the paper's experiments
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Layer:
+    """Device buffers of one linear layer (all allocated up front; the library allocates nothing)."""
+
+    def __init__(self, tw, torch, synth, cfg, gi, dev):
+        g = synth.CONFIGS[cfg]["gemms"][gi]
+        self.name, self.M, self.K, self.N = g.name, g.M, g.K, g.N
+        M, K, N = g.M, g.K, g.N
+        x, w, dy = synth.fp8_linear_inputs(cfg, gi)
+        self.host = (x, w, dy)
+        up = lambda b: torch.from_numpy(b.view("int16")).to(dev).view(torch.bfloat16)
+        self.x, self.w, self.dy = up(x), up(w), up(dy)
+        u8 = lambda *s: torch.empty(s, dtype=torch.uint8, device=dev)
+        bf = lambda *s: torch.empty(s, dtype=torch.bfloat16, device=dev)
+        self.xq, self.xqT, self.wq, self.wqT = u8(M, K), u8(K, M), u8(N, K), u8(K, N)
+        self.dyq, self.dyqT = u8(M, N), u8(N, M)
+        self.y, self.dx, self.dw = bf(M, N), bf(M, K), bf(N, K)
+        self.sc = torch.zeros(16, dtype=torch.float32, device=dev)
+        self.S = torch.zeros(2, dtype=torch.float64, device=dev)
+        self.ws = torch.empty(tw.tweo_workspace_bytes(tw.TWEO_OP_FP8_LINEAR_FWD_BF16, M, N, K),
+                              dtype=torch.uint8, device=dev)
+        self.flops = 6.0 * M * N * K
+
+
+def run_step(tw, layers, ev=None):
+    """The whole path through the low-level entry points (the same launches the *_bf16 wrappers
+    make), so that the GEMM launches can be bracketed by events."""
+    for L in layers:
+        sc = L.sc
+        tw.tweo_amax(L.x, sc[0:1])
+        tw.tweo_amax(L.w, sc[4:5])
+        tw.tweo_quantize_e4m3(L.x, sc[0:1], L.xq, L.xqT, sc[1:2], sc[2:3])
+        tw.tweo_quantize_e4m3(L.w, sc[4:5], L.wq, L.wqT, sc[5:6], sc[6:7])
+        if ev is not None:
+            ev.start()
+        tw.tweo_fp8_linear_fwd(L.xq, sc[2:3], L.wq, sc[6:7], L.y, pen=PEN, penalty_sum=L.S,
+                               workspace=L.ws)
+        if ev is not None:
+            ev.stop(2.0 * L.M * L.N * L.K)
+        tw.tweo_amax(L.dy, sc[8:9])
+        tw.tweo_quantize_e4m3(L.dy, sc[8:9], L.dyq, L.dyqT, sc[9:10], sc[10:11])
+        if ev is not None:
+            ev.start()
+        tw.tweo_fp8_linear_bwd(L.dyq, L.dyqT, sc[10:11], L.wqT, sc[6:7], L.xqT, sc[2:3], L.M, L.N,
+                               L.K, L.dx, L.dw, L.ws)
+        if ev is not None:
+            ev.stop(4.0 * L.M * L.N * L.K)
+
+
+class GemmEvents:
+    """HIP events on the launch stream around the GEMM launches of the timed steps."""
+
+    def __init__(self, torch):
+        self.torch, self.pairs, self.flops = torch, [], 0.0
+
+    def start(self):
+        self._s = self.torch.cuda.Event(enable_timing=True)
+        self._s.record()
+
+    def stop(self, flops):
+        e = self.torch.cuda.Event(enable_timing=True)
+        e.record()
+        self.pairs.append((self._s, e))
+        self.flops += flops
+
+    def total_ms(self):
+        return sum(s.elapsed_time(e) for s, e in self.pairs)
+
+
+def time_elementwise(tw, torch, L, iters=20):
+    """GB/s of the amax and quantize passes on this layer's largest activation (algorithmic bytes)."""
+    out = {}
+    n = L.M * L.K
+    for name, fn, bytes_per_elt in (
+            ("amax", lambda: tw.tweo_amax(L.x, L.sc[0:1]), 2.0),
+            ("quantize_e4m3_T", lambda: tw.tweo_quantize_e4m3(L.x, L.sc[0:1], L.xq, L.xqT), 4.0),
+            ("quantize_e4m3", lambda: tw.tweo_quantize_e4m3(L.x, L.sc[0:1], L.xq, None), 3.0)):
+        for _ in range(3):
+            fn()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(iters):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        ms = s.elapsed_time(e) / iters
+        out[name] = {"GB/s": round(n * bytes_per_elt / ms / 1e6, 1), "us": round(ms * 1e3, 2),
+                     "MB": round(n * bytes_per_elt / 1e6, 1)}
+    return out
+
+
+def time_w8a8(tw, torch, synth, dev, iters=20):
+    """W8A8 INT8 inference GEMM at the 7B qkv shape (K=4096, N=12288) for M in {1,16,64,4096}."""
+    import numpy as np
+    res = {}
+    K, N = 4096, 12288
+    wq = torch.randint(-127, 128, (N, K), dtype=torch.int8, device=dev)
+    for M in (1, 16, 64, 4096):
+        xq = torch.randint(-127, 128, (M, K), dtype=torch.int8, device=dev)
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        ws = torch.empty(tw.tweo_workspace_bytes(tw.TWEO_OP_W8A8_LINEAR, M, N, K), dtype=torch.uint8,
+                         device=dev)
+        fn = lambda: tw.tweo_w8a8_linear(xq, wq, 1e-4, y, ws)
+        for _ in range(3):
+            fn()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(iters):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        ms = s.elapsed_time(e) / iters
+        bytes_ = M * K + N * K + 2 * M * N
+        res["M=%d" % M] = {"us": round(ms * 1e3, 2), "TOP/s": round(2.0 * M * N * K / ms / 1e9, 2),
+                           "GB/s": round(bytes_ / ms / 1e6, 1)}
+    return res
+
+
+def cpu_baseline(synth, cfg, host=None, target_s=5.0):
+    """The CPU oracle, as it stands, on a bounded row sample of the first GEMM of the workload."""
+    import numpy as np
+    import oracle
+    g = synth.CONFIGS[cfg]["gemms"][0]
+    M, K, N = g.M, g.K, g.N
+    x, w, dy = host if host is not None else synth.fp8_linear_inputs(cfg, 0)
+    rows_q = min(M, 8192)
+
+    def quant(t):
+        s, si = oracle.scale_from_amax(oracle.amax_bf16(t))
+        q, _ = oracle.quantize_e4m3(t, s, transpose=False)
+        return q, si
+
+    t0 = time.perf_counter()
+    xq, sxi = quant(x[:rows_q])
+    wq, swi = quant(w)
+    dyq, sdyi = quant(dy[:rows_q])
+    t_cast = time.perf_counter() - t0
+    # calibrate on a few rows, then size each GEMM leg for about target_s seconds
+    probe = np.arange(0, min(rows_q, 16))
+    t0 = time.perf_counter()
+    oracle.fp8_linear_fwd(xq, wq, sxi, swi, rows=probe, want_abs=False)
+    per_row = (time.perf_counter() - t0) / len(probe)
+    r = int(max(16, min(rows_q, target_s / max(per_row, 1e-9))))
+    rows = np.arange(r)
+    t0 = time.perf_counter()
+    oracle.fp8_linear_fwd(xq, wq, sxi, swi, rows=rows, want_abs=False)
+    oracle.fp8_linear_dgrad(dyq, wq, sdyi, swi, rows=rows, want_abs=False)
+    rn = min(N, max(8, r * N // rows_q))  # same flop count as one of the other two legs
+    oracle.fp8_linear_wgrad(dyq, xq, sdyi, sxi, rows=np.arange(rn), want_abs=False)
+    t_gemm = time.perf_counter() - t0
+    flops = 2.0 * r * N * K * 2 + 2.0 * rn * rows_q * K
+    return {"value": round(flops / t_gemm / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "%s: fp64 oracle fwd+dgrad on %d rows of M, wgrad on %d rows of N over %d "
+                      "tokens (%.1f s); casts of those rows %.2f s not included"
+                      % (g.name, r, rn, rows_q, t_gemm, t_cast)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--tile", type=int, default=0, help="force a GEMM tile variant (0 = heuristic)")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (the path has no multi-GPU part); "
+            "--gpus %d is not supported" % a.gpus)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_23225_amd as tw
+    from paper_2511_23225_amd import synth
+    if not os.path.exists(tw.LIB_PATH):
+        from paper_2511_23225_amd import build as b
+        b.build_library()
+    tw.load()
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(3)
+    dev = "cuda:0"
+    cfg = WORKLOADS[a.workload]
+    t0 = time.perf_counter()
+    layers = [Layer(tw, torch, synth, cfg, gi, dev) for gi in range(len(synth.CONFIGS[cfg]["gemms"]))]
+    log("inputs generated and uploaded in %.1f s" % (time.perf_counter() - t0))
+    tw.tweo_set_gemm_tile(a.tile)
+    step_flops = sum(L.flops for L in layers)
+    host0 = layers[0].host
+    for L in layers:
+        L.host = None
+
+    for _ in range(a.warmup):
+        run_step(tw, layers)
+    torch.cuda.synchronize()
+    ev = GemmEvents(torch)
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        run_step(tw, layers, ev)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / a.steps
+    gemm_ms = ev.total_ms()
+    n_gemm_launches = a.steps * len(layers) * 3
+    value = step_flops / (ms_per_step * 1e-3) / 1e12
+    gemm_tflops = ev.flops / (gemm_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "FP8 linear fwd+bwd TFLOP/s (+penalty), end to end from bf16 operands",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3 (fp32 accumulate)",
+        "data": "synthetic",
+        "config": {"workload": synth.CONFIGS[cfg]["name"],
+                   "gemms": ["%s %dx%dx%d" % (L.name, L.M, L.K, L.N) for L in layers],
+                   "flop_per_step": step_flops, "penalty": "tau=3 p=4 eps=1e-6, fused",
+                   "tile": a.tile},
+        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel (fp8 fwd/dgrad/wgrad)",
+                     "achieved": round(gemm_tflops, 2), "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(gemm_tflops / FP8_PEAK_TFLOPS, 4), "traffic": None,
+                     "avg_launch_us": round(gemm_ms * 1e3 / n_gemm_launches, 2),
+                     "launches": n_gemm_launches},
+        "pct_of_fp8_peak_end_to_end": round(100.0 * value / FP8_PEAK_TFLOPS, 2),
+        "paper_context": "+36% training throughput FP8 over BF16 (hardware unstated)",
+    }
+    if not a.no_extras:
+        big = max(layers, key=lambda L: L.M * L.K)
+        out["elementwise"] = time_elementwise(tw, torch, big)
+        out["elementwise"]["peak_GB/s"] = HBM_PEAK_GBS
+        del layers
+        torch.cuda.empty_cache()
+        out["w8a8_qkv_4096x12288"] = time_w8a8(tw, torch, synth, dev)
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(synth, cfg, host0)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
