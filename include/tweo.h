@@ -181,11 +181,13 @@ tweo_status tweo_fp8_linear_bwd_bf16(const void *dy_bf16, const tweo_fp8_saved *
                                      size_t workspace_bytes, void *stream);
 
 /*
- * Tuning hook for benchmarks and tests: forces the GEMM workgroup tile
- * (0 = choose from the shape, the default; 1 = 256x256, 2 = 256x128,
- * 3 = 128x128, 4 = 64x64).  Process-wide, not thread safe.  Results are
- * identical up to the fp32 summation order.  Returns TWEO_ERR_INVALID_ARG
- * for an unknown variant.
+ * Tuning hook for benchmarks and tests: forces the GEMM kernel variant
+ * (0 = choose from the shape, the default; 1-4 = register-staged kernel with
+ * a 256x256, 256x128, 128x128, 64x64 workgroup tile; 5-8 = DMA-pipelined
+ * kernel: 256x256 with 4 waves, 256x256 with 8 waves, 256x128, 128x128; a
+ * DMA variant falls back to its register-staged twin when K % 64 != 0).
+ * Process-wide, not thread safe.  Results are identical up to the fp32
+ * summation order.  Returns TWEO_ERR_INVALID_ARG for an unknown variant.
  */
 tweo_status tweo_set_gemm_tile(int variant);
 

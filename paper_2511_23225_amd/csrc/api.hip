@@ -55,7 +55,7 @@ const char *tweo_status_string(tweo_status s)
 
 tweo_status tweo_set_gemm_tile(int variant)
 {
-    if (variant < 0 || variant > 4)
+    if (variant < 0 || variant > gemm_num_variants())
         return TWEO_ERR_INVALID_ARG;
     set_gemm_tile_override(variant);
     return TWEO_OK;

@@ -70,6 +70,134 @@ __device__ __forceinline__ void tile_of_workgroup(int wg, int tiles_m, int tiles
     tn = in_group / gsz;
 }
 
+// Epilogue shared by the GEMM kernels.  An MFMA 32x32 block leaves C[m, n] in
+// acc[4q + r] with m = lane%32 and n = 8q + 4*(lane/32) + r, i.e. a lane holds
+// four consecutive n of one row.  To write whole 128-byte lines, each wave
+// passes one 32-row band of its sub-tile at a time through its own slice of LDS
+// (fp32, row stride TN*4+16 bytes: conflict-free for the 16-byte writes and
+// reads) and reads it back with TN/8 lanes per row, 8 consecutive n per lane.
+// That lane then applies the scale, adds the residual (16-byte load), rounds to
+// bf16, stores 16 bytes, and accumulates the penalty term (|a| / (tau+eps))^p of
+// the value as stored (Sec. 3.3); the terms are reduced lane -> wave ->
+// workgroup into one fp32 partial per workgroup.  The caller must have placed a
+// workgroup barrier between the last LDS read of the main loop and this call.
+template <typename T>
+struct EpiLayout {
+    static constexpr int ROW_BYTES = T::TN * 4 + 16;
+    static constexpr int WAVE_BYTES = 32 * ROW_BYTES;
+    static constexpr int LPR = T::TN / 8;       // lanes per row when reading back
+    static constexpr int ROWS_PER_PASS = kWave / LPR;
+    static constexpr int PASSES = 32 / ROWS_PER_PASS;
+    static_assert(WAVE_BYTES * (T::THREADS / kWave) <= T::LDS_BYTES, "epilogue staging fits in LDS");
+};
+
+// PMODE: 0 = no penalty, 4 = p == 4 (the paper's setting), -1 = any other integer p.
+template <typename T, bool INT8, int PMODE, typename ACC>
+__device__ __forceinline__ void epilogue_impl(const GemmDev &g, ACC (&acc)[T::MT][T::NT],
+                                              uint8_t *smem, int tm, int tn, int wm, int wn,
+                                              int lane, int wave, int tid, int partial_index)
+{
+    using E = EpiLayout<T>;
+    const int l31 = lane & 31, lh = lane >> 5;
+    float alpha;
+    if constexpr (INT8)
+        alpha = g.alpha;
+    else
+        alpha = (*g.s0) * (*g.s1);
+    float pen = 0.0f;
+    uint8_t *stage = smem + wave * E::WAVE_BYTES;
+    uint8_t *wr = stage + l31 * E::ROW_BYTES + lh * 16;
+    const int rd_row = lane / E::LPR, rd_seg = lane % E::LPR;
+    const uint8_t *rd = stage + rd_row * E::ROW_BYTES + rd_seg * 32;
+    const int n = tn * T::BN + wn * T::TN + rd_seg * 8;
+    const bool n_ok = n < g.N;
+    const bool has_res = g.residual != nullptr;
+#pragma unroll
+    for (int i = 0; i < T::MT; ++i) {
+#pragma unroll
+        for (int j = 0; j < T::NT; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                v4f v;
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    v[r] = (float)acc[i][j][4 * q + r] * alpha;
+                *(v4f *)(wr + j * 128 + q * 32) = v;
+            }
+        // the wave reads only what it wrote itself: LDS executes a wave's accesses in order
+#pragma unroll
+        for (int ps = 0; ps < E::PASSES; ++ps) {
+            const v4f lo = *(const v4f *)(rd + ps * E::ROWS_PER_PASS * E::ROW_BYTES);
+            const v4f hi = *(const v4f *)(rd + ps * E::ROWS_PER_PASS * E::ROW_BYTES + 16);
+            const int m = tm * T::BM + wm * T::TM + i * 32 + ps * E::ROWS_PER_PASS + rd_row;
+            if (m < g.M && n_ok) {
+                const int64_t o = (int64_t)m * g.N + n;
+                float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                if (has_res) {
+                    const uint4 rr = *(const uint4 *)(g.residual + o);
+                    v[0] += bf16lo_to_f32(rr.x);
+                    v[1] += bf16hi_to_f32(rr.x);
+                    v[2] += bf16lo_to_f32(rr.y);
+                    v[3] += bf16hi_to_f32(rr.y);
+                    v[4] += bf16lo_to_f32(rr.z);
+                    v[5] += bf16hi_to_f32(rr.z);
+                    v[6] += bf16lo_to_f32(rr.w);
+                    v[7] += bf16hi_to_f32(rr.w);
+                }
+                const uint4 packed = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
+                                                pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+                *(uint4 *)(g.out + o) = packed;
+                if constexpr (PMODE != 0) {
+                    const float t[8] = {bf16lo_to_f32(packed.x), bf16hi_to_f32(packed.x),
+                                        bf16lo_to_f32(packed.y), bf16hi_to_f32(packed.y),
+                                        bf16lo_to_f32(packed.z), bf16hi_to_f32(packed.z),
+                                        bf16lo_to_f32(packed.w), bf16hi_to_f32(packed.w)};
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) {
+                        const float u = __builtin_fabsf(t[r]) * g.inv_tau;
+                        if constexpr (PMODE == 4) {
+                            const float u2 = u * u;
+                            pen = __builtin_fmaf(u2, u2, pen);
+                        } else {
+                            float w = u;
+                            for (int e = 1; e < g.p; ++e)
+                                w *= u;
+                            pen += w;
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if constexpr (PMODE != 0) {
+        __shared__ float red[T::THREADS / kWave];
+        pen = wave_reduce_sum(pen);
+        if (lane == 0)
+            red[wave] = pen;
+        __syncthreads();
+        if (tid == 0) {
+            float s = 0.0f;
+#pragma unroll
+            for (int w = 0; w < T::THREADS / kWave; ++w)
+                s += red[w];
+            g.partials[partial_index] = s;
+        }
+    }
+}
+
+template <typename T, bool INT8, typename ACC>
+__device__ __forceinline__ void epilogue(const GemmDev &g, ACC (&acc)[T::MT][T::NT], uint8_t *smem,
+                                         int tm, int tn, int wm, int wn, int lane, int wave, int tid,
+                                         int partial_index)
+{
+    if (g.p == 4)
+        epilogue_impl<T, INT8, 4>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, partial_index);
+    else if (g.p == 0)
+        epilogue_impl<T, INT8, 0>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, partial_index);
+    else
+        epilogue_impl<T, INT8, -1>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, partial_index);
+}
+
 template <typename T, bool INT8>
 __global__ __launch_bounds__(T::THREADS) void gemm_nt_kernel(GemmDev g)
 {
@@ -209,75 +337,446 @@ __global__ __launch_bounds__(T::THREADS) void gemm_nt_kernel(GemmDev g)
         __syncthreads();
     }
 
-    // ---- epilogue -------------------------------------------------------------
-    // acc[i][j][4q + r] holds C[m, n] with m = lane%32 (+ block), n = 8q + 4*(lane/32) + r:
-    // four consecutive n per lane -> one 8-byte bf16x4 store.
-    float alpha;
-    if constexpr (INT8)
-        alpha = g.alpha;
-    else
-        alpha = (*g.s0) * (*g.s1);
-    float pen = 0.0f;
-    const int m_base = tm * BM + wm * T::TM + l31;
-    const int n_base = tn * BN + wn * T::TN + lh * 4;
+    // the loop ends with a barrier: every wave is done reading the stages
+    epilogue<T, INT8>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, blockIdx.x);
+}
+
+// ---------------------------------------------------------------------------
+// Pipelined kernel: global -> LDS by direct DMA loads (global_load_lds_dwordx4,
+// no staging registers), NS stages of 64 bytes of K each, one workgroup barrier
+// per stage, MFMA operand fragments double-buffered in registers so that the
+// LDS reads of stage s+1 run under the MFMAs of stage s.  Needs K % 64 == 0.
+//
+// LDS layout of a stage: BM rows of A then BN rows of B, 64 bytes per row, the
+// four 16-byte chunks of a row XOR-swizzled with (row/4)%4: 16 consecutive rows
+// reading the same logical chunk then cover all 64 banks exactly once.  A DMA
+// instruction of one wave writes 1024 contiguous LDS bytes (lane*16) = 16 rows;
+// the swizzle is applied by choosing which global chunk each lane fetches.
+template <int BM_, int BN_, int WM_, int WN_, int NS_, int WPE_ = 1>
+struct TileD {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NS = NS_;
+    static constexpr int WPE = WPE_;  // waves per SIMD the register budget must allow
+    static constexpr int NWAVES = WM * WN, THREADS = NWAVES * kWave;
+    static constexpr int TM = BM / WM, TN = BN / WN;
+    static constexpr int MT = TM / 32, NT = TN / 32;
+    static constexpr int BK = 64;
+    static constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = NS * STAGE_BYTES;
+    static constexpr int A_DMA = BM / (16 * NWAVES), B_DMA = BN / (16 * NWAVES);  // per wave per stage
+    static constexpr int LOADS = A_DMA + B_DMA;
+    static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be made of 32x32 blocks");
+    static_assert(BM % (16 * NWAVES) == 0 && BN % (16 * NWAVES) == 0, "DMA split");
+    static_assert(NS >= 3 && LOADS * (NS - 2) < 64, "vmcnt range");
+};
+
+// One 16-byte-per-lane DMA load: LDS[m0 + lane*16 ..] = global[base + voff ..].
+__device__ __forceinline__ void dma_load16(uint32_t lds_addr, const uint8_t *base, uint32_t voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+__device__ __forceinline__ void block_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <typename T, bool INT8>
+__global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_dma_kernel(GemmDev g)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int wm = wave / T::WN, wn = wave % T::WN;
+    int tm, tn;
+    tile_of_workgroup(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
+
+    // ---- DMA addressing -----------------------------------------------------
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
+    const uint8_t *Ag = g.A + (int64_t)tm * T::BM * g.K;
+    const uint8_t *Bg = g.B + (int64_t)tn * T::BN * g.K;
+    const int a_rows = g.M - tm * T::BM, b_rows = g.N - tn * T::BN;
+    uint32_t a_voff[T::A_DMA], b_voff[T::B_DMA];
 #pragma unroll
-    for (int i = 0; i < T::MT; ++i) {
-        const int m = m_base + i * 32;
+    for (int i = 0; i < T::A_DMA; ++i) {
+        int row = (i * T::NWAVES + wave) * 16 + (lane >> 2);
+        int c = (lane & 3) ^ ((row >> 2) & 3);
+        int grow = row < a_rows ? row : a_rows - 1;  // rows past M are loaded twice, never stored
+        a_voff[i] = (uint32_t)grow * (uint32_t)g.K + c * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < T::B_DMA; ++i) {
+        int row = (i * T::NWAVES + wave) * 16 + (lane >> 2);
+        int c = (lane & 3) ^ ((row >> 2) & 3);
+        int grow = row < b_rows ? row : b_rows - 1;
+        b_voff[i] = (uint32_t)grow * (uint32_t)g.K + c * 16;
+    }
+    auto issue_stage = [&](int s) {
+        const uint32_t dst = lds_base + (s % T::NS) * T::STAGE_BYTES + wave * 1024;
+        const uint8_t *ap = Ag + (int64_t)s * T::BK, *bp = Bg + (int64_t)s * T::BK;
+#pragma unroll
+        for (int i = 0; i < T::A_DMA; ++i)
+            dma_load16(dst + i * T::NWAVES * 1024, ap, a_voff[i]);
+#pragma unroll
+        for (int i = 0; i < T::B_DMA; ++i)
+            dma_load16(dst + T::A_BYTES + i * T::NWAVES * 1024, bp, b_voff[i]);
+    };
+
+    // ---- fragments ------------------------------------------------------------
+    const int l31 = lane & 31, lh = lane >> 5;
+    const int sw = (l31 >> 2) & 3;
+    // logical chunks of this lane: FP8 takes 32 contiguous bytes (chunks 2h, 2h+1) for one
+    // K=64 MFMA; INT8 takes chunk h for the first K=32 MFMA and chunk 2+h for the second.
+    const int c0 = INT8 ? lh : 2 * lh, c1 = INT8 ? 2 + lh : 2 * lh + 1;
+    const int a_frag0 = (wm * T::TM + l31) * T::BK, b_frag0 = T::A_BYTES + (wn * T::TN + l31) * T::BK;
+    const int off0 = (c0 ^ sw) * 16, off1 = (c1 ^ sw) * 16;
+    struct Frag {
+        v4i a0[T::MT], a1[T::MT], b0[T::NT], b1[T::NT];
+    };
+    auto load_frags = [&](Frag &f, int s) {
+        const uint8_t *st = smem + (s % T::NS) * T::STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < T::MT; ++i) {
+            f.a0[i] = *(const v4i *)(st + a_frag0 + i * 32 * T::BK + off0);
+            f.a1[i] = *(const v4i *)(st + a_frag0 + i * 32 * T::BK + off1);
+        }
 #pragma unroll
         for (int j = 0; j < T::NT; ++j) {
+            f.b0[j] = *(const v4i *)(st + b_frag0 + j * 32 * T::BK + off0);
+            f.b1[j] = *(const v4i *)(st + b_frag0 + j * 32 * T::BK + off1);
+        }
+    };
+    using acc_t = typename std::conditional<INT8, v16i, v16f>::type;
+    acc_t acc[T::MT][T::NT];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n_base + j * 32 + q * 8;
-                if (m < g.M && n < g.N) {
-                    const int64_t o = (int64_t)m * g.N + n;
-                    float v[4];
+    for (int i = 0; i < T::MT; ++i)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        v[r] = (float)acc[i][j][4 * q + r] * alpha;
-                    if (g.residual) {
-                        uint2 rr = *(const uint2 *)(g.residual + o);
-                        v[0] += bf16lo_to_f32(rr.x);
-                        v[1] += bf16hi_to_f32(rr.x);
-                        v[2] += bf16lo_to_f32(rr.y);
-                        v[3] += bf16hi_to_f32(rr.y);
-                    }
-                    uint2 packed = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-                    *(uint2 *)(g.out + o) = packed;
-                    if (g.p != 0) {
-                        // penalty of the value as stored (bf16): (|a| / (tau+eps))^p
-                        float t[4] = {bf16lo_to_f32(packed.x), bf16hi_to_f32(packed.x),
-                                      bf16lo_to_f32(packed.y), bf16hi_to_f32(packed.y)};
+        for (int j = 0; j < T::NT; ++j)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            float u = __builtin_fabsf(t[r]) * g.inv_tau;
-                            if (g.p == 4) {
-                                float u2 = u * u;
-                                pen += u2 * u2;
-                            } else {
-                                float w = u;
-                                for (int e = 1; e < g.p; ++e)
-                                    w *= u;
-                                pen += w;
-                            }
-                        }
-                    }
+            for (int v = 0; v < 16; ++v)
+                acc[i][j][v] = 0;
+    auto mfma_stage = [&](const Frag &f) {
+#pragma unroll
+        for (int i = 0; i < T::MT; ++i)
+#pragma unroll
+            for (int j = 0; j < T::NT; ++j) {
+                if constexpr (INT8) {
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.b0[j], f.a0[i], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.b1[j], f.a1[i], acc[i][j], 0, 0, 0);
+                } else {
+                    v8i fa = {f.a0[i][0], f.a0[i][1], f.a0[i][2], f.a0[i][3],
+                              f.a1[i][0], f.a1[i][1], f.a1[i][2], f.a1[i][3]};
+                    v8i fb = {f.b0[j][0], f.b0[j][1], f.b0[j][2], f.b0[j][3],
+                              f.b1[j][0], f.b1[j][1], f.b1[j][2], f.b1[j][3]};
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb, fa, acc[i][j], 0, 0,
+                                                                                0, 0, 0, 0);
                 }
             }
-        }
-    }
-    if (g.p != 0) {
-        __shared__ float red[T::THREADS / kWave];
-        pen = wave_reduce_sum(pen);
-        if (lane == 0)
-            red[wave] = pen;
-        __syncthreads();
-        if (tid == 0) {
-            float s = 0.0f;
+    };
+
+    // ---- pipeline ---------------------------------------------------------------
+    // Invariant at the top of iteration s: stages <= s+NS-2 have been issued.
+    const int kt = g.K / T::BK;
 #pragma unroll
-            for (int w = 0; w < T::THREADS / kWave; ++w)
-                s += red[w];
-            g.partials[blockIdx.x] = s;
+    for (int s = 0; s < T::NS - 1; ++s)
+        if (s < kt)
+            issue_stage(s);
+    if (kt >= T::NS - 1)
+        wait_vmcnt<T::LOADS *(T::NS - 2)>();
+    else
+        wait_vmcnt<0>();
+    block_barrier();
+    Frag fr[2];
+    load_frags(fr[0], 0);
+    // Steady state: stage ss with ss + NS - 1 < kt.  Two stages per trip so that the two
+    // fragment buffers have fixed names; the body is one basic block (no conditions), which
+    // lets the scheduler run the LDS reads of stage ss+1 under the MFMAs of stage ss.
+    auto steady_step = [&](int ss, const Frag &cur, Frag &nxt) {
+        // stage ss+1 must have landed (for every wave) before its fragments are read; the
+        // barrier also frees the buffer of stage ss-1 for the DMA issued right after it
+        wait_vmcnt<T::LOADS *(T::NS - 3)>();
+        block_barrier();
+        issue_stage(ss + T::NS - 1);
+        load_frags(nxt, ss + 1);
+        mfma_stage(cur);
+        // ask the scheduler for: MFMA, a few LDS reads, MFMA, ... so the reads of the next
+        // stage are in flight while this stage's MFMAs occupy the matrix pipe
+        constexpr int N_MFMA = T::MT * T::NT * (INT8 ? 2 : 1), N_DS = 2 * (T::MT + T::NT);
+        constexpr int DS_PER = (N_DS + N_MFMA - 2) / (N_MFMA - 1);
+#pragma unroll
+        for (int k = 0; k < N_MFMA; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, DS_PER, 0);  // DS reads
         }
+    };
+    auto tail_step = [&](int ss, const Frag &cur, Frag &nxt) {
+        if (ss + 1 < kt) {
+            wait_vmcnt<0>();
+            block_barrier();
+            if (ss + T::NS - 1 < kt)
+                issue_stage(ss + T::NS - 1);
+            load_frags(nxt, ss + 1);
+        }
+        mfma_stage(cur);
+    };
+    int s = 0;
+    const int steady_end = kt - (T::NS - 1);
+    for (; s + 1 < steady_end; s += 2) {
+        steady_step(s, fr[0], fr[1]);
+        steady_step(s + 1, fr[1], fr[0]);
+    }
+    for (; s < kt; s += 2) {
+        tail_step(s, fr[0], fr[1]);
+        if (s + 1 < kt)
+            tail_step(s + 1, fr[1], fr[0]);
+    }
+    block_barrier();  // every wave is done reading the stages before they are reused
+    epilogue<T, INT8>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, blockIdx.x);
+}
+
+// ---------------------------------------------------------------------------
+// Persistent streaming kernel (K % 128 == 0): the large-shape workhorse.
+//
+// What measurement on gfx950 dictated:
+//  * the L2 -> CU path moves ~23 TB/s (whole chip) when every wave-level load
+//    covers whole 128-byte lines, but only ~15 TB/s in 64-byte pieces, and a
+//    256x256 tile at MFMA peak needs 19.5 TB/s.  So a stage is 128 bytes of K
+//    per row (one full line per row per DMA instruction: 8 rows x 128 B);
+//  * 64 KB in flight per CU is enough to reach that rate, so two stages of
+//    (BM+BN) x 128 B are used for the 256x256 tile (128 KB of the 160 KB LDS);
+//  * with one workgroup per CU, prologue, epilogue and the burst of output
+//    writes of a tile are exposed.  Workgroups are therefore persistent: before
+//    the epilogue of tile t the DMA loads of the first stage(s) of tile t+1 are
+//    already issued, and the stores of tile t drain under the MFMAs of t+1.
+//
+// A stage holds two K=64 MFMA slabs.  Fragments are double-buffered in
+// registers across the stage barrier: the last slab of stage s-1 is multiplied
+// after the barrier of stage s, under the LDS reads of the first slab of s.
+// LDS rows are 128 bytes; the eight 16-byte chunks of a row are XOR-swizzled
+// with (row/2)%8, which makes the 16-byte fragment reads of 16 consecutive rows
+// cover all 64 banks once and does not depend on the 32-row block index.
+template <int BM_, int BN_, int WM_, int WN_, int NS_, int WPE_>
+struct TileS {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NS = NS_, WPE = WPE_;
+    static constexpr int NWAVES = WM * WN, THREADS = NWAVES * kWave;
+    static constexpr int TM = BM / WM, TN = BN / WN;
+    static constexpr int MT = TM / 32, NT = TN / 32;
+    static constexpr int BK = 128;
+    static constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int A_DMA = BM / (8 * NWAVES), B_DMA = BN / (8 * NWAVES);  // per wave per stage
+    static constexpr int LOADS = A_DMA + B_DMA;
+    static constexpr int EPI_ROW = TN * 4 + 16, EPI_BYTES = NWAVES * 32 * EPI_ROW;
+    // stages 0..NS-2 of the next tile are prefetched under the epilogue, which stages its
+    // output in the LDS behind them
+    static constexpr int EPI_OFFSET = (NS - 1) * STAGE_BYTES;
+    static constexpr int LDS_BYTES =
+        NS * STAGE_BYTES > EPI_OFFSET + EPI_BYTES ? NS * STAGE_BYTES : EPI_OFFSET + EPI_BYTES;
+    static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be made of 32x32 blocks");
+    static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "DMA split");
+    static_assert(NS >= 2 && LOADS * (NS - 1) < 64, "vmcnt range");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS capacity");
+};
+
+// raster of tile ids: groups of 8 tile rows, column-major inside a group
+__device__ __forceinline__ void tile_from_id(int id, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    constexpr int GROUP = 8;
+    const int width = GROUP * tiles_n;
+    const int group = id / width, first_m = group * GROUP;
+    const int gsz = (tiles_m - first_m) < GROUP ? (tiles_m - first_m) : GROUP;
+    const int in_group = id - group * width;
+    tm = first_m + in_group % gsz;
+    tn = in_group / gsz;
+}
+
+template <typename T, bool INT8>
+__global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(GemmDev g)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int wm = wave / T::WN, wn = wave % T::WN;
+    const int total = g.tiles_m * g.tiles_n;
+    // Persistent schedule: round r hands tile ids [r*G, (r+1)*G) to the G workgroups; inside a
+    // round each XCD (workgroup index mod 8) gets a contiguous run of ids, i.e. neighbouring
+    // tiles, so that the 32 CUs behind one L2 share A and B panels.
+    const int G = gridDim.x;
+    const int xcd = blockIdx.x & 7, per_xcd = G >> 3, rem_xcd = G & 7;
+    const int slot = xcd * per_xcd + (xcd < rem_xcd ? xcd : rem_xcd) + (blockIdx.x >> 3);
+
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
+    const int dma_row = lane >> 3, dma_p = lane & 7;
+    const uint8_t *Ag, *Bg;
+    uint32_t a_voff[T::A_DMA], b_voff[T::B_DMA];
+    auto set_tile = [&](int tm, int tn) {
+        Ag = g.A + (int64_t)tm * T::BM * g.K;
+        Bg = g.B + (int64_t)tn * T::BN * g.K;
+        const int a_rows = g.M - tm * T::BM, b_rows = g.N - tn * T::BN;
+#pragma unroll
+        for (int i = 0; i < T::A_DMA; ++i) {
+            const int row = (i * T::NWAVES + wave) * 8 + dma_row;
+            const int c = dma_p ^ ((row >> 1) & 7);
+            const int grow = row < a_rows ? row : a_rows - 1;  // rows past M: loaded twice, never stored
+            a_voff[i] = (uint32_t)grow * (uint32_t)g.K + c * 16;
+        }
+#pragma unroll
+        for (int i = 0; i < T::B_DMA; ++i) {
+            const int row = (i * T::NWAVES + wave) * 8 + dma_row;
+            const int c = dma_p ^ ((row >> 1) & 7);
+            const int grow = row < b_rows ? row : b_rows - 1;
+            b_voff[i] = (uint32_t)grow * (uint32_t)g.K + c * 16;
+        }
+    };
+    auto issue_stage = [&](int s) {
+        const uint32_t dst = lds_base + (s % T::NS) * T::STAGE_BYTES + wave * 1024;
+        const uint8_t *ap = Ag + (int64_t)s * T::BK, *bp = Bg + (int64_t)s * T::BK;
+#pragma unroll
+        for (int i = 0; i < T::A_DMA; ++i)
+            dma_load16(dst + i * T::NWAVES * 1024, ap, a_voff[i]);
+#pragma unroll
+        for (int i = 0; i < T::B_DMA; ++i)
+            dma_load16(dst + T::A_BYTES + i * T::NWAVES * 1024, bp, b_voff[i]);
+    };
+
+    // fragment addressing: lane (l31, lh) reads row l31 of each 32-row block; logical chunks of
+    // slab kk: FP8 4kk+2lh, 4kk+2lh+1 (32 contiguous bytes for one K=64 MFMA);
+    // INT8 4kk+lh and 4kk+2+lh (one chunk for each of the two K=32 MFMAs)
+    const int l31 = lane & 31, lh = lane >> 5;
+    const int sw = (l31 >> 1) & 7;
+    int frag_off[2][2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+        const int c0 = INT8 ? 4 * kk + lh : 4 * kk + 2 * lh;
+        const int c1 = INT8 ? 4 * kk + 2 + lh : 4 * kk + 2 * lh + 1;
+        frag_off[kk][0] = (c0 ^ sw) * 16;
+        frag_off[kk][1] = (c1 ^ sw) * 16;
+    }
+    const int a_frag0 = (wm * T::TM + l31) * T::BK, b_frag0 = T::A_BYTES + (wn * T::TN + l31) * T::BK;
+    struct Frag {
+        v4i a0[T::MT], a1[T::MT], b0[T::NT], b1[T::NT];
+    };
+    auto load_frags = [&](Frag &f, int s, int kk) {
+        const uint8_t *st = smem + (s % T::NS) * T::STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < T::MT; ++i) {
+            f.a0[i] = *(const v4i *)(st + a_frag0 + i * 32 * T::BK + frag_off[kk][0]);
+            f.a1[i] = *(const v4i *)(st + a_frag0 + i * 32 * T::BK + frag_off[kk][1]);
+        }
+#pragma unroll
+        for (int j = 0; j < T::NT; ++j) {
+            f.b0[j] = *(const v4i *)(st + b_frag0 + j * 32 * T::BK + frag_off[kk][0]);
+            f.b1[j] = *(const v4i *)(st + b_frag0 + j * 32 * T::BK + frag_off[kk][1]);
+        }
+    };
+    using acc_t = typename std::conditional<INT8, v16i, v16f>::type;
+    acc_t acc[T::MT][T::NT];
+    auto mfma_slab = [&](const Frag &f) {
+#pragma unroll
+        for (int i = 0; i < T::MT; ++i)
+#pragma unroll
+            for (int j = 0; j < T::NT; ++j) {
+                if constexpr (INT8) {
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.b0[j], f.a0[i], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.b1[j], f.a1[i], acc[i][j], 0, 0, 0);
+                } else {
+                    v8i fa = {f.a0[i][0], f.a0[i][1], f.a0[i][2], f.a0[i][3],
+                              f.a1[i][0], f.a1[i][1], f.a1[i][2], f.a1[i][3]};
+                    v8i fb = {f.b0[j][0], f.b0[j][1], f.b0[j][2], f.b0[j][3],
+                              f.b1[j][0], f.b1[j][1], f.b1[j][2], f.b1[j][3]};
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb, fa, acc[i][j], 0, 0,
+                                                                                0, 0, 0, 0);
+                }
+            }
+    };
+    // one MFMA, then a few LDS reads, ... : reads of the next slab run under this slab's MFMAs
+    auto interleave = [&]() {
+        constexpr int N_MFMA = T::MT * T::NT * (INT8 ? 2 : 1), N_DS = 2 * (T::MT + T::NT);
+        constexpr int DS_PER = (N_DS + N_MFMA - 2) / (N_MFMA - 1);
+#pragma unroll
+        for (int k = 0; k < N_MFMA; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, DS_PER, 0);
+        }
+    };
+
+    const int kt = g.K / T::BK;
+    Frag fr[2];
+    int id = slot;
+    int tm = 0, tn = 0;
+    if (id < total) {
+        tile_from_id(id, g.tiles_m, g.tiles_n, tm, tn);
+        set_tile(tm, tn);
+#pragma unroll
+        for (int s = 0; s < T::NS - 1; ++s)
+            if (s < kt)
+                issue_stage(s);
+    }
+    while (id < total) {
+#pragma unroll
+        for (int i = 0; i < T::MT; ++i)
+#pragma unroll
+            for (int j = 0; j < T::NT; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    acc[i][j][v] = 0;
+
+        // ---- stage 0: nothing to multiply yet.  vmcnt(0) also covers the previous tile's stores.
+        wait_vmcnt<0>();
+        block_barrier();
+        if (T::NS - 1 < kt)
+            issue_stage(T::NS - 1);
+        load_frags(fr[0], 0, 0);
+        load_frags(fr[1], 0, 1);
+        mfma_slab(fr[0]);
+        // ---- steady stages: s + NS - 1 < kt
+        int s = 1;
+        for (; s + T::NS - 1 < kt; ++s) {
+            // stage s has landed for every wave; the barrier also frees the buffer of stage s-1
+            wait_vmcnt<T::LOADS *(T::NS - 2)>();
+            block_barrier();
+            issue_stage(s + T::NS - 1);
+            load_frags(fr[0], s, 0);
+            mfma_slab(fr[1]);
+            interleave();
+            load_frags(fr[1], s, 1);
+            mfma_slab(fr[0]);
+            interleave();
+        }
+        // ---- tail stages: nothing left to issue
+        for (; s < kt; ++s) {
+            wait_vmcnt<0>();
+            block_barrier();
+            load_frags(fr[0], s, 0);
+            mfma_slab(fr[1]);
+            load_frags(fr[1], s, 1);
+            mfma_slab(fr[0]);
+        }
+        mfma_slab(fr[1]);
+
+        // ---- tile boundary: every wave is done reading the stages; start the next tile's loads,
+        //      then write this tile out (its stores drain under the next tile's MFMAs)
+        block_barrier();
+        const int cur_tm = tm, cur_tn = tn, cur_id = id;
+        id += G;
+        if (id < total) {
+            tile_from_id(id, g.tiles_m, g.tiles_n, tm, tn);
+            set_tile(tm, tn);
+#pragma unroll
+            for (int s2 = 0; s2 < T::NS - 1; ++s2)
+                if (s2 < kt)
+                    issue_stage(s2);
+        }
+        epilogue<T, INT8>(g, acc, smem + T::EPI_OFFSET, cur_tm, cur_tn, wm, wn, lane, wave, tid, cur_id);
     }
 }
 
@@ -288,52 +787,120 @@ typedef Tile<256, 256, 2, 2> T256x256;
 typedef Tile<256, 128, 2, 2> T256x128;
 typedef Tile<128, 128, 2, 2> T128x128;
 typedef Tile<64, 64, 1, 1> T64x64;
+typedef TileD<256, 256, 2, 2, 4> D256x256w4;
+typedef TileD<256, 256, 2, 4, 4, 2> D256x256w8;
+typedef TileD<256, 128, 2, 2, 4> D256x128w4;
+typedef TileD<128, 128, 2, 2, 4, 2> D128x128w4;
+typedef TileD<256, 128, 2, 2, 3, 2> D256x128o2;  // two workgroups per CU
+typedef TileD<128, 256, 2, 2, 3, 2> D128x256o2;
+typedef TileS<256, 256, 2, 4, 2, 2> S256x256w8;  // persistent, 8 waves, one workgroup per CU
+typedef TileS<256, 128, 2, 2, 3, 1> S256x128w4;
+typedef TileS<128, 128, 2, 2, 2, 2> S128x128w4;  // two workgroups per CU
 
 static int g_tile_override = 0;
 void set_gemm_tile_override(int variant) { g_tile_override = variant; }
 
-// 1: 256x256, 2: 256x128, 3: 128x128, 4: 64x64
-static int pick_tile(int64_t M, int64_t N, int64_t K)
+// Kernel variants.  1-4: register-staged kernel (any K % 16 == 0), tiles 256x256, 256x128,
+// 128x128, 64x64.  5-8: DMA-pipelined kernel (K % 64 == 0): 256x256 with 4 waves, 256x256 with
+// 8 waves, 256x128, 128x128.
+constexpr int kNumVariants = 13;
+static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256, 256, 128, 256, 128, 256, 256, 128};
+static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128};
+int gemm_num_variants() { return kNumVariants; }
+
+static int num_cus()
 {
-    if (g_tile_override)
-        return g_tile_override;
-    (void)K;
-    auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-    if (tiles(256, 256) >= 2 * 256)
-        return 1;
-    if (tiles(256, 128) >= 2 * 256)
-        return 2;
-    if (tiles(128, 128) >= 256)
-        return 3;
-    if (M * N <= 128 * 128 * 16)
-        return 4;
-    return 3;
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+    }
+    return n;
 }
 
-static void tile_dims(int v, int &bm, int &bn)
+static int pick_variant(int64_t M, int64_t N, int64_t K)
 {
-    switch (v) {
-    case 1: bm = 256; bn = 256; break;
-    case 2: bm = 256; bn = 128; break;
-    case 3: bm = 128; bn = 128; break;
-    default: bm = 64; bn = 64; break;
+    auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+    int v = g_tile_override;
+    if (v == 0) {
+        if (M * N <= 128 * 128 * 16) {
+            v = 4;
+        } else {
+            // rounds of tiles over the machine x cost of a tile; per-workgroup speeds are measured
+            // ratios: the persistent 256x256 kernel owns a CU, the 128x128 one shares it in pairs
+            const double cus = num_cus();
+            auto cost = [&](int bm, int bn, double slots, double speed) {
+                const double rounds = (double)((tiles(bm, bn) + (int64_t)slots - 1) / (int64_t)slots);
+                return rounds * bm * bn / speed;
+            };
+            const double c11 = cost(256, 256, cus, 1.0);
+            const double c13 = cost(128, 128, 2 * cus, 0.425);
+            v = c11 <= c13 ? 11 : 13;
+        }
     }
+    if (v >= 11 && K % 128 != 0)  // streaming kernel needs whole 128-byte stages
+        v = (v == 11) ? 6 : (v == 12 ? 7 : 8);
+    if (v >= 5 && K % 64 != 0)
+        v = (v == 5 || v == 6) ? 1 : ((v == 7 || v == 9) ? 2 : 3);
+    return v;
 }
 
 int fp8_gemm_workgroups(int64_t M, int64_t N, int64_t K)
 {
-    int bm, bn;
-    tile_dims(pick_tile(M, N, K), bm, bn);
-    return (int)(((M + bm - 1) / bm) * ((N + bn - 1) / bn));
+    const int v = pick_variant(M, N, K);
+    return (int)(((M + kVariantBM[v] - 1) / kVariantBM[v]) * ((N + kVariantBN[v] - 1) / kVariantBN[v]));
 }
 
-template <typename T, bool INT8>
+template <typename T, bool INT8, bool DMA>
 static hipError_t launch_tile(const GemmArgs &a, hipStream_t s)
 {
     static bool attr_done = false;  // per instantiation
-    auto kern = gemm_nt_kernel<T, INT8>;
+    const void *kern;
+    if constexpr (DMA)
+        kern = (const void *)gemm_nt_dma_kernel<T, INT8>;
+    else
+        kern = (const void *)gemm_nt_kernel<T, INT8>;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern,
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           T::LDS_BYTES);
+        if (e != hipSuccess)
+            return e;
+        attr_done = true;
+    }
+    GemmDev g;
+    g.A = a.A;
+    g.B = a.B;
+    g.M = (int)a.M;
+    g.N = (int)a.N;
+    g.K = (int)a.K;
+    g.s0 = a.s0;
+    g.s1 = a.s1;
+    g.alpha = a.alpha;
+    g.residual = (const uint16_t *)a.residual;
+    g.out = (uint16_t *)a.out;
+    g.inv_tau = a.inv_tau;
+    g.p = a.p;
+    g.partials = a.partials;
+    g.tiles_m = (int)((a.M + T::BM - 1) / T::BM);
+    g.tiles_n = (int)((a.N + T::BN - 1) / T::BN);
+    const dim3 grid((unsigned)(g.tiles_m * g.tiles_n)), block(T::THREADS);
+    if constexpr (DMA)
+        hipLaunchKernelGGL((gemm_nt_dma_kernel<T, INT8>), grid, block, T::LDS_BYTES, s, g);
+    else
+        hipLaunchKernelGGL((gemm_nt_kernel<T, INT8>), grid, block, T::LDS_BYTES, s, g);
+    return hipGetLastError();
+}
+
+template <typename T, bool INT8, int WG_PER_CU>
+static hipError_t launch_stream(const GemmArgs &a, hipStream_t s)
+{
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_stream_kernel<T, INT8>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
         if (e != hipSuccess)
             return e;
@@ -355,7 +922,11 @@ static hipError_t launch_tile(const GemmArgs &a, hipStream_t s)
     g.partials = a.partials;
     g.tiles_m = (int)((a.M + T::BM - 1) / T::BM);
     g.tiles_n = (int)((a.N + T::BN - 1) / T::BN);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(T::THREADS),
+    const int total = g.tiles_m * g.tiles_n;
+    int grid = num_cus() * WG_PER_CU;
+    if (grid > total)
+        grid = total;
+    hipLaunchKernelGGL((gemm_nt_stream_kernel<T, INT8>), dim3((unsigned)grid), dim3(T::THREADS),
                        T::LDS_BYTES, s, g);
     return hipGetLastError();
 }
@@ -363,11 +934,20 @@ static hipError_t launch_tile(const GemmArgs &a, hipStream_t s)
 template <bool INT8>
 static hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
-    switch (pick_tile(a.M, a.N, a.K)) {
-    case 1: return launch_tile<T256x256, INT8>(a, s);
-    case 2: return launch_tile<T256x128, INT8>(a, s);
-    case 3: return launch_tile<T128x128, INT8>(a, s);
-    default: return launch_tile<T64x64, INT8>(a, s);
+    switch (pick_variant(a.M, a.N, a.K)) {
+    case 1: return launch_tile<T256x256, INT8, false>(a, s);
+    case 2: return launch_tile<T256x128, INT8, false>(a, s);
+    case 3: return launch_tile<T128x128, INT8, false>(a, s);
+    case 4: return launch_tile<T64x64, INT8, false>(a, s);
+    case 5: return launch_tile<D256x256w4, INT8, true>(a, s);
+    case 6: return launch_tile<D256x256w8, INT8, true>(a, s);
+    case 7: return launch_tile<D256x128w4, INT8, true>(a, s);
+    case 8: return launch_tile<D128x128w4, INT8, true>(a, s);
+    case 9: return launch_tile<D256x128o2, INT8, true>(a, s);
+    case 10: return launch_tile<D128x256o2, INT8, true>(a, s);
+    case 11: return launch_stream<S256x256w8, INT8, 1>(a, s);
+    case 12: return launch_stream<S256x128w4, INT8, 1>(a, s);
+    default: return launch_stream<S128x128w4, INT8, 2>(a, s);
     }
 }
 

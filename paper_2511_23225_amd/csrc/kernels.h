@@ -39,5 +39,6 @@ hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s);
 
 // Tile-shape override for benchmarking sweeps: 0 = heuristic.
 void set_gemm_tile_override(int variant);
+int gemm_num_variants();
 
 }  // namespace tweo

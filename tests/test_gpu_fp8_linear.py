@@ -24,7 +24,7 @@ def oracle_quantized(x):
 
 
 def run_fwd(xq, wq, sxi, swi, M, N, K, residual=None, pen=PEN):
-    y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)  # poisoned
     S = torch.zeros(2, dtype=torch.float64, device=DEV)
     ws = workspace(tw.TWEO_OP_FP8_LINEAR_FWD, M, N, K)
     tw.tweo_fp8_linear_fwd(to_dev(xq), scalar_f32(sxi), to_dev(wq), scalar_f32(swi), y,
@@ -41,10 +41,11 @@ CASES = [  # (cfg, gemm, M, K, N): several tiles and ragged tails in M and N
     (2, 0, 333, 256, 1000),
     (3, 4, 130, 1408, 72),
     (0, 0, 16, 16, 8),
+    (3, 0, 777, 256, 520),
 ]
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13])
 @pytest.mark.parametrize("case", CASES)
 def test_fwd_with_penalty(case, tile):
     cfg, gi, M, K, N = case
@@ -118,7 +119,7 @@ def test_penalty_printed_regimes_through_the_gemm():
         assert abs(S / (M * N) - printed) <= 1e-6 * printed
 
 
-@pytest.mark.parametrize("tile", [0, 1, 3, 4])
+@pytest.mark.parametrize("tile", [0, 1, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13])
 @pytest.mark.parametrize("case", [(0, 0, 256, 512, 512), (1, 1, 208, 256, 144), (3, 0, 144, 640, 400)])
 def test_bwd(case, tile):
     cfg, gi, M, K, N = case
@@ -129,8 +130,8 @@ def test_bwd(case, tile):
     dyq, dyqT, sdyi = oracle_quantized(dy)
     dx_ref, dx_abs = oracle.fp8_linear_dgrad(dyq, wq, sdyi, swi)
     dw_ref, dw_abs = oracle.fp8_linear_wgrad(dyq, xq, sdyi, sxi)
-    dx = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
-    dw = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+    dx = torch.full((M, K), float('nan'), dtype=torch.bfloat16, device=DEV)
+    dw = torch.full((N, K), float('nan'), dtype=torch.bfloat16, device=DEV)
     tw.tweo_set_gemm_tile(tile)
     try:
         tw.tweo_fp8_linear_bwd(to_dev(dyq), to_dev(dyqT), scalar_f32(sdyi), to_dev(wqT),
@@ -155,9 +156,9 @@ def test_whole_path_from_bf16_and_determinism():
         dyq, dyqT = u8(M, N), u8(N, M)
         sc = torch.full((16,), -3.0, dtype=torch.float32, device=DEV)
         saved = tw.make_saved(xq, xqT, wq, wqT, sc)
-        y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
-        dx = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
-        dw = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+        y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)  # poisoned
+        dx = torch.full((M, K), float('nan'), dtype=torch.bfloat16, device=DEV)
+        dw = torch.full((N, K), float('nan'), dtype=torch.bfloat16, device=DEV)
         S = torch.zeros(2, dtype=torch.float64, device=DEV)
         ws = workspace(tw.TWEO_OP_FP8_LINEAR_FWD_BF16, M, N, K)
         tw.tweo_fp8_linear_fwd_bf16(xd, wd, y, saved, pen=PEN, penalty_sum=S, workspace=ws)

@@ -15,7 +15,7 @@ def say(*a):
     print(*a, flush=True)
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13])
 @pytest.mark.parametrize("shape", [(1, 4096, 264), (16, 1024, 512), (64, 2048, 136), (200, 512, 392),
                                    (512, 768, 256), (33, 11008, 72)])
 def test_w8a8_bit_exact(shape, tile):
@@ -31,7 +31,7 @@ def test_w8a8_bit_exact(shape, tile):
     oxq = oracle.quantize_i8(x, inv_x)
     assert np.array_equal(xq.cpu().numpy(), oxq)
     owq = oracle.quantize_i8(w, inv_w)
-    y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)  # poisoned
     tw.tweo_set_gemm_tile(tile)
     try:
         tw.tweo_w8a8_linear(xq, to_dev(owq), alpha, y, workspace(tw.TWEO_OP_W8A8_LINEAR, M, N, K))
@@ -49,6 +49,6 @@ def test_w8a8_extreme_accumulators():
     xq = np.full((M, K), 127, np.int8)
     wq = np.full((N, K), -127, np.int8)
     wq[::2] = 127
-    y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)  # poisoned
     tw.tweo_w8a8_linear(to_dev(xq), to_dev(wq), 1.0, y, workspace(tw.TWEO_OP_W8A8_LINEAR, M, N, K))
     assert np.array_equal(bf16_bits(y), oracle.w8a8_linear(xq, wq, 1.0))
