@@ -23,8 +23,7 @@ hipError_t launch_fill_u32(uint32_t *p, int n, uint32_t v, hipStream_t s)
 
 // ---------------------------------------------------------------------------
 // amax (Sec. 4.3 / Eq. 4): max over the whole tensor of the 15-bit magnitude
-// patterns.  2 B/element of HBM reads, nothing else: 16-byte loads, four in
-// flight per lane, packed 16-bit max, wave shuffle + LDS tree, then one integer
+// patterns.  2 B/element of HBM reads, nothing else: 16-byte loads, packed 16-bit max, wave shuffle + LDS tree, then one integer
 // atomicMax per workgroup on the fp32 bit pattern (positive floats order like
 // unsigned integers, so the result is exact and order independent).
 constexpr int kAmaxThreads = 256;
@@ -44,23 +43,31 @@ __device__ __forceinline__ uint32_t pk_absmax4(uint32_t m, uint4 v)
     return pk_absmax(m, v.w);
 }
 
+// Each workgroup owns one contiguous chunk of the tensor and walks it with
+// eight 16-byte loads in flight per lane (measured: ~30 % more bandwidth than a
+// grid-stride walk, whose concurrent streams are megabytes apart).
+constexpr int kAmaxUnroll = 8;
+
 __global__ __launch_bounds__(kAmaxThreads) void amax_kernel(const uint4 *__restrict__ x,
-                                                            int64_t n_vec,
+                                                            int64_t n_vec, int64_t per_block,
                                                             const uint16_t *__restrict__ tail,
                                                             int n_tail, uint32_t *out)
 {
     __shared__ uint32_t red[kAmaxThreads / kWave];
-    const int64_t stride = (int64_t)gridDim.x * kAmaxThreads;
-    int64_t i = (int64_t)blockIdx.x * kAmaxThreads + threadIdx.x;
+    const int64_t b0 = (int64_t)blockIdx.x * per_block;
+    const int64_t b1 = b0 + per_block < n_vec ? b0 + per_block : n_vec;
+    int64_t i = b0 + threadIdx.x;
     uint32_t m = 0;
-    for (; i + 3 * stride < n_vec; i += 4 * stride) {
-        uint4 v0 = x[i], v1 = x[i + stride], v2 = x[i + 2 * stride], v3 = x[i + 3 * stride];
-        m = pk_absmax4(m, v0);
-        m = pk_absmax4(m, v1);
-        m = pk_absmax4(m, v2);
-        m = pk_absmax4(m, v3);
+    for (; i + (kAmaxUnroll - 1) * kAmaxThreads < b1; i += kAmaxUnroll * kAmaxThreads) {
+        uint4 v[kAmaxUnroll];
+#pragma unroll
+        for (int u = 0; u < kAmaxUnroll; ++u)
+            v[u] = x[i + u * kAmaxThreads];
+#pragma unroll
+        for (int u = 0; u < kAmaxUnroll; ++u)
+            m = pk_absmax4(m, v[u]);
     }
-    for (; i < n_vec; i += stride)
+    for (; i < b1; i += kAmaxThreads)
         m = pk_absmax4(m, x[i]);
     if (blockIdx.x == 0 && (int)threadIdx.x < n_tail)
         m = pk_absmax(m, tail[threadIdx.x]);
@@ -73,22 +80,28 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_kernel(const uint4 *__restr
 #pragma unroll
         for (int w = 1; w < kAmaxThreads / kWave; ++w)
             r = red[w] > r ? red[w] : r;
-        atomicMax(out, r << 16);  // bf16 magnitude widened to the fp32 pattern
+        // bf16 magnitude widened to the fp32 pattern.  The result only grows, so a workgroup
+        // whose maximum is already covered skips the atomic (they serialise on one address).
+        const uint32_t mine = r << 16;
+        if (mine > __atomic_load_n(out, __ATOMIC_RELAXED))
+            atomicMax(out, mine);
     }
 }
 
 hipError_t launch_amax(const void *x_bf16, int64_t n, float *amax_zeroed, hipStream_t s)
 {
-    int64_t n_vec = n / 8;
-    int n_tail = (int)(n % 8);
-    int64_t blocks = (n_vec + kAmaxThreads * 4 - 1) / (kAmaxThreads * 4);
+    const int64_t n_vec = n / 8;
+    const int n_tail = (int)(n % 8);
+    // chunks of at least 32 KB (one unrolled trip), at most 4096 workgroups
+    int64_t blocks = n_vec / (kAmaxUnroll * kAmaxThreads);
     if (blocks < 1)
         blocks = 1;
-    if (blocks > 256 * 8)
-        blocks = 256 * 8;
+    if (blocks > 4096)
+        blocks = 4096;
+    const int64_t per_block = (n_vec + blocks - 1) / blocks;
     hipLaunchKernelGGL(amax_kernel, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, s,
-                       (const uint4 *)x_bf16, n_vec, (const uint16_t *)x_bf16 + n_vec * 8, n_tail,
-                       (uint32_t *)amax_zeroed);
+                       (const uint4 *)x_bf16, n_vec, per_block,
+                       (const uint16_t *)x_bf16 + n_vec * 8, n_tail, (uint32_t *)amax_zeroed);
     return hipGetLastError();
 }
 
@@ -197,13 +210,94 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
     }
 }
 
+// Same cast for shapes with rows % 16 == 0 and cols % 16 == 0: a lane owns a
+// 16x16 block (two 16-byte loads per row), so q is written in 16-byte pieces
+// that 8 neighbouring lanes join into whole 128-byte lines, and - after sixteen
+// 4x4 byte transposes - qT likewise.  A wave covers 128x128 elements, a
+// workgroup 256x256.
+constexpr int kQuantBigTile = 256;
+
+template <bool WITH_T>
+__global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
+    const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
+    const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
+    float *scale_out, float *scale_inv_out)
+{
+    const float scale = scale_from_amax(*amax);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (scale_out)
+            *scale_out = scale;
+        if (scale_inv_out)
+            *scale_inv_out = 1.0f / scale;
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int64_t by = blockIdx.x / tiles_x, bx = blockIdx.x % tiles_x;
+    const int64_t r0 = by * kQuantBigTile + (wave >> 1) * 128 + (lane >> 3) * 16;
+    const int64_t c0 = bx * kQuantBigTile + (wave & 1) * 128 + (lane & 7) * 16;
+    if (c0 >= cols || r0 >= rows)
+        return;
+    uint32_t qd[16][4];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        uint4 in[8][2];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint4 *src = (const uint4 *)(x + (r0 + half * 8 + i) * cols + c0);
+            in[i][0] = src[0];
+            in[i][1] = src[1];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = half * 8 + i;
+#pragma unroll
+            for (int w = 0; w < 2; ++w) {
+                const uint4 v = in[i][w];
+                qd[r][2 * w] = cvt4_e4m3(bf16lo_to_f32(v.x) * scale, bf16hi_to_f32(v.x) * scale,
+                                         bf16lo_to_f32(v.y) * scale, bf16hi_to_f32(v.y) * scale);
+                qd[r][2 * w + 1] = cvt4_e4m3(bf16lo_to_f32(v.z) * scale, bf16hi_to_f32(v.z) * scale,
+                                             bf16lo_to_f32(v.w) * scale, bf16hi_to_f32(v.w) * scale);
+            }
+            *(uint4 *)(q + (r0 + r) * cols + c0) = make_uint4(qd[r][0], qd[r][1], qd[r][2], qd[r][3]);
+        }
+    }
+    if (WITH_T) {
+#pragma unroll
+        for (int C = 0; C < 4; ++C) {
+            uint32_t t[4][4];  // t[R][k]: column 4C+k, rows 4R..4R+3
+#pragma unroll
+            for (int R = 0; R < 4; ++R)
+                transpose4x4_bytes(qd[4 * R][C], qd[4 * R + 1][C], qd[4 * R + 2][C], qd[4 * R + 3][C],
+                                   t[R][0], t[R][1], t[R][2], t[R][3]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                *(uint4 *)(qT + (c0 + 4 * C + k) * rows + r0) =
+                    make_uint4(t[0][k], t[1][k], t[2][k], t[3][k]);
+        }
+    }
+}
+
 hipError_t launch_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
                                 uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
                                 hipStream_t s)
 {
-    int64_t tiles_x = (cols + kQuantTileCols - 1) / kQuantTileCols;
-    int64_t tiles_y = (rows + kQuantTileRows - 1) / kQuantTileRows;
-    dim3 grid((unsigned)(tiles_x * tiles_y)), block(kQuantThreads);
+    const dim3 block(kQuantThreads);
+    if (rows % 16 == 0 && cols % 16 == 0) {
+        const int64_t tiles_x = (cols + kQuantBigTile - 1) / kQuantBigTile;
+        const int64_t tiles_y = (rows + kQuantBigTile - 1) / kQuantBigTile;
+        const dim3 grid((unsigned)(tiles_x * tiles_y));
+        if (qT)
+            hipLaunchKernelGGL(quantize_e4m3_16x16_kernel<true>, grid, block, 0, s,
+                               (const uint16_t *)x_bf16, rows, cols, tiles_x, amax, q, qT, scale_out,
+                               scale_inv_out);
+        else
+            hipLaunchKernelGGL(quantize_e4m3_16x16_kernel<false>, grid, block, 0, s,
+                               (const uint16_t *)x_bf16, rows, cols, tiles_x, amax, q, qT, scale_out,
+                               scale_inv_out);
+        return hipGetLastError();
+    }
+    const int64_t tiles_x = (cols + kQuantTileCols - 1) / kQuantTileCols;
+    const int64_t tiles_y = (rows + kQuantTileRows - 1) / kQuantTileRows;
+    const dim3 grid((unsigned)(tiles_x * tiles_y));
     if (qT)
         hipLaunchKernelGGL(quantize_e4m3_kernel<true>, grid, block, 0, s, (const uint16_t *)x_bf16,
                            rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out);
