@@ -781,6 +781,102 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
 }
 
 // ---------------------------------------------------------------------------
+// W8A8 linear for small M (decode-time batches, M <= 64): the product is bound
+// by streaming the N x K weight bytes from HBM once, so there is no LDS staging
+// and no tiling of K across workgroups.  A workgroup owns 16*NBLK weight rows;
+// its 8 waves split K into 8 contiguous slices, each wave multiplies its slice
+// with v_mfma_i32_16x16x64_i8 (operands loaded straight from global memory in
+// the MFMA lane layout: row = lane%16, 16 bytes at k = 16*(lane/16)), and the 8
+// partial int32 tiles are added through LDS - exact, so the result is the same
+// bits as any other summation order.  y = bf16(fp32(acc) * alpha) (Sec. 4.4).
+template <int NBLK, int MB, int UNROLL, int WAVES, bool IL>
+__global__ __launch_bounds__(WAVES * 64) void w8a8_skinny_kernel(const int8_t *__restrict__ X,
+                                                          const int8_t *__restrict__ W, int M, int N,
+                                                          int K, float alpha, uint16_t *__restrict__ Y)
+{
+    constexpr int STEP = 64;
+    __shared__ v4i red[WAVES][MB][kWave];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int r16 = lane & 15, kc = lane >> 4;
+    const int n0 = blockIdx.x * 16 * NBLK;
+    // K is cut in 64-byte steps; wave w takes a contiguous run of them (IL = false) or every
+    // WAVES-th step (IL = true: the waves of a workgroup then read adjacent 64-byte columns)
+    const int steps = K / STEP, per = (steps + WAVES - 1) / WAVES;
+    const int s_begin = IL ? wave : wave * per;
+    const int s_end = IL ? steps : (s_begin + per < steps ? s_begin + per : steps);
+    constexpr int S_INC = IL ? WAVES : 1;
+    const int8_t *wp[NBLK], *xp[MB];
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+        int n = n0 + b * 16 + r16;
+        n = n < N ? n : N - 1;  // rows past N: duplicates, never stored
+        wp[b] = W + (int64_t)n * K + kc * 16;
+    }
+#pragma unroll
+    for (int b = 0; b < MB; ++b) {
+        int m = b * 16 + r16;
+        m = m < M ? m : M - 1;
+        xp[b] = X + (int64_t)m * K + kc * 16;
+    }
+    v4i acc[NBLK][MB];
+#pragma unroll
+    for (int a = 0; a < NBLK; ++a)
+#pragma unroll
+        for (int b = 0; b < MB; ++b)
+            acc[a][b] = v4i{0, 0, 0, 0};
+    for (int s = s_begin; s < s_end; s += UNROLL * S_INC) {
+        v4i wf[UNROLL][NBLK], xf[UNROLL][MB];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            // past the slice end: re-read this trip's first step (in bounds), its MFMA is skipped
+            const int su = s + u * S_INC;
+            const int64_t k = (int64_t)(su < s_end ? su : s) * STEP;
+#pragma unroll
+            for (int a = 0; a < NBLK; ++a)
+                wf[u][a] = *(const v4i *)(wp[a] + k);
+#pragma unroll
+            for (int b = 0; b < MB; ++b)
+                xf[u][b] = *(const v4i *)(xp[b] + k);
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            if (s + u * S_INC < s_end) {
+#pragma unroll
+                for (int a = 0; a < NBLK; ++a)
+#pragma unroll
+                    for (int b = 0; b < MB; ++b)
+                        // first operand -> register index (n), second -> lane%16 (m)
+                        acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[u][a], xf[u][b], acc[a][b],
+                                                                         0, 0, 0);
+            }
+    }
+    // acc[v] of lane l is C[n = 4*(l/16) + v, m = l%16] of its 16x16 block
+#pragma unroll
+    for (int a = 0; a < NBLK; ++a) {
+        if (a > 0)
+            __syncthreads();
+#pragma unroll
+        for (int b = 0; b < MB; ++b)
+            red[wave][b][lane] = acc[a][b];
+        __syncthreads();
+        for (int t = tid; t < MB * kWave; t += WAVES * kWave) {
+            const int b = t / kWave, l = t % kWave;
+            v4i sum = red[0][b][l];
+#pragma unroll
+            for (int w = 1; w < WAVES; ++w)
+                sum += red[w][b][l];
+            const int m = b * 16 + (l & 15), n = n0 + a * 16 + 4 * (l >> 4);
+            if (m < M && n < N) {
+                const uint2 packed =
+                    make_uint2(pack_bf16x2((float)sum[0] * alpha, (float)sum[1] * alpha),
+                               pack_bf16x2((float)sum[2] * alpha, (float)sum[3] * alpha));
+                *(uint2 *)(Y + (int64_t)m * N + n) = packed;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 
 typedef Tile<256, 256, 2, 2> T256x256;
@@ -952,6 +1048,29 @@ static hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 }
 
 hipError_t launch_fp8_gemm(const GemmArgs &a, hipStream_t s) { return launch_gemm<false>(a, s); }
-hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s) { return launch_gemm<true>(a, s); }
+template <int NBLK, int MB, int UNROLL, int WAVES, bool IL>
+static hipError_t launch_skinny(const GemmArgs &a, hipStream_t s)
+{
+    const unsigned grid = (unsigned)((a.N + 16 * NBLK - 1) / (16 * NBLK));
+    hipLaunchKernelGGL((w8a8_skinny_kernel<NBLK, MB, UNROLL, WAVES, IL>), dim3(grid), dim3(WAVES * 64), 0, s, (const int8_t *)a.A,
+                       (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, (uint16_t *)a.out);
+    return hipGetLastError();
+}
+
+hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s)
+{
+    // small M: weight-streaming kernel (forced variants keep the tiled kernels, for tests)
+    if (g_tile_override == 0 && a.M <= 64 && a.K % 64 == 0 && a.N % 4 == 0) {
+        // measured on the 7B shapes: enough workgroups to cover the CUs matters more than the
+        // re-reads of X from L2, so few weight rows per workgroup when N is small
+        const bool wide = a.N >= 8192;
+        if (a.M <= 16)
+            return wide ? launch_skinny<1, 1, 8, 8, true>(a, s) : launch_skinny<1, 1, 4, 16, true>(a, s);
+        if (a.M <= 32)
+            return launch_skinny<2, 2, 8, 8, false>(a, s);
+        return wide ? launch_skinny<4, 4, 4, 8, true>(a, s) : launch_skinny<1, 4, 4, 16, true>(a, s);
+    }
+    return launch_gemm<true>(a, s);
+}
 
 }  // namespace tweo

@@ -49,7 +49,13 @@ def inject_sparse_outliers(x, frac, lo, hi, rng):
     k = int(round(frac * flat.size))
     if k == 0:
         return x
-    pos = rng.choice(flat.size, size=k, replace=False)
+    # k distinct positions, uniform: draw with a little slack, drop repeats, keep the first k
+    pos = np.empty(0, np.int64)
+    while pos.size < k:
+        draw = rng.integers(0, flat.size, size=k + k // 8 + 16)
+        _, first = np.unique(np.concatenate([pos, draw]), return_index=True)
+        pos = np.concatenate([pos, draw])[np.sort(first)]
+    pos = pos[:k]
     mag = rng.uniform(lo, hi, size=k).astype(np.float32)
     sgn = np.where(rng.integers(0, 2, size=k) == 0, np.float32(-1), np.float32(1))
     flat[pos] = mag * sgn

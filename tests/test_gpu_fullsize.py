@@ -1,0 +1,152 @@
+"""GPU parity at the workloads' full sizes, in the launch configuration bench.py times
+(shape heuristic, whole path from bf16 operands).  The oracle checks every amax and scale,
+whole quantized tensors where that takes seconds (row samples otherwise), GEMM outputs on
+sampled rows (rows are independent, so a sampled row is checked exactly as a full run
+would), and the penalty either against the full oracle (small layers) or through the
+property that holds at any size: it equals the sum over the tensor the kernel stored."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2511_23225_amd as tw
+from paper_2511_23225_amd import synth
+from gpu_util import DEV, PEN, to_dev_bf16, bf16_bits, check_gemm, workspace
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def run_layer(x, w, dy, M, K, N, residual=None):
+    u8 = lambda *s: torch.empty(s, dtype=torch.uint8, device=DEV)
+    nan = lambda *s: torch.full(s, float("nan"), dtype=torch.bfloat16, device=DEV)
+    t = dict(xq=u8(M, K), xqT=u8(K, M), wq=u8(N, K), wqT=u8(K, N), dyq=u8(M, N), dyqT=u8(N, M),
+             y=nan(M, N), dx=nan(M, K), dw=nan(N, K),
+             sc=torch.full((16,), -1.0, dtype=torch.float32, device=DEV),
+             S=torch.zeros(2, dtype=torch.float64, device=DEV))
+    saved = tw.make_saved(t["xq"], t["xqT"], t["wq"], t["wqT"], t["sc"])
+    ws = workspace(tw.TWEO_OP_FP8_LINEAR_FWD_BF16, M, N, K)
+    tw.tweo_fp8_linear_fwd_bf16(to_dev_bf16(x), to_dev_bf16(w), t["y"], saved,
+                                residual_bf16=None if residual is None else to_dev_bf16(residual),
+                                pen=PEN, penalty_sum=t["S"], workspace=ws)
+    tw.tweo_fp8_linear_bwd_bf16(to_dev_bf16(dy), saved, K, t["dyq"], t["dyqT"], t["dx"], t["dw"], ws)
+    torch.cuda.synchronize()
+    return t
+
+
+def rows_sample(n, count, seed):
+    rng = np.random.default_rng(seed)
+    picks = rng.choice(n, size=min(count, n), replace=False)
+    edge = np.array([0, n - 1, min(n - 1, 255), min(n - 1, 256)])
+    return np.unique(np.concatenate([picks, edge]))
+
+
+def check_quantized(name, bits, q_dev, qT_dev, scale, rows):
+    """Every byte of q against the oracle; qT against the oracle's transpose on the whole tensor
+    (rows is None) or on the sampled rows (= columns of qT).  Returns the oracle's q."""
+    want, wantT = oracle.quantize_e4m3(bits, scale, transpose=rows is None)
+    assert np.array_equal(q_dev.cpu().numpy(), want), name
+    if rows is None:
+        assert np.array_equal(qT_dev.cpu().numpy(), wantT), name + " (transposed)"
+    else:
+        idx = torch.from_numpy(rows).to(DEV)
+        assert np.array_equal(qT_dev[:, idx].cpu().numpy(), want[rows].T), name + " (transposed)"
+    return want
+
+
+CASES = [  # (cfg, gemm index, full oracle for the forward + penalty?)
+    (1, 1, True),    # GPT-2 proj 8192x768x768
+    (1, 0, False),   # GPT-2 qkv 8192x768x2304
+    (1, 3, False),   # GPT-2 fc2 8192x3072x768
+    (2, 1, False),   # ViT fc1 50432x768x3072 (channel outliers)
+    (2, 2, False),   # ViT fc2 50432x3072x768
+    (3, 0, False),   # LLaMA qkv 16384x2048x6144
+    (3, 4, False),   # LLaMA down 16384x5632x2048
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_full_size_layer(case):
+    cfg, gi, full = case
+    g = synth.CONFIGS[cfg]["gemms"][gi]
+    M, K, N = g.M, g.K, g.N
+    say("full size cfg=%d %s M=%d K=%d N=%d" % (cfg, g.name, M, K, N))
+    x, w, dy = synth.fp8_linear_inputs(cfg, gi)
+    residual = synth.residual_input(cfg, gi, M, N) if g.name in ("fc2", "down", "proj") else None
+    t = run_layer(x, w, dy, M, K, N, residual)
+    say("  gpu done")
+    sc = t["sc"].cpu().numpy()
+    # amax and scales: exact, on the whole tensors
+    want_sc = []
+    for bits in (x, w, dy):
+        a = oracle.amax_bf16(bits)
+        want_sc += [a, *oracle.scale_from_amax(a)]
+    assert np.array_equal(sc[:9], np.array(want_sc, np.float32))
+    sx, sxi, sw, swi, sdy, sdyi = want_sc[1], want_sc[2], want_sc[4], want_sc[5], want_sc[7], want_sc[8]
+    # quantized bytes: W whole; X whole when it is small, else sampled rows; dY sampled rows
+    rm = rows_sample(M, 192, 11 * cfg + gi)
+    wq = check_quantized("wq", w, t["wq"], t["wqT"], sw, None)
+    xq = check_quantized("xq", x, t["xq"], t["xqT"], sx, rm)
+    dyq = check_quantized("dyq", dy, t["dyq"], t["dyqT"], sdy, rm)
+    say("  quantized bytes ok")
+    rs = rm[:64]
+    # forward on sampled rows (or all rows)
+    if full:
+        ref, refabs, refbf = oracle.fp8_linear_fwd(xq, wq, sxi, swi, residual=residual)
+        check_gemm(bf16_bits(t["y"]), ref, refabs, K, "fwd")
+        Sref = oracle.penalty_sum(refbf, *PEN)
+        S = float(t["S"].cpu()[0])
+        assert abs(S - Sref) <= 1e-4 * Sref, (S, Sref)
+    else:
+        ref, refabs, _ = oracle.fp8_linear_fwd(xq, wq, sxi, swi, residual=residual, rows=rs)
+        got = bf16_bits(t["y"][torch.from_numpy(rs).to(DEV)])
+        check_gemm(got, ref, refabs, K, "fwd rows")
+        # penalty: equals the sum over the stored tensor (fp64 on the device copy, chunked)
+        S = float(t["S"].cpu()[0])
+        S_self = 0.0
+        for r0 in range(0, M, 4096):
+            blk = t["y"][r0:r0 + 4096].to(torch.float64).abs() / (PEN[0] + PEN[1])
+            S_self += float((blk ** PEN[2]).sum().cpu())
+        assert abs(S - S_self) <= 2e-6 * S_self, (S, S_self)
+    say("  fwd ok")
+    # dgrad on sampled rows of M
+    dx_ref, dx_abs = oracle.fp8_linear_dgrad(dyq, wq, sdyi, swi, rows=rs)
+    got = bf16_bits(t["dx"][torch.from_numpy(rs).to(DEV)])
+    check_gemm(got, dx_ref, dx_abs, N, "dgrad rows")
+    say("  dgrad ok")
+    # wgrad on sampled rows of N (the contraction runs over all of M)
+    rn = rows_sample(N, 24, 7 * cfg + gi)
+    dw_ref, dw_abs = oracle.fp8_linear_wgrad(dyq, xq, sdyi, sxi, rows=rn)
+    got = bf16_bits(t["dw"][torch.from_numpy(rn).to(DEV)])
+    check_gemm(got, dw_ref, dw_abs, M, "wgrad rows")
+    say("  wgrad ok")
+
+
+@pytest.mark.parametrize("M", [1, 16, 64, 4096])
+@pytest.mark.parametrize("gi", [0, 3])
+def test_full_size_w8a8(gi, M):
+    g = synth.CONFIGS[4]["gemms"][gi]
+    K, N = g.K, g.N
+    say("full size w8a8 %s M=%d K=%d N=%d" % (g.name, M, K, N))
+    x, w = synth.w8a8_inputs(gi, M)
+    ax, aw = oracle.amax_bf16(x), oracle.amax_bf16(w)
+    inv_x, inv_w = np.float32(127.0) / ax, np.float32(127.0) / aw
+    alpha = (ax / np.float32(127.0)) * (aw / np.float32(127.0))
+    xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
+    tw.tweo_quantize_i8(to_dev_bf16(x), inv_x, xq)
+    wq = torch.empty((N, K), dtype=torch.int8, device=DEV)
+    tw.tweo_quantize_i8(to_dev_bf16(w), inv_w, wq)  # weights: same kernel, offline
+    oxq, owq = oracle.quantize_i8(x, inv_x), oracle.quantize_i8(w, inv_w)
+    assert np.array_equal(xq.cpu().numpy(), oxq) and np.array_equal(wq.cpu().numpy(), owq)
+    y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+    tw.tweo_w8a8_linear(xq, wq, alpha, y, workspace(tw.TWEO_OP_W8A8_LINEAR, M, N, K))
+    torch.cuda.synchronize()
+    if M <= 64:
+        assert np.array_equal(bf16_bits(y), oracle.w8a8_linear(oxq, owq, alpha))
+    else:
+        rs = rows_sample(M, 48, gi)
+        want = oracle.w8a8_linear(np.ascontiguousarray(oxq[rs]), owq, alpha)
+        assert np.array_equal(bf16_bits(y[torch.from_numpy(rs).to(DEV)]), want)
