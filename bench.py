@@ -194,7 +194,9 @@ def main():
     ap.add_argument("--workload", default="llama", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
-    ap.add_argument("--tile", type=int, default=0, help="force a GEMM tile variant (0 = heuristic)")
+    ap.add_argument("--tile", type=int, default=0, help="force a GEMM kernel variant (0 = heuristic)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run plain device copies of 256 MiB (for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (the path has no multi-GPU part); "
@@ -212,6 +214,15 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(3)
     dev = "cuda:0"
+    if a.copy_calibration:
+        n = 256 << 20
+        src = torch.full((n,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(max(1, a.steps)):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_each_way": n, "copies": max(1, a.steps)}), flush=True)
+        return
     cfg = WORKLOADS[a.workload]
     t0 = time.perf_counter()
     layers = [Layer(tw, torch, synth, cfg, gi, dev) for gi in range(len(synth.CONFIGS[cfg]["gemms"]))]

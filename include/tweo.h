@@ -181,13 +181,16 @@ tweo_status tweo_fp8_linear_bwd_bf16(const void *dy_bf16, const tweo_fp8_saved *
                                      size_t workspace_bytes, void *stream);
 
 /*
- * Tuning hook for benchmarks and tests: forces the GEMM kernel variant
- * (0 = choose from the shape, the default; 1-4 = register-staged kernel with
- * a 256x256, 256x128, 128x128, 64x64 workgroup tile; 5-8 = DMA-pipelined
- * kernel: 256x256 with 4 waves, 256x256 with 8 waves, 256x128, 128x128; a
- * DMA variant falls back to its register-staged twin when K % 64 != 0).
- * Process-wide, not thread safe.  Results are identical up to the fp32
- * summation order.  Returns TWEO_ERR_INVALID_ARG for an unknown variant.
+ * Tuning hook for benchmarks and tests: forces the GEMM kernel variant.
+ * 0 = choose from the shape (the default).  1-4 = register-staged kernel, tiles
+ * 256x256, 256x128, 128x128, 64x64 (any K % 16 == 0).  5-10 = DMA-pipelined
+ * kernel with 64-byte stages (K % 64 == 0): 256x256 with 4 waves, with 8 waves,
+ * 256x128, 128x128, and 256x128 / 128x256 at two workgroups per CU.  11-14 =
+ * persistent streaming kernel with 128-byte stages (K % 128 == 0): 256x256,
+ * 256x128, 128x128, 192x256.  A variant whose K requirement is not met falls
+ * back to the nearest one that fits.  Process-wide, not thread safe.  Results
+ * are identical up to the fp32 summation order.  Returns
+ * TWEO_ERR_INVALID_ARG for an unknown variant.
  */
 tweo_status tweo_set_gemm_tile(int variant);
 

@@ -892,6 +892,7 @@ typedef TileD<128, 256, 2, 2, 3, 2> D128x256o2;
 typedef TileS<256, 256, 2, 4, 2, 2> S256x256w8;  // persistent, 8 waves, one workgroup per CU
 typedef TileS<256, 128, 2, 2, 3, 1> S256x128w4;
 typedef TileS<128, 128, 2, 2, 2, 2> S128x128w4;  // two workgroups per CU
+typedef TileS<192, 256, 2, 4, 2, 2> S192x256w8;  // for tile counts that 256x256 quantises badly
 
 static int g_tile_override = 0;
 void set_gemm_tile_override(int variant) { g_tile_override = variant; }
@@ -899,9 +900,9 @@ void set_gemm_tile_override(int variant) { g_tile_override = variant; }
 // Kernel variants.  1-4: register-staged kernel (any K % 16 == 0), tiles 256x256, 256x128,
 // 128x128, 64x64.  5-8: DMA-pipelined kernel (K % 64 == 0): 256x256 with 4 waves, 256x256 with
 // 8 waves, 256x128, 128x128.
-constexpr int kNumVariants = 13;
-static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256, 256, 128, 256, 128, 256, 256, 128};
-static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128};
+constexpr int kNumVariants = 14;
+static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256, 256, 128, 256, 128, 256, 256, 128, 192};
+static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128, 256};
 int gemm_num_variants() { return kNumVariants; }
 
 static int num_cus()
@@ -935,11 +936,19 @@ static int pick_variant(int64_t M, int64_t N, int64_t K)
             };
             const double c11 = cost(256, 256, cus, 1.0);
             const double c13 = cost(128, 128, 2 * cus, 0.425);
-            v = c11 <= c13 ? 11 : 13;
+            const double c14 = cost(192, 256, cus, 0.97);
+            v = 11;
+            double best = c11;
+            if (c14 < best) {
+                v = 14;
+                best = c14;
+            }
+            if (c13 < best)
+                v = 13;
         }
     }
     if (v >= 11 && K % 128 != 0)  // streaming kernel needs whole 128-byte stages
-        v = (v == 11) ? 6 : (v == 12 ? 7 : 8);
+        v = (v == 11 || v == 14) ? 6 : (v == 12 ? 7 : 8);
     if (v >= 5 && K % 64 != 0)
         v = (v == 5 || v == 6) ? 1 : ((v == 7 || v == 9) ? 2 : 3);
     return v;
@@ -1043,7 +1052,8 @@ static hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     case 10: return launch_tile<D128x256o2, INT8, true>(a, s);
     case 11: return launch_stream<S256x256w8, INT8, 1>(a, s);
     case 12: return launch_stream<S256x128w4, INT8, 1>(a, s);
-    default: return launch_stream<S128x128w4, INT8, 2>(a, s);
+    case 13: return launch_stream<S128x128w4, INT8, 2>(a, s);
+    default: return launch_stream<S192x256w8, INT8, 1>(a, s);
     }
 }
 

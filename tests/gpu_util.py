@@ -66,3 +66,25 @@ def check_gemm(got_bits, ref64, refabs, K, what):
     nrm = np.linalg.norm(diff) / max(np.linalg.norm(ref64), 1e-300)
     assert nrm < 3e-3, "%s: normwise error %g" % (what, nrm)
     return nrm
+
+
+def penalty_terms(bits, pen):
+    v = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return (np.abs(v) / (pen[0] + pen[1])) ** pen[2]
+
+
+def check_penalty(S, got_bits, ref_bits, Sref, pen, strict, what="penalty"):
+    """Penalty parity.  strict: |S - Sref| <= 1e-4 Sref, the bar for the paper's setting on
+    workload-like tensors.  On tiny tensors the sum is carried by a handful of elements, and a
+    stored value may legitimately differ from the oracle's by one bf16 ulp when the exact result
+    sits at a rounding boundary (fp32 vs fp64 arithmetic in front of the rounding; each such
+    element was already accepted by check_gemm).  There the bar is 1e-4 Sref plus the change
+    those elements alone explain; anything the fused reduction itself got wrong is far larger."""
+    tol = 1e-4 * Sref
+    if not strict:
+        flip = got_bits != ref_bits
+        tol += np.abs(penalty_terms(got_bits[flip], pen) - penalty_terms(ref_bits[flip], pen)).sum()
+    assert abs(S - Sref) <= tol, "%s: S=%r Sref=%r rel=%g" % (what, S, Sref, (S - Sref) / Sref)
+    # the fused reduction agrees with the tensor the kernel stored (a property, not parity)
+    S_self = penalty_terms(got_bits, pen).sum()
+    assert abs(S - S_self) <= 2e-6 * S_self, (S, S_self)
