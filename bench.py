@@ -19,6 +19,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 WORKLOADS = {"single": 0, "gpt2": 1, "vit": 2, "llama": 3}
+PROFILE_TRAFFIC = os.path.join(ROOT, "profiles", "fp8_gemm_llama_block_pmc_traffic.txt")
 FP8_PEAK_TFLOPS = 5000.0   # MI355X dense FP8 MFMA
 INT8_PEAK_TOPS = 5000.0
 HBM_PEAK_GBS = 8000.0
@@ -186,6 +187,17 @@ def cpu_baseline(synth, cfg, host=None, target_s=5.0):
                       % (g.name, r, rn, rows_q, t_gemm, t_cast)}
 
 
+def profiled_traffic(workload):
+    """HBM-side bytes per GEMM launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs of this command, scaled by a plain copy); only known for the default workload."""
+    if workload != "llama" or not os.path.exists(PROFILE_TRAFFIC):
+        return None
+    for line in open(PROFILE_TRAFFIC):
+        if line.startswith("gemm_traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -258,9 +270,14 @@ def main():
                    "gemms": ["%s %dx%dx%d" % (L.name, L.M, L.K, L.N) for L in layers],
                    "flop_per_step": step_flops, "penalty": "tau=3 p=4 eps=1e-6, fused",
                    "tile": a.tile},
-        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel (fp8 fwd/dgrad/wgrad)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_nt_stream_kernel (fp8 fwd/dgrad/wgrad)",
                      "achieved": round(gemm_tflops, 2), "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(gemm_tflops / FP8_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(gemm_tflops / FP8_PEAK_TFLOPS, 4),
+                     "traffic": profiled_traffic(a.workload) if a.tile == 0 else None,
+                     "algorithmic_bytes_per_launch": round(
+                         sum((L.M * L.K + L.N * L.K + 2 * L.M * L.N) + (L.M * L.N + L.N * L.K + 2 * L.M * L.K)
+                             + (L.M * L.N + L.M * L.K + 2 * L.N * L.K) for L in layers) / (3.0 * len(layers))),
+                     "flop_per_launch": round(step_flops / (3.0 * len(layers))),
                      "avg_launch_us": round(gemm_ms * 1e3 / n_gemm_launches, 2),
                      "launches": n_gemm_launches},
         "pct_of_fp8_peak_end_to_end": round(100.0 * value / FP8_PEAK_TFLOPS, 2),
