@@ -15,8 +15,9 @@ constexpr int64_t kMaxDim = (int64_t)1 << 30;
 
 inline bool dims_ok(int64_t M, int64_t N, int64_t K)
 {
-    return M > 0 && N > 0 && K > 0 && M <= kMaxDim && N <= kMaxDim && K <= ((int64_t)1 << 24) &&
-           M * N < ((int64_t)1 << 40);
+    // N <= 2^24 and K <= 2^24 keep the kernels' 32-bit row offsets (up to 256 rows) in range
+    return M > 0 && N > 0 && K > 0 && M <= kMaxDim && N <= ((int64_t)1 << 24) &&
+           K <= ((int64_t)1 << 24) && M * N < ((int64_t)1 << 40);
 }
 
 // upper bound on the number of GEMM workgroups for any tile shape

@@ -88,14 +88,25 @@ struct EpiLayout {
     static constexpr int LPR = T::TN / 8;       // lanes per row when reading back
     static constexpr int ROWS_PER_PASS = kWave / LPR;
     static constexpr int PASSES = 32 / ROWS_PER_PASS;
-    static_assert(WAVE_BYTES * (T::THREADS / kWave) <= T::LDS_BYTES, "epilogue staging fits in LDS");
+    // bf16 staging (no residual): half the bytes, so two bands fit and band i+1 can be written
+    // while band i is still being read back
+    static constexpr int ROW2_BYTES = T::TN * 2 + 16;
+    static constexpr int BAND2_BYTES = 32 * ROW2_BYTES;
+    static_assert(2 * BAND2_BYTES <= WAVE_BYTES + 1024, "bf16 double buffer fits the slice (with slack)");
+    static constexpr int SLICE_BYTES = WAVE_BYTES > 2 * BAND2_BYTES ? WAVE_BYTES : 2 * BAND2_BYTES;
+    static_assert(SLICE_BYTES * (T::THREADS / kWave) <= T::LDS_BYTES, "epilogue staging fits in LDS");
 };
 
-// PMODE: 0 = no penalty, 4 = p == 4 (the paper's setting), -1 = any other integer p.
-template <typename T, bool INT8, int PMODE, typename ACC>
+// Specialisations: PMODE 4 (p == 4, the paper's setting), 0 (no penalty) or -1 (p read at run
+// time); RES 1 / 0 (residual present / absent) or -1 (tested at run time); INTERIOR true when the
+// whole tile lies inside the matrix, so that no store needs a predicate.  The interior
+// specialisations are straight-line code per band: a predicate or a run-time test per pass
+// would cut the code into one basic block per pass and chain sixteen LDS round trips.
+template <typename T, bool INT8, int PMODE, int RES, bool INTERIOR, typename ACC, typename HOOK>
 __device__ __forceinline__ void epilogue_impl(const GemmDev &g, ACC (&acc)[T::MT][T::NT],
                                               uint8_t *smem, int tm, int tn, int wm, int wn,
-                                              int lane, int wave, int tid, int partial_index)
+                                              int lane, int wave, int tid, int partial_index,
+                                              HOOK &band_hook)
 {
     using E = EpiLayout<T>;
     const int l31 = lane & 31, lh = lane >> 5;
@@ -105,15 +116,66 @@ __device__ __forceinline__ void epilogue_impl(const GemmDev &g, ACC (&acc)[T::MT
     else
         alpha = (*g.s0) * (*g.s1);
     float pen = 0.0f;
-    uint8_t *stage = smem + wave * E::WAVE_BYTES;
+    uint8_t *stage = smem + wave * E::SLICE_BYTES;
     uint8_t *wr = stage + l31 * E::ROW_BYTES + lh * 16;
     const int rd_row = lane / E::LPR, rd_seg = lane % E::LPR;
     const uint8_t *rd = stage + rd_row * E::ROW_BYTES + rd_seg * 32;
-    const int n = tn * T::BN + wn * T::TN + rd_seg * 8;
-    const bool n_ok = n < g.N;
-    const bool has_res = g.residual != nullptr;
+    // addressing: a uniform base per (band, pass) plus one 32-bit byte offset per lane
+    const int m0 = tm * T::BM + wm * T::TM, n0 = tn * T::BN + wn * T::TN;
+    const uint32_t lane_off = ((uint32_t)rd_row * (uint32_t)g.N + (uint32_t)rd_seg * 8u) * 2u;
+    const int64_t base_off = ((int64_t)m0 * g.N + n0) * 2;
+    uint8_t *out_base = (uint8_t *)g.out + base_off;
+    const uint8_t *res_base = (const uint8_t *)g.residual + base_off;
+    const int rows_left = g.M - m0 - rd_row;  // row r of the sub-tile is valid for this lane if r < rows_left
+    const bool n_ok = n0 + rd_seg * 8 < g.N;
+    const bool has_res = RES < 0 ? g.residual != nullptr : RES != 0;
+    const bool has_pen = PMODE < 0 ? g.p != 0 : PMODE != 0;
+    if constexpr (RES == 0 && INTERIOR && PMODE >= 0) {
+        // Fast path: round to bf16 in the MFMA layout, stage packed values (half the LDS bytes),
+        // two bands in flight.
+        uint8_t *wr2 = stage + l31 * E::ROW2_BYTES + lh * 8;
+        const uint8_t *rd2 = stage + rd_row * E::ROW2_BYTES + rd_seg * 16;
+        auto write_band = [&](int i) {
+#pragma unroll
+            for (int j = 0; j < T::NT; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint2 pk = make_uint2(pack_bf16x2((float)acc[i][j][4 * q + 0] * alpha,
+                                                            (float)acc[i][j][4 * q + 1] * alpha),
+                                                pack_bf16x2((float)acc[i][j][4 * q + 2] * alpha,
+                                                            (float)acc[i][j][4 * q + 3] * alpha));
+                    *(uint2 *)(wr2 + (i & 1) * E::BAND2_BYTES + j * 64 + q * 16) = pk;
+                }
+        };
+        write_band(0);
+#pragma unroll
+        for (int i = 0; i < T::MT; ++i) {
+            band_hook(i);
+            if (i + 1 < T::MT)
+                write_band(i + 1);
+#pragma unroll
+            for (int ps = 0; ps < E::PASSES; ++ps) {
+                const uint4 packed = *(const uint4 *)(rd2 + (i & 1) * E::BAND2_BYTES +
+                                                      ps * E::ROWS_PER_PASS * E::ROW2_BYTES);
+                const int64_t row_off = (int64_t)(i * 32 + ps * E::ROWS_PER_PASS) * g.N * 2;
+                *(uint4 *)(out_base + row_off + lane_off) = packed;
+                if constexpr (PMODE == 4) {
+                    const float t[8] = {bf16lo_to_f32(packed.x), bf16hi_to_f32(packed.x),
+                                        bf16lo_to_f32(packed.y), bf16hi_to_f32(packed.y),
+                                        bf16lo_to_f32(packed.z), bf16hi_to_f32(packed.z),
+                                        bf16lo_to_f32(packed.w), bf16hi_to_f32(packed.w)};
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) {
+                        const float a2 = t[r] * t[r];
+                        pen = __builtin_fmaf(a2, a2, pen);
+                    }
+                }
+            }
+        }
+    } else {
 #pragma unroll
     for (int i = 0; i < T::MT; ++i) {
+        band_hook(i);  // the caller's work to spread over the bands (e.g. next tile's DMA issue)
 #pragma unroll
         for (int j = 0; j < T::NT; ++j)
 #pragma unroll
@@ -129,12 +191,12 @@ __device__ __forceinline__ void epilogue_impl(const GemmDev &g, ACC (&acc)[T::MT
         for (int ps = 0; ps < E::PASSES; ++ps) {
             const v4f lo = *(const v4f *)(rd + ps * E::ROWS_PER_PASS * E::ROW_BYTES);
             const v4f hi = *(const v4f *)(rd + ps * E::ROWS_PER_PASS * E::ROW_BYTES + 16);
-            const int m = tm * T::BM + wm * T::TM + i * 32 + ps * E::ROWS_PER_PASS + rd_row;
-            if (m < g.M && n_ok) {
-                const int64_t o = (int64_t)m * g.N + n;
+            const int row_u = i * 32 + ps * E::ROWS_PER_PASS;  // uniform row of this pass
+            if (INTERIOR || (row_u < rows_left && n_ok)) {
+                const int64_t row_off = (int64_t)row_u * g.N * 2;
                 float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                 if (has_res) {
-                    const uint4 rr = *(const uint4 *)(g.residual + o);
+                    const uint4 rr = *(const uint4 *)(res_base + row_off + lane_off);
                     v[0] += bf16lo_to_f32(rr.x);
                     v[1] += bf16hi_to_f32(rr.x);
                     v[2] += bf16lo_to_f32(rr.y);
@@ -146,19 +208,20 @@ __device__ __forceinline__ void epilogue_impl(const GemmDev &g, ACC (&acc)[T::MT
                 }
                 const uint4 packed = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
                                                 pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
-                *(uint4 *)(g.out + o) = packed;
-                if constexpr (PMODE != 0) {
+                *(uint4 *)(out_base + row_off + lane_off) = packed;
+                if (has_pen) {
                     const float t[8] = {bf16lo_to_f32(packed.x), bf16hi_to_f32(packed.x),
                                         bf16lo_to_f32(packed.y), bf16hi_to_f32(packed.y),
                                         bf16lo_to_f32(packed.z), bf16hi_to_f32(packed.z),
                                         bf16lo_to_f32(packed.w), bf16hi_to_f32(packed.w)};
 #pragma unroll
                     for (int r = 0; r < 8; ++r) {
-                        const float u = __builtin_fabsf(t[r]) * g.inv_tau;
                         if constexpr (PMODE == 4) {
-                            const float u2 = u * u;
-                            pen = __builtin_fmaf(u2, u2, pen);
+                            // sum a^4 here, times (1/(tau+eps))^4 once per lane below
+                            const float a2 = t[r] * t[r];
+                            pen = __builtin_fmaf(a2, a2, pen);
                         } else {
+                            const float u = __builtin_fabsf(t[r]) * g.inv_tau;
                             float w = u;
                             for (int e = 1; e < g.p; ++e)
                                 w *= u;
@@ -169,8 +232,13 @@ __device__ __forceinline__ void epilogue_impl(const GemmDev &g, ACC (&acc)[T::MT
             }
         }
     }
-    if constexpr (PMODE != 0) {
+    }
+    if (has_pen) {  // uniform over the workgroup
         __shared__ float red[T::THREADS / kWave];
+        if constexpr (PMODE == 4) {
+            const float it2 = g.inv_tau * g.inv_tau;
+            pen *= it2 * it2;
+        }
         pen = wave_reduce_sum(pen);
         if (lane == 0)
             red[wave] = pen;
@@ -185,17 +253,28 @@ __device__ __forceinline__ void epilogue_impl(const GemmDev &g, ACC (&acc)[T::MT
     }
 }
 
-template <typename T, bool INT8, typename ACC>
+struct NoBandHook {
+    __device__ __forceinline__ void operator()(int) const {}
+};
+
+template <typename T, bool INT8, typename ACC, typename HOOK>
 __device__ __forceinline__ void epilogue(const GemmDev &g, ACC (&acc)[T::MT][T::NT], uint8_t *smem,
                                          int tm, int tn, int wm, int wn, int lane, int wave, int tid,
-                                         int partial_index)
+                                         int partial_index, HOOK &band_hook)
 {
-    if (g.p == 4)
-        epilogue_impl<T, INT8, 4>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, partial_index);
-    else if (g.p == 0)
-        epilogue_impl<T, INT8, 0>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, partial_index);
+    const bool interior = (tm + 1) * T::BM <= g.M && (tn + 1) * T::BN <= g.N;
+    const bool res = g.residual != nullptr;
+#define TWEO_EPI(PM, RS, IN) \
+    epilogue_impl<T, INT8, PM, RS, IN>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, partial_index, band_hook)
+    if (interior && g.p == 4 && !res)
+        TWEO_EPI(4, 0, true);
+    else if (interior && g.p == 4)
+        TWEO_EPI(4, 1, true);
+    else if (interior && g.p == 0 && !res)
+        TWEO_EPI(0, 0, true);
     else
-        epilogue_impl<T, INT8, -1>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, partial_index);
+        TWEO_EPI(-1, -1, false);
+#undef TWEO_EPI
 }
 
 template <typename T, bool INT8>
@@ -338,7 +417,8 @@ __global__ __launch_bounds__(T::THREADS) void gemm_nt_kernel(GemmDev g)
     }
 
     // the loop ends with a barrier: every wave is done reading the stages
-    epilogue<T, INT8>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, blockIdx.x);
+    NoBandHook no_hook;
+    epilogue<T, INT8>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, blockIdx.x, no_hook);
 }
 
 // ---------------------------------------------------------------------------
@@ -541,7 +621,8 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_dma_kernel(GemmDev
             tail_step(s + 1, fr[1], fr[0]);
     }
     block_barrier();  // every wave is done reading the stages before they are reused
-    epilogue<T, INT8>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, blockIdx.x);
+    NoBandHook no_hook;
+    epilogue<T, INT8>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, blockIdx.x, no_hook);
 }
 
 // ---------------------------------------------------------------------------
@@ -575,7 +656,8 @@ struct TileS {
     static constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int A_DMA = BM / (8 * NWAVES), B_DMA = BN / (8 * NWAVES);  // per wave per stage
     static constexpr int LOADS = A_DMA + B_DMA;
-    static constexpr int EPI_ROW = TN * 4 + 16, EPI_BYTES = NWAVES * 32 * EPI_ROW;
+    static constexpr int EPI_FP32 = 32 * (TN * 4 + 16), EPI_BF16 = 2 * 32 * (TN * 2 + 16);
+    static constexpr int EPI_BYTES = NWAVES * (EPI_FP32 > EPI_BF16 ? EPI_FP32 : EPI_BF16);
     // stages 0..NS-2 of the next tile are prefetched under the epilogue, which stages its
     // output in the LDS behind them
     static constexpr int EPI_OFFSET = (NS - 1) * STAGE_BYTES;
@@ -698,15 +780,57 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
                 }
             }
     };
-    // one MFMA, then a few LDS reads, ... : reads of the next slab run under this slab's MFMAs
-    auto interleave = [&]() {
-        constexpr int N_MFMA = T::MT * T::NT * (INT8 ? 2 : 1), N_DS = 2 * (T::MT + T::NT);
-        constexpr int DS_PER = (N_DS + N_MFMA - 2) / (N_MFMA - 1);
+
+    // Steady-state slab: MFMA unit k (one 32x32 block), then one piece of the next slab's
+    // fragments, then one piece of the DMA of a later stage, with a scheduling fence after each
+    // unit.  Spreading the DMA instructions over the MFMAs keeps a wave from sitting in the
+    // vector-memory issue queue (a 64 KB stage is 64 KB/clk-limited address work) while the
+    // matrix pipe runs dry.
+    auto issue_piece = [&](int s, int idx) {
+        const uint32_t dst = lds_base + (s % T::NS) * T::STAGE_BYTES + wave * 1024;
 #pragma unroll
-        for (int k = 0; k < N_MFMA; ++k) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, DS_PER, 0);
+        for (int i = 0; i < T::A_DMA; ++i)
+            if (idx == i)
+                dma_load16(dst + i * T::NWAVES * 1024, Ag + (int64_t)s * T::BK, a_voff[i]);
+#pragma unroll
+        for (int i = 0; i < T::B_DMA; ++i)
+            if (idx == T::A_DMA + i)
+                dma_load16(dst + T::A_BYTES + i * T::NWAVES * 1024, Bg + (int64_t)s * T::BK, b_voff[i]);
+    };
+    auto slab_step = [&](const Frag &cur, Frag &nxt, int s_ld, int kk_ld, int dma_stage) {
+        constexpr int UNITS = T::MT * T::NT;
+        constexpr int DMA_PER = (T::LOADS + UNITS - 1) / UNITS;
+        const uint8_t *st = smem + (s_ld % T::NS) * T::STAGE_BYTES;
+#pragma unroll
+        for (int k = 0; k < UNITS; ++k) {
+            const int i = k / T::NT, j = k % T::NT;
+            if constexpr (INT8) {
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.b0[j], cur.a0[i], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.b1[j], cur.a1[i], acc[i][j], 0, 0, 0);
+            } else {
+                v8i fa = {cur.a0[i][0], cur.a0[i][1], cur.a0[i][2], cur.a0[i][3],
+                          cur.a1[i][0], cur.a1[i][1], cur.a1[i][2], cur.a1[i][3]};
+                v8i fb = {cur.b0[j][0], cur.b0[j][1], cur.b0[j][2], cur.b0[j][3],
+                          cur.b1[j][0], cur.b1[j][1], cur.b1[j][2], cur.b1[j][3]};
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb, fa, acc[i][j], 0, 0, 0, 0,
+                                                                            0, 0);
+            }
+            if (k < T::MT) {
+                nxt.a0[k] = *(const v4i *)(st + a_frag0 + k * 32 * T::BK + frag_off[kk_ld][0]);
+                nxt.a1[k] = *(const v4i *)(st + a_frag0 + k * 32 * T::BK + frag_off[kk_ld][1]);
+            } else if (k < T::MT + T::NT) {
+                nxt.b0[k - T::MT] = *(const v4i *)(st + b_frag0 + (k - T::MT) * 32 * T::BK + frag_off[kk_ld][0]);
+                nxt.b1[k - T::MT] = *(const v4i *)(st + b_frag0 + (k - T::MT) * 32 * T::BK + frag_off[kk_ld][1]);
+            }
+            if (dma_stage >= 0) {
+#pragma unroll
+                for (int d = 0; d < DMA_PER; ++d)
+                    if (k * DMA_PER + d < T::LOADS)
+                        issue_piece(dma_stage, k * DMA_PER + d);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
+        static_assert(T::MT + T::NT <= UNITS, "fragment pieces fit in the MFMA units of a slab");
     };
 
     const int kt = g.K / T::BK;
@@ -730,6 +854,12 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
                 for (int v = 0; v < 16; ++v)
                     acc[i][j][v] = 0;
 
+        // coordinates of the next tile: scalar divisions, done here so that they are off the
+        // critical path at the tile boundary
+        int next_tm = 0, next_tn = 0;
+        if (id + G < total)
+            tile_from_id(id + G, g.tiles_m, g.tiles_n, next_tm, next_tn);
+
         // ---- stage 0: nothing to multiply yet.  vmcnt(0) also covers the previous tile's stores.
         wait_vmcnt<0>();
         block_barrier();
@@ -744,13 +874,8 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
             // stage s has landed for every wave; the barrier also frees the buffer of stage s-1
             wait_vmcnt<T::LOADS *(T::NS - 2)>();
             block_barrier();
-            issue_stage(s + T::NS - 1);
-            load_frags(fr[0], s, 0);
-            mfma_slab(fr[1]);
-            interleave();
-            load_frags(fr[1], s, 1);
-            mfma_slab(fr[0]);
-            interleave();
+            slab_step(fr[1], fr[0], s, 0, s + T::NS - 1);
+            slab_step(fr[0], fr[1], s, 1, -1);
         }
         // ---- tail stages: nothing left to issue
         for (; s < kt; ++s) {
@@ -768,15 +893,29 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
         block_barrier();
         const int cur_tm = tm, cur_tn = tn, cur_id = id;
         id += G;
-        if (id < total) {
-            tile_from_id(id, g.tiles_m, g.tiles_n, tm, tn);
+        const bool have_next = id < total;
+        if (have_next) {
+            tm = next_tm;
+            tn = next_tn;
             set_tile(tm, tn);
-#pragma unroll
-            for (int s2 = 0; s2 < T::NS - 1; ++s2)
-                if (s2 < kt)
-                    issue_stage(s2);
         }
-        epilogue<T, INT8>(g, acc, smem + T::EPI_OFFSET, cur_tm, cur_tn, wm, wn, lane, wave, tid, cur_id);
+        // the next tile's first stage(s) are issued piecewise, one share per epilogue band, so
+        // that no wave queues up behind 64 KB of address work before it can start its epilogue
+        auto prefetch_hook = [&](int band) {
+            if (have_next) {
+                constexpr int PER_BAND = (T::LOADS + T::MT - 1) / T::MT;
+#pragma unroll
+                for (int s2 = 0; s2 < T::NS - 1; ++s2)
+                    if (s2 < kt) {
+#pragma unroll
+                        for (int d = 0; d < PER_BAND; ++d)
+                            if (band * PER_BAND + d < T::LOADS)
+                                issue_piece(s2, band * PER_BAND + d);
+                    }
+            }
+        };
+        epilogue<T, INT8>(g, acc, smem + T::EPI_OFFSET, cur_tm, cur_tn, wm, wn, lane, wave, tid, cur_id,
+                          prefetch_hook);
     }
 }
 
