@@ -20,7 +20,8 @@ inline bool dims_ok(int64_t M, int64_t N, int64_t K)
            K <= ((int64_t)1 << 24) && M * N < ((int64_t)1 << 40);
 }
 
-// upper bound on the number of GEMM workgroups for any tile shape
+// upper bound on the number of penalty partials for any kernel (one per workgroup of the tiled
+// kernels, whose tiles are at least 64x64; the persistent kernels write fewer)
 inline size_t partial_slots(int64_t M, int64_t N) { return (size_t)(((M + 63) / 64) * ((N + 63) / 64)); }
 
 tweo_status check_penalty(const tweo_penalty_cfg *pen, double *penalty_sum, float &inv_tau, int &p)
@@ -138,8 +139,7 @@ tweo_status tweo_fp8_linear_fwd(const uint8_t *xq, const float *sx_inv, const ui
     if (e != hipSuccess)
         return TWEO_ERR_HIP;
     if (p != 0)
-        e = launch_penalty_finish((const float *)workspace, fp8_gemm_workgroups(M, N, K),
-                                  penalty_sum, s);
+        e = launch_penalty_finish((const float *)workspace, fp8_gemm_partials(a), penalty_sum, s);
     return hip_status(e);
 }
 

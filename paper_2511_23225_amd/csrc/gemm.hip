@@ -15,8 +15,8 @@
 // eight 16-byte chunks whose position is XOR-swizzled with the row number so
 // that the 16-byte-per-lane fragment reads of 32 different rows spread over
 // all banks.
-#include "kernels.h"
-#include "device_utils.h"
+#include "gemm_common.h"
+#include "gemm_defer.h"
 
 namespace tweo {
 
@@ -39,18 +39,6 @@ struct Tile {
     static_assert((BM * 8) % THREADS == 0 && (BN * 8) % THREADS == 0, "loader split");
 };
 
-struct GemmDev {
-    const uint8_t *A, *B;
-    int M, N, K;
-    const float *s0, *s1;
-    float alpha;
-    const uint16_t *residual;
-    uint16_t *out;
-    float inv_tau;
-    int p;
-    float *partials;
-    int tiles_m, tiles_n;
-};
 
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give
 // every XCD a contiguous run of tile ids, and walk tile ids in groups of 8 tile
@@ -449,27 +437,6 @@ struct TileD {
     static_assert(NS >= 3 && LOADS * (NS - 2) < 64, "vmcnt range");
 };
 
-// One 16-byte-per-lane DMA load: LDS[m0 + lane*16 ..] = global[base + voff ..].
-__device__ __forceinline__ void dma_load16(uint32_t lds_addr, const uint8_t *base, uint32_t voff)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(base)
-                 : "memory", "m0");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
-__device__ __forceinline__ void block_barrier()
-{
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
 
 template <typename T, bool INT8>
 __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_dma_kernel(GemmDev g)
@@ -669,17 +636,6 @@ struct TileS {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS capacity");
 };
 
-// raster of tile ids: groups of 8 tile rows, column-major inside a group
-__device__ __forceinline__ void tile_from_id(int id, int tiles_m, int tiles_n, int &tm, int &tn)
-{
-    constexpr int GROUP = 8;
-    const int width = GROUP * tiles_n;
-    const int group = id / width, first_m = group * GROUP;
-    const int gsz = (tiles_m - first_m) < GROUP ? (tiles_m - first_m) : GROUP;
-    const int in_group = id - group * width;
-    tm = first_m + in_group % gsz;
-    tn = in_group / gsz;
-}
 
 template <typename T, bool INT8>
 __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(GemmDev g)
@@ -1037,11 +993,12 @@ static int g_tile_override = 0;
 void set_gemm_tile_override(int variant) { g_tile_override = variant; }
 
 // Kernel variants.  1-4: register-staged kernel (any K % 16 == 0), tiles 256x256, 256x128,
-// 128x128, 64x64.  5-8: DMA-pipelined kernel (K % 64 == 0): 256x256 with 4 waves, 256x256 with
-// 8 waves, 256x128, 128x128.
-constexpr int kNumVariants = 14;
-static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256, 256, 128, 256, 128, 256, 256, 128, 192};
-static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128, 256};
+// 128x128, 64x64.  5-10: DMA-pipelined kernel (K % 64 == 0).  11-14: persistent streaming kernel
+// (K % 128 == 0): 256x256, 256x128, 128x128, 192x256.  15: deferred-epilogue persistent kernel
+// (256x256, four waves; M, N % 256 == 0, K % 128 == 0, K >= 512).
+constexpr int kNumVariants = 15;
+static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256, 256, 128, 256, 128, 256, 256, 128, 192, 256};
+static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128, 256, 256};
 int gemm_num_variants() { return kNumVariants; }
 
 static int num_cus()
@@ -1056,6 +1013,14 @@ static int num_cus()
             n = 256;
     }
     return n;
+}
+
+constexpr int kMaxDeferWorkgroups = 1024;
+static int defer_workgroups(int64_t M, int64_t N)
+{
+    const int64_t tiles = (M / 256) * (N / 256);
+    const int64_t cap = num_cus() < kMaxDeferWorkgroups ? num_cus() : kMaxDeferWorkgroups;
+    return (int)(tiles < cap ? tiles : cap);
 }
 
 static int pick_variant(int64_t M, int64_t N, int64_t K)
@@ -1084,6 +1049,13 @@ static int pick_variant(int64_t M, int64_t N, int64_t K)
             }
             if (c13 < best)
                 v = 13;
+            // The deferred-epilogue kernel wins where tile boundaries are frequent (short K) and
+            // every workgroup owns several tiles to hide epilogues under (measured: +5..15 % at
+            // K <= 2048, level at K = 4096, behind at K >= 5632 where its single wave per SIMD
+            // has nothing to cover the operand-stream waits with).
+            if (v == 11 && M % 256 == 0 && N % 256 == 0 && K % 128 == 0 && K >= 512 && K <= 2560 &&
+                tiles(256, 256) >= 2 * (int64_t)cus)
+                v = 15;
         }
     }
     if (v >= 11 && K % 128 != 0)  // streaming kernel needs whole 128-byte stages
@@ -1093,10 +1065,28 @@ static int pick_variant(int64_t M, int64_t N, int64_t K)
     return v;
 }
 
-int fp8_gemm_workgroups(int64_t M, int64_t N, int64_t K)
+// The deferred-epilogue kernel covers whole 256x256 tiles, K in whole stages with enough of
+// them to drain a tile under, no residual, p in {0, 4}.
+static bool defer_ok(const GemmArgs &a)
 {
-    const int v = pick_variant(M, N, K);
-    return (int)(((M + kVariantBM[v] - 1) / kVariantBM[v]) * ((N + kVariantBN[v] - 1) / kVariantBN[v]));
+    return a.M % 256 == 0 && a.N % 256 == 0 && a.K % 128 == 0 && a.K >= 512 && a.residual == nullptr &&
+           (a.p == 0 || a.p == 4) && a.N <= ((int64_t)1 << 22);
+}
+
+static int resolve_variant(const GemmArgs &a)
+{
+    int v = pick_variant(a.M, a.N, a.K);
+    if (v == 15 && !defer_ok(a))
+        v = 11;
+    return v;
+}
+
+int fp8_gemm_partials(const GemmArgs &a)
+{
+    const int v = resolve_variant(a);
+    if (v == 15)  // one partial per wave of each workgroup (never more than per 64x64 block)
+        return defer_workgroups(a.M, a.N) * DeferTile::PARTIALS_PER_WG;
+    return (int)(((a.M + kVariantBM[v] - 1) / kVariantBM[v]) * ((a.N + kVariantBN[v] - 1) / kVariantBN[v]));
 }
 
 template <typename T, bool INT8, bool DMA>
@@ -1175,10 +1165,52 @@ static hipError_t launch_stream(const GemmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+template <bool INT8, int PMODE, int UPS>
+static hipError_t launch_defer_inst(const GemmArgs &a, hipStream_t s)
+{
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_defer_kernel<INT8, PMODE, UPS>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, DeferTile::LDS_BYTES);
+        if (e != hipSuccess)
+            return e;
+        attr_done = true;
+    }
+    GemmDev g;
+    g.A = a.A;
+    g.B = a.B;
+    g.M = (int)a.M;
+    g.N = (int)a.N;
+    g.K = (int)a.K;
+    g.s0 = a.s0;
+    g.s1 = a.s1;
+    g.alpha = a.alpha;
+    g.residual = nullptr;
+    g.out = (uint16_t *)a.out;
+    g.inv_tau = a.inv_tau;
+    g.p = a.p;
+    g.partials = a.partials;
+    g.tiles_m = (int)(a.M / 256);
+    g.tiles_n = (int)(a.N / 256);
+    const int grid = defer_workgroups(a.M, a.N);
+    hipLaunchKernelGGL((gemm_nt_defer_kernel<INT8, PMODE, UPS>), dim3((unsigned)grid), dim3(DeferTile::THREADS),
+                       DeferTile::LDS_BYTES, s, g);
+    return hipGetLastError();
+}
+
+template <bool INT8>
+static hipError_t launch_defer(const GemmArgs &a, hipStream_t s)
+{
+    const bool one = a.K >= 1024;  // one unit per stage needs 8 stages
+    if (a.p == 4)
+        return one ? launch_defer_inst<INT8, 4, 1>(a, s) : launch_defer_inst<INT8, 4, 2>(a, s);
+    return one ? launch_defer_inst<INT8, 0, 1>(a, s) : launch_defer_inst<INT8, 0, 2>(a, s);
+}
+
 template <bool INT8>
 static hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
-    switch (pick_variant(a.M, a.N, a.K)) {
+    switch (resolve_variant(a)) {
     case 1: return launch_tile<T256x256, INT8, false>(a, s);
     case 2: return launch_tile<T256x128, INT8, false>(a, s);
     case 3: return launch_tile<T128x128, INT8, false>(a, s);
@@ -1192,7 +1224,8 @@ static hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     case 11: return launch_stream<S256x256w8, INT8, 1>(a, s);
     case 12: return launch_stream<S256x128w4, INT8, 1>(a, s);
     case 13: return launch_stream<S128x128w4, INT8, 2>(a, s);
-    default: return launch_stream<S192x256w8, INT8, 1>(a, s);
+    case 14: return launch_stream<S192x256w8, INT8, 1>(a, s);
+    default: return launch_defer<INT8>(a, s);
     }
 }
 

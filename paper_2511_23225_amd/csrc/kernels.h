@@ -32,8 +32,8 @@ struct GemmArgs {
     float *partials;        // one fp32 per workgroup when p != 0
 };
 
-// Number of workgroups (= penalty partials) the FP8 GEMM uses for this shape.
-int fp8_gemm_workgroups(int64_t M, int64_t N, int64_t K);
+// Number of fp32 penalty partials the FP8 GEMM writes for these arguments.
+int fp8_gemm_partials(const GemmArgs &a);
 hipError_t launch_fp8_gemm(const GemmArgs &a, hipStream_t s);
 hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s);
 

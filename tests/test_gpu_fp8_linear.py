@@ -65,6 +65,41 @@ def test_fwd_with_penalty(case, tile):
     check_penalty(S, got, refbf, Sref, PEN, strict=(M, K, N) == (256, 512, 512))
 
 
+# shapes the deferred-epilogue kernel (variant 15) takes: whole 256x256 tiles; K = 512 drains two
+# output units per stage, K >= 1024 one; 272 and 544 tiles give workgroups 2 and 3 tiles on a
+# 256-CU machine, i.e. first tile, tiles drained under their successor, and last tile
+DEFER_CASES = [
+    (0, 0, 512, 1024, 768),
+    (1, 0, 1024, 512, 512),
+    (3, 0, 4352, 1024, 4096),
+    (3, 1, 8192, 1152, 4352),
+    (2, 0, 4352, 640, 4096),
+]
+
+
+@pytest.mark.parametrize("case", DEFER_CASES)
+def test_fwd_deferred_epilogue_kernel(case):
+    cfg, gi, M, K, N = case
+    say("fwd deferred cfg=%d gemm=%d M=%d K=%d N=%d" % (cfg, gi, M, K, N))
+    x, w, _ = synth.fp8_linear_inputs(cfg, gi, M=M, K=K, N=N)
+    xq, _, sxi = oracle_quantized(x)
+    wq, _, swi = oracle_quantized(w)
+    ref, refabs, refbf = oracle.fp8_linear_fwd(xq, wq, sxi, swi)
+    outs = []
+    for pen in (PEN, None):
+        tw.tweo_set_gemm_tile(15)
+        try:
+            got, S = run_fwd(xq, wq, sxi, swi, M, N, K, pen=pen)
+        finally:
+            tw.tweo_set_gemm_tile(0)
+        check_gemm(got, ref, refabs, K, "fwd")
+        if pen:
+            Sref = oracle.penalty_sum(refbf, *PEN)
+            check_penalty(S, got, refbf, Sref, PEN, strict=M * N >= 1 << 20)
+        outs.append(got)
+    assert np.array_equal(outs[0], outs[1])  # the penalty does not change the stored output
+
+
 def test_fwd_residual_is_block_output():
     # y = x + f(x): the penalised tensor is the block output (Sec. 3.3)
     cfg, gi, M, K, N = 1, 3, 384, 1024, 256
@@ -120,8 +155,9 @@ def test_penalty_printed_regimes_through_the_gemm():
         assert abs(S / (M * N) - printed) <= 1e-6 * printed
 
 
-@pytest.mark.parametrize("tile", [0, 1, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14])
-@pytest.mark.parametrize("case", [(0, 0, 256, 512, 512), (1, 1, 208, 256, 144), (3, 0, 144, 640, 400)])
+@pytest.mark.parametrize("tile", [0, 1, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15])
+@pytest.mark.parametrize("case", [(0, 0, 256, 512, 512), (1, 1, 208, 256, 144), (3, 0, 144, 640, 400),
+                                  (3, 0, 1024, 512, 768)])
 def test_bwd(case, tile):
     cfg, gi, M, K, N = case
     say("bwd cfg=%d M=%d K=%d N=%d tile=%d" % (cfg, M, K, N, tile))

@@ -43,6 +43,27 @@ def test_w8a8_bit_exact(shape, tile):
     assert np.array_equal(bf16_bits(y), want)
 
 
+@pytest.mark.parametrize("shape", [(512, 1024, 768), (1024, 512, 512), (4352, 1024, 4096)])
+def test_w8a8_deferred_epilogue_kernel_bit_exact(shape):
+    # whole 256x256 tiles: the shapes the deferred-epilogue kernel (variant 15) takes; the last
+    # one gives some workgroups two tiles on a 256-CU machine
+    M, K, N = shape
+    say("w8a8 deferred M=%d K=%d N=%d" % (M, K, N))
+    x, w = synth.w8a8_inputs(0, M, K=K, N=N)
+    ax, aw = oracle.amax_bf16(x), oracle.amax_bf16(w)
+    inv_x, inv_w = np.float32(127.0) / ax, np.float32(127.0) / aw
+    alpha = (ax / np.float32(127.0)) * (aw / np.float32(127.0))
+    oxq, owq = oracle.quantize_i8(x, inv_x), oracle.quantize_i8(w, inv_w)
+    y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)  # poisoned
+    tw.tweo_set_gemm_tile(15)
+    try:
+        tw.tweo_w8a8_linear(to_dev(oxq), to_dev(owq), alpha, y, workspace(tw.TWEO_OP_W8A8_LINEAR, M, N, K))
+        torch.cuda.synchronize()
+    finally:
+        tw.tweo_set_gemm_tile(0)
+    assert np.array_equal(bf16_bits(y), oracle.w8a8_linear(oxq, owq, alpha))
+
+
 def test_w8a8_extreme_accumulators():
     # +-127 everywhere: |acc| = 127*127*K exceeds 2^24, exercising the int32 -> fp32 rounding
     M, K, N = 64, 11008, 128
