@@ -207,6 +207,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--tile", type=int, default=0, help="force a GEMM kernel variant (0 = heuristic)")
+    ap.add_argument("--stream-k", action="store_true",
+                    help="switch the K-split of partial last rounds of tiles on")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of 256 MiB (for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
@@ -240,6 +242,7 @@ def main():
     layers = [Layer(tw, torch, synth, cfg, gi, dev) for gi in range(len(synth.CONFIGS[cfg]["gemms"]))]
     log("inputs generated and uploaded in %.1f s" % (time.perf_counter() - t0))
     tw.tweo_set_gemm_tile(a.tile)
+    tw.tweo_set_stream_k(a.stream_k)
     step_flops = sum(L.flops for L in layers)
     host0 = layers[0].host
     for L in layers:
@@ -256,6 +259,14 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / a.steps
     gemm_ms = ev.total_ms()
+    # per-call detail on stderr: the event pairs alternate forward, backward per layer
+    for li, L in enumerate(layers):
+        f = [s.elapsed_time(e) for k, (s, e) in enumerate(ev.pairs) if k % (2 * len(layers)) == 2 * li]
+        b = [s.elapsed_time(e) for k, (s, e) in enumerate(ev.pairs) if k % (2 * len(layers)) == 2 * li + 1]
+        fl = 2.0 * L.M * L.N * L.K
+        log("  %-5s fwd %7.1f us %6.0f TFLOP/s   bwd (dgrad+wgrad) %7.1f us %6.0f TFLOP/s" % (
+            L.name, 1e3 * sum(f) / len(f), fl / (sum(f) / len(f)) / 1e9,
+            1e3 * sum(b) / len(b), 2 * fl / (sum(b) / len(b)) / 1e9))
     n_gemm_launches = a.steps * len(layers) * 3
     value = step_flops / (ms_per_step * 1e-3) / 1e12
     gemm_tflops = ev.flops / (gemm_ms * 1e-3) / 1e12

@@ -55,9 +55,17 @@ enum {
     TWEO_OP_FP8_LINEAR_BWD_BF16 = 4
 };
 
-/* Bytes of device workspace the given operation needs for these sizes (a
+/* Bytes of device workspace the given operation can use for these sizes (a
  * multiple of 256; never 0).  The workspace needs no initialisation and may be
- * reused by the next call on the same stream. */
+ * reused by the next call on the same stream.  It has two parts: the TWEO
+ * penalty partial sums of a forward call (a few KB, required whenever a penalty
+ * is asked for: less is TWEO_ERR_WORKSPACE), then - only after
+ * tweo_set_stream_k(1) - scratch that lets a GEMM whose tile count does not fill
+ * the CUs evenly split the K loop of its last tiles over all CUs (two fp32 tiles
+ * per CU, 128 MB on a 256-CU device; only counted when a contraction of the
+ * operation is at least 2048 long).  A caller that passes a workspace without
+ * the second part gets the same results up to the fp32 summation order, from
+ * the plain schedule. */
 size_t tweo_workspace_bytes(int op, int64_t M, int64_t N, int64_t K);
 
 const char *tweo_status_string(tweo_status s);
@@ -190,9 +198,17 @@ tweo_status tweo_fp8_linear_bwd_bf16(const void *dy_bf16, const tweo_fp8_saved *
  * 256x128, 128x128, 192x256.  A variant whose K requirement is not met falls
  * back to the nearest one that fits.  Process-wide, not thread safe.  Results
  * are identical up to the fp32 summation order.  Returns
- * TWEO_ERR_INVALID_ARG for an unknown variant.
+ * TWEO_ERR_INVALID_ARG for an unknown variant.  Variant 15 is the
+ * deferred-epilogue persistent kernel (256x256 tiles, M and N multiples of 256,
+ * K a multiple of 128 and at least 512, no residual, p in {0, 4}); it falls back
+ * to variant 11 otherwise.
  */
 tweo_status tweo_set_gemm_tile(int variant);
+
+/* Switch the K-splitting of a GEMM's last, partial round of tiles (see
+ * tweo_workspace_bytes) on (non-zero) or off (0, the default: on MI355X the
+ * plain schedule measured faster).  Process-wide, not thread safe. */
+tweo_status tweo_set_stream_k(int on);
 
 #ifdef __cplusplus
 }

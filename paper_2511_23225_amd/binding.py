@@ -18,7 +18,8 @@ TWEO_OK, TWEO_ERR_INVALID_ARG, TWEO_ERR_UNSUPPORTED, TWEO_ERR_WORKSPACE, TWEO_ER
 
 EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quantize_e4m3",
            "tweo_fp8_linear_fwd", "tweo_fp8_linear_bwd", "tweo_quantize_i8", "tweo_w8a8_linear",
-           "tweo_fp8_linear_fwd_bf16", "tweo_fp8_linear_bwd_bf16", "tweo_set_gemm_tile")
+           "tweo_fp8_linear_fwd_bf16", "tweo_fp8_linear_bwd_bf16", "tweo_set_gemm_tile",
+           "tweo_set_stream_k")
 
 
 class TweoError(RuntimeError):
@@ -66,6 +67,7 @@ def load():
     L.tweo_fp8_linear_bwd_bf16.argtypes = [vp, ctypes.POINTER(Fp8Saved), i64, i64, i64, vp, vp, vp,
                                            vp, vp, sz, vp]
     L.tweo_set_gemm_tile.argtypes = [ctypes.c_int]
+    L.tweo_set_stream_k.argtypes = [ctypes.c_int]
     for name in EXPORTS:
         if name not in ("tweo_workspace_bytes", "tweo_status_string"):
             getattr(L, name).restype = ctypes.c_int
@@ -110,6 +112,10 @@ def tweo_workspace_bytes(op, M, N, K):
 
 def tweo_set_gemm_tile(variant):
     _check(load().tweo_set_gemm_tile(int(variant)), "tweo_set_gemm_tile")
+
+
+def tweo_set_stream_k(on):
+    _check(load().tweo_set_stream_k(1 if on else 0), "tweo_set_stream_k")
 
 
 def tweo_amax(x_bf16, amax_out):

@@ -55,6 +55,12 @@ const char *tweo_status_string(tweo_status s)
     return "unknown status";
 }
 
+tweo_status tweo_set_stream_k(int on)
+{
+    set_stream_k(on != 0);
+    return TWEO_OK;
+}
+
 tweo_status tweo_set_gemm_tile(int variant)
 {
     if (variant < 0 || variant > gemm_num_variants())
@@ -63,19 +69,46 @@ tweo_status tweo_set_gemm_tile(int variant)
     return TWEO_OK;
 }
 
+// Workspace layout: penalty partials (forward only), then the stream-K scratch.  The scratch is
+// asked for only while stream-K is switched on and a contraction is long enough for it to be
+// considered; a caller that passes less simply gets the plain schedule.
+inline size_t penalty_bytes(int64_t M, int64_t N) { return round256(partial_slots(M, N) * sizeof(float)); }
+inline bool stream_k_candidate(int64_t rows, int64_t cols, int64_t contraction)
+{
+    return stream_k_enabled() && contraction >= 2048 && rows >= 256 && cols >= 256;
+}
+
 size_t tweo_workspace_bytes(int op, int64_t M, int64_t N, int64_t K)
 {
-    (void)K;
-    if (M <= 0 || N <= 0)
+    if (M <= 0 || N <= 0 || K <= 0)
         return 256;
     switch (op) {
     case TWEO_OP_FP8_LINEAR_FWD:
     case TWEO_OP_FP8_LINEAR_FWD_BF16:
-        return round256(partial_slots(M, N) * sizeof(float));
+        return penalty_bytes(M, N) + (stream_k_candidate(M, N, K) ? stream_k_workspace_bytes() : 0);
+    case TWEO_OP_FP8_LINEAR_BWD:
+    case TWEO_OP_FP8_LINEAR_BWD_BF16:
+        return 256 + (stream_k_candidate(M, K, N) || stream_k_candidate(N, K, M) ? stream_k_workspace_bytes() : 0);
+    case TWEO_OP_W8A8_LINEAR:
+        return 256 + (stream_k_candidate(M, N, K) ? stream_k_workspace_bytes() : 0);
     default:
         return 256;
     }
 }
+
+namespace {
+// the stream-K part of a caller's workspace that starts `skip` bytes in (or nothing)
+inline void attach_stream_k(GemmArgs &a, void *workspace, size_t workspace_bytes, size_t skip)
+{
+    a.sk_workspace = nullptr;
+    a.sk_workspace_bytes = 0;
+    if (workspace && aligned16(workspace) && ((reinterpret_cast<uintptr_t>(workspace) + skip) & 255u) == 0 &&
+        workspace_bytes > skip) {
+        a.sk_workspace = (uint8_t *)workspace + skip;
+        a.sk_workspace_bytes = workspace_bytes - skip;
+    }
+}
+}  // namespace
 
 tweo_status tweo_amax(const void *x_bf16, int64_t n, float *amax_out, void *stream)
 {
@@ -118,8 +151,7 @@ tweo_status tweo_fp8_linear_fwd(const uint8_t *xq, const float *sx_inv, const ui
     tweo_status st = check_penalty(pen, penalty_sum, inv_tau, p);
     if (st != TWEO_OK)
         return st;
-    if (p != 0 && (!workspace || workspace_bytes < tweo_workspace_bytes(TWEO_OP_FP8_LINEAR_FWD, M, N, K) ||
-                   !aligned16(workspace)))
+    if (p != 0 && (!workspace || workspace_bytes < penalty_bytes(M, N) || !aligned16(workspace)))
         return TWEO_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     GemmArgs a{};
@@ -135,6 +167,7 @@ tweo_status tweo_fp8_linear_fwd(const uint8_t *xq, const float *sx_inv, const ui
     a.inv_tau = inv_tau;
     a.p = p;
     a.partials = (float *)workspace;
+    attach_stream_k(a, workspace, workspace_bytes, penalty_bytes(M, N));
     hipError_t e = launch_fp8_gemm(a, s);
     if (e != hipSuccess)
         return TWEO_ERR_HIP;
@@ -149,8 +182,6 @@ tweo_status tweo_fp8_linear_bwd(const uint8_t *dyq, const uint8_t *dyqT, const f
                                 void *dx_bf16, void *dw_bf16, void *workspace,
                                 size_t workspace_bytes, void *stream)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     if (M <= 0 || N <= 0 || K <= 0 || !sdy_inv || (!dx_bf16 && !dw_bf16))
         return TWEO_ERR_INVALID_ARG;
     if (dx_bf16 && (!dyq || !wqT || !sw_inv || !aligned16(dyq) || !aligned16(wqT) || !aligned16(dx_bf16)))
@@ -171,6 +202,7 @@ tweo_status tweo_fp8_linear_bwd(const uint8_t *dyq, const uint8_t *dyqT, const f
         a.s0 = sdy_inv;
         a.s1 = sw_inv;
         a.out = dx_bf16;
+        attach_stream_k(a, workspace, workspace_bytes, 256);
         hipError_t e = launch_fp8_gemm(a, s);
         if (e != hipSuccess)
             return TWEO_ERR_HIP;
@@ -185,6 +217,7 @@ tweo_status tweo_fp8_linear_bwd(const uint8_t *dyq, const uint8_t *dyqT, const f
         a.s0 = sdy_inv;
         a.s1 = sx_inv;
         a.out = dw_bf16;
+        attach_stream_k(a, workspace, workspace_bytes, 256);
         hipError_t e = launch_fp8_gemm(a, s);
         if (e != hipSuccess)
             return TWEO_ERR_HIP;
@@ -206,8 +239,6 @@ tweo_status tweo_w8a8_linear(const int8_t *xq, const int8_t *wq, int64_t M, int6
                              float alpha, void *y_bf16, void *workspace, size_t workspace_bytes,
                              void *stream)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     if (!xq || !wq || !y_bf16 || M <= 0 || N <= 0 || K <= 0 || !aligned16(xq) || !aligned16(wq) ||
         !aligned16(y_bf16))
         return TWEO_ERR_INVALID_ARG;
@@ -221,6 +252,7 @@ tweo_status tweo_w8a8_linear(const int8_t *xq, const int8_t *wq, int64_t M, int6
     a.K = K;
     a.alpha = alpha;
     a.out = y_bf16;
+    attach_stream_k(a, workspace, workspace_bytes, 256);
     return hip_status(launch_i8_gemm(a, (hipStream_t)stream));
 }
 
@@ -242,7 +274,7 @@ tweo_status tweo_fp8_linear_fwd_bf16(const void *x_bf16, const void *w_bf16,
     tweo_status st = check_penalty(pen, penalty_sum, inv_tau, p);
     if (st != TWEO_OK)
         return st;
-    if (p != 0 && (!workspace || workspace_bytes < tweo_workspace_bytes(TWEO_OP_FP8_LINEAR_FWD_BF16, M, N, K)))
+    if (p != 0 && (!workspace || workspace_bytes < penalty_bytes(M, N)))
         return TWEO_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     float *sc = saved->scalars;

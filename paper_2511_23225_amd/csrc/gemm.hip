@@ -637,7 +637,20 @@ struct TileS {
 };
 
 
-template <typename T, bool INT8>
+//
+// SK ("stream-K"): when the tile count is not a multiple of the workgroup count, the last,
+// partial round would leave CUs idle (176 or 192 tiles of a weight gradient on 256 CUs: a
+// quarter to a third of the machine).  With SK the whole rounds are handed out as before and
+// the K loops of the remaining tiles are cut into one contiguous range of stages per workgroup
+// (cut points snapped away from tile ends).  A workgroup that multiplied only part of a tile's
+// K range writes its fp32 (int32) accumulators to a slot of the workspace and counts itself in
+// on the tile's counter; whoever arrives last adds all slots of the tile in K order - a fixed
+// order, whoever that is - and runs the ordinary epilogue.  Nobody waits for anybody.
+// Measured on MI355X this is slower than leaving the CUs idle (every tile of the split round is
+// finished by a fixup at the very end of the kernel: a burst of device-scope slot traffic with
+// nothing left to hide it under; 192x256 tiles fix the common tile counts instead), so it is
+// off unless tweo_set_stream_k(1) asks for it; the parity tests keep it honest.
+template <typename T, bool INT8, bool SK>
 __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(GemmDev g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -789,19 +802,79 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
         static_assert(T::MT + T::NT <= UNITS, "fragment pieces fit in the MFMA units of a slab");
     };
 
-    const int kt = g.K / T::BK;
+    const int kt_full = g.K / T::BK;
     Frag fr[2];
-    int id = slot;
-    int tm = 0, tn = 0;
-    if (id < total) {
-        tile_from_id(id, g.tiles_m, g.tiles_n, tm, tn);
-        set_tile(tm, tn);
+
+    // ---- work units of this workgroup: whole tiles, then (SK) the segments of its stage range
+    struct Unit {
+        int tm, tn, s0, kt, id, seg;  // kt: stages in the unit; id: tile id; seg: ordinal in the range
+    };
+    const int sk_rounds = SK ? g.sk_full_rounds : 0;
+    const int sk_first = sk_rounds * G;               // first tile id of the remainder
+    const int sk_tiles = SK ? total - sk_first : 0;   // < G
+    // start of workgroup w's range in the remainder's stage space [0, sk_tiles * kt_full)
+    auto sk_bound = [&](int w) -> int64_t {
+        constexpr int SNAP = 4;
+        int64_t x = (int64_t)w * sk_tiles * kt_full / G;
+        const int o = (int)(x % kt_full);
+        if (o < SNAP)
+            x -= o;
+        else if (o > kt_full - SNAP)
+            x += kt_full - o;
+        return x;
+    };
+    int64_t sk_x0 = 0, sk_x1 = 0;
+    if constexpr (SK) {
+        sk_x0 = sk_bound(slot);
+        sk_x1 = sk_bound(slot + 1);
+    }
+    auto get_unit = [&](int u, Unit &U) -> bool {
+        if (!SK || u < sk_rounds) {
+            const int id = slot + u * G;
+            if (id >= (SK ? sk_first : total))
+                return false;
+            tile_from_id(id, g.tiles_m, g.tiles_n, U.tm, U.tn);
+            U.s0 = 0;
+            U.kt = kt_full;
+            U.id = id;
+            U.seg = 0;
+            return true;
+        }
+        int64_t pos = sk_x0;
+        for (int c = 0;; ++c) {
+            if (pos >= sk_x1)
+                return false;
+            const int rt = (int)(pos / kt_full), s0 = (int)(pos % kt_full);
+            const int64_t left = sk_x1 - pos;
+            const int len = left < kt_full - s0 ? (int)left : kt_full - s0;
+            if (c == u - sk_rounds) {
+                U.id = sk_first + rt;
+                tile_from_id(U.id, g.tiles_m, g.tiles_n, U.tm, U.tn);
+                U.s0 = s0;
+                U.kt = len;
+                U.seg = c;
+                return true;
+            }
+            pos += len;
+        }
+    };
+    auto set_unit = [&](const Unit &U) {
+        set_tile(U.tm, U.tn);
+        Ag += (int64_t)U.s0 * T::BK;
+        Bg += (int64_t)U.s0 * T::BK;
+    };
+
+    Unit cur, nxt;
+    int u = 0;
+    bool have = get_unit(0, cur);
+    if (have) {
+        set_unit(cur);
 #pragma unroll
         for (int s = 0; s < T::NS - 1; ++s)
-            if (s < kt)
+            if (s < cur.kt)
                 issue_stage(s);
     }
-    while (id < total) {
+    while (have) {
 #pragma unroll
         for (int i = 0; i < T::MT; ++i)
 #pragma unroll
@@ -810,11 +883,10 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
                 for (int v = 0; v < 16; ++v)
                     acc[i][j][v] = 0;
 
-        // coordinates of the next tile: scalar divisions, done here so that they are off the
-        // critical path at the tile boundary
-        int next_tm = 0, next_tn = 0;
-        if (id + G < total)
-            tile_from_id(id + G, g.tiles_m, g.tiles_n, next_tm, next_tn);
+        // the next unit: scalar divisions, done here so that they are off the critical path at
+        // the unit boundary
+        const bool have_next = get_unit(u + 1, nxt);
+        const int kt = cur.kt;
 
         // ---- stage 0: nothing to multiply yet.  vmcnt(0) also covers the previous tile's stores.
         wait_vmcnt<0>();
@@ -844,25 +916,19 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
         }
         mfma_slab(fr[1]);
 
-        // ---- tile boundary: every wave is done reading the stages; start the next tile's loads,
-        //      then write this tile out (its stores drain under the next tile's MFMAs)
+        // ---- unit boundary: every wave is done reading the stages; start the next unit's loads,
+        //      then write this tile out (its stores drain under the next unit's MFMAs)
         block_barrier();
-        const int cur_tm = tm, cur_tn = tn, cur_id = id;
-        id += G;
-        const bool have_next = id < total;
-        if (have_next) {
-            tm = next_tm;
-            tn = next_tn;
-            set_tile(tm, tn);
-        }
-        // the next tile's first stage(s) are issued piecewise, one share per epilogue band, so
+        if (have_next)
+            set_unit(nxt);
+        // the next unit's first stage(s) are issued piecewise, one share per epilogue band, so
         // that no wave queues up behind 64 KB of address work before it can start its epilogue
         auto prefetch_hook = [&](int band) {
             if (have_next) {
                 constexpr int PER_BAND = (T::LOADS + T::MT - 1) / T::MT;
 #pragma unroll
                 for (int s2 = 0; s2 < T::NS - 1; ++s2)
-                    if (s2 < kt) {
+                    if (s2 < nxt.kt) {
 #pragma unroll
                         for (int d = 0; d < PER_BAND; ++d)
                             if (band * PER_BAND + d < T::LOADS)
@@ -870,8 +936,109 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
                     }
             }
         };
-        epilogue<T, INT8>(g, acc, smem + T::EPI_OFFSET, cur_tm, cur_tn, wm, wn, lane, wave, tid, cur_id,
-                          prefetch_hook);
+        bool whole = true;
+        if constexpr (SK)
+            whole = cur.s0 == 0 && cur.kt == kt_full;
+        if (whole) {
+            epilogue<T, INT8>(g, acc, smem + T::EPI_OFFSET, cur.tm, cur.tn, wm, wn, lane, wave, tid, cur.id,
+                              prefetch_hook);
+        } else {
+            __shared__ int sk_arrival;
+            using word_t = typename std::conditional<INT8, int, float>::type;
+            constexpr int SLOT_WORDS = T::BM * T::BN;
+#pragma unroll
+            for (int b = 0; b < T::MT; ++b)
+                prefetch_hook(b);
+            // This workgroup's slot: 2 per workgroup (first / later segment of its range); pairs
+            // of accumulator words, layout [wave][block][pair][lane], every store 512 B contiguous.
+            // The slots are written and read with device-scope (cache-bypassing) accesses: the
+            // workgroups of a tile may sit behind different L2s, and a fence that writes back and
+            // invalidates a whole L2 would throw away the operand panels its 32 CUs share.
+            typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+            constexpr int kDeviceScope = 16;  // cache policy bit sc1: performed at device scope
+            constexpr uint32_t SLOT_BYTES = (uint32_t)SLOT_WORDS * 4;
+            auto slot_rsrc = [&](int w, int later) {
+                return __builtin_amdgcn_make_buffer_rsrc(
+                    (uint8_t *)g.sk_partials + (size_t)(2 * w + later) * SLOT_BYTES, 0, (int)SLOT_BYTES, 0x00020000);
+            };
+            const uint32_t lane_off = ((uint32_t)wave * T::MT * T::NT * 4 * kWave + lane) * 16u;
+            {
+                const auto mine = slot_rsrc(slot, cur.seg > 0 ? 1 : 0);
+#pragma unroll
+                for (int i = 0; i < T::MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < T::NT; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const u4 v = {__builtin_bit_cast(uint32_t, (word_t)acc[i][j][4 * q]),
+                                          __builtin_bit_cast(uint32_t, (word_t)acc[i][j][4 * q + 1]),
+                                          __builtin_bit_cast(uint32_t, (word_t)acc[i][j][4 * q + 2]),
+                                          __builtin_bit_cast(uint32_t, (word_t)acc[i][j][4 * q + 3])};
+                            __builtin_amdgcn_raw_buffer_store_b128(v, mine, lane_off + ((i * T::NT + j) * 4 + q) * kWave * 16,
+                                                                   0, kDeviceScope);
+                        }
+            }
+            // pieces of this tile, in K order: the workgroups whose ranges meet its stage interval
+            const int rt = cur.id - sk_first;
+            const int64_t lo = (int64_t)rt * kt_full, hi = lo + kt_full;
+            int w_a = (int)(lo * G / ((int64_t)sk_tiles * kt_full));
+            if (w_a > G - 1)
+                w_a = G - 1;
+            while (w_a > 0 && sk_bound(w_a) > lo)
+                --w_a;
+            while (w_a + 1 < G && sk_bound(w_a + 1) <= lo)
+                ++w_a;
+            int pieces = 0;
+            for (int w = w_a; w < G && sk_bound(w) < hi; ++w)
+                if (sk_bound(w + 1) > sk_bound(w))
+                    ++pieces;
+            // every store of the slot has been acknowledged before the arrival is counted
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            wait_vmcnt<0>();
+            __syncthreads();
+            if (tid == 0)
+                sk_arrival = (int)__hip_atomic_fetch_add(g.sk_counters + rt, 1u, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            const bool last = sk_arrival == pieces - 1;
+            if (last) {
+#pragma unroll
+                for (int i = 0; i < T::MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < T::NT; ++j)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            acc[i][j][v] = 0;
+                for (int w = w_a; w < G && sk_bound(w) < hi; ++w) {
+                    if (sk_bound(w + 1) <= sk_bound(w))
+                        continue;
+                    const auto src = slot_rsrc(w, sk_bound(w) >= lo ? 0 : 1);
+#pragma unroll
+                    for (int i = 0; i < T::MT; ++i) {
+                        u4 v[T::NT][4];  // a band's worth of loads in flight
+#pragma unroll
+                        for (int j = 0; j < T::NT; ++j)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                v[j][q] = __builtin_amdgcn_raw_buffer_load_b128(
+                                    src, lane_off + ((i * T::NT + j) * 4 + q) * kWave * 16, 0, kDeviceScope);
+#pragma unroll
+                        for (int j = 0; j < T::NT; ++j)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                                for (int r = 0; r < 4; ++r)
+                                    acc[i][j][4 * q + r] += __builtin_bit_cast(word_t, v[j][q][r]);
+                    }
+                }
+                NoBandHook no_hook;
+                epilogue<T, INT8>(g, acc, smem + T::EPI_OFFSET, cur.tm, cur.tn, wm, wn, lane, wave, tid, cur.id,
+                                  no_hook);
+            }
+        }
+        cur = nxt;
+        have = have_next;
+        ++u;
     }
 }
 
@@ -989,8 +1156,21 @@ typedef TileS<256, 128, 2, 2, 3, 1> S256x128w4;
 typedef TileS<128, 128, 2, 2, 2, 2> S128x128w4;  // two workgroups per CU
 typedef TileS<192, 256, 2, 4, 2, 2> S192x256w8;  // for tile counts that 256x256 quantises badly
 
+int num_cus_public();
 static int g_tile_override = 0;
+static bool g_stream_k_off = true;  // measured slower than the plain schedule on MI355X: opt-in
 void set_gemm_tile_override(int variant) { g_tile_override = variant; }
+void set_stream_k(bool on) { g_stream_k_off = !on; }
+bool stream_k_enabled() { return !g_stream_k_off; }
+
+// stream-K workspace: arrival counters (one per remainder tile, fewer than workgroups), then two
+// accumulator slots of one tile per workgroup
+constexpr size_t kStreamKCounterBytes = 4096;
+constexpr int kStreamKMaxWorkgroups = 1024;
+size_t stream_k_workspace_bytes()
+{
+    return kStreamKCounterBytes + (size_t)2 * num_cus_public() * 256 * 256 * 4;
+}
 
 // Kernel variants.  1-4: register-staged kernel (any K % 16 == 0), tiles 256x256, 256x128,
 // 128x128, 64x64.  5-10: DMA-pipelined kernel (K % 64 == 0).  11-14: persistent streaming kernel
@@ -1001,6 +1181,8 @@ static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256,
 static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128, 256, 256};
 int gemm_num_variants() { return kNumVariants; }
 
+static int num_cus();
+int num_cus_public() { return num_cus(); }
 static int num_cus()
 {
     static int n = 0;
@@ -1129,12 +1311,31 @@ static hipError_t launch_tile(const GemmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
-template <typename T, bool INT8, int WG_PER_CU>
-static hipError_t launch_stream(const GemmArgs &a, hipStream_t s)
+// Stream-K pays when a tile count leaves a noticeable part of the last round idle and each
+// workgroup's share of the remainder is long enough to amortise a fixup.
+static bool stream_k_plan(int64_t total_tiles, int64_t kt, int grid, const GemmArgs &a, size_t slot_bytes,
+                          int &full_rounds)
+{
+    if (g_stream_k_off || total_tiles <= 0 || grid <= 0)
+        return false;
+    full_rounds = (int)(total_tiles / grid);
+    const int64_t rem = total_tiles % grid;
+    if (rem == 0 || kt < 16 || rem * kt / grid < 16)
+        return false;
+    const int64_t rounds = full_rounds + 1;
+    if ((double)(rounds * grid - total_tiles) / (double)(rounds * grid) < 0.04)
+        return false;
+    const size_t need = kStreamKCounterBytes + (size_t)2 * grid * slot_bytes;
+    return a.sk_workspace != nullptr && a.sk_workspace_bytes >= need &&
+           ((uintptr_t)a.sk_workspace & 255u) == 0;
+}
+
+template <typename T, bool INT8, int WG_PER_CU, bool SK>
+static hipError_t launch_stream_inst(const GemmArgs &a, hipStream_t s, int grid, int full_rounds)
 {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_stream_kernel<T, INT8>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_stream_kernel<T, INT8, SK>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
         if (e != hipSuccess)
             return e;
@@ -1156,13 +1357,36 @@ static hipError_t launch_stream(const GemmArgs &a, hipStream_t s)
     g.partials = a.partials;
     g.tiles_m = (int)((a.M + T::BM - 1) / T::BM);
     g.tiles_n = (int)((a.N + T::BN - 1) / T::BN);
-    const int total = g.tiles_m * g.tiles_n;
-    int grid = num_cus() * WG_PER_CU;
-    if (grid > total)
-        grid = total;
-    hipLaunchKernelGGL((gemm_nt_stream_kernel<T, INT8>), dim3((unsigned)grid), dim3(T::THREADS),
+    g.sk_full_rounds = full_rounds;
+    g.sk_counters = (uint32_t *)a.sk_workspace;
+    g.sk_partials = (uint8_t *)a.sk_workspace + kStreamKCounterBytes;
+    if constexpr (SK) {
+        hipError_t e = launch_fill_u32(g.sk_counters, (int)(kStreamKCounterBytes / 4), 0u, s);
+        if (e != hipSuccess)
+            return e;
+    }
+    hipLaunchKernelGGL((gemm_nt_stream_kernel<T, INT8, SK>), dim3((unsigned)grid), dim3(T::THREADS),
                        T::LDS_BYTES, s, g);
     return hipGetLastError();
+}
+
+template <typename T, bool INT8, int WG_PER_CU>
+static hipError_t launch_stream(const GemmArgs &a, hipStream_t s)
+{
+    const int64_t total = ((a.M + T::BM - 1) / T::BM) * ((a.N + T::BN - 1) / T::BN);
+    int grid = num_cus() * WG_PER_CU;
+    if (grid > total)
+        grid = (int)total;
+    if constexpr (WG_PER_CU == 1) {
+        // stream-K always runs one workgroup on every CU (with fewer tiles than CUs the split
+        // remainder is the whole job)
+        int full_rounds = 0;
+        const int cus = num_cus();
+        if (cus <= kStreamKMaxWorkgroups &&
+            stream_k_plan(total, a.K / T::BK, cus, a, (size_t)T::BM * T::BN * 4, full_rounds))
+            return launch_stream_inst<T, INT8, WG_PER_CU, true>(a, s, cus, full_rounds);
+    }
+    return launch_stream_inst<T, INT8, WG_PER_CU, false>(a, s, grid, 0);
 }
 
 template <bool INT8, int PMODE, int UPS>

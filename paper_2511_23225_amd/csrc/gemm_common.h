@@ -18,6 +18,11 @@ struct GemmDev {
     int p;
     float *partials;
     int tiles_m, tiles_n;
+    // stream-K only: whole rounds of tiles before the split remainder, fp32/int32 accumulator
+    // slots (2 per workgroup, one tile each) and one arrival counter per remainder tile (zeroed)
+    int sk_full_rounds;
+    void *sk_partials;
+    uint32_t *sk_counters;
 };
 
 // raster of tile ids: groups of 8 tile rows, column-major inside a group

@@ -30,12 +30,19 @@ struct GemmArgs {
     float inv_tau;          // 1 / (tau + eps)
     int p;                  // penalty power; 0 = no penalty
     float *partials;        // one fp32 per workgroup when p != 0
+    void *sk_workspace;     // stream-K scratch (256-byte aligned) or nullptr: then no stream-K
+    size_t sk_workspace_bytes;
 };
 
 // Number of fp32 penalty partials the FP8 GEMM writes for these arguments.
 int fp8_gemm_partials(const GemmArgs &a);
 hipError_t launch_fp8_gemm(const GemmArgs &a, hipStream_t s);
 hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s);
+
+// Bytes of stream-K scratch that let every shape use it on this device.
+size_t stream_k_workspace_bytes();
+void set_stream_k(bool on);
+bool stream_k_enabled();
 
 // Tile-shape override for benchmarking sweeps: 0 = heuristic.
 void set_gemm_tile_override(int variant);

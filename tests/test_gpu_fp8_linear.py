@@ -100,6 +100,33 @@ def test_fwd_deferred_epilogue_kernel(case):
     assert np.array_equal(outs[0], outs[1])  # the penalty does not change the stored output
 
 
+@pytest.mark.parametrize("with_residual", [False, True])
+def test_fwd_stream_k_split_of_the_last_round(with_residual):
+    # 64 tiles of 256x256 and a long K on a 256-CU machine: the K loop of every tile is cut over
+    # four workgroups, partial accumulators go through the workspace, the last arrival adds them
+    # in K order and runs the epilogue (scale, residual, bf16, penalty).  Checked on every
+    # element, against the plain schedule, and for run-to-run identity.
+    cfg, gi, M, K, N = 3, 0, 2048, 8192, 2048
+    say("fwd stream-K M=%d K=%d N=%d residual=%s" % (M, K, N, with_residual))
+    x, w, _ = synth.fp8_linear_inputs(cfg, gi, M=M, K=K, N=N)
+    res = synth.residual_input(cfg, gi, M, N) if with_residual else None
+    xq, _, sxi = oracle_quantized(x)
+    wq, _, swi = oracle_quantized(w)
+    ref, refabs, refbf = oracle.fp8_linear_fwd(xq, wq, sxi, swi, residual=res)
+    Sref = oracle.penalty_sum(refbf, *PEN)
+    runs = []
+    for on in (True, True, False):
+        tw.tweo_set_stream_k(on)
+        try:
+            got, S = run_fwd(xq, wq, sxi, swi, M, N, K, residual=res)
+        finally:
+            tw.tweo_set_stream_k(False)
+        check_gemm(got, ref, refabs, K, "fwd stream-K=%s" % on)
+        check_penalty(S, got, refbf, Sref, PEN, strict=True)
+        runs.append((got, S))
+    assert np.array_equal(runs[0][0], runs[1][0]) and runs[0][1] == runs[1][1]  # deterministic
+
+
 def test_fwd_residual_is_block_output():
     # y = x + f(x): the penalised tensor is the block output (Sec. 3.3)
     cfg, gi, M, K, N = 1, 3, 384, 1024, 256

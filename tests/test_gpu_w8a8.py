@@ -64,6 +64,28 @@ def test_w8a8_deferred_epilogue_kernel_bit_exact(shape):
     assert np.array_equal(bf16_bits(y), oracle.w8a8_linear(oxq, owq, alpha))
 
 
+def test_w8a8_stream_k_bit_exact():
+    # 64 tiles, long K, K-split switched on: int32 partial accumulators are added exactly, so the
+    # result is the same bits as the plain schedule's and the oracle's
+    M, K, N = 2048, 8192, 2048
+    say("w8a8 stream-K M=%d K=%d N=%d" % (M, K, N))
+    x, w = synth.w8a8_inputs(0, M, K=K, N=N)
+    ax, aw = oracle.amax_bf16(x), oracle.amax_bf16(w)
+    inv_x, inv_w = np.float32(127.0) / ax, np.float32(127.0) / aw
+    alpha = (ax / np.float32(127.0)) * (aw / np.float32(127.0))
+    oxq, owq = oracle.quantize_i8(x, inv_x), oracle.quantize_i8(w, inv_w)
+    want = oracle.w8a8_linear(oxq, owq, alpha)
+    for on in (True, False):
+        y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)  # poisoned
+        tw.tweo_set_stream_k(on)
+        try:
+            tw.tweo_w8a8_linear(to_dev(oxq), to_dev(owq), alpha, y, workspace(tw.TWEO_OP_W8A8_LINEAR, M, N, K))
+            torch.cuda.synchronize()
+        finally:
+            tw.tweo_set_stream_k(False)
+        assert np.array_equal(bf16_bits(y), want)
+
+
 def test_w8a8_extreme_accumulators():
     # +-127 everywhere: |acc| = 127*127*K exceeds 2^24, exercising the int32 -> fp32 rounding
     M, K, N = 64, 11008, 128
