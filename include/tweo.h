@@ -96,6 +96,38 @@ tweo_status tweo_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, c
                                void *stream);
 
 /*
+ * Delayed scaling, the form of per-tensor scaling the paper trained with
+ * (Sec. 4.3: one scale per tensor, amax history of length 16): the cast of step
+ * t uses scale_t = 448 / max(amax_{t-16} .. amax_{t-1}), fixed before the tensor
+ * is seen, and returns the tensor's own amax to the history, so the tensor is
+ * read once (2 B read + 1 (+1) B written per element, against two reads with
+ * tweo_amax + tweo_quantize_e4m3).  The paper names the history length, not the
+ * reduction over it: the maximum is used.  An empty history (the first call on a
+ * state: pass bootstrap != 0) takes the scale from the tensor's own amax, i.e. a
+ * current-scaling step.  Values beyond the delayed scale's range saturate to
+ * +-448.  Guards on the scale as in tweo_quantize_e4m3.
+ *
+ * The state is TWEO_DELAYED_STATE_WORDS 32-bit words of device memory owned by
+ * the caller, one per scaled tensor; it is the only state of the recipe (copy it
+ * out to checkpoint it).  Word layout: [0..15] amax ring, [16] accumulator (0
+ * between calls), [17] next scale, [18] its inverse, [19] ring position,
+ * [20] entries filled, [21] the scale the last cast used, [22] its inverse -
+ * TWEO_DELAYED_USED_SCALE_INV is the word a GEMM dequantises with.
+ *   tweo_delayed_state_init: clears a state (scales = 1).
+ *   tweo_quantize_e4m3_delayed: x_bf16 [rows, cols] -> q [rows, cols], optional
+ *   qT [cols, rows]; updates the state.  Arguments and errors as
+ *   tweo_quantize_e4m3; state 16-byte aligned.
+ */
+#define TWEO_DELAYED_STATE_WORDS 32
+#define TWEO_DELAYED_NEXT_SCALE 17
+#define TWEO_DELAYED_USED_SCALE 21
+#define TWEO_DELAYED_USED_SCALE_INV 22
+size_t tweo_delayed_state_bytes(void);
+tweo_status tweo_delayed_state_init(void *state, void *stream);
+tweo_status tweo_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
+                                       int bootstrap, uint8_t *q, uint8_t *qT, void *stream);
+
+/*
  * FP8 linear forward with the TWEO penalty fused into the epilogue
  * (Sec. 4.3 for the per-tensor FP8 linear; Sec. 3.3 for the penalty).
  *   acc[m,n] = sum_k dec(xq[m,k]) * dec(wq[n,k])            (fp32 accumulate)
@@ -130,6 +162,22 @@ tweo_status tweo_fp8_linear_bwd(const uint8_t *dyq, const uint8_t *dyqT, const f
                                 const float *sx_inv, int64_t M, int64_t N, int64_t K,
                                 void *dx_bf16, void *dw_bf16, void *workspace,
                                 size_t workspace_bytes, void *stream);
+
+/*
+ * Gradient of the TWEO penalty, added to the incoming output gradient before it
+ * is cast for the backward GEMMs.  Not printed in the paper: it is the
+ * derivative of the loss of Sec. 3.3 (lambda / L * mean (|a| / (tau+eps))^p)
+ * with respect to the penalised activation a:
+ *   out[i] = bf16( dy[i] + g * p * sign(a[i]) * (|a[i]| / (tau+eps))^(p-1) / (tau+eps) ),
+ * g = lambda / (L * numel) chosen by the caller.  fp32 arithmetic.
+ *   dy_bf16, a_bf16, out_bf16 [n] device, 16-byte aligned, n % 8 == 0; out may
+ *   be dy (in place).  sign(0) = 0; a NaN activation gives a NaN gradient.
+ * Errors: TWEO_ERR_INVALID_ARG (null, misaligned, tau <= 0, eps < 0, NaN g),
+ * TWEO_ERR_UNSUPPORTED (n % 8 != 0, p outside 1..8).
+ */
+tweo_status tweo_penalty_grad_inject(const void *dy_bf16, const void *a_bf16, int64_t n,
+                                     const tweo_penalty_cfg *pen, float g, void *out_bf16,
+                                     void *stream);
 
 /*
  * Static per-tensor INT8 quantisation (Sec. 4.4 Eq. 4 with b = 8, Q_8 = 127):

@@ -182,6 +182,51 @@ def penalty_grad(a_bf16, tau=3.0, eps=1e-6, p=4, g=1.0):
     return out
 
 
+class DelayedScaling:
+    """Per-tensor delayed scaling as the paper ran it (Sec. 4.3: amax history of length 16).
+
+    The cast of step t uses 448 / max(amax of steps t-16 .. t-1); the paper names the history
+    length, not the reduction over it (reading: the maximum).  An empty history takes the
+    tensor's own amax (a current-scaling step).  Plain Python around the scalar routines."""
+
+    LENGTH = 16
+
+    def __init__(self):
+        self.history = []          # most recent last, at most LENGTH entries
+        self.next_scale = np.float32(1.0)
+
+    def _max(self):
+        # maximum on the magnitude bit patterns, like amax itself (NaN above Inf above finite)
+        bits = [int(np.float32(a).view(np.uint32)) for a in self.history]
+        return np.uint32(max(bits)).view(np.float32) if bits else np.float32(0.0)
+
+    def cast(self, x_bf16, transpose=True):
+        """-> (q, qT, scale_used, scale_used_inv); appends this tensor's amax to the history."""
+        a = np.float32(amax_bf16(x_bf16))
+        if not self.history:                      # bootstrap
+            self.history.append(a)
+            used, used_inv = scale_from_amax(self._max())
+        else:
+            used = self.next_scale
+            used_inv = np.float32(1.0) / np.float32(used)
+            self.history.append(a)
+        self.history = self.history[-self.LENGTH:]
+        self.next_scale = np.float32(scale_from_amax(self._max())[0])
+        qq, qqT = quantize_e4m3(x_bf16, used, transpose=transpose)
+        return qq, qqT, np.float32(used), np.float32(used_inv)
+
+
+def penalty_grad_inject(dy_bf16, a_bf16, tau=3.0, eps=1e-6, p=4, g=1.0):
+    """dy + d(penalty)/da rounded to bf16, and the unrounded fp64 sums."""
+    dy, a = _c(dy_bf16, np.uint16), _c(a_bf16, np.uint16)
+    assert dy.shape == a.shape
+    out = np.empty(a.shape, np.uint16)
+    exact = np.empty(a.shape, np.float64)
+    lib().orc_penalty_grad_inject(_p(dy, _u16), _p(a, _u16), _i64(a.size), _f64(tau), _f64(eps),
+                                  ctypes.c_int(p), _f64(g), _p(out, _u16), _p(exact, _f64))
+    return out, exact
+
+
 def quantize_i8(x, inv_step):
     x = _c(x, np.uint16)
     q = np.empty(x.shape, np.int8)

@@ -333,6 +333,26 @@ void orc_penalty_grad(const uint16_t *a, int64_t n, double tau, double eps, int 
     }
 }
 
+/*
+ * The same gradient added to the incoming output gradient, as the backward pass
+ * sees it (bf16 in, bf16 out): out = bf16( dy + d(penalty)/da ), evaluated in
+ * fp64 and rounded fp32 -> bf16 like every stored result in this file.  Also
+ * returns the unrounded sums (may be NULL).
+ */
+void orc_penalty_grad_inject(const uint16_t *dy, const uint16_t *a, int64_t n, double tau, double eps,
+                             int p, double g, uint16_t *out, double *exact)
+{
+    double denom = tau + eps;
+    for (int64_t i = 0; i < n; ++i) {
+        double v = (double)orc_bf16_to_f32(a[i]);
+        double sgn = (v > 0) - (v < 0);
+        double t = (double)orc_bf16_to_f32(dy[i]) + g * p * sgn * pow(fabs(v) / denom, (double)(p - 1)) / denom;
+        if (exact)
+            exact[i] = t;
+        out[i] = orc_f32_to_bf16((float)t);
+    }
+}
+
 /* ------------------------------------------------------------- INT8 W8A8 */
 
 /*

@@ -19,7 +19,8 @@ TWEO_OK, TWEO_ERR_INVALID_ARG, TWEO_ERR_UNSUPPORTED, TWEO_ERR_WORKSPACE, TWEO_ER
 EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quantize_e4m3",
            "tweo_fp8_linear_fwd", "tweo_fp8_linear_bwd", "tweo_quantize_i8", "tweo_w8a8_linear",
            "tweo_fp8_linear_fwd_bf16", "tweo_fp8_linear_bwd_bf16", "tweo_set_gemm_tile",
-           "tweo_set_stream_k")
+           "tweo_set_stream_k", "tweo_penalty_grad_inject", "tweo_delayed_state_bytes",
+           "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed")
 
 
 class TweoError(RuntimeError):
@@ -68,8 +69,13 @@ def load():
                                            vp, vp, sz, vp]
     L.tweo_set_gemm_tile.argtypes = [ctypes.c_int]
     L.tweo_set_stream_k.argtypes = [ctypes.c_int]
+    L.tweo_delayed_state_bytes.argtypes = []
+    L.tweo_delayed_state_bytes.restype = ctypes.c_size_t
+    L.tweo_delayed_state_init.argtypes = [vp, vp]
+    L.tweo_quantize_e4m3_delayed.argtypes = [vp, i64, i64, vp, ctypes.c_int, vp, vp, vp]
+    L.tweo_penalty_grad_inject.argtypes = [vp, vp, i64, ctypes.POINTER(PenaltyCfg), ctypes.c_float, vp, vp]
     for name in EXPORTS:
-        if name not in ("tweo_workspace_bytes", "tweo_status_string"):
+        if name not in ("tweo_workspace_bytes", "tweo_status_string", "tweo_delayed_state_bytes"):
             getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -116,6 +122,29 @@ def tweo_set_gemm_tile(variant):
 
 def tweo_set_stream_k(on):
     _check(load().tweo_set_stream_k(1 if on else 0), "tweo_set_stream_k")
+
+
+def tweo_penalty_grad_inject(dy_bf16, a_bf16, pen, g, out_bf16):
+    cfg = PenaltyCfg(float(pen[0]), float(pen[1]), int(pen[2]))
+    _check(load().tweo_penalty_grad_inject(_ptr(dy_bf16), _ptr(a_bf16), dy_bf16.numel(), ctypes.byref(cfg),
+                                           float(g), _ptr(out_bf16), _stream()), "tweo_penalty_grad_inject")
+
+
+DELAYED_STATE_WORDS, DELAYED_NEXT_SCALE, DELAYED_USED_SCALE, DELAYED_USED_SCALE_INV = 32, 17, 21, 22
+
+
+def tweo_delayed_state_bytes():
+    return int(load().tweo_delayed_state_bytes())
+
+
+def tweo_delayed_state_init(state):
+    _check(load().tweo_delayed_state_init(_ptr(state), _stream()), "tweo_delayed_state_init")
+
+
+def tweo_quantize_e4m3_delayed(x_bf16, state, q, qT=None, bootstrap=False):
+    rows, cols = x_bf16.shape
+    _check(load().tweo_quantize_e4m3_delayed(_ptr(x_bf16), rows, cols, _ptr(state), 1 if bootstrap else 0,
+                                             _ptr(q), _ptr(qT), _stream()), "tweo_quantize_e4m3_delayed")
 
 
 def tweo_amax(x_bf16, amax_out):

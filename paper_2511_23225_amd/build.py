@@ -7,7 +7,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libtweo_hip.so")
 SOURCES = ["api.hip", "elementwise.hip", "gemm.hip"]
-HEADERS = ["kernels.h", "device_utils.h", os.path.join("..", "..", "include", "tweo.h")]
+HEADERS = ["kernels.h", "device_utils.h", "gemm_common.h", "gemm_defer.h", os.path.join("..", "..", "include", "tweo.h")]
 # packed-fp32 code generation is switched off: the compiler must not form v_pk_*_f32
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Xclang",
          "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]

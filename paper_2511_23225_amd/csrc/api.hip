@@ -134,6 +134,27 @@ tweo_status tweo_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, c
                                            scale_inv_out, (hipStream_t)stream));
 }
 
+size_t tweo_delayed_state_bytes(void) { return TWEO_DELAYED_STATE_WORDS * sizeof(float); }
+
+tweo_status tweo_delayed_state_init(void *state, void *stream)
+{
+    if (!state || !aligned16(state))
+        return TWEO_ERR_INVALID_ARG;
+    return hip_status(launch_delayed_state_init(state, (hipStream_t)stream));
+}
+
+tweo_status tweo_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
+                                       int bootstrap, uint8_t *q, uint8_t *qT, void *stream)
+{
+    if (!x_bf16 || !state || !q || rows <= 0 || cols <= 0 || !aligned16(x_bf16) || !aligned16(q) ||
+        !aligned16(state) || (qT && !aligned16(qT)))
+        return TWEO_ERR_INVALID_ARG;
+    if (cols % 8 != 0 || rows > kMaxDim || cols > kMaxDim)
+        return TWEO_ERR_UNSUPPORTED;
+    return hip_status(launch_quantize_e4m3_delayed(x_bf16, rows, cols, state, bootstrap != 0, q, qT,
+                                                   (hipStream_t)stream));
+}
+
 tweo_status tweo_fp8_linear_fwd(const uint8_t *xq, const float *sx_inv, const uint8_t *wq,
                                 const float *sw_inv, const void *residual_bf16, int64_t M,
                                 int64_t N, int64_t K, void *y_bf16, const tweo_penalty_cfg *pen,
@@ -223,6 +244,22 @@ tweo_status tweo_fp8_linear_bwd(const uint8_t *dyq, const uint8_t *dyqT, const f
             return TWEO_ERR_HIP;
     }
     return TWEO_OK;
+}
+
+tweo_status tweo_penalty_grad_inject(const void *dy_bf16, const void *a_bf16, int64_t n,
+                                     const tweo_penalty_cfg *pen, float g, void *out_bf16, void *stream)
+{
+    if (!dy_bf16 || !a_bf16 || !out_bf16 || !pen || n <= 0 || !aligned16(dy_bf16) || !aligned16(a_bf16) ||
+        !aligned16(out_bf16) || !(g == g))
+        return TWEO_ERR_INVALID_ARG;
+    if (!(pen->tau > 0.0f) || !(pen->eps >= 0.0f))
+        return TWEO_ERR_INVALID_ARG;
+    if (n % 8 != 0 || pen->p < 1 || pen->p > 8)
+        return TWEO_ERR_UNSUPPORTED;
+    const double denom = (double)pen->tau + (double)pen->eps;
+    return hip_status(launch_penalty_grad_inject(dy_bf16, a_bf16, n, (float)(1.0 / denom),
+                                                 (float)((double)g * pen->p / denom), pen->p, out_bf16,
+                                                 (hipStream_t)stream));
 }
 
 tweo_status tweo_quantize_i8(const void *x_bf16, int64_t n, float inv_step, int8_t *out,

@@ -163,13 +163,35 @@ __device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint3
     t3 = __builtin_amdgcn_perm(p3, p1, 0x07060302u);         // a3 b3 c3 d3
 }
 
-template <bool WITH_T>
+// Delayed scaling (Sec. 4.3: the recipe the paper trained with) hands the cast a scale that was
+// fixed before this tensor was seen and wants this tensor's amax back for the history: DELAYED
+// kernels read the scale itself from `amax`, and add the maximum magnitude pattern of what they
+// load to *amax_acc (one atomicMax per workgroup, skipped when already covered).
+__device__ __forceinline__ void quant_amax_commit(uint32_t m, uint32_t *amax_acc)
+{
+    __shared__ uint32_t red[kQuantThreads / kWave];
+    uint32_t r = (m & 0xFFFFu) > (m >> 16) ? (m & 0xFFFFu) : (m >> 16);
+    r = wave_reduce_max_u32(r);
+    if ((threadIdx.x & (kWave - 1)) == 0)
+        red[threadIdx.x / kWave] = r;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kQuantThreads / kWave; ++w)
+            r = red[w] > r ? red[w] : r;
+        const uint32_t mine = r << 16;
+        if (mine > __atomic_load_n(amax_acc, __ATOMIC_RELAXED))
+            atomicMax(amax_acc, mine);
+    }
+}
+
+template <bool WITH_T, bool DELAYED>
 __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
     const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
     const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
-    float *scale_out, float *scale_inv_out)
+    float *scale_out, float *scale_inv_out, uint32_t *amax_acc)
 {
-    const float scale = scale_from_amax(*amax);
+    const float scale = DELAYED ? *amax : scale_from_amax(*amax);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         if (scale_out)
             *scale_out = scale;
@@ -180,16 +202,23 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
     const int64_t by = blockIdx.x / tiles_x, bx = blockIdx.x % tiles_x;
     const int64_t r0 = by * kQuantTileRows + (lane >> 3) * 8;
     const int64_t c0 = bx * kQuantTileCols + wave * 64 + (lane & 7) * 8;
-    if (c0 >= cols || r0 >= rows)
-        return;
-
+    // lanes outside the tensor load nothing and store nothing, but every lane reaches the one
+    // workgroup barrier of the amax commit
+    const bool active = c0 < cols && r0 < rows;
     uint4 in[8];
+    uint32_t mx = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         in[i] = make_uint4(0, 0, 0, 0);
-        if (r0 + i < rows)
+        if (active && r0 + i < rows)
             in[i] = *(const uint4 *)(x + (r0 + i) * cols + c0);
+        if constexpr (DELAYED)
+            mx = pk_absmax4(mx, in[i]);
     }
+    if constexpr (DELAYED)
+        quant_amax_commit(mx, amax_acc);
+    if (!active)
+        return;
     uint32_t lo[8], hi[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -230,13 +259,13 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
 // workgroup 256x256.
 constexpr int kQuantBigTile = 256;
 
-template <bool WITH_T>
+template <bool WITH_T, bool DELAYED>
 __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
     const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
     const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
-    float *scale_out, float *scale_inv_out)
+    float *scale_out, float *scale_inv_out, uint32_t *amax_acc)
 {
-    const float scale = scale_from_amax(*amax);
+    const float scale = DELAYED ? *amax : scale_from_amax(*amax);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         if (scale_out)
             *scale_out = scale;
@@ -247,9 +276,14 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
     const int64_t by = blockIdx.x / tiles_x, bx = blockIdx.x % tiles_x;
     const int64_t r0 = by * kQuantBigTile + (wave >> 1) * 128 + (lane >> 3) * 16;
     const int64_t c0 = bx * kQuantBigTile + (wave & 1) * 128 + (lane & 7) * 16;
-    if (c0 >= cols || r0 >= rows)
-        return;
+    const bool active = c0 < cols && r0 < rows;  // whole 16x16 blocks: in or out
+    if constexpr (!DELAYED) {
+        if (!active)
+            return;
+    }
     uint32_t qd[16][4];
+    uint32_t mx = 0;
+    if (active) {
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         uint4 in[8][2];
@@ -258,6 +292,8 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
             const uint4 *src = (const uint4 *)(x + (r0 + half * 8 + i) * cols + c0);
             in[i][0] = src[0];
             in[i][1] = src[1];
+            if constexpr (DELAYED)
+                mx = pk_absmax4(pk_absmax4(mx, in[i][0]), in[i][1]);
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -273,6 +309,12 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
             *(uint4 *)(q + (r0 + r) * cols + c0) = make_uint4(qd[r][0], qd[r][1], qd[r][2], qd[r][3]);
         }
     }
+    }
+    // every lane, active or not, reaches the one workgroup barrier of the amax commit
+    if constexpr (DELAYED)
+        quant_amax_commit(mx, amax_acc);
+    if (!active)
+        return;
     if (WITH_T) {
 #pragma unroll
         for (int C = 0; C < 4; ++C) {
@@ -289,9 +331,10 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
     }
 }
 
-hipError_t launch_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
-                                uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
-                                hipStream_t s)
+template <bool DELAYED>
+static hipError_t launch_quantize_e4m3_impl(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
+                                            uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
+                                            uint32_t *amax_acc, hipStream_t s)
 {
     const dim3 block(kQuantThreads);
     if (rows % 16 == 0 && cols % 16 == 0) {
@@ -299,24 +342,107 @@ hipError_t launch_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, 
         const int64_t tiles_y = (rows + kQuantBigTile - 1) / kQuantBigTile;
         const dim3 grid((unsigned)(tiles_x * tiles_y));
         if (qT)
-            hipLaunchKernelGGL(quantize_e4m3_16x16_kernel<true>, grid, block, 0, s,
+            hipLaunchKernelGGL((quantize_e4m3_16x16_kernel<true, DELAYED>), grid, block, 0, s,
                                (const uint16_t *)x_bf16, rows, cols, tiles_x, amax, q, qT, scale_out,
-                               scale_inv_out);
+                               scale_inv_out, amax_acc);
         else
-            hipLaunchKernelGGL(quantize_e4m3_16x16_kernel<false>, grid, block, 0, s,
+            hipLaunchKernelGGL((quantize_e4m3_16x16_kernel<false, DELAYED>), grid, block, 0, s,
                                (const uint16_t *)x_bf16, rows, cols, tiles_x, amax, q, qT, scale_out,
-                               scale_inv_out);
+                               scale_inv_out, amax_acc);
         return hipGetLastError();
     }
     const int64_t tiles_x = (cols + kQuantTileCols - 1) / kQuantTileCols;
     const int64_t tiles_y = (rows + kQuantTileRows - 1) / kQuantTileRows;
     const dim3 grid((unsigned)(tiles_x * tiles_y));
     if (qT)
-        hipLaunchKernelGGL(quantize_e4m3_kernel<true>, grid, block, 0, s, (const uint16_t *)x_bf16,
-                           rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out);
+        hipLaunchKernelGGL((quantize_e4m3_kernel<true, DELAYED>), grid, block, 0, s, (const uint16_t *)x_bf16,
+                           rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out, amax_acc);
     else
-        hipLaunchKernelGGL(quantize_e4m3_kernel<false>, grid, block, 0, s, (const uint16_t *)x_bf16,
-                           rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out);
+        hipLaunchKernelGGL((quantize_e4m3_kernel<false, DELAYED>), grid, block, 0, s, (const uint16_t *)x_bf16,
+                           rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out, amax_acc);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
+                                uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
+                                hipStream_t s)
+{
+    return launch_quantize_e4m3_impl<false>(x_bf16, rows, cols, amax, q, qT, scale_out, scale_inv_out,
+                                            nullptr, s);
+}
+
+// ---------------------------------------------------------------------------
+// Delayed-scaling state (Sec. 4.3: amax history of length 16).  32 words in device memory:
+//   [0..15] amax history ring   [16] amax of the tensor being cast (accumulator, 0 between calls)
+//   [17] scale for the next cast, [18] its inverse   [19] ring position   [20] entries filled
+//   [21] scale the last cast used, [22] its inverse (what the GEMM dequantises with)
+// The scale of step t is 448 / max(history) over the up to 16 amax values of steps t-16..t-1 (the
+// paper names the length, not the reduction: max); an empty history bootstraps from the
+// tensor's own amax.  Guards as for the current-scaling scale.
+__global__ void delayed_state_init_kernel(uint32_t *st)
+{
+    const int i = threadIdx.x;
+    if (i < 32)
+        st[i] = (i == 17 || i == 18 || i == 21 || i == 22) ? f32_to_bits(1.0f) : 0u;
+}
+
+// Consumes the accumulated amax: remembers the scale that was just used, pushes the amax into
+// the ring, derives the next scale, clears the accumulator.  One thread.
+__global__ void delayed_state_update_kernel(uint32_t *st, int bootstrap)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0)
+        return;
+    int pos = (int)st[19], filled = (int)st[20];
+    if (!bootstrap) {  // a bootstrap cast has not happened yet: nothing was "used"
+        st[21] = st[17];
+        st[22] = st[18];
+    }
+    st[pos & 15] = st[16];
+    pos = (pos + 1) & 15;
+    filled = filled < 16 ? filled + 1 : 16;
+    uint32_t m = 0;
+    for (int k = 0; k < 16; ++k)
+        m = st[k] > m ? st[k] : m;  // magnitude patterns order like unsigned integers (NaN on top)
+    const float scale = scale_from_amax(bits_to_f32(m));
+    st[17] = f32_to_bits(scale);
+    st[18] = f32_to_bits(1.0f / scale);
+    st[19] = (uint32_t)pos;
+    st[20] = (uint32_t)filled;
+    st[16] = 0u;
+    if (bootstrap) {  // the cast that follows uses this scale
+        st[21] = st[17];
+        st[22] = st[18];
+    }
+}
+
+hipError_t launch_delayed_state_init(void *state, hipStream_t s)
+{
+    hipLaunchKernelGGL(delayed_state_init_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
+                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s)
+{
+    float *st = (float *)state;
+    hipError_t e;
+    if (bootstrap) {
+        // empty history: this tensor's own amax makes the scale (two passes, once)
+        e = launch_amax(x_bf16, rows * cols, st + 16, s);
+        if (e != hipSuccess)
+            return e;
+        hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 1);
+        e = hipGetLastError();
+        if (e != hipSuccess)
+            return e;
+        return launch_quantize_e4m3_impl<true>(x_bf16, rows, cols, st + 21, q, qT, nullptr, nullptr,
+                                               (uint32_t *)st + 24, s);  // amax goes to a spare word
+    }
+    e = launch_quantize_e4m3_impl<true>(x_bf16, rows, cols, st + 17, q, qT, nullptr, nullptr,
+                                        (uint32_t *)st + 16, s);
+    if (e != hipSuccess)
+        return e;
+    hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 0);
     return hipGetLastError();
 }
 
@@ -360,6 +486,68 @@ hipError_t launch_quantize_i8(const void *x_bf16, int64_t n, float inv_step, int
         blocks = 256 * 16;
     hipLaunchKernelGGL(quantize_i8_kernel, dim3((unsigned)blocks), dim3(kQi8Threads), 0, s,
                        (const uint4 *)x_bf16, n_vec, inv_step, (uint2 *)out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Penalty-gradient injection (the derivative of the loss of Sec. 3.3 with
+// respect to the penalised activation, added to the incoming output gradient):
+//   out = bf16( dy + coef * sign(a) * (|a| / (tau+eps))^(p-1) ),
+//   coef = g * p / (tau+eps), g = the caller's lambda / (L * numel).
+// 6 B/element of HBM traffic (two 2-byte reads, one 2-byte write); fp32
+// arithmetic, the power by repeated multiplication (p is a small integer).
+constexpr int kInjectThreads = 256;
+
+template <int P>
+__device__ __forceinline__ float inject_one(float dy, float a, float inv_tau, float coef, int p)
+{
+    const float u = __builtin_fabsf(a) * inv_tau;
+    float w = 1.0f;
+    if constexpr (P == 4) {
+        w = u * u * u;
+    } else {
+        for (int e = 1; e < p; ++e)
+            w *= u;
+    }
+    const float t = coef * w;
+    // sign(a) = 0 for a = 0; a NaN activation poisons the gradient, as it should
+    return dy + (a > 0.0f ? t : (a < 0.0f ? -t : (a == 0.0f ? 0.0f : a)));
+}
+
+template <int P>
+__global__ __launch_bounds__(kInjectThreads) void penalty_grad_inject_kernel(
+    const uint4 *__restrict__ dy, const uint4 *__restrict__ act, int64_t n_vec, float inv_tau, float coef,
+    int p, uint4 *__restrict__ out)
+{
+    const int64_t stride = (int64_t)gridDim.x * kInjectThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kInjectThreads + threadIdx.x; i < n_vec; i += stride) {
+        const uint4 d = dy[i], a = act[i];
+        const uint32_t dd[4] = {d.x, d.y, d.z, d.w}, aa[4] = {a.x, a.y, a.z, a.w};
+        uint32_t r[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            r[k] = pack_bf16x2(
+                inject_one<P>(bf16lo_to_f32(dd[k]), bf16lo_to_f32(aa[k]), inv_tau, coef, p),
+                inject_one<P>(bf16hi_to_f32(dd[k]), bf16hi_to_f32(aa[k]), inv_tau, coef, p));
+        out[i] = make_uint4(r[0], r[1], r[2], r[3]);
+    }
+}
+
+hipError_t launch_penalty_grad_inject(const void *dy_bf16, const void *a_bf16, int64_t n, float inv_tau,
+                                      float coef, int p, void *out_bf16, hipStream_t s)
+{
+    const int64_t n_vec = n / 8;
+    int64_t blocks = (n_vec + kInjectThreads - 1) / kInjectThreads;
+    if (blocks > 256 * 16)
+        blocks = 256 * 16;
+    if (p == 4)
+        hipLaunchKernelGGL(penalty_grad_inject_kernel<4>, dim3((unsigned)blocks), dim3(kInjectThreads), 0, s,
+                           (const uint4 *)dy_bf16, (const uint4 *)a_bf16, n_vec, inv_tau, coef, p,
+                           (uint4 *)out_bf16);
+    else
+        hipLaunchKernelGGL(penalty_grad_inject_kernel<0>, dim3((unsigned)blocks), dim3(kInjectThreads), 0, s,
+                           (const uint4 *)dy_bf16, (const uint4 *)a_bf16, n_vec, inv_tau, coef, p,
+                           (uint4 *)out_bf16);
     return hipGetLastError();
 }
 

@@ -13,9 +13,14 @@ hipError_t launch_amax(const void *x_bf16, int64_t n, float *amax_zeroed, hipStr
 hipError_t launch_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
                                 uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
                                 hipStream_t s);
+hipError_t launch_delayed_state_init(void *state, hipStream_t s);
+hipError_t launch_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
+                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s);
 hipError_t launch_quantize_i8(const void *x_bf16, int64_t n, float inv_step, int8_t *out,
                               hipStream_t s);
 hipError_t launch_penalty_finish(const float *partials, int n, double *out, hipStream_t s);
+hipError_t launch_penalty_grad_inject(const void *dy_bf16, const void *a_bf16, int64_t n, float inv_tau,
+                                      float coef, int p, void *out_bf16, hipStream_t s);
 
 // C[M,N] = A[M,K] * B[N,K]^T on 8-bit operands, both K-contiguous.
 struct GemmArgs {

@@ -106,3 +106,70 @@ def test_quantize_i8(n):
     out = torch.empty(8, dtype=torch.int8, device=DEV)
     tw.tweo_quantize_i8(to_dev_bf16(special), 1.0, out)
     assert np.array_equal(out.cpu().numpy(), oracle.quantize_i8(special, 1.0))
+
+
+@pytest.mark.parametrize("pen,g", [((3.0, 1e-6, 4), 1e-3), ((3.0, 1e-6, 4), 0.5), ((2.0, 0.0, 2), 0.1),
+                                   ((4.0, 1e-6, 3), 0.05), ((3.0, 1e-6, 1), 0.2)])
+def test_penalty_gradient_injection(pen, g):
+    # dy' = dy + d(penalty)/da (the derivative of the loss of Sec. 3.3), fp32 on the GPU against
+    # the fp64 oracle: within bf16 output rounding plus the fp32 arithmetic in front of it
+    n = 256 * 1024 + 8
+    say("penalty gradient injection", pen, g)
+    rng = np.random.default_rng(int(pen[2]) * 7 + 1)
+    a = synth.f32_to_bf16_bits((rng.standard_normal(n) * 6).astype(np.float32))
+    a[:6] = [0x0000, 0x8000, 0x4110, 0xC110, 0x4680, 0xC680]  # +-0, +-9, +-16384
+    dy = synth.f32_to_bf16_bits(rng.standard_normal(n).astype(np.float32))
+    want_bits, exact = oracle.penalty_grad_inject(dy, a, *pen, g=g)
+    out = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    tw.tweo_penalty_grad_inject(to_dev_bf16(dy), to_dev_bf16(a), pen, g, out)
+    torch.cuda.synchronize()
+    got_bits = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    got = synth.bf16_bits_to_f32(got_bits).astype(np.float64)
+    d = synth.bf16_bits_to_f32(dy).astype(np.float64)
+    # 2^-9 relative for the rounding to bf16, 2^-20 of each term for the fp32 arithmetic
+    tol = 2.0 ** -8 * np.abs(exact) + 2.0 ** -20 * (np.abs(d) + np.abs(exact - d)) + 1e-30
+    assert np.all(np.abs(got - exact) <= tol)
+    assert np.mean(got_bits == want_bits) > 0.99  # all but the odd boundary case are the same bits
+    assert got[0] == d[0] and got[1] == d[1]       # sign(0) = 0
+    # in place
+    buf = to_dev_bf16(dy).clone()
+    tw.tweo_penalty_grad_inject(buf, to_dev_bf16(a), pen, g, buf)
+    torch.cuda.synchronize()
+    assert np.array_equal(buf.view(torch.int16).cpu().numpy().view(np.uint16), got_bits)
+
+
+@pytest.mark.parametrize("shape", [(256, 512), (200, 136), (48, 4096), (1024, 768)])
+def test_delayed_scaling_sequence(shape):
+    # 20 steps of the delayed-scaling cast (Sec. 4.3: amax history of length 16) with a spike at
+    # step 3: bytes, transposed bytes and every word of the state bit-exact against the oracle
+    rows, cols = shape
+    say("delayed scaling", shape)
+    ref = oracle.DelayedScaling()
+    state = torch.full((tw.DELAYED_STATE_WORDS,), -7.0, dtype=torch.float32, device=DEV)
+    tw.tweo_delayed_state_init(state)
+    q = torch.empty((rows, cols), dtype=torch.uint8, device=DEV)
+    qT = torch.empty((cols, rows), dtype=torch.uint8, device=DEV)
+    rng = np.random.default_rng(rows + cols)
+    for step in range(20):
+        v = (rng.standard_normal((rows, cols)) * (1.0 + 0.1 * step)).astype(np.float32)
+        if step == 3:
+            v[rng.integers(rows), rng.integers(cols)] = -4321.0
+        if step == 7:
+            v[:] = 0.0      # an all-zero tensor: amax 0 enters the history
+        x = synth.f32_to_bf16_bits(v)
+        oq, oqT, used, used_inv = ref.cast(x)
+        q.fill_(0x55)
+        qT.fill_(0x55)
+        tw.tweo_quantize_e4m3_delayed(to_dev_bf16(x), state, q, qT, bootstrap=(step == 0))
+        torch.cuda.synchronize()
+        st = state.cpu().numpy()
+        assert np.array_equal(q.cpu().numpy(), oq), step
+        assert np.array_equal(qT.cpu().numpy(), oqT), step
+        assert st[tw.DELAYED_USED_SCALE].view(np.uint32) == np.float32(used).view(np.uint32), step
+        assert st[tw.DELAYED_USED_SCALE_INV].view(np.uint32) == np.float32(used_inv).view(np.uint32), step
+        assert st[tw.DELAYED_NEXT_SCALE].view(np.uint32) == np.float32(ref.next_scale).view(np.uint32), step
+        assert st[16] == 0.0                                   # accumulator cleared
+        assert int(st[20:21].view(np.uint32)[0]) == len(ref.history)
+        ring = np.sort(st[:16].view(np.uint32))[::-1][:len(ref.history)]
+        want = np.sort(np.array(ref.history, np.float32).view(np.uint32))[::-1]
+        assert np.array_equal(ring, want), step

@@ -236,3 +236,52 @@ def test_quantize_subnormal_fp32_products_are_honoured():
     q, _ = oracle.quantize_e4m3(x, np.finfo(np.float32).max, transpose=False)
     f = synth.bf16_bits_to_f32(x) * np.finfo(np.float32).max
     assert q.tolist() == [[brute_encode(v) for v in f[0]]]
+
+
+# ------------------------------------------------------------ delayed scaling (Sec. 4.3)
+
+
+def _tensor_with_amax(amax, seed, shape=(16, 32)):
+    rng = np.random.default_rng(seed)
+    v = (rng.uniform(-0.5, 0.5, shape) * amax).astype(np.float32)
+    v[0, 0] = amax
+    return synth.f32_to_bf16_bits(v)
+
+
+def test_delayed_scaling_window_of_sixteen():
+    # what the recipe fixes: the scale of a step comes from the amax values of up to 16 earlier
+    # steps and never from the tensor itself (except on an empty history)
+    d = oracle.DelayedScaling()
+    amaxes = [2.0] * 3 + [512.0] + [2.0] * 20
+    used = []
+    for t, a in enumerate(amaxes):
+        q, qT, s, si = d.cast(_tensor_with_amax(a, t))
+        used.append(float(s))
+        assert np.array_equal(qT, q.T)
+        assert np.float32(si) == np.float32(1.0) / np.float32(s)
+    assert used[0] == 448.0 / 2.0                      # bootstrap: own amax
+    assert used[1] == used[2] == used[3] == 448.0 / 2.0  # the spike at step 3 is cast with the old scale
+    assert all(u == 448.0 / 512.0 for u in used[4:20])  # ... and then rules the next 16 steps
+    assert all(u == 448.0 / 2.0 for u in used[20:])      # and is forgotten afterwards
+    assert len(d.history) == 16
+
+
+def test_delayed_scaling_saturates_what_the_old_scale_cannot_hold():
+    # the paper's point about this recipe: a spike the history has not seen overflows the format
+    d = oracle.DelayedScaling()
+    d.cast(_tensor_with_amax(1.0, 0))
+    x = _tensor_with_amax(64.0, 1)
+    q, _, s, _ = d.cast(x)
+    assert float(s) == 448.0
+    vals = synth.bf16_bits_to_f32(x).astype(np.float64) * 448.0
+    assert np.all((q[np.abs(vals) >= 448.0] & 0x7F) == 0x7E)   # saturated, never the NaN code
+    assert np.array_equal(q, oracle.quantize_e4m3(x, np.float32(448.0))[0])
+
+
+def test_delayed_scaling_bootstrap_is_current_scaling():
+    x, _, _ = synth.fp8_linear_inputs(0, 0)
+    d = oracle.DelayedScaling()
+    q, qT, s, si = d.cast(x)
+    s_ref, si_ref = oracle.scale_from_amax(oracle.amax_bf16(x))
+    assert s == s_ref and si == si_ref
+    assert np.array_equal(q, oracle.quantize_e4m3(x, s_ref)[0])

@@ -205,6 +205,23 @@ def test_penalty_gradient_finite_differences():
         assert np.isclose(g[i], (f(vp) - f(vm)) / (2 * h), rtol=1e-6, atol=1e-9)
 
 
+def test_penalty_gradient_injection_is_dy_plus_gradient():
+    # the injected gradient is the incoming one plus the finite-difference-pinned derivative,
+    # rounded to bf16; zero activation adds nothing; sign follows the activation
+    rng = np.random.default_rng(8)
+    a = synth.f32_to_bf16_bits((rng.standard_normal(256) * 5).astype(np.float32))
+    dy = synth.f32_to_bf16_bits(rng.standard_normal(256).astype(np.float32))
+    a[:4] = [0x0000, 0x8000, 0x4110, 0xC110]  # +0, -0, +9, -9
+    out, exact = oracle.penalty_grad_inject(dy, a, g=0.25)
+    want = synth.bf16_bits_to_f32(dy).astype(np.float64) + oracle.penalty_grad(a, g=0.25)
+    assert np.allclose(exact, want, rtol=0, atol=0)
+    assert np.array_equal(out, synth.f32_to_bf16_bits(exact.astype(np.float32)))
+    d = synth.bf16_bits_to_f32(dy).astype(np.float64)
+    assert exact[0] == d[0] and exact[1] == d[1]
+    step = 0.25 * 4 * (9.0 / (3.0 + 1e-6)) ** 3 / (3.0 + 1e-6)  # closed form at |a| = 9 = 3 tau
+    assert np.isclose(exact[2] - d[2], step, rtol=1e-12) and np.isclose(exact[3] - d[3], -step, rtol=1e-12)
+
+
 # ------------------------------------------------------------------- INT8
 
 
