@@ -51,6 +51,8 @@ class Layer:
         self.ws = torch.empty(tw.tweo_workspace_bytes(tw.TWEO_OP_FP8_LINEAR_FWD_BF16, M, N, K),
                               dtype=torch.uint8, device=dev)
         self.flops = 6.0 * M * N * K
+        # delayed-scaling states of the three scaled tensors (x, w, dy)
+        self.st = [torch.zeros(tw.DELAYED_STATE_WORDS, dtype=torch.float32, device=dev) for _ in range(3)]
 
 
 def run_step(tw, layers, ev=None):
@@ -76,6 +78,21 @@ def run_step(tw, layers, ev=None):
                                L.K, L.dx, L.dw, L.ws)
         if ev is not None:
             ev.stop(4.0 * L.M * L.N * L.K)
+
+
+def run_step_delayed(tw, layers, bootstrap=False):
+    """The same step with the paper's delayed scaling (Sec. 4.3): every tensor is cast in one
+    pass with the scale its amax history fixed beforehand; no separate amax pass."""
+    inv = tw.DELAYED_USED_SCALE_INV
+    for L in layers:
+        sx, sw, sdy = L.st
+        tw.tweo_quantize_e4m3_delayed(L.x, sx, L.xq, L.xqT, bootstrap=bootstrap)
+        tw.tweo_quantize_e4m3_delayed(L.w, sw, L.wq, L.wqT, bootstrap=bootstrap)
+        tw.tweo_fp8_linear_fwd(L.xq, sx[inv:inv + 1], L.wq, sw[inv:inv + 1], L.y, pen=PEN, penalty_sum=L.S,
+                               workspace=L.ws)
+        tw.tweo_quantize_e4m3_delayed(L.dy, sdy, L.dyq, L.dyqT, bootstrap=bootstrap)
+        tw.tweo_fp8_linear_bwd(L.dyq, L.dyqT, sdy[inv:inv + 1], L.wqT, sw[inv:inv + 1], L.xqT,
+                               sx[inv:inv + 1], L.M, L.N, L.K, L.dx, L.dw, L.ws)
 
 
 class GemmEvents:
@@ -301,6 +318,21 @@ def main():
         "paper_context": "+36% training throughput FP8 over BF16 (hardware unstated)",
     }
     if not a.no_extras:
+        # the paper's own scaling mode, same step otherwise (reported beside, never as `value`)
+        for L in layers:
+            for st in L.st:
+                tw.tweo_delayed_state_init(st)
+        run_step_delayed(tw, layers, bootstrap=True)
+        for _ in range(2):
+            run_step_delayed(tw, layers)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            run_step_delayed(tw, layers)
+        torch.cuda.synchronize()
+        ms_d = (time.perf_counter() - t0) * 1e3 / a.steps
+        out["delayed_scaling_history16"] = {"ms_per_step": round(ms_d, 4),
+                                            "TFLOP/s": round(step_flops / (ms_d * 1e-3) / 1e12, 2)}
         big = max(layers, key=lambda L: L.M * L.K)
         out["elementwise"] = time_elementwise(tw, torch, big)
         out["elementwise"]["peak_GB/s"] = HBM_PEAK_GBS

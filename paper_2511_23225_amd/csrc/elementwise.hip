@@ -273,17 +273,17 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
             *scale_inv_out = 1.0f / scale;
     }
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int64_t by = blockIdx.x / tiles_x, bx = blockIdx.x % tiles_x;
+    uint32_t mx = 0;
+    // DELAYED: a bounded grid walks the tiles (its one atomic per workgroup is then a few hundred
+    // per tensor, not thousands); otherwise one tile per workgroup
+    const int64_t n_tiles = DELAYED ? tiles_x * ((rows + kQuantBigTile - 1) / kQuantBigTile) : (int64_t)blockIdx.x + 1;
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int64_t by = tile / tiles_x, bx = tile % tiles_x;
     const int64_t r0 = by * kQuantBigTile + (wave >> 1) * 128 + (lane >> 3) * 16;
     const int64_t c0 = bx * kQuantBigTile + (wave & 1) * 128 + (lane & 7) * 16;
-    const bool active = c0 < cols && r0 < rows;  // whole 16x16 blocks: in or out
-    if constexpr (!DELAYED) {
-        if (!active)
-            return;
-    }
+    if (c0 >= cols || r0 >= rows)  // whole 16x16 blocks: in or out
+        continue;
     uint32_t qd[16][4];
-    uint32_t mx = 0;
-    if (active) {
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         uint4 in[8][2];
@@ -309,12 +309,6 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
             *(uint4 *)(q + (r0 + r) * cols + c0) = make_uint4(qd[r][0], qd[r][1], qd[r][2], qd[r][3]);
         }
     }
-    }
-    // every lane, active or not, reaches the one workgroup barrier of the amax commit
-    if constexpr (DELAYED)
-        quant_amax_commit(mx, amax_acc);
-    if (!active)
-        return;
     if (WITH_T) {
 #pragma unroll
         for (int C = 0; C < 4; ++C) {
@@ -329,6 +323,10 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
                     make_uint4(t[0][k], t[1][k], t[2][k], t[3][k]);
         }
     }
+    }
+    // every lane reaches the one workgroup barrier of the amax commit
+    if constexpr (DELAYED)
+        quant_amax_commit(mx, amax_acc);
 }
 
 template <bool DELAYED>
@@ -340,7 +338,10 @@ static hipError_t launch_quantize_e4m3_impl(const void *x_bf16, int64_t rows, in
     if (rows % 16 == 0 && cols % 16 == 0) {
         const int64_t tiles_x = (cols + kQuantBigTile - 1) / kQuantBigTile;
         const int64_t tiles_y = (rows + kQuantBigTile - 1) / kQuantBigTile;
-        const dim3 grid((unsigned)(tiles_x * tiles_y));
+        int64_t n_wg = tiles_x * tiles_y;
+        if (DELAYED && n_wg > 1024)
+            n_wg = 1024;
+        const dim3 grid((unsigned)n_wg);
         if (qT)
             hipLaunchKernelGGL((quantize_e4m3_16x16_kernel<true, DELAYED>), grid, block, 0, s,
                                (const uint16_t *)x_bf16, rows, cols, tiles_x, amax, q, qT, scale_out,
