@@ -74,39 +74,55 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
 
     // ---- operand stream (direct-to-LDS loads), running ahead of the MFMAs -----------------
     // One instruction of a wave fills 1 KB = 8 rows x 128 B; lane -> (row, 16-byte chunk), the
-    // chunk XOR-swizzled with (row/2)%8.  Piece pc < 8 is A rows (pc*4 + wave)*8.., pc >= 8 B.
+    // chunk XOR-swizzled with (row/2)%8.  Piece p of an operand is its rows (p*4 + wave)*8.. .
+    // A and B are two streams of their own over (tile, stage): the B half of an LDS stage is
+    // released (and refilled) earlier than the A half.  An instruction costs three issue slots:
+    // LDS destination = constant + buffer offset, one wait state, the load with a per-piece
+    // row offset register and the stream's scalar address.
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
     const int dma_row = lane >> 3, dma_p = lane & 7;
-    const uint32_t dma_voff = (uint32_t)(wave * 8 + dma_row) * (uint32_t)g.K +
-                              (uint32_t)((dma_p ^ ((dma_row >> 1) + 4 * (wave & 1))) << 4);
-    const int64_t rows32 = (int64_t)32 * g.K;
-    int dma_id = slot, dma_s = 0;
-    uint32_t dma_buf = 0;
-    const uint8_t *Ad, *Bd;
-    auto dma_set_tile = [&](int id) {
+    uint32_t voffs[8];
+#pragma unroll
+    for (int p8 = 0; p8 < 8; ++p8)
+        voffs[p8] = (uint32_t)(p8 * 32 + wave * 8 + dma_row) * (uint32_t)g.K +
+                    (uint32_t)((dma_p ^ ((dma_row >> 1) + 4 * (wave & 1))) << 4);
+    struct Stream {
+        const uint8_t *ptr;  // first row of the tile's panel, at the stage to load next
+        int s, id;           // that stage and its tile id
+        uint32_t bufoff;     // LDS buffer it goes to: 0 or STAGE_BYTES
+    };
+    Stream sa, sb;
+    auto stream_set = [&](Stream &st, bool is_b) {
         int tm, tn;
-        tile_from_id(id, g.tiles_m, g.tiles_n, tm, tn);
-        Ad = g.A + (int64_t)tm * T::BM * g.K;
-        Bd = g.B + (int64_t)tn * T::BN * g.K;
+        tile_from_id(st.id, g.tiles_m, g.tiles_n, tm, tn);
+        st.ptr = is_b ? g.B + (int64_t)tn * T::BN * g.K : g.A + (int64_t)tm * T::BM * g.K;
+        st.s = 0;
     };
-    auto dma_piece = [&](int pc) {
-        const uint32_t dst = lds_base + dma_buf * T::STAGE_BYTES + (pc < 8 ? 0 : T::A_BYTES) +
-                             ((pc & 7) * 4 + wave) * 1024;
-        const uint8_t *src = (pc < 8 ? Ad : Bd) + (int64_t)dma_s * T::BK + (pc & 7) * rows32;
-        dma_load16(dst, src, dma_voff);
-    };
-    // After the last piece of a stage.  Past the workgroup's last stage the stream keeps
-    // re-reading that stage (in bounds) into buffers nobody multiplies from any more: the main
-    // loop stays free of branches.
-    auto dma_advance = [&]() {
-        dma_buf ^= 1;
-        if (dma_s + 1 < kt) {
-            ++dma_s;
-        } else if (dma_id + G < total) {
-            dma_s = 0;
-            dma_id += G;
-            dma_set_tile(dma_id);
+    // Past the workgroup's last stage a stream keeps re-reading that stage (in bounds) into
+    // buffers nobody multiplies from any more: the main loop stays free of branches.
+    auto stream_advance = [&](Stream &st, bool is_b) {
+        st.bufoff ^= T::STAGE_BYTES;
+        if (st.s + 1 < kt) {
+            ++st.s;
+            st.ptr += T::BK;
+        } else if (st.id + G < total) {
+            st.id += G;
+            stream_set(st, is_b);
         }
+    };
+    auto dma_piece_a = [&](int p8) {
+        const uint32_t dst0 = lds_base + (p8 * 4 + wave) * 1024;
+        asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
+                     :
+                     : "s"(dst0), "s"(sa.bufoff), "v"(voffs[p8]), "s"(sa.ptr)
+                     : "memory", "m0", "scc");
+    };
+    auto dma_piece_b = [&](int p8) {
+        const uint32_t dst0 = lds_base + T::A_BYTES + (p8 * 4 + wave) * 1024;
+        asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
+                     :
+                     : "s"(dst0), "s"(sb.bufoff), "v"(voffs[p8]), "s"(sb.ptr)
+                     : "memory", "m0", "scc");
     };
 
     // ---- fragment addressing ---------------------------------------------------------------
@@ -323,14 +339,18 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int t = kk * 16 + i * 4 + j;
-                    if (kk == 1 && i == 3 && j == 0) {
-                        // every LDS read of this stage has been issued; wait for them and for this
-                        // wave's share of the next stage (and the drain's stores), then publish
-                        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                    if (t == 16) {
+                        // every wave has read the B half of this stage (its slab-1 fragments were
+                        // requested in slots 12..15): the half can be refilled
+                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                         block_barrier();
-#ifdef TWEO_DEFER_STAMPS
-                        if (g.residual && blockIdx.x == 8 && tid == 0 && stamp_n < 300) ((unsigned long long *)g.residual)[stamp_n++] = __builtin_amdgcn_s_memtime();
-#endif
+                    }
+                    if (t == 28) {
+                        // every LDS read of this stage has been issued: wait for them and for this
+                        // wave's share of the next stage (everything but the eight B pieces of the
+                        // stage after next, the youngest loads), then publish
+                        asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+                        block_barrier();
                         flip_stage();
                     }
                     mfma(i, j);
@@ -342,17 +362,20 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
                     }
                     if (i == 3)
                         load_b(fb[j], kk ^ 1, j);
-                    // loads of the stage after next: 8 pieces behind the barrier, 8 at the start
-                    // of the following stage
-                    if (kk == 1 && i == 3) {
-                        dma_piece(2 * j);
-                        dma_piece(2 * j + 1);
-                    }
-                    if (kk == 0 && i == 0) {
-                        dma_piece(8 + 2 * j);
-                        dma_piece(8 + 2 * j + 1);
-                        if (j == 3)
-                            dma_advance();
+                    // operand stream, at most one piece per slot: A of the next stage (second
+                    // half of its pieces) in slots 0..3, B of the stage after next in slots 16..23
+                    // (its buffer half was released at slot 16), A of the stage after next (first
+                    // half) in slots 28..31 (released at slot 28)
+                    if (t < 4) {
+                        dma_piece_a(4 + t);
+                        if (t == 3)
+                            stream_advance(sa, false);
+                    } else if (t >= 16 && t < 24) {
+                        dma_piece_b(t - 16);
+                        if (t == 23)
+                            stream_advance(sb, true);
+                    } else if (t >= 28) {
+                        dma_piece_a(t - 28);
                     }
                     if (DR >= 0)
                         drain_step(UPS * DR, t);
@@ -361,16 +384,26 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     };
     using std::integral_constant;
 
-    // ---- prologue: stage 0 whole, the first 8 pieces of stage 1 ---------------------------
-    dma_set_tile(slot);
+    // ---- prologue: stage 0 whole, B of stage 1, the first four A pieces of stage 1 ----------
+    sa.id = sb.id = slot;
+    sa.bufoff = sb.bufoff = 0;
+    stream_set(sa, false);
+    stream_set(sb, true);
 #pragma unroll
-    for (int pc = 0; pc < T::PIECES; ++pc)
-        dma_piece(pc);
-    dma_advance();
+    for (int p8 = 0; p8 < 8; ++p8)
+        dma_piece_a(p8);
+    stream_advance(sa, false);
 #pragma unroll
-    for (int pc = 0; pc < 8; ++pc)
-        dma_piece(pc);
-    wait_vmcnt<8>();
+    for (int r = 0; r < 2; ++r) {
+#pragma unroll
+        for (int p8 = 0; p8 < 8; ++p8)
+            dma_piece_b(p8);
+        stream_advance(sb, true);
+    }
+#pragma unroll
+    for (int p8 = 0; p8 < 4; ++p8)
+        dma_piece_a(p8);
+    wait_vmcnt<12>();
     block_barrier();
     load_a(fa[0], 0, 0);
 #pragma unroll
