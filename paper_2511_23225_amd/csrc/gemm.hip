@@ -1389,12 +1389,12 @@ static hipError_t launch_stream(const GemmArgs &a, hipStream_t s)
     return launch_stream_inst<T, INT8, WG_PER_CU, false>(a, s, grid, 0);
 }
 
-template <bool INT8, int PMODE, int UPS>
+template <bool INT8, int PMODE, int D>
 static hipError_t launch_defer_inst(const GemmArgs &a, hipStream_t s)
 {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_defer_kernel<INT8, PMODE, UPS>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_defer_kernel<INT8, PMODE, D>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, DeferTile::LDS_BYTES);
         if (e != hipSuccess)
             return e;
@@ -1417,7 +1417,7 @@ static hipError_t launch_defer_inst(const GemmArgs &a, hipStream_t s)
     g.tiles_m = (int)(a.M / 256);
     g.tiles_n = (int)(a.N / 256);
     const int grid = defer_workgroups(a.M, a.N);
-    hipLaunchKernelGGL((gemm_nt_defer_kernel<INT8, PMODE, UPS>), dim3((unsigned)grid), dim3(DeferTile::THREADS),
+    hipLaunchKernelGGL((gemm_nt_defer_kernel<INT8, PMODE, D>), dim3((unsigned)grid), dim3(DeferTile::THREADS),
                        DeferTile::LDS_BYTES, s, g);
     return hipGetLastError();
 }
@@ -1425,10 +1425,16 @@ static hipError_t launch_defer_inst(const GemmArgs &a, hipStream_t s)
 template <bool INT8>
 static hipError_t launch_defer(const GemmArgs &a, hipStream_t s)
 {
-    const bool one = a.K >= 1024;  // one unit per stage needs 8 stages
-    if (a.p == 4)
-        return one ? launch_defer_inst<INT8, 4, 1>(a, s) : launch_defer_inst<INT8, 4, 2>(a, s);
-    return one ? launch_defer_inst<INT8, 0, 1>(a, s) : launch_defer_inst<INT8, 0, 2>(a, s);
+    // a tile is written out over the first 15, 7 or 3 stages of the next one (never its last)
+    const int64_t kt = a.K / DeferTile::BK;
+    if (a.p == 4) {
+        if (kt >= 16)
+            return launch_defer_inst<INT8, 4, 15>(a, s);
+        return kt >= 8 ? launch_defer_inst<INT8, 4, 7>(a, s) : launch_defer_inst<INT8, 4, 3>(a, s);
+    }
+    if (kt >= 16)
+        return launch_defer_inst<INT8, 0, 15>(a, s);
+    return kt >= 8 ? launch_defer_inst<INT8, 0, 7>(a, s) : launch_defer_inst<INT8, 0, 3>(a, s);
 }
 
 template <bool INT8>

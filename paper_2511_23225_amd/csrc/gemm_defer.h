@@ -10,23 +10,29 @@
 // owns: the loads of the next tile's first stages are issued while the current
 // tile is still being multiplied.
 //
-// What is new here is where the epilogue runs.  When a tile's last MFMA is
-// done, the accumulators are scaled and rounded to bf16 in place (128 packed
-// registers) and the next tile's MFMAs start at once; the packed values are
-// written out *during the first stages of the next tile*: a few instructions
-// after each MFMA pass them through a wave-private LDS strip (so that stores
-// cover whole 128-byte lines), add their TWEO penalty terms (Sec. 3.3; the
-// term of the value as stored) and store them.  The matrix pipe therefore only
-// waits for the conversion, not for the LDS round trip, the stores or the
-// penalty arithmetic.
+// A wave issues one instruction every four cycles and a 32x32x64 MFMA keeps the
+// matrix pipe busy for 64, so an MFMA "slot" has room for about sixteen
+// instructions: everything besides the MFMAs (fragment reads, operand loads,
+// the whole epilogue) is cut into pieces of a few instructions and dealt out
+// over the slots.
+//
+//  * Operand stream: the B half of an LDS stage has been read by slot 16 of the
+//    stage, the A half by slot 28; each half gets its own workgroup barrier and
+//    is refilled right behind it, at most one load instruction per slot.  The
+//    wait in front of the second barrier leaves the youngest eight loads in
+//    flight, so the load pipe never drains.
+//  * Epilogue: a block of accumulators is final after its MFMA in the tile's
+//    last K slab.  From two slots later on it is scaled and rounded to bf16 in
+//    place (half a block per slot, into 128 packed registers), and the next
+//    tile's first MFMA on that block starts from zero (no clearing).  The packed
+//    values are written out *during the next tile*: a few instructions per slot
+//    pass them through a wave-private LDS strip (so that stores cover whole
+//    128-byte lines), add their TWEO penalty terms (Sec. 3.3; the term of the
+//    value as stored) and store them.
 //
 // Fragments are single-buffered in registers and refilled just in time: the
 // A fragment of row i+1 is read while row i multiplies, the B fragment j of the
-// next K slab is read right after its last use in the current slab.  One
-// workgroup barrier per stage, placed before the last MFMA row of the stage:
-// at that point every LDS read of the stage has been issued and waited for, so
-// the barrier both publishes the next stage and frees this one for the loads
-// of the stage after next.
+// next K slab is read right after its last use in the current slab.
 #pragma once
 #include "gemm_common.h"
 
@@ -39,15 +45,22 @@ struct DeferTile {
     static constexpr int STRIP_BYTES = 32 * STRIP_ROW;    // one 32x64 unit per wave
     static constexpr int STRIP_OFFSET = 2 * STAGE_BYTES;
     static constexpr int LDS_BYTES = STRIP_OFFSET + NWAVES * STRIP_BYTES;
-    static constexpr int PIECES = 16;                     // DMA instructions per wave per stage
     static constexpr int UNITS = 8;                       // 32x64 output units per wave per tile
+    static constexpr int STEPS_PER_UNIT = 18;             // micro-steps of writing a unit out
+    static constexpr int DRAIN_STEPS = UNITS * STEPS_PER_UNIT;
+    static constexpr int HALVES = 32;                     // half blocks to convert per tile
     static constexpr int PARTIALS_PER_WG = NWAVES;       // one fp32 sum per wave
     static_assert(LDS_BYTES <= 160 * 1024, "LDS capacity");
+    // Half block h of the finishing tile is converted in this slot, counted from the start of
+    // the tile's last stage (slots 32.. are the next tile's first stage).  Block b = h/2 gets its
+    // last MFMA in slot 16 + b and its first MFMA of the next tile in slot 32 + b.
+    static constexpr int convert_slot(int h) { return 18 + h * 29 / 32; }
 };
 
-// PMODE: 4 = TWEO penalty with p = 4 (the paper's setting), 0 = none.  UPS: output units drained
-// per stage of the next tile, 1 (needs K >= 1024) or 2 (needs K >= 512).
-template <bool INT8, int PMODE, int UPS>
+// PMODE: 4 = TWEO penalty with p = 4 (the paper's setting), 0 = none.  D: number of stages of
+// the next tile over which the write-out of a tile is spread (3, 7 or 15; needs K >= 128 * (D + 1):
+// the tile's last stage, which converts its own blocks, takes no part in it).
+template <bool INT8, int PMODE, int D>
 __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(GemmDev g)
 {
     using T = DeferTile;
@@ -166,8 +179,9 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     // fill the accumulation register file exactly, and only a hard constraint keeps the register
     // allocator from parking blocks in VGPRs and copying them around every use.  Consecutive
     // MFMAs never touch the same block (a block recurs after 16), and the fragments come straight
-    // from LDS reads (the compiler's own s_waitcnt covers asm operands); the one software-visible
-    // hazard, reading a block right after its last MFMA, is covered by the no-ops in convert().
+    // from LDS reads (the compiler's own s_waitcnt covers asm operands).  The one software-visible
+    // hazard, reading a block right after its last MFMA, is avoided by the schedule: a block is
+    // converted at least two slots after that MFMA was issued.
     auto mfma = [&](int i, int j) {
         if constexpr (INT8) {
             const v4i a0 = {fa[i & 1][0], fa[i & 1][1], fa[i & 1][2], fa[i & 1][3]};
@@ -181,18 +195,18 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
             asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[j]), "v"(fa[i & 1]));
         }
     };
-    // A block is cleared by a multiplication of zeros: it runs on the matrix pipe, under the
-    // conversion arithmetic of the other blocks.  The zero register is written once, here (the
-    // compiler cannot re-create it next to a use: an MFMA must not read a register in the
-    // cycles right after a vector-ALU write, and nothing pads asm statements).
-    uint32_t zero_lo, zero_hi;
-    asm volatile("v_mov_b32 %0, 0\n\tv_mov_b32 %1, 0\n\ts_nop 4" : "=v"(zero_lo), "=v"(zero_hi));
-    auto clear_block = [&](int i, int j) {
+    // first MFMA of a block in a tile: accumulates onto zero
+    auto mfma_first = [&](int i, int j) {
         if constexpr (INT8) {
-            const long z = (long)(((uint64_t)zero_hi << 32) | zero_lo);
-            asm volatile("s_nop 4\n\tv_mfma_i32_32x32x16_i8 %0, %1, %1, 0" : "=a"(acc[i][j]) : "v"(z));
+            const v4i a0 = {fa[i & 1][0], fa[i & 1][1], fa[i & 1][2], fa[i & 1][3]};
+            const v4i a1 = {fa[i & 1][4], fa[i & 1][5], fa[i & 1][6], fa[i & 1][7]};
+            const v4i b0 = {fb[j][0], fb[j][1], fb[j][2], fb[j][3]};
+            const v4i b1 = {fb[j][4], fb[j][5], fb[j][6], fb[j][7]};
+            asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, 0\n\tv_mfma_i32_32x32x32_i8 %0, %3, %4, %0"
+                         : "=&a"(acc[i][j])
+                         : "v"(b0), "v"(a0), "v"(b1), "v"(a1));
         } else {
-            asm volatile("s_nop 4\n\tv_mfma_f32_32x32x2_f32 %0, %1, %1, 0" : "=a"(acc[i][j]) : "v"(zero_lo));
+            asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, 0" : "=&a"(acc[i][j]) : "v"(fb[j]), "v"(fa[i & 1]));
         }
     };
 
@@ -200,50 +214,34 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     // packed[i][j][2q+h]: bf16 pair (rows l31, columns j*32 + 8q + 4lh + 2h, +1) of block (i, j)
     uint32_t packed[4][4][8];
     float pen = 0.0f;
-    int ptm = 0, ptn = 0;  // tile whose values sit in `packed`
     uint8_t *strip = smem + T::STRIP_OFFSET + wave * T::STRIP_BYTES;
     uint8_t *strip_wr = strip + l31 * T::STRIP_ROW + lh * 8;
     const uint8_t *strip_rd = strip + (lane >> 3) * T::STRIP_ROW + (lane & 7) * 16;
     const uint32_t out_lane = ((uint32_t)(lane >> 3) * (uint32_t)g.N + (uint32_t)(lane & 7) * 8u) * 2u;
-    auto convert = [&]() {
-        // the last MFMA (16 passes) must have written its block before it is read
-        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-        uint32_t chain = 0;
+    // half h of block b = h/2 (i = b/4, j = b%4): accumulator words 8*(h%2) .. +7
+    auto convert_half = [&](int h) {
+        const int i = h >> 3, j = (h >> 1) & 3, q0 = (h & 1) * 2;
+        asm volatile("" : "+a"(acc[i][j]));
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                // One block at a time: the empty asm ties the reads of this block behind the
-                // last value of the previous one (otherwise all 256 accumulators are copied to
-                // VGPRs up front and spill).
-                asm volatile("" : "+a"(acc[i][j]), "+v"(chain));
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    packed[i][j][2 * q + 0] = pack_bf16x2((float)acc[i][j][4 * q + 0] * alpha,
-                                                          (float)acc[i][j][4 * q + 1] * alpha);
-                    packed[i][j][2 * q + 1] = pack_bf16x2((float)acc[i][j][4 * q + 2] * alpha,
-                                                          (float)acc[i][j][4 * q + 3] * alpha);
-                }
-                // ... and this one makes the eight results exist here, not whenever the
-                // instruction selector gets round to them (pure arithmetic floats past fences)
-                asm volatile(""
-                             : "+v"(packed[i][j][0]), "+v"(packed[i][j][1]), "+v"(packed[i][j][2]),
-                               "+v"(packed[i][j][3]), "+v"(packed[i][j][4]), "+v"(packed[i][j][5]),
-                               "+v"(packed[i][j][6]), "+v"(packed[i][j][7]));
-                chain = packed[i][j][7];
-                clear_block(i, j);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        for (int q = q0; q < q0 + 2; ++q) {
+            packed[i][j][2 * q + 0] = pack_bf16x2((float)acc[i][j][4 * q + 0] * alpha,
+                                                  (float)acc[i][j][4 * q + 1] * alpha);
+            packed[i][j][2 * q + 1] = pack_bf16x2((float)acc[i][j][4 * q + 2] * alpha,
+                                                  (float)acc[i][j][4 * q + 3] * alpha);
+        }
+        // make the four results exist here, not whenever the instruction selector gets round to
+        // them (pure arithmetic floats past fences)
+        asm volatile(""
+                     : "+v"(packed[i][j][2 * q0]), "+v"(packed[i][j][2 * q0 + 1]),
+                       "+v"(packed[i][j][2 * q0 + 2]), "+v"(packed[i][j][2 * q0 + 3]));
     };
-    // unit u = (band i = u/2, column half jh = u%2): 32 rows x 64 columns of the wave's sub-tile
-    auto unit_write = [&](int u) {
+    // unit u = (band i = u/2, column half jh = u%2) = blocks 2u, 2u+1: 32 rows x 64 columns
+    auto unit_write = [&](int u, int jl) {
         const int i = u >> 1, jh = u & 1;
 #pragma unroll
-        for (int jl = 0; jl < 2; ++jl)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                *(uint2 *)(strip_wr + jl * 64 + q * 16) =
-                    make_uint2(packed[i][2 * jh + jl][2 * q], packed[i][2 * jh + jl][2 * q + 1]);
+        for (int q = 0; q < 4; ++q)
+            *(uint2 *)(strip_wr + jl * 64 + q * 16) =
+                make_uint2(packed[i][2 * jh + jl][2 * q], packed[i][2 * jh + jl][2 * q + 1]);
     };
     v4i dr[2];  // values of the pass being written out, and of the next one (read ahead)
     auto unit_read = [&](int ps) { dr[ps & 1] = *(const v4i *)(strip_rd + ps * 8 * T::STRIP_ROW); };
@@ -258,17 +256,23 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
             asm volatile("" : "+v"(pen));
         }
     };
+    // Stores walk the wave's sub-tile with one scalar pointer: 8 rows down per pass, back up after
+    // the left half of a band, 128 bytes to the right (instruction offset) for the right half.
+    const uint8_t *sp = nullptr;
+    const int64_t rows8 = (int64_t)g.N * 16;
+    auto store_begin = [&](int tm, int tn) {
+        sp = (const uint8_t *)g.out +
+             (((int64_t)tm * T::BM + wm * 128) * g.N + (int64_t)tn * T::BN + wn * 128) * 2;
+    };
     auto unit_store = [&](int u, int ps) {
-        const int i = u >> 1, jh = u & 1;
-        const int64_t row = (int64_t)ptm * T::BM + wm * 128 + i * 32 + ps * 8;
-        const int64_t col = (int64_t)ptn * T::BN + wn * 128 + jh * 64;
-        // scalar base + one shared 32-bit lane offset: no per-store address registers
-        const uint8_t *base = (const uint8_t *)g.out + (row * g.N + col) * 2;
-#ifndef EXP_NOSTORE
-        asm volatile("global_store_dwordx4 %0, %1, %2" : : "v"(out_lane), "v"(dr[ps & 1]), "s"(base) : "memory");
-#else
-        asm volatile("; no store %0 %1 %2" : : "v"(out_lane), "v"(dr[ps & 1]), "s"(base) : "memory");
-#endif
+        if (u & 1)
+            asm volatile("global_store_dwordx4 %0, %1, %2 offset:128" : : "v"(out_lane), "v"(dr[ps & 1]), "s"(sp) : "memory");
+        else
+            asm volatile("global_store_dwordx4 %0, %1, %2" : : "v"(out_lane), "v"(dr[ps & 1]), "s"(sp) : "memory");
+        if (ps == 3 && !(u & 1))
+            sp -= 3 * rows8;
+        else
+            sp += rows8;
     };
     // The penalty terms are summed per lane over every tile of the workgroup (a few thousand
     // fp32 terms), reduced over the wave once, at the end, and written as
@@ -282,56 +286,38 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
                 g.partials[blockIdx.x * T::PARTIALS_PER_WG + wave] = v;
         }
     };
-    // Micro-steps of draining, one per MFMA slot.  A unit: step 0 writes it to the strip, step 1
-    // reads pass 0 back; then each pass takes 4 (UPS == 1) or 2 (UPS == 2) steps, each adding a
-    // share of the pass's penalty terms; the first also reads the next pass ahead (so that no
-    // step waits for LDS), the last stores the pass.  UPS == 2 appends the second unit.
-    auto drain_step = [&](int ua, int st) {
-        constexpr int SPP = UPS == 1 ? 4 : 2;      // steps per pass
-        constexpr int WPS = 4 / SPP;               // dwords of the pass per step
-        constexpr int PER_UNIT = 2 + 4 * SPP;
-        if (st < 0 || st >= UPS * PER_UNIT)
-            return;
-        const int u = ua + st / PER_UNIT, k = st % PER_UNIT;
+    // Micro-step q of writing a tile out: unit q / 18, then step 0 writes the left block of the
+    // unit to the strip, step 1 the right block and reads pass 0 back; each of the four passes
+    // (8 rows x 64 columns) then takes four steps, each adding the penalty terms of one dword per
+    // lane; the first also reads the next pass ahead (so that no step waits for LDS), the last
+    // stores the pass.
+    auto drain_step = [&](int q) {
+        const int u = q / T::STEPS_PER_UNIT, k = q % T::STEPS_PER_UNIT;
         if (k == 0) {
-            unit_write(u);
+            unit_write(u, 0);
         } else if (k == 1) {
+            unit_write(u, 1);
             unit_read(0);
         } else {
-            const int ps = (k - 2) / SPP, part = (k - 2) % SPP;
+            const int ps = (k - 2) >> 2, part = (k - 2) & 3;
             if (part == 0 && ps < 3)
                 unit_read(ps + 1);
-#pragma unroll
-            for (int w = 0; w < WPS; ++w)
-                pen_word((uint32_t)dr[ps & 1][part * WPS + w]);
-            if (part == SPP - 1)
+            pen_word((uint32_t)dr[ps & 1][part]);
+            if (part == 3)
                 unit_store(u, ps);
         }
     };
-    auto drain_units_now = [&](int first_unit) {  // not overlapped: the rest of a tile, at once
-#pragma unroll
-        for (int u = 0; u < T::UNITS; ++u)
-            if (u >= first_unit) {
-                unit_write(u);
-#pragma unroll
-                for (int ps = 0; ps < 4; ++ps) {
-                    unit_read(ps);
-#pragma unroll
-                    for (int w = 0; w < 4; ++w)
-                        pen_word((uint32_t)dr[ps & 1][w]);
-                    unit_store(u, ps);
-                }
-            }
-    };
 
-#ifdef TWEO_DEFER_STAMPS
-    int stamp_n = 0;
-#endif
     // ---- one stage: 2 slabs x 16 MFMA slots ------------------------------------------------
     // On entry fa[0] and fb[0..3] hold the fragments of slab 0 (row 0 / all columns) of this
-    // stage.  DR >= 0: drain units UPS*DR .. UPS*DR + UPS-1 of the previous tile along the way.
-    auto stage = [&](auto dr_c) {
-        constexpr int DR = decltype(dr_c)::value;
+    // stage.  DR >= 0: this is stage DR of a tile whose predecessor is being written out: the
+    // micro-steps are dealt evenly over the slots of the first D stages, from slot 2 on.  FIRST: a
+    // tile starts (1: the workgroup's first tile, 2: a later one, which also converts the last
+    // half blocks of its predecessor).  LAST: a tile ends: its blocks are converted as they finish.
+    constexpr int W = D * 32 - 2;
+    auto stage = [&](auto dr_c, auto first_c, auto last_c) {
+        constexpr int DR = decltype(dr_c)::value, FIRST = decltype(first_c)::value;
+        constexpr bool LAST = decltype(last_c)::value;
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
@@ -353,7 +339,10 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
                         block_barrier();
                         flip_stage();
                     }
-                    mfma(i, j);
+                    if (FIRST != 0 && kk == 0)
+                        mfma_first(i, j);
+                    else
+                        mfma(i, j);
                     if (j == 0) {
                         if (i < 3)
                             load_a(fa[(i + 1) & 1], kk, i + 1);
@@ -377,12 +366,32 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
                     } else if (t >= 28) {
                         dma_piece_a(t - 28);
                     }
-                    if (DR >= 0)
-                        drain_step(UPS * DR, t);
+                    // conversion of the tile that ends here / ended in the previous stage
+#pragma unroll
+                    for (int h = 0; h < T::HALVES; ++h)
+                        if ((LAST && T::convert_slot(h) == t) || (FIRST == 2 && T::convert_slot(h) == t + 32))
+                            convert_half(h);
+                    // write-out of the previous tile
+                    if (DR >= 0) {
+                        const int w = DR * 32 + t - 2;
+                        if (w >= 0 && w < W) {
+                            const int q_lo = (w * T::DRAIN_STEPS + W - 1) / W;
+                            const int q_hi = ((w + 1) * T::DRAIN_STEPS + W - 1) / W;
+                            static_assert(T::DRAIN_STEPS <= 2 * W, "at most two micro-steps per slot");
+                            if (q_lo < q_hi)
+                                drain_step(q_lo);
+                            if (q_lo + 1 < q_hi)
+                                drain_step(q_lo + 1);
+                        }
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
     };
     using std::integral_constant;
+    using std::true_type;
+    using std::false_type;
+    typedef integral_constant<int, -1> no_drain;
+    typedef integral_constant<int, 0> mid;
 
     // ---- prologue: stage 0 whole, B of stage 1, the first four A pieces of stage 1 ----------
     sa.id = sb.id = slot;
@@ -410,44 +419,65 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     for (int j = 0; j < 4; ++j)
         load_b(fb[j], 0, j);
 
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            clear_block(i, j);
-
-    // first tile: nothing to drain yet
+    // first tile: nothing to write out yet
     int id = slot;
     {
         int tm, tn;
         tile_from_id(id, g.tiles_m, g.tiles_n, tm, tn);
-        for (int s = 0; s < kt; ++s)
-            stage(integral_constant<int, -1>{});
-        convert();
-        ptm = tm;
-        ptn = tn;
+        stage(no_drain{}, integral_constant<int, 1>{}, false_type{});
+        for (int s = 1; s < kt - 1; ++s)
+            stage(no_drain{}, mid{}, false_type{});
+        stage(no_drain{}, mid{}, true_type{});
+        store_begin(tm, tn);
     }
-    // every further tile drains its predecessor during its first 8 / UPS stages
+    // every further tile writes its predecessor out during its first D stages
     for (id += G; id < total; id += G) {
         int tm, tn;
         tile_from_id(id, g.tiles_m, g.tiles_n, tm, tn);
-        stage(integral_constant<int, 0>{});
-        stage(integral_constant<int, 1>{});
-        stage(integral_constant<int, 2>{});
-        stage(integral_constant<int, 3>{});
-        if constexpr (UPS == 1) {
-            stage(integral_constant<int, 4>{});
-            stage(integral_constant<int, 5>{});
-            stage(integral_constant<int, 6>{});
-            stage(integral_constant<int, 7>{});
+        stage(integral_constant<int, 0>{}, integral_constant<int, 2>{}, false_type{});
+        stage(integral_constant<int, 1>{}, mid{}, false_type{});
+        stage(integral_constant<int, 2>{}, mid{}, false_type{});
+        if constexpr (D >= 7) {
+            stage(integral_constant<int, 3>{}, mid{}, false_type{});
+            stage(integral_constant<int, 4>{}, mid{}, false_type{});
+            stage(integral_constant<int, 5>{}, mid{}, false_type{});
+            stage(integral_constant<int, 6>{}, mid{}, false_type{});
         }
-        for (int s = T::UNITS / UPS; s < kt; ++s)
-            stage(integral_constant<int, -1>{});
-        convert();
-        ptm = tm;
-        ptn = tn;
+        if constexpr (D >= 15) {
+            stage(integral_constant<int, 7>{}, mid{}, false_type{});
+            stage(integral_constant<int, 8>{}, mid{}, false_type{});
+            stage(integral_constant<int, 9>{}, mid{}, false_type{});
+            stage(integral_constant<int, 10>{}, mid{}, false_type{});
+            stage(integral_constant<int, 11>{}, mid{}, false_type{});
+            stage(integral_constant<int, 12>{}, mid{}, false_type{});
+            stage(integral_constant<int, 13>{}, mid{}, false_type{});
+            stage(integral_constant<int, 14>{}, mid{}, false_type{});
+        }
+        for (int s = D; s < kt - 1; ++s)
+            stage(no_drain{}, mid{}, false_type{});
+        stage(no_drain{}, mid{}, true_type{});
+        store_begin(tm, tn);
     }
-    drain_units_now(0);
+    // the workgroup's last tile: the rest of its conversion, then all of its write-out at once
+#pragma unroll
+    for (int h = 0; h < T::HALVES; ++h)
+        if (T::convert_slot(h) >= 32) {
+            convert_half(h);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+    for (int u = 0; u < T::UNITS; ++u) {
+        unit_write(u, 0);
+        unit_write(u, 1);
+#pragma unroll
+        for (int ps = 0; ps < 4; ++ps) {
+            unit_read(ps);
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                pen_word((uint32_t)dr[ps & 1][w]);
+            unit_store(u, ps);
+        }
+    }
     pen_flush();
     wait_vmcnt<0>();  // the operand stream's last (unused) loads must land before the LDS is released
 }
