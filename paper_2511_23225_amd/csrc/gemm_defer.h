@@ -23,12 +23,16 @@
 //    flight, so the load pipe never drains.
 //  * Epilogue: a block of accumulators is final after its MFMA in the tile's
 //    last K slab.  From two slots later on it is scaled and rounded to bf16 in
-//    place (half a block per slot, into 128 packed registers), and the next
-//    tile's first MFMA on that block starts from zero (no clearing).  The packed
-//    values are written out *during the next tile*: a few instructions per slot
-//    pass them through a wave-private LDS strip (so that stores cover whole
-//    128-byte lines), add their TWEO penalty terms (Sec. 3.3; the term of the
-//    value as stored) and store them.
+//    place (half a block per slot, into 128 packed registers; the accumulator
+//    reads are issued back to back, a read followed at once by its use stalls),
+//    and the next tile's first MFMA on that block starts from zero (no
+//    clearing).  The packed values are written out *during the next tile*, a
+//    few instructions per slot: a lane of the MFMA layout holds four consecutive
+//    columns of a row and lane + 32 the next four, so one v_permlane32_swap per
+//    register pair gives every lane eight consecutive columns (16 bytes) to
+//    store; the TWEO penalty terms (Sec. 3.3; the term of the value as stored)
+//    are added from the same registers.  No LDS round trip: extra LDS
+//    instructions cost the matrix pipe about 25 cycles each.
 //
 // Fragments are single-buffered in registers and refilled just in time: the
 // A fragment of row i+1 is read while row i multiplies, the B fragment j of the
@@ -41,13 +45,9 @@ namespace tweo {
 struct DeferTile {
     static constexpr int BM = 256, BN = 256, BK = 128, NWAVES = 4, THREADS = 256;
     static constexpr int A_BYTES = BM * BK, STAGE_BYTES = (BM + BN) * BK;
-    static constexpr int STRIP_ROW = 128 + 16;            // 64 bf16 + padding (conflict-free)
-    static constexpr int STRIP_BYTES = 32 * STRIP_ROW;    // one 32x64 unit per wave
-    static constexpr int STRIP_OFFSET = 2 * STAGE_BYTES;
-    static constexpr int LDS_BYTES = STRIP_OFFSET + NWAVES * STRIP_BYTES;
-    static constexpr int UNITS = 8;                       // 32x64 output units per wave per tile
-    static constexpr int STEPS_PER_UNIT = 18;             // micro-steps of writing a unit out
-    static constexpr int DRAIN_STEPS = UNITS * STEPS_PER_UNIT;
+    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+    static constexpr int STEPS_PER_BLOCK = 8;             // micro-steps of writing a block out
+    static constexpr int DRAIN_STEPS = 16 * STEPS_PER_BLOCK;
     static constexpr int HALVES = 32;                     // half blocks to convert per tile
     static constexpr int PARTIALS_PER_WG = NWAVES;       // one fp32 sum per wave
     static_assert(LDS_BYTES <= 160 * 1024, "LDS capacity");
@@ -214,37 +214,28 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     // packed[i][j][2q+h]: bf16 pair (rows l31, columns j*32 + 8q + 4lh + 2h, +1) of block (i, j)
     uint32_t packed[4][4][8];
     float pen = 0.0f;
-    uint8_t *strip = smem + T::STRIP_OFFSET + wave * T::STRIP_BYTES;
-    uint8_t *strip_wr = strip + l31 * T::STRIP_ROW + lh * 8;
-    const uint8_t *strip_rd = strip + (lane >> 3) * T::STRIP_ROW + (lane & 7) * 16;
-    const uint32_t out_lane = ((uint32_t)(lane >> 3) * (uint32_t)g.N + (uint32_t)(lane & 7) * 8u) * 2u;
     // half h of block b = h/2 (i = b/4, j = b%4): accumulator words 8*(h%2) .. +7
     auto convert_half = [&](int h) {
         const int i = h >> 3, j = (h >> 1) & 3, q0 = (h & 1) * 2;
-        asm volatile("" : "+a"(acc[i][j]));
+        typedef typename std::conditional<INT8, int, float>::type word_t;
+        word_t t[8];
+        asm volatile("v_accvgpr_read_b32 %0, %8\n\tv_accvgpr_read_b32 %1, %9\n\t"
+                     "v_accvgpr_read_b32 %2, %10\n\tv_accvgpr_read_b32 %3, %11\n\t"
+                     "v_accvgpr_read_b32 %4, %12\n\tv_accvgpr_read_b32 %5, %13\n\t"
+                     "v_accvgpr_read_b32 %6, %14\n\tv_accvgpr_read_b32 %7, %15"
+                     : "=v"(t[0]), "=v"(t[1]), "=v"(t[2]), "=v"(t[3]), "=v"(t[4]), "=v"(t[5]), "=v"(t[6]), "=v"(t[7])
+                     : "a"(acc[i][j][4 * q0 + 0]), "a"(acc[i][j][4 * q0 + 1]), "a"(acc[i][j][4 * q0 + 2]),
+                       "a"(acc[i][j][4 * q0 + 3]), "a"(acc[i][j][4 * q0 + 4]), "a"(acc[i][j][4 * q0 + 5]),
+                       "a"(acc[i][j][4 * q0 + 6]), "a"(acc[i][j][4 * q0 + 7]));
 #pragma unroll
-        for (int q = q0; q < q0 + 2; ++q) {
-            packed[i][j][2 * q + 0] = pack_bf16x2((float)acc[i][j][4 * q + 0] * alpha,
-                                                  (float)acc[i][j][4 * q + 1] * alpha);
-            packed[i][j][2 * q + 1] = pack_bf16x2((float)acc[i][j][4 * q + 2] * alpha,
-                                                  (float)acc[i][j][4 * q + 3] * alpha);
-        }
+        for (int d = 0; d < 4; ++d)
+            packed[i][j][2 * q0 + d] = pack_bf16x2((float)t[2 * d] * alpha, (float)t[2 * d + 1] * alpha);
         // make the four results exist here, not whenever the instruction selector gets round to
         // them (pure arithmetic floats past fences)
         asm volatile(""
                      : "+v"(packed[i][j][2 * q0]), "+v"(packed[i][j][2 * q0 + 1]),
                        "+v"(packed[i][j][2 * q0 + 2]), "+v"(packed[i][j][2 * q0 + 3]));
     };
-    // unit u = (band i = u/2, column half jh = u%2) = blocks 2u, 2u+1: 32 rows x 64 columns
-    auto unit_write = [&](int u, int jl) {
-        const int i = u >> 1, jh = u & 1;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            *(uint2 *)(strip_wr + jl * 64 + q * 16) =
-                make_uint2(packed[i][2 * jh + jl][2 * q], packed[i][2 * jh + jl][2 * q + 1]);
-    };
-    v4i dr[2];  // values of the pass being written out, and of the next one (read ahead)
-    auto unit_read = [&](int ps) { dr[ps & 1] = *(const v4i *)(strip_rd + ps * 8 * T::STRIP_ROW); };
     auto pen_word = [&](uint32_t d) {  // two stored values
         if constexpr (PMODE == 4) {
             const float t0 = bf16lo_to_f32(d), t1 = bf16hi_to_f32(d);
@@ -256,24 +247,49 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
             asm volatile("" : "+v"(pen));
         }
     };
-    // Stores walk the wave's sub-tile with one scalar pointer: 8 rows down per pass, back up after
-    // the left half of a band, 128 bytes to the right (instruction offset) for the right half.
+    // Stores walk the wave's sub-tile with one scalar pointer (first row of the band of blocks
+    // being written); block column and column half go into the instruction's offset field.
+    // Lane (row l31, half lh) stores the 16 bytes at row l31, columns 8*lh .. 8*lh+7 of a half.
     const uint8_t *sp = nullptr;
-    const int64_t rows8 = (int64_t)g.N * 16;
+    const int64_t rows32 = (int64_t)g.N * 64;
+    const uint32_t out_lane = (uint32_t)l31 * (uint32_t)g.N * 2u + (uint32_t)lh * 16u;
     auto store_begin = [&](int tm, int tn) {
         sp = (const uint8_t *)g.out +
              (((int64_t)tm * T::BM + wm * 128) * g.N + (int64_t)tn * T::BN + wn * 128) * 2;
     };
-    auto unit_store = [&](int u, int ps) {
-        if (u & 1)
-            asm volatile("global_store_dwordx4 %0, %1, %2 offset:128" : : "v"(out_lane), "v"(dr[ps & 1]), "s"(sp) : "memory");
-        else
-            asm volatile("global_store_dwordx4 %0, %1, %2" : : "v"(out_lane), "v"(dr[ps & 1]), "s"(sp) : "memory");
-        if (ps == 3 && !(u & 1))
-            sp -= 3 * rows8;
-        else
-            sp += rows8;
+    // Micro-step q of writing a tile out: block q / 8 (in conversion order), column half
+    // P = (q % 8) / 4 (register words 4P .. 4P+3 = columns 16P .. 16P+15 of the block).  Step 0
+    // of a half exchanges words between lane and lane + 32 (word 4P+2 of the lower lanes <-> word
+    // 4P of the upper ones, likewise 4P+3 <-> 4P+1), after which the four words of a lane are
+    // eight consecutive columns; steps 1 and 2 add the penalty terms; step 3 stores.
+    auto drain_step = [&](int q) {
+        const int b = q / T::STEPS_PER_BLOCK, i = b >> 2, j = b & 3;
+        const int P = (q % T::STEPS_PER_BLOCK) >> 2, k = q & 3;
+        uint32_t *w = &packed[i][j][4 * P];
+        if (k == 0) {
+            // the swap reads its operands early: two wait states after a vector-ALU write (the
+            // compiler may have placed a register copy right in front of this statement)
+            asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %2\n\tv_permlane32_swap_b32 %1, %3"
+                         : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]));
+        } else if (k == 1) {
+            pen_word(w[0]);
+            pen_word(w[1]);
+        } else if (k == 2) {
+            pen_word(w[2]);
+            pen_word(w[3]);
+        } else {
+            const v4i v = {(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+            // a store of more than 8 bytes reads its data late: nothing may write those
+            // registers in the next wait states (the compiler does not know this is a store)
+            asm volatile("global_store_dwordx4 %0, %1, %2 offset:%3\n\ts_nop 1"
+                         :
+                         : "v"(out_lane), "v"(v), "s"(sp), "n"(j * 64 + P * 32)
+                         : "memory");
+            if (j == 3 && P == 1)
+                sp += rows32;
+        }
     };
+
     // The penalty terms are summed per lane over every tile of the workgroup (a few thousand
     // fp32 terms), reduced over the wave once, at the end, and written as
     // partials[workgroup][wave]; the finishing kernel adds them in index order in fp64.
@@ -284,27 +300,6 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
             const float v = wave_reduce_sum(pen * (it2 * it2));
             if (lane == 0)
                 g.partials[blockIdx.x * T::PARTIALS_PER_WG + wave] = v;
-        }
-    };
-    // Micro-step q of writing a tile out: unit q / 18, then step 0 writes the left block of the
-    // unit to the strip, step 1 the right block and reads pass 0 back; each of the four passes
-    // (8 rows x 64 columns) then takes four steps, each adding the penalty terms of one dword per
-    // lane; the first also reads the next pass ahead (so that no step waits for LDS), the last
-    // stores the pass.
-    auto drain_step = [&](int q) {
-        const int u = q / T::STEPS_PER_UNIT, k = q % T::STEPS_PER_UNIT;
-        if (k == 0) {
-            unit_write(u, 0);
-        } else if (k == 1) {
-            unit_write(u, 1);
-            unit_read(0);
-        } else {
-            const int ps = (k - 2) >> 2, part = (k - 2) & 3;
-            if (part == 0 && ps < 3)
-                unit_read(ps + 1);
-            pen_word((uint32_t)dr[ps & 1][part]);
-            if (part == 3)
-                unit_store(u, ps);
         }
     };
 
@@ -466,18 +461,10 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-    for (int u = 0; u < T::UNITS; ++u) {
-        unit_write(u, 0);
-        unit_write(u, 1);
+    for (int b = 0; b < 16; ++b)
 #pragma unroll
-        for (int ps = 0; ps < 4; ++ps) {
-            unit_read(ps);
-#pragma unroll
-            for (int w = 0; w < 4; ++w)
-                pen_word((uint32_t)dr[ps & 1][w]);
-            unit_store(u, ps);
-        }
-    }
+        for (int k = 0; k < T::STEPS_PER_BLOCK; ++k)
+            drain_step(b * T::STEPS_PER_BLOCK + k);
     pen_flush();
     wait_vmcnt<0>();  // the operand stream's last (unused) loads must land before the LDS is released
 }
