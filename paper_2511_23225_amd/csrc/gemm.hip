@@ -1231,12 +1231,10 @@ static int pick_variant(int64_t M, int64_t N, int64_t K)
             }
             if (c13 < best)
                 v = 13;
-            // The deferred-epilogue kernel wins where tile boundaries are frequent (short K) and
-            // every workgroup owns several tiles to hide epilogues under (measured: +5..15 % at
-            // K <= 2048, level at K = 4096, behind at K >= 5632 where its single wave per SIMD
-            // has nothing to cover the operand-stream waits with).
-            if (v == 11 && M % 256 == 0 && N % 256 == 0 && K % 128 == 0 && K >= 512 && K <= 2560 &&
-                tiles(256, 256) >= 2 * (int64_t)cus)
+            // The deferred-epilogue kernel (one wave per SIMD, operand halves refilled behind
+            // their own barriers) is the faster 256x256 kernel whenever every CU gets a tile.
+            if (v == 11 && M % 256 == 0 && N % 256 == 0 && K % 128 == 0 && K >= 512 &&
+                tiles(256, 256) >= (int64_t)cus)
                 v = 15;
         }
     }

@@ -453,20 +453,45 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
         stage(no_drain{}, mid{}, true_type{});
         store_begin(tm, tn);
     }
-    // the workgroup's last tile: the rest of its conversion, then all of its write-out at once
+    // The workgroup's last tile: the rest of its conversion, then its write-out with nothing to
+    // hide it under.  Here every CU of the chip stores at the same time, and 16-byte pieces would
+    // queue up at the L2s (eight times the requests of whole lines).  The LDS is idle now, so a
+    // band of the wave's sub-tile (32 rows x 128 columns) goes through a wave-private 32 KB of
+    // the stage buffers and comes back with 16 lanes per row: whole 128-byte lines per store.
 #pragma unroll
     for (int h = 0; h < T::HALVES; ++h)
         if (T::convert_slot(h) >= 32) {
             convert_half(h);
             __builtin_amdgcn_sched_barrier(0);
         }
+    wait_vmcnt<0>();  // the operand stream's last (unused) loads have landed in the stage buffers
+    block_barrier();  // ... and every wave is done reading them
+    {
+        constexpr int ROW = 256 + 16;  // bytes: 128 bf16 + padding
+        uint8_t *tb = smem + wave * 32768;
+        uint8_t *tb_wr = tb + l31 * ROW + lh * 8;
+        const uint8_t *tb_rd = tb + (lane >> 4) * ROW + (lane & 15) * 16;
+        const uint32_t lane_off = (uint32_t)(lane >> 4) * (uint32_t)g.N * 2u + (uint32_t)(lane & 15) * 16u;
+        const int64_t rows4 = (int64_t)g.N * 8;
 #pragma unroll
-    for (int b = 0; b < 16; ++b)
+        for (int i = 0; i < 4; ++i) {
 #pragma unroll
-        for (int k = 0; k < T::STEPS_PER_BLOCK; ++k)
-            drain_step(b * T::STEPS_PER_BLOCK + k);
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *(uint2 *)(tb_wr + j * 64 + q * 16) = make_uint2(packed[i][j][2 * q], packed[i][j][2 * q + 1]);
+#pragma unroll
+            for (int ps = 0; ps < 8; ++ps) {
+                const v4i d = *(const v4i *)(tb_rd + ps * 4 * ROW);
+#pragma unroll
+                for (int w = 0; w < 4; ++w)
+                    pen_word((uint32_t)d[w]);
+                asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" : : "v"(lane_off), "v"(d), "s"(sp) : "memory");
+                sp += rows4;
+            }
+        }
+    }
     pen_flush();
-    wait_vmcnt<0>();  // the operand stream's last (unused) loads must land before the LDS is released
 }
 
 }  // namespace tweo

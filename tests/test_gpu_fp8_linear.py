@@ -65,15 +65,18 @@ def test_fwd_with_penalty(case, tile):
     check_penalty(S, got, refbf, Sref, PEN, strict=(M, K, N) == (256, 512, 512))
 
 
-# shapes the deferred-epilogue kernel (variant 15) takes: whole 256x256 tiles; K = 512 drains two
-# output units per stage, K >= 1024 one; 272 and 544 tiles give workgroups 2 and 3 tiles on a
-# 256-CU machine, i.e. first tile, tiles drained under their successor, and last tile
+# shapes the deferred-epilogue kernel (variant 15) takes: whole 256x256 tiles; a tile is written
+# out over the first 3 (K < 1024), 7 (K < 2048) or 15 stages of its successor; 272 and 544 tiles
+# give workgroups 2 and 3 tiles on a 256-CU machine, i.e. first tile, tiles written out under
+# their successor, and last tile
 DEFER_CASES = [
     (0, 0, 512, 1024, 768),
     (1, 0, 1024, 512, 512),
     (3, 0, 4352, 1024, 4096),
     (3, 1, 8192, 1152, 4352),
     (2, 0, 4352, 640, 4096),
+    (3, 0, 4352, 2048, 8192),
+    (3, 2, 8192, 2304, 4352),
 ]
 
 
@@ -98,6 +101,36 @@ def test_fwd_deferred_epilogue_kernel(case):
             check_penalty(S, got, refbf, Sref, PEN, strict=M * N >= 1 << 20)
         outs.append(got)
     assert np.array_equal(outs[0], outs[1])  # the penalty does not change the stored output
+
+
+@pytest.mark.parametrize("shape", [(16384, 2048, 6144), (16384, 5632, 2048), (8192, 768, 3072), (4096, 512, 16384)])
+def test_fwd_deferred_kernel_matches_streaming_kernel_bitwise(shape):
+    # Both kernels add a block's K slabs in the same order with the same MFMA, so their outputs
+    # are the same bits; at these sizes every workgroup owns several tiles (first tile, tiles
+    # written out under their successor, last tile), twice over to catch anything left behind
+    M, K, N = shape
+    say("fwd deferred vs streaming M=%d K=%d N=%d" % (M, K, N))
+    g = torch.Generator(device=DEV)
+    g.manual_seed(M + 3 * K + 7 * N)
+    xq = torch.randint(0, 0x78, (M, K), dtype=torch.uint8, device=DEV, generator=g)
+    wq = torch.randint(0, 0x78, (N, K), dtype=torch.uint8, device=DEV, generator=g)
+    xq |= torch.randint(0, 2, (M, K), dtype=torch.uint8, device=DEV, generator=g) << 7
+    sc = scalar_f32(0.01)
+    ws = workspace(tw.TWEO_OP_FP8_LINEAR_FWD, M, N, K)
+    outs, sums = [], []
+    for tile in (11, 15, 15):
+        y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)
+        S = torch.zeros(2, dtype=torch.float64, device=DEV)
+        tw.tweo_set_gemm_tile(tile)
+        try:
+            tw.tweo_fp8_linear_fwd(xq, sc, wq, sc, y, pen=PEN, penalty_sum=S, workspace=ws)
+            torch.cuda.synchronize()
+        finally:
+            tw.tweo_set_gemm_tile(0)
+        outs.append(y.view(torch.int16))
+        sums.append(float(S.cpu()[0]))
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert abs(sums[1] - sums[0]) <= 1e-5 * abs(sums[0]) and sums[1] == sums[2]
 
 
 @pytest.mark.parametrize("with_residual", [False, True])
