@@ -1175,10 +1175,11 @@ size_t stream_k_workspace_bytes()
 // Kernel variants.  1-4: register-staged kernel (any K % 16 == 0), tiles 256x256, 256x128,
 // 128x128, 64x64.  5-10: DMA-pipelined kernel (K % 64 == 0).  11-14: persistent streaming kernel
 // (K % 128 == 0): 256x256, 256x128, 128x128, 192x256.  15: deferred-epilogue persistent kernel
-// (256x256, four waves; M, N % 256 == 0, K % 128 == 0, K >= 512).
-constexpr int kNumVariants = 15;
-static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256, 256, 128, 256, 128, 256, 256, 128, 192, 256};
-static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128, 256, 256};
+// (256x256, four waves; M, N % 256 == 0, K % 128 == 0, K >= 512).  16: the same kernel on 192x256
+// tiles (any M, K >= 2048).
+constexpr int kNumVariants = 16;
+static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256, 256, 128, 256, 128, 256, 256, 128, 192, 256, 192};
+static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128, 256, 256, 256};
 int gemm_num_variants() { return kNumVariants; }
 
 static int num_cus();
@@ -1198,9 +1199,9 @@ static int num_cus()
 }
 
 constexpr int kMaxDeferWorkgroups = 1024;
-static int defer_workgroups(int64_t M, int64_t N)
+static int defer_workgroups(int64_t M, int64_t N, int bm = 256)
 {
-    const int64_t tiles = (M / 256) * (N / 256);
+    const int64_t tiles = ((M + bm - 1) / bm) * (N / 256);
     const int64_t cap = num_cus() < kMaxDeferWorkgroups ? num_cus() : kMaxDeferWorkgroups;
     return (int)(tiles < cap ? tiles : cap);
 }
@@ -1236,10 +1237,12 @@ static int pick_variant(int64_t M, int64_t N, int64_t K)
             if (v == 11 && M % 256 == 0 && N % 256 == 0 && K % 128 == 0 && K >= 512 &&
                 tiles(256, 256) >= (int64_t)cus)
                 v = 15;
+            if (v == 14 && N % 256 == 0 && K % 128 == 0 && K >= 2048)
+                v = 16;
         }
     }
-    if (v >= 11 && K % 128 != 0)  // streaming kernel needs whole 128-byte stages
-        v = (v == 11 || v == 14) ? 6 : (v == 12 ? 7 : 8);
+    if (v >= 11 && K % 128 != 0)  // the persistent kernels need whole 128-byte stages
+        v = (v == 11 || v >= 14) ? 6 : (v == 12 ? 7 : 8);
     if (v >= 5 && K % 64 != 0)
         v = (v == 5 || v == 6) ? 1 : ((v == 7 || v == 9) ? 2 : 3);
     return v;
@@ -1253,19 +1256,27 @@ static bool defer_ok(const GemmArgs &a)
            (a.p == 0 || a.p == 4) && a.N <= ((int64_t)1 << 22);
 }
 
+static bool defer192_ok(const GemmArgs &a)
+{
+    return a.N % 256 == 0 && a.K % 128 == 0 && a.K >= 2048 && a.residual == nullptr &&
+           (a.p == 0 || a.p == 4) && a.N <= ((int64_t)1 << 22);
+}
+
 static int resolve_variant(const GemmArgs &a)
 {
     int v = pick_variant(a.M, a.N, a.K);
     if (v == 15 && !defer_ok(a))
         v = 11;
+    if (v == 16 && !defer192_ok(a))
+        v = 14;
     return v;
 }
 
 int fp8_gemm_partials(const GemmArgs &a)
 {
     const int v = resolve_variant(a);
-    if (v == 15)  // one partial per wave of each workgroup (never more than per 64x64 block)
-        return defer_workgroups(a.M, a.N) * DeferTile::PARTIALS_PER_WG;
+    if (v == 15 || v == 16)  // one partial per wave of each workgroup (never more than per 64x64 block)
+        return defer_workgroups(a.M, a.N, kVariantBM[v]) * DeferTile<4>::PARTIALS_PER_WG;
     return (int)(((a.M + kVariantBM[v] - 1) / kVariantBM[v]) * ((a.N + kVariantBN[v] - 1) / kVariantBN[v]));
 }
 
@@ -1387,13 +1398,14 @@ static hipError_t launch_stream(const GemmArgs &a, hipStream_t s)
     return launch_stream_inst<T, INT8, WG_PER_CU, false>(a, s, grid, 0);
 }
 
-template <bool INT8, int PMODE, int D>
+template <bool INT8, int PMODE, int D, int MT>
 static hipError_t launch_defer_inst(const GemmArgs &a, hipStream_t s)
 {
+    using T = DeferTile<MT>;
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_defer_kernel<INT8, PMODE, D>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, DeferTile::LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_defer_kernel<INT8, PMODE, D, MT>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
         if (e != hipSuccess)
             return e;
         attr_done = true;
@@ -1412,11 +1424,11 @@ static hipError_t launch_defer_inst(const GemmArgs &a, hipStream_t s)
     g.inv_tau = a.inv_tau;
     g.p = a.p;
     g.partials = a.partials;
-    g.tiles_m = (int)(a.M / 256);
-    g.tiles_n = (int)(a.N / 256);
-    const int grid = defer_workgroups(a.M, a.N);
-    hipLaunchKernelGGL((gemm_nt_defer_kernel<INT8, PMODE, D>), dim3((unsigned)grid), dim3(DeferTile::THREADS),
-                       DeferTile::LDS_BYTES, s, g);
+    g.tiles_m = (int)((a.M + T::BM - 1) / T::BM);
+    g.tiles_n = (int)(a.N / T::BN);
+    const int grid = defer_workgroups(a.M, a.N, T::BM);
+    hipLaunchKernelGGL((gemm_nt_defer_kernel<INT8, PMODE, D, MT>), dim3((unsigned)grid), dim3(T::THREADS),
+                       T::LDS_BYTES, s, g);
     return hipGetLastError();
 }
 
@@ -1424,15 +1436,22 @@ template <bool INT8>
 static hipError_t launch_defer(const GemmArgs &a, hipStream_t s)
 {
     // a tile is written out over the first 15, 7 or 3 stages of the next one (never its last)
-    const int64_t kt = a.K / DeferTile::BK;
+    const int64_t kt = a.K / 128;
     if (a.p == 4) {
         if (kt >= 16)
-            return launch_defer_inst<INT8, 4, 15>(a, s);
-        return kt >= 8 ? launch_defer_inst<INT8, 4, 7>(a, s) : launch_defer_inst<INT8, 4, 3>(a, s);
+            return launch_defer_inst<INT8, 4, 15, 4>(a, s);
+        return kt >= 8 ? launch_defer_inst<INT8, 4, 7, 4>(a, s) : launch_defer_inst<INT8, 4, 3, 4>(a, s);
     }
     if (kt >= 16)
-        return launch_defer_inst<INT8, 0, 15>(a, s);
-    return kt >= 8 ? launch_defer_inst<INT8, 0, 7>(a, s) : launch_defer_inst<INT8, 0, 3>(a, s);
+        return launch_defer_inst<INT8, 0, 15, 4>(a, s);
+    return kt >= 8 ? launch_defer_inst<INT8, 0, 7, 4>(a, s) : launch_defer_inst<INT8, 0, 3, 4>(a, s);
+}
+
+// 192x256 tiles: long contractions only (K >= 2048)
+template <bool INT8>
+static hipError_t launch_defer192(const GemmArgs &a, hipStream_t s)
+{
+    return a.p == 4 ? launch_defer_inst<INT8, 4, 15, 3>(a, s) : launch_defer_inst<INT8, 0, 15, 3>(a, s);
 }
 
 template <bool INT8>
@@ -1453,7 +1472,8 @@ static hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     case 12: return launch_stream<S256x128w4, INT8, 1>(a, s);
     case 13: return launch_stream<S128x128w4, INT8, 2>(a, s);
     case 14: return launch_stream<S192x256w8, INT8, 1>(a, s);
-    default: return launch_defer<INT8>(a, s);
+    case 15: return launch_defer<INT8>(a, s);
+    default: return launch_defer192<INT8>(a, s);
     }
 }
 

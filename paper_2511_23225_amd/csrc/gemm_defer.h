@@ -42,28 +42,40 @@
 
 namespace tweo {
 
+// MT: 32-row blocks per wave along M (4: 256x256 tile, 3: 192x256 tile, for row counts that
+// 256 quantises badly, e.g. weight gradients with fewer tiles than CUs).  The 192-row variant
+// also takes a ragged last row of tiles (M not a multiple of 192): rows past M are loaded as
+// copies of the last valid row and neither stored nor counted in the penalty.
+template <int MT_>
 struct DeferTile {
-    static constexpr int BM = 256, BN = 256, BK = 128, NWAVES = 4, THREADS = 256;
+    static constexpr int MT = MT_, NB = MT * 4;           // MFMA blocks per wave: MT x 4
+    static constexpr int BM = MT * 64, BN = 256, BK = 128, NWAVES = 4, THREADS = 256;
     static constexpr int A_BYTES = BM * BK, STAGE_BYTES = (BM + BN) * BK;
-    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+    static constexpr int STAGE_STRIDE = 65536;            // power of two: buffers are toggled by XOR
+    static constexpr int LDS_BYTES = 2 * STAGE_STRIDE;
+    static constexpr int SLAB = NB, SLOTS = 2 * NB;       // MFMA slots per K slab / per stage
+    static constexpr int NA = BM / 32, NBP = BN / 32;     // operand pieces per wave per stage
     static constexpr int STEPS_PER_BLOCK = 8;             // micro-steps of writing a block out
-    static constexpr int DRAIN_STEPS = 16 * STEPS_PER_BLOCK;
-    static constexpr int HALVES = 32;                     // half blocks to convert per tile
+    static constexpr int DRAIN_STEPS = NB * STEPS_PER_BLOCK;
+    static constexpr int HALVES = 2 * NB;                 // half blocks to convert per tile
     static constexpr int PARTIALS_PER_WG = NWAVES;       // one fp32 sum per wave
-    static_assert(LDS_BYTES <= 160 * 1024, "LDS capacity");
+    static constexpr bool EDGE = MT == 3;                 // M may end inside the last row of tiles
+    static_assert(STAGE_BYTES <= STAGE_STRIDE && LDS_BYTES <= 160 * 1024, "LDS capacity");
+    static_assert(SLAB + NBP <= SLOTS - 4 && NA / 2 <= 4, "operand pieces fit their slots");
     // Half block h of the finishing tile is converted in this slot, counted from the start of
-    // the tile's last stage (slots 32.. are the next tile's first stage).  Block b = h/2 gets its
-    // last MFMA in slot 16 + b and its first MFMA of the next tile in slot 32 + b.
-    static constexpr int convert_slot(int h) { return 18 + h * 29 / 32; }
+    // the tile's last stage (slots SLOTS.. are the next tile's first stage).  Block b = h/2 gets
+    // its last MFMA in slot SLAB + b and its first MFMA of the next tile in slot SLOTS + b: the
+    // conversions are spread over the slots SLAB + 2 .. SLOTS + NB - 2.
+    static constexpr int convert_slot(int h) { return SLAB + 2 + h * (2 * NB - 3) / (2 * NB); }
 };
 
 // PMODE: 4 = TWEO penalty with p = 4 (the paper's setting), 0 = none.  D: number of stages of
 // the next tile over which the write-out of a tile is spread (3, 7 or 15; needs K >= 128 * (D + 1):
 // the tile's last stage, which converts its own blocks, takes no part in it).
-template <bool INT8, int PMODE, int D>
-__global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(GemmDev g)
+template <bool INT8, int PMODE, int D, int MT>
+__global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
 {
-    using T = DeferTile;
+    using T = DeferTile<MT>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -95,14 +107,16 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
     const int dma_row = lane >> 3, dma_p = lane & 7;
     uint32_t voffs[8];
+    const uint32_t dma_chunk = (uint32_t)((dma_p ^ ((dma_row >> 1) + 4 * (wave & 1))) << 4);
 #pragma unroll
     for (int p8 = 0; p8 < 8; ++p8)
-        voffs[p8] = (uint32_t)(p8 * 32 + wave * 8 + dma_row) * (uint32_t)g.K +
-                    (uint32_t)((dma_p ^ ((dma_row >> 1) + 4 * (wave & 1))) << 4);
+        voffs[p8] = (uint32_t)(p8 * 32 + wave * 8 + dma_row) * (uint32_t)g.K + dma_chunk;
+    // A rows of a ragged last tile are clamped to the last valid one (EDGE only)
+    uint32_t voffs_a[T::EDGE ? T::NA : 1];
     struct Stream {
         const uint8_t *ptr;  // first row of the tile's panel, at the stage to load next
         int s, id;           // that stage and its tile id
-        uint32_t bufoff;     // LDS buffer it goes to: 0 or STAGE_BYTES
+        uint32_t bufoff;     // LDS buffer it goes to: 0 or STAGE_STRIDE
     };
     Stream sa, sb;
     auto stream_set = [&](Stream &st, bool is_b) {
@@ -110,11 +124,21 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
         tile_from_id(st.id, g.tiles_m, g.tiles_n, tm, tn);
         st.ptr = is_b ? g.B + (int64_t)tn * T::BN * g.K : g.A + (int64_t)tm * T::BM * g.K;
         st.s = 0;
+        if constexpr (T::EDGE) {
+            if (!is_b) {
+                const int valid = g.M - tm * T::BM;  // >= 1
+#pragma unroll
+                for (int p8 = 0; p8 < T::NA; ++p8) {
+                    const int r = p8 * 32 + wave * 8 + dma_row;
+                    voffs_a[p8] = (uint32_t)(r < valid ? r : valid - 1) * (uint32_t)g.K + dma_chunk;
+                }
+            }
+        }
     };
     // Past the workgroup's last stage a stream keeps re-reading that stage (in bounds) into
     // buffers nobody multiplies from any more: the main loop stays free of branches.
     auto stream_advance = [&](Stream &st, bool is_b) {
-        st.bufoff ^= T::STAGE_BYTES;
+        st.bufoff ^= T::STAGE_STRIDE;
         if (st.s + 1 < kt) {
             ++st.s;
             st.ptr += T::BK;
@@ -127,7 +151,7 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
         const uint32_t dst0 = lds_base + (p8 * 4 + wave) * 1024;
         asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
                      :
-                     : "s"(dst0), "s"(sa.bufoff), "v"(voffs[p8]), "s"(sa.ptr)
+                     : "s"(dst0), "s"(sa.bufoff), "v"(T::EDGE ? voffs_a[T::EDGE ? p8 : 0] : voffs[p8]), "s"(sa.ptr)
                      : "memory", "m0", "scc");
     };
     auto dma_piece_b = [&](int p8) {
@@ -147,8 +171,8 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     for (int kk = 0; kk < 2; ++kk) {
         const int c0 = INT8 ? 4 * kk + lh : 4 * kk + 2 * lh;
         const int c1 = INT8 ? 4 * kk + 2 + lh : 4 * kk + 2 * lh + 1;
-        pa[kk][0] = (wm * 128 + l31) * T::BK + ((c0 ^ sw) << 4);
-        pa[kk][1] = (wm * 128 + l31) * T::BK + ((c1 ^ sw) << 4);
+        pa[kk][0] = (wm * MT * 32 + l31) * T::BK + ((c0 ^ sw) << 4);
+        pa[kk][1] = (wm * MT * 32 + l31) * T::BK + ((c1 ^ sw) << 4);
         pb[kk][0] = T::A_BYTES + (wn * 128 + l31) * T::BK + ((c0 ^ sw) << 4);
         pb[kk][1] = T::A_BYTES + (wn * 128 + l31) * T::BK + ((c1 ^ sw) << 4);
     }
@@ -157,8 +181,8 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                pa[kk][h] ^= T::STAGE_BYTES;
-                pb[kk][h] ^= T::STAGE_BYTES;
+                pa[kk][h] ^= T::STAGE_STRIDE;
+                pb[kk][h] ^= T::STAGE_STRIDE;
             }
     };
     v8i fa[2], fb[4];
@@ -174,7 +198,7 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     };
 
     using acc_t = typename std::conditional<INT8, v16i, v16f>::type;
-    acc_t acc[4][4];
+    acc_t acc[MT][4];
     // The MFMAs are written as asm with accumulator-register constraints: the 256 accumulators
     // fill the accumulation register file exactly, and only a hard constraint keeps the register
     // allocator from parking blocks in VGPRs and copying them around every use.  Consecutive
@@ -182,41 +206,44 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     // from LDS reads (the compiler's own s_waitcnt covers asm operands).  The one software-visible
     // hazard, reading a block right after its last MFMA, is avoided by the schedule: a block is
     // converted at least two slots after that MFMA was issued.
-    auto mfma = [&](int i, int j) {
+    // the A fragment of row i of slab kk sits in fa[(kk * MT + i) % 2]
+    auto mfma = [&](int kk, int i, int j) {
+        const int ab = (kk * MT + i) & 1;
         if constexpr (INT8) {
-            const v4i a0 = {fa[i & 1][0], fa[i & 1][1], fa[i & 1][2], fa[i & 1][3]};
-            const v4i a1 = {fa[i & 1][4], fa[i & 1][5], fa[i & 1][6], fa[i & 1][7]};
+            const v4i a0 = {fa[ab][0], fa[ab][1], fa[ab][2], fa[ab][3]};
+            const v4i a1 = {fa[ab][4], fa[ab][5], fa[ab][6], fa[ab][7]};
             const v4i b0 = {fb[j][0], fb[j][1], fb[j][2], fb[j][3]};
             const v4i b1 = {fb[j][4], fb[j][5], fb[j][6], fb[j][7]};
             asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0\n\tv_mfma_i32_32x32x32_i8 %0, %3, %4, %0"
                          : "+a"(acc[i][j])
                          : "v"(b0), "v"(a0), "v"(b1), "v"(a1));
         } else {
-            asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[j]), "v"(fa[i & 1]));
+            asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[j]), "v"(fa[ab]));
         }
     };
     // first MFMA of a block in a tile: accumulates onto zero
-    auto mfma_first = [&](int i, int j) {
+    auto mfma_first = [&](int kk, int i, int j) {
+        const int ab = (kk * MT + i) & 1;
         if constexpr (INT8) {
-            const v4i a0 = {fa[i & 1][0], fa[i & 1][1], fa[i & 1][2], fa[i & 1][3]};
-            const v4i a1 = {fa[i & 1][4], fa[i & 1][5], fa[i & 1][6], fa[i & 1][7]};
+            const v4i a0 = {fa[ab][0], fa[ab][1], fa[ab][2], fa[ab][3]};
+            const v4i a1 = {fa[ab][4], fa[ab][5], fa[ab][6], fa[ab][7]};
             const v4i b0 = {fb[j][0], fb[j][1], fb[j][2], fb[j][3]};
             const v4i b1 = {fb[j][4], fb[j][5], fb[j][6], fb[j][7]};
             asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, 0\n\tv_mfma_i32_32x32x32_i8 %0, %3, %4, %0"
                          : "=&a"(acc[i][j])
                          : "v"(b0), "v"(a0), "v"(b1), "v"(a1));
         } else {
-            asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, 0" : "=&a"(acc[i][j]) : "v"(fb[j]), "v"(fa[i & 1]));
+            asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, 0" : "=&a"(acc[i][j]) : "v"(fb[j]), "v"(fa[ab]));
         }
     };
 
     // ---- deferred epilogue -----------------------------------------------------------------
     // packed[i][j][2q+h]: bf16 pair (rows l31, columns j*32 + 8q + 4lh + 2h, +1) of block (i, j)
-    uint32_t packed[4][4][8];
+    uint32_t packed[MT][4][8];
     float pen = 0.0f;
     // half h of block b = h/2 (i = b/4, j = b%4): accumulator words 8*(h%2) .. +7
     auto convert_half = [&](int h) {
-        const int i = h >> 3, j = (h >> 1) & 3, q0 = (h & 1) * 2;
+        const int i = h >> 3, j = (h >> 1) & 3, q0 = (h & 1) * 2;  // block h/2 = 4i + j
         typedef typename std::conditional<INT8, int, float>::type word_t;
         word_t t[8];
         asm volatile("v_accvgpr_read_b32 %0, %8\n\tv_accvgpr_read_b32 %1, %9\n\t"
@@ -253,9 +280,12 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     const uint8_t *sp = nullptr;
     const int64_t rows32 = (int64_t)g.N * 64;
     const uint32_t out_lane = (uint32_t)l31 * (uint32_t)g.N * 2u + (uint32_t)lh * 16u;
+    int prow_left = 0;  // EDGE: rows of the wave's sub-tile inside the matrix, for the tile in `packed`
     auto store_begin = [&](int tm, int tn) {
+        if constexpr (T::EDGE)
+            prow_left = g.M - tm * T::BM - wm * MT * 32;
         sp = (const uint8_t *)g.out +
-             (((int64_t)tm * T::BM + wm * 128) * g.N + (int64_t)tn * T::BN + wn * 128) * 2;
+             (((int64_t)tm * T::BM + wm * MT * 32) * g.N + (int64_t)tn * T::BN + wn * 128) * 2;
     };
     // Micro-step q of writing a tile out: block q / 8 (in conversion order), column half
     // P = (q % 8) / 4 (register words 4P .. 4P+3 = columns 16P .. 16P+15 of the block).  Step 0
@@ -266,18 +296,23 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
         const int b = q / T::STEPS_PER_BLOCK, i = b >> 2, j = b & 3;
         const int P = (q % T::STEPS_PER_BLOCK) >> 2, k = q & 3;
         uint32_t *w = &packed[i][j][4 * P];
+        const bool row_ok = !T::EDGE || i * 32 + l31 < prow_left;
         if (k == 0) {
             // the swap reads its operands early: two wait states after a vector-ALU write (the
             // compiler may have placed a register copy right in front of this statement)
             asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %2\n\tv_permlane32_swap_b32 %1, %3"
                          : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]));
         } else if (k == 1) {
-            pen_word(w[0]);
-            pen_word(w[1]);
+            if (PMODE != 0 && row_ok) {
+                pen_word(w[0]);
+                pen_word(w[1]);
+            }
         } else if (k == 2) {
-            pen_word(w[2]);
-            pen_word(w[3]);
-        } else {
+            if (PMODE != 0 && row_ok) {
+                pen_word(w[2]);
+                pen_word(w[3]);
+            }
+        } else if (row_ok) {
             const v4i v = {(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
             // a store of more than 8 bytes reads its data late: nothing may write those
             // registers in the next wait states (the compiler does not know this is a store)
@@ -285,9 +320,9 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
                          :
                          : "v"(out_lane), "v"(v), "s"(sp), "n"(j * 64 + P * 32)
                          : "memory");
-            if (j == 3 && P == 1)
-                sp += rows32;
         }
+        if (k == 3 && j == 3 && P == 1)
+            sp += rows32;
     };
 
     // The penalty terms are summed per lane over every tile of the workgroup (a few thousand
@@ -309,24 +344,24 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     // micro-steps are dealt evenly over the slots of the first D stages, from slot 2 on.  FIRST: a
     // tile starts (1: the workgroup's first tile, 2: a later one, which also converts the last
     // half blocks of its predecessor).  LAST: a tile ends: its blocks are converted as they finish.
-    constexpr int W = D * 32 - 2;
+    constexpr int W = D * T::SLOTS - 2;
     auto stage = [&](auto dr_c, auto first_c, auto last_c) {
         constexpr int DR = decltype(dr_c)::value, FIRST = decltype(first_c)::value;
         constexpr bool LAST = decltype(last_c)::value;
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < MT; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int t = kk * 16 + i * 4 + j;
-                    if (t == 16) {
+                    const int t = kk * T::SLAB + i * 4 + j;
+                    if (t == T::SLAB) {
                         // every wave has read the B half of this stage (its slab-1 fragments were
-                        // requested in slots 12..15): the half can be refilled
+                        // requested in the last four slots of slab 0): the half can be refilled
                         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                         block_barrier();
                     }
-                    if (t == 28) {
+                    if (t == T::SLOTS - 4) {
                         // every LDS read of this stage has been issued: wait for them and for this
                         // wave's share of the next stage (everything but the eight B pieces of the
                         // stage after next, the youngest loads), then publish
@@ -335,40 +370,40 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
                         flip_stage();
                     }
                     if (FIRST != 0 && kk == 0)
-                        mfma_first(i, j);
+                        mfma_first(kk, i, j);
                     else
-                        mfma(i, j);
+                        mfma(kk, i, j);
                     if (j == 0) {
-                        if (i < 3)
-                            load_a(fa[(i + 1) & 1], kk, i + 1);
+                        if (i < MT - 1)
+                            load_a(fa[(kk * MT + i + 1) & 1], kk, i + 1);
                         else
-                            load_a(fa[0], kk ^ 1, 0);  // next slab (after the flip: next stage)
+                            load_a(fa[((kk ^ 1) * MT) & 1], kk ^ 1, 0);  // next slab (after the flip: next stage)
                     }
-                    if (i == 3)
+                    if (i == MT - 1)
                         load_b(fb[j], kk ^ 1, j);
                     // operand stream, at most one piece per slot: A of the next stage (second
-                    // half of its pieces) in slots 0..3, B of the stage after next in slots 16..23
-                    // (its buffer half was released at slot 16), A of the stage after next (first
-                    // half) in slots 28..31 (released at slot 28)
-                    if (t < 4) {
-                        dma_piece_a(4 + t);
-                        if (t == 3)
+                    // half of its pieces) in the first slots, B of the stage after next right
+                    // behind the first barrier (which released its buffer half), A of the stage
+                    // after next (first half) behind the second barrier
+                    if (t < T::NA / 2) {
+                        dma_piece_a(T::NA / 2 + t);
+                        if (t == T::NA / 2 - 1)
                             stream_advance(sa, false);
-                    } else if (t >= 16 && t < 24) {
-                        dma_piece_b(t - 16);
-                        if (t == 23)
+                    } else if (t >= T::SLAB && t < T::SLAB + T::NBP) {
+                        dma_piece_b(t - T::SLAB);
+                        if (t == T::SLAB + T::NBP - 1)
                             stream_advance(sb, true);
-                    } else if (t >= 28) {
-                        dma_piece_a(t - 28);
+                    } else if (t >= T::SLOTS - 4 && t < T::SLOTS - 4 + T::NA / 2) {
+                        dma_piece_a(t - (T::SLOTS - 4));
                     }
                     // conversion of the tile that ends here / ended in the previous stage
 #pragma unroll
                     for (int h = 0; h < T::HALVES; ++h)
-                        if ((LAST && T::convert_slot(h) == t) || (FIRST == 2 && T::convert_slot(h) == t + 32))
+                        if ((LAST && T::convert_slot(h) == t) || (FIRST == 2 && T::convert_slot(h) == t + T::SLOTS))
                             convert_half(h);
                     // write-out of the previous tile
                     if (DR >= 0) {
-                        const int w = DR * 32 + t - 2;
+                        const int w = DR * T::SLOTS + t - 2;
                         if (w >= 0 && w < W) {
                             const int q_lo = (w * T::DRAIN_STEPS + W - 1) / W;
                             const int q_hi = ((w + 1) * T::DRAIN_STEPS + W - 1) / W;
@@ -388,26 +423,26 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     typedef integral_constant<int, -1> no_drain;
     typedef integral_constant<int, 0> mid;
 
-    // ---- prologue: stage 0 whole, B of stage 1, the first four A pieces of stage 1 ----------
+    // ---- prologue: stage 0 whole, B of stage 1, the first half of the A pieces of stage 1 ----
     sa.id = sb.id = slot;
     sa.bufoff = sb.bufoff = 0;
     stream_set(sa, false);
     stream_set(sb, true);
 #pragma unroll
-    for (int p8 = 0; p8 < 8; ++p8)
+    for (int p8 = 0; p8 < T::NA; ++p8)
         dma_piece_a(p8);
     stream_advance(sa, false);
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
 #pragma unroll
-        for (int p8 = 0; p8 < 8; ++p8)
+        for (int p8 = 0; p8 < T::NBP; ++p8)
             dma_piece_b(p8);
         stream_advance(sb, true);
     }
 #pragma unroll
-    for (int p8 = 0; p8 < 4; ++p8)
+    for (int p8 = 0; p8 < T::NA / 2; ++p8)
         dma_piece_a(p8);
-    wait_vmcnt<12>();
+    wait_vmcnt<T::NBP + T::NA / 2>();
     block_barrier();
     load_a(fa[0], 0, 0);
 #pragma unroll
@@ -460,7 +495,7 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
     // the stage buffers and comes back with 16 lanes per row: whole 128-byte lines per store.
 #pragma unroll
     for (int h = 0; h < T::HALVES; ++h)
-        if (T::convert_slot(h) >= 32) {
+        if (T::convert_slot(h) >= T::SLOTS) {
             convert_half(h);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -474,7 +509,7 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
         const uint32_t lane_off = (uint32_t)(lane >> 4) * (uint32_t)g.N * 2u + (uint32_t)(lane & 15) * 16u;
         const int64_t rows4 = (int64_t)g.N * 8;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < MT; ++i) {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -483,10 +518,12 @@ __global__ __launch_bounds__(DeferTile::THREADS, 1) void gemm_nt_defer_kernel(Ge
 #pragma unroll
             for (int ps = 0; ps < 8; ++ps) {
                 const v4i d = *(const v4i *)(tb_rd + ps * 4 * ROW);
+                if (!T::EDGE || i * 32 + ps * 4 + (lane >> 4) < prow_left) {
 #pragma unroll
-                for (int w = 0; w < 4; ++w)
-                    pen_word((uint32_t)d[w]);
-                asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" : : "v"(lane_off), "v"(d), "s"(sp) : "memory");
+                    for (int w = 0; w < 4; ++w)
+                        pen_word((uint32_t)d[w]);
+                    asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" : : "v"(lane_off), "v"(d), "s"(sp) : "memory");
+                }
                 sp += rows4;
             }
         }

@@ -103,13 +103,45 @@ def test_fwd_deferred_epilogue_kernel(case):
     assert np.array_equal(outs[0], outs[1])  # the penalty does not change the stored output
 
 
-@pytest.mark.parametrize("shape", [(16384, 2048, 6144), (16384, 5632, 2048), (8192, 768, 3072), (4096, 512, 16384)])
+# the 192x256 flavour of the deferred-epilogue kernel (variant 16): any M (rows past M in the last
+# row of tiles are loaded as copies, never stored or penalised), K >= 2048; 22 x 12 = 264 tiles
+# give some workgroups a second tile
+DEFER192_CASES = [
+    (3, 0, 448, 2048, 512),
+    (3, 1, 4160, 2048, 3072),
+    (2, 0, 1000 // 8 * 8, 2304, 256),
+]
+
+
+@pytest.mark.parametrize("case", DEFER192_CASES)
+def test_fwd_deferred_epilogue_kernel_192(case):
+    cfg, gi, M, K, N = case
+    say("fwd deferred 192 cfg=%d gemm=%d M=%d K=%d N=%d" % (cfg, gi, M, K, N))
+    x, w, _ = synth.fp8_linear_inputs(cfg, gi, M=M, K=K, N=N)
+    xq, _, sxi = oracle_quantized(x)
+    wq, _, swi = oracle_quantized(w)
+    ref, refabs, refbf = oracle.fp8_linear_fwd(xq, wq, sxi, swi)
+    for pen in (PEN, None):
+        tw.tweo_set_gemm_tile(16)
+        try:
+            got, S = run_fwd(xq, wq, sxi, swi, M, N, K, pen=pen)
+        finally:
+            tw.tweo_set_gemm_tile(0)
+        check_gemm(got, ref, refabs, K, "fwd")
+        if pen:
+            Sref = oracle.penalty_sum(refbf, *PEN)
+            check_penalty(S, got, refbf, Sref, PEN, strict=M * N >= 1 << 20)
+
+
+@pytest.mark.parametrize("shape", [(16384, 2048, 6144, 15), (16384, 5632, 2048, 15), (8192, 768, 3072, 15),
+                                   (4096, 512, 16384, 15), (6144, 16384, 2048, 16), (5632, 16384, 2048, 16),
+                                   (2048, 16384, 5632, 16), (12352, 2048, 4096, 16)])
 def test_fwd_deferred_kernel_matches_streaming_kernel_bitwise(shape):
     # Both kernels add a block's K slabs in the same order with the same MFMA, so their outputs
     # are the same bits; at these sizes every workgroup owns several tiles (first tile, tiles
     # written out under their successor, last tile), twice over to catch anything left behind
-    M, K, N = shape
-    say("fwd deferred vs streaming M=%d K=%d N=%d" % (M, K, N))
+    M, K, N, variant = shape
+    say("fwd deferred (variant %d) vs streaming M=%d K=%d N=%d" % (variant, M, K, N))
     g = torch.Generator(device=DEV)
     g.manual_seed(M + 3 * K + 7 * N)
     xq = torch.randint(0, 0x78, (M, K), dtype=torch.uint8, device=DEV, generator=g)
@@ -118,7 +150,7 @@ def test_fwd_deferred_kernel_matches_streaming_kernel_bitwise(shape):
     sc = scalar_f32(0.01)
     ws = workspace(tw.TWEO_OP_FP8_LINEAR_FWD, M, N, K)
     outs, sums = [], []
-    for tile in (11, 15, 15):
+    for tile in (11, variant, variant):
         y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)
         S = torch.zeros(2, dtype=torch.float64, device=DEV)
         tw.tweo_set_gemm_tile(tile)
