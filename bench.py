@@ -47,6 +47,7 @@ class Layer:
         self.dyq, self.dyqT = u8(M, N), u8(N, M)
         self.y, self.dx, self.dw = bf(M, N), bf(M, K), bf(N, K)
         self.sc = torch.zeros(16, dtype=torch.float32, device=dev)
+        self.saved = tw.make_saved(self.xq, self.xqT, self.wq, self.wqT, self.sc)
         self.S = torch.zeros(2, dtype=torch.float64, device=dev)
         self.ws = torch.empty(tw.tweo_workspace_bytes(tw.TWEO_OP_FP8_LINEAR_FWD_BF16, M, N, K),
                               dtype=torch.uint8, device=dev)
@@ -56,28 +57,16 @@ class Layer:
 
 
 def run_step(tw, layers, ev=None):
-    """The whole path through the low-level entry points (the same launches the *_bf16 wrappers
-    make), so that the GEMM launches can be bracketed by events."""
+    """The whole path through the two bf16 entry points: amax and casts of X and W, forward GEMM
+    with the penalty epilogue and its finishing sum; amax and cast of dY, dgrad and wgrad GEMMs.
+    `ev`: the three GEMM kernels of every layer record their own start and end events."""
     for L in layers:
-        sc = L.sc
-        tw.tweo_amax(L.x, sc[0:1])
-        tw.tweo_amax(L.w, sc[4:5])
-        tw.tweo_quantize_e4m3(L.x, sc[0:1], L.xq, L.xqT, sc[1:2], sc[2:3])
-        tw.tweo_quantize_e4m3(L.w, sc[4:5], L.wq, L.wqT, sc[5:6], sc[6:7])
         if ev is not None:
-            ev.start()
-        tw.tweo_fp8_linear_fwd(L.xq, sc[2:3], L.wq, sc[6:7], L.y, pen=PEN, penalty_sum=L.S,
-                               workspace=L.ws)
+            ev.arm(1, 2.0 * L.M * L.N * L.K)
+        tw.tweo_fp8_linear_fwd_bf16(L.x, L.w, L.y, L.saved, pen=PEN, penalty_sum=L.S, workspace=L.ws)
         if ev is not None:
-            ev.stop(2.0 * L.M * L.N * L.K)
-        tw.tweo_amax(L.dy, sc[8:9])
-        tw.tweo_quantize_e4m3(L.dy, sc[8:9], L.dyq, L.dyqT, sc[9:10], sc[10:11])
-        if ev is not None:
-            ev.start()
-        tw.tweo_fp8_linear_bwd(L.dyq, L.dyqT, sc[10:11], L.wqT, sc[6:7], L.xqT, sc[2:3], L.M, L.N,
-                               L.K, L.dx, L.dw, L.ws)
-        if ev is not None:
-            ev.stop(4.0 * L.M * L.N * L.K)
+            ev.arm(2, 2.0 * L.M * L.N * L.K)
+        tw.tweo_fp8_linear_bwd_bf16(L.dy, L.saved, L.K, L.dyq, L.dyqT, L.dx, L.dw, L.ws)
 
 
 def run_step_delayed(tw, layers, bootstrap=False):
@@ -96,23 +85,29 @@ def run_step_delayed(tw, layers, bootstrap=False):
 
 
 class GemmEvents:
-    """HIP events on the launch stream around the GEMM launches of the timed steps."""
+    """HIP events that the GEMM kernels of the timed steps record at their own start and end
+    (tweo_profile_gemm_launches: hipExtLaunchKernelGGL on the launch stream), so that a pair
+    times one kernel launch, like a profiler's kernel trace does, without draining the stream."""
 
-    def __init__(self, torch):
-        self.torch, self.pairs, self.flops = torch, [], 0.0
+    def __init__(self, torch, tw):
+        self.torch, self.tw, self.pairs, self.flops = torch, tw, [], []
 
-    def start(self):
-        self._s = self.torch.cuda.Event(enable_timing=True)
-        self._s.record()
-
-    def stop(self, flops):
+    def _event(self):
         e = self.torch.cuda.Event(enable_timing=True)
-        e.record()
-        self.pairs.append((self._s, e))
-        self.flops += flops
+        e.record()  # creates the handle
+        return e
 
-    def total_ms(self):
-        return sum(s.elapsed_time(e) for s, e in self.pairs)
+    def arm(self, launches, flops_each):
+        evs = []
+        for _ in range(launches):
+            s, e = self._event(), self._event()
+            self.pairs.append((s, e))
+            self.flops.append(flops_each)
+            evs += [s.cuda_event, e.cuda_event]
+        self.tw.tweo_profile_gemm_launches(evs)
+
+    def durations_ms(self):
+        return [s.elapsed_time(e) for s, e in self.pairs]
 
 
 def time_elementwise(tw, torch, L, iters=20):
@@ -271,28 +266,28 @@ def main():
     for _ in range(a.warmup):
         run_step(tw, layers)
     torch.cuda.synchronize()
-    # HIP events bracket the GEMM launches of every EVENT_EVERY-th timed step (an event costs the
-    # stream ~5 us, four per layer: bracketing every step would tax the whole-step figure by 3 %)
-    ev = GemmEvents(torch)
-    evented = sum(1 for i in range(a.steps) if i % EVENT_EVERY == 0)
+    # The GEMM kernels of every EVENT_EVERY-th timed step record their own start/end events.
+    ev = GemmEvents(torch, tw)
     t0 = time.perf_counter()
     for i in range(a.steps):
         run_step(tw, layers, ev if i % EVENT_EVERY == 0 else None)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / a.steps
-    gemm_ms = ev.total_ms()
-    # per-call detail on stderr: the event pairs alternate forward, backward per layer
+    dur = ev.durations_ms()
+    gemm_ms = sum(dur)
+    # per-kernel detail on stderr: three launches per layer per timed step (fwd, dgrad, wgrad)
+    per_step = 3 * len(layers)
     for li, L in enumerate(layers):
-        f = [s.elapsed_time(e) for k, (s, e) in enumerate(ev.pairs) if k % (2 * len(layers)) == 2 * li]
-        b = [s.elapsed_time(e) for k, (s, e) in enumerate(ev.pairs) if k % (2 * len(layers)) == 2 * li + 1]
         fl = 2.0 * L.M * L.N * L.K
-        log("  %-5s fwd %7.1f us %6.0f TFLOP/s   bwd (dgrad+wgrad) %7.1f us %6.0f TFLOP/s" % (
-            L.name, 1e3 * sum(f) / len(f), fl / (sum(f) / len(f)) / 1e9,
-            1e3 * sum(b) / len(b), 2 * fl / (sum(b) / len(b)) / 1e9))
-    n_gemm_launches = evented * len(layers) * 3
+        parts = []
+        for k, name in enumerate(("fwd", "dgrad", "wgrad")):
+            d = [dur[j] for j in range(len(dur)) if j % per_step == 3 * li + k]
+            parts.append("%s %7.1f us %5.0f TFLOP/s" % (name, 1e3 * sum(d) / len(d), fl / (sum(d) / len(d)) / 1e9))
+        log("  %-5s %s" % (L.name, "   ".join(parts)))
+    n_gemm_launches = len(dur)
     value = step_flops / (ms_per_step * 1e-3) / 1e12
-    gemm_tflops = ev.flops / (gemm_ms * 1e-3) / 1e12
+    gemm_tflops = sum(ev.flops) / (gemm_ms * 1e-3) / 1e12
 
     out = {
         "metric": "FP8 linear fwd+bwd TFLOP/s (+penalty), end to end from bf16 operands",
@@ -304,7 +299,7 @@ def main():
                    "gemms": ["%s %dx%dx%d" % (L.name, L.M, L.K, L.N) for L in layers],
                    "flop_per_step": step_flops, "penalty": "tau=3 p=4 eps=1e-6, fused",
                    "tile": a.tile},
-        "roofline": {"bound": "mfma", "kernel": "gemm_nt_stream_kernel (fp8 fwd/dgrad/wgrad)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_nt_defer_kernel / gemm_nt_stream_kernel (fp8 fwd, dgrad, wgrad)",
                      "achieved": round(gemm_tflops, 2), "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tflops / FP8_PEAK_TFLOPS, 4),
                      "traffic": profiled_traffic(a.workload) if a.tile == 0 else None,

@@ -249,9 +249,24 @@ tweo_status tweo_fp8_linear_bwd_bf16(const void *dy_bf16, const tweo_fp8_saved *
  * TWEO_ERR_INVALID_ARG for an unknown variant.  Variant 15 is the
  * deferred-epilogue persistent kernel (256x256 tiles, M and N multiples of 256,
  * K a multiple of 128 and at least 512, no residual, p in {0, 4}); it falls back
- * to variant 11 otherwise.
+ * to variant 11 otherwise.  Variant 16 is the same kernel on 192x256 tiles (any
+ * M, N a multiple of 256, K a multiple of 128 and at least 2048); it falls back
+ * to variant 14 otherwise.
  */
 tweo_status tweo_set_gemm_tile(int variant);
+
+/*
+ * Measurement hook for benchmarks: the next `pairs` GEMM kernels that the
+ * library launches (FP8 or INT8, any entry point) record events[2i] when the
+ * kernel starts and events[2i + 1] when it ends, i.e. the kernel's own duration
+ * (events recorded on the stream around a call also time the gap that recording
+ * them opens in front of the kernel).  `events`: host array of 2 * pairs
+ * hipEvent_t handles created by the caller with timing enabled; at most 8
+ * pairs; pairs = 0 cancels.  Process-wide, not thread safe.  Returns
+ * TWEO_ERR_INVALID_ARG for a null handle, TWEO_ERR_UNSUPPORTED for more than 8
+ * pairs.
+ */
+tweo_status tweo_profile_gemm_launches(void *const *events, int pairs);
 
 /* Switch the K-splitting of a GEMM's last, partial round of tiles (see
  * tweo_workspace_bytes) on (non-zero) or off (0, the default: on MI355X the

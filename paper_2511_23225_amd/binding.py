@@ -20,7 +20,7 @@ EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quan
            "tweo_fp8_linear_fwd", "tweo_fp8_linear_bwd", "tweo_quantize_i8", "tweo_w8a8_linear",
            "tweo_fp8_linear_fwd_bf16", "tweo_fp8_linear_bwd_bf16", "tweo_set_gemm_tile",
            "tweo_set_stream_k", "tweo_penalty_grad_inject", "tweo_delayed_state_bytes",
-           "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed")
+           "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed", "tweo_profile_gemm_launches")
 
 
 class TweoError(RuntimeError):
@@ -69,6 +69,7 @@ def load():
                                            vp, vp, sz, vp]
     L.tweo_set_gemm_tile.argtypes = [ctypes.c_int]
     L.tweo_set_stream_k.argtypes = [ctypes.c_int]
+    L.tweo_profile_gemm_launches.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
     L.tweo_delayed_state_bytes.argtypes = []
     L.tweo_delayed_state_bytes.restype = ctypes.c_size_t
     L.tweo_delayed_state_init.argtypes = [vp, vp]
@@ -122,6 +123,13 @@ def tweo_set_gemm_tile(variant):
 
 def tweo_set_stream_k(on):
     _check(load().tweo_set_stream_k(1 if on else 0), "tweo_set_stream_k")
+
+
+def tweo_profile_gemm_launches(events):
+    """events: flat list of hipEvent_t handles (ints), start/stop per upcoming GEMM kernel launch."""
+    n = len(events)
+    arr = (ctypes.c_void_p * max(n, 1))(*[ctypes.c_void_p(int(e)) for e in events])
+    _check(load().tweo_profile_gemm_launches(arr, n // 2), "tweo_profile_gemm_launches")
 
 
 def tweo_penalty_grad_inject(dy_bf16, a_bf16, pen, g, out_bf16):

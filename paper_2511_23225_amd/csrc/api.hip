@@ -61,6 +61,16 @@ tweo_status tweo_set_stream_k(int on)
     return TWEO_OK;
 }
 
+tweo_status tweo_profile_gemm_launches(void *const *events, int pairs)
+{
+    if (pairs < 0 || (pairs > 0 && !events))
+        return TWEO_ERR_INVALID_ARG;
+    for (int i = 0; i < 2 * pairs; ++i)
+        if (!events[i])
+            return TWEO_ERR_INVALID_ARG;
+    return set_profile_events(events, pairs) ? TWEO_OK : TWEO_ERR_UNSUPPORTED;
+}
+
 tweo_status tweo_set_gemm_tile(int variant)
 {
     if (variant < 0 || variant > gemm_num_variants())
@@ -316,14 +326,13 @@ tweo_status tweo_fp8_linear_fwd_bf16(const void *x_bf16, const void *w_bf16,
     hipStream_t s = (hipStream_t)stream;
     float *sc = saved->scalars;
     hipError_t e = launch_fill_u32((uint32_t *)sc, 6, 0u, s);
+    // activation and weight share one amax launch and one cast launch (a kernel of its own for
+    // the small weight tensor is mostly launch and tail latency)
     if (e == hipSuccess)
-        e = launch_amax(x_bf16, M * K, sc + 0, s);
+        e = launch_amax2(x_bf16, M * K, sc + 0, w_bf16, N * K, sc + 3, s);
     if (e == hipSuccess)
-        e = launch_amax(w_bf16, N * K, sc + 3, s);
-    if (e == hipSuccess)
-        e = launch_quantize_e4m3(x_bf16, M, K, sc + 0, saved->xq, saved->xqT, sc + 1, sc + 2, s);
-    if (e == hipSuccess)
-        e = launch_quantize_e4m3(w_bf16, N, K, sc + 3, saved->wq, saved->wqT, sc + 4, sc + 5, s);
+        e = launch_quantize2_e4m3(x_bf16, M, K, sc + 0, saved->xq, saved->xqT, sc + 1, sc + 2, w_bf16, N, K,
+                                  sc + 3, saved->wq, saved->wqT, sc + 4, sc + 5, s);
     if (e != hipSuccess)
         return TWEO_ERR_HIP;
     return tweo_fp8_linear_fwd(saved->xq, sc + 2, saved->wq, sc + 5, residual_bf16, M, N, K, y_bf16,

@@ -52,13 +52,12 @@ __device__ __forceinline__ uint32_t pk_absmax4(uint32_t m, uint4 v)
 // grid-stride walk, whose concurrent streams are megabytes apart).
 constexpr int kAmaxUnroll = 8;
 
-__global__ __launch_bounds__(kAmaxThreads) void amax_kernel(const uint4 *__restrict__ x,
-                                                            int64_t n_vec, int64_t per_block,
-                                                            const uint16_t *__restrict__ tail,
-                                                            int n_tail, uint32_t *out)
+__device__ __forceinline__ void amax_body(const uint4 *__restrict__ x, int64_t n_vec, int64_t per_block,
+                                          int block, const uint16_t *__restrict__ tail, int n_tail,
+                                          uint32_t *out)
 {
     __shared__ uint32_t red[kAmaxThreads / kWave];
-    const int64_t b0 = (int64_t)blockIdx.x * per_block;
+    const int64_t b0 = (int64_t)block * per_block;
     const int64_t b1 = b0 + per_block < n_vec ? b0 + per_block : n_vec;
     int64_t i = b0 + threadIdx.x;
     uint32_t m = 0;
@@ -73,7 +72,7 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_kernel(const uint4 *__restr
     }
     for (; i < b1; i += kAmaxThreads)
         m = pk_absmax4(m, x[i]);
-    if (blockIdx.x == 0 && (int)threadIdx.x < n_tail)
+    if (block == 0 && (int)threadIdx.x < n_tail)
         m = pk_absmax(m, tail[threadIdx.x]);
     uint32_t r = (m & 0xFFFFu) > (m >> 16) ? (m & 0xFFFFu) : (m >> 16);
     r = wave_reduce_max_u32(r);
@@ -92,11 +91,29 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_kernel(const uint4 *__restr
     }
 }
 
-hipError_t launch_amax(const void *x_bf16, int64_t n, float *amax_zeroed, hipStream_t s)
+__global__ __launch_bounds__(kAmaxThreads) void amax_kernel(const uint4 *__restrict__ x,
+                                                            int64_t n_vec, int64_t per_block,
+                                                            const uint16_t *__restrict__ tail,
+                                                            int n_tail, uint32_t *out)
 {
-    const int64_t n_vec = n / 8;
-    const int n_tail = (int)(n % 8);
-    // chunks of at least 128 KB (one unrolled trip), at most one workgroup per CU
+    amax_body(x, n_vec, per_block, (int)blockIdx.x, tail, n_tail, out);
+}
+
+// Two tensors in one launch (the activation and the weight of a linear layer): workgroups
+// [0, blocks0) reduce the first, the rest the second.  Element counts are multiples of 8.
+__global__ __launch_bounds__(kAmaxThreads) void amax2_kernel(const uint4 *__restrict__ x0, int64_t n_vec0,
+                                                             int64_t per_block0, int blocks0, uint32_t *out0,
+                                                             const uint4 *__restrict__ x1, int64_t n_vec1,
+                                                             int64_t per_block1, uint32_t *out1)
+{
+    if ((int)blockIdx.x < blocks0)
+        amax_body(x0, n_vec0, per_block0, (int)blockIdx.x, nullptr, 0, out0);
+    else
+        amax_body(x1, n_vec1, per_block1, (int)blockIdx.x - blocks0, nullptr, 0, out1);
+}
+
+static int amax_cus()
+{
     static int cus = 0;
     if (cus == 0) {
         int dev = 0, v = 0;
@@ -106,6 +123,38 @@ hipError_t launch_amax(const void *x_bf16, int64_t n, float *amax_zeroed, hipStr
         else
             cus = 256;
     }
+    return cus;
+}
+
+hipError_t launch_amax2(const void *x0_bf16, int64_t n0, float *amax0_zeroed, const void *x1_bf16, int64_t n1,
+                        float *amax1_zeroed, hipStream_t s)
+{
+    // the workgroups of one wave over the CUs are shared out in proportion to the tensor sizes
+    const int cus = amax_cus();
+    const int64_t v0 = n0 / 8, v1 = n1 / 8;
+    const int64_t chunk = kAmaxUnroll * kAmaxThreads;
+    int64_t b1 = (int64_t)((double)cus * (double)v1 / (double)(v0 + v1) + 0.5);
+    if (b1 < 1)
+        b1 = 1;
+    if (b1 > cus - 1)
+        b1 = cus - 1;
+    int64_t b0 = cus - b1;
+    if (b0 > (v0 + chunk - 1) / chunk)
+        b0 = (v0 + chunk - 1) / chunk;
+    if (b1 > (v1 + chunk - 1) / chunk)
+        b1 = (v1 + chunk - 1) / chunk;
+    hipLaunchKernelGGL(amax2_kernel, dim3((unsigned)(b0 + b1)), dim3(kAmaxThreads), 0, s, (const uint4 *)x0_bf16, v0,
+                       (v0 + b0 - 1) / b0, (int)b0, (uint32_t *)amax0_zeroed, (const uint4 *)x1_bf16, v1,
+                       (v1 + b1 - 1) / b1, (uint32_t *)amax1_zeroed);
+    return hipGetLastError();
+}
+
+hipError_t launch_amax(const void *x_bf16, int64_t n, float *amax_zeroed, hipStream_t s)
+{
+    const int64_t n_vec = n / 8;
+    const int n_tail = (int)(n % 8);
+    // chunks of at least 128 KB (one unrolled trip), at most one workgroup per CU
+    const int cus = amax_cus();
     int64_t blocks = n_vec / (kAmaxUnroll * kAmaxThreads);
     if (blocks < 1)
         blocks = 1;
@@ -260,13 +309,13 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
 constexpr int kQuantBigTile = 256;
 
 template <bool WITH_T, bool DELAYED>
-__global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
+__device__ __forceinline__ void quantize_e4m3_16x16_body(
     const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
     const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
-    float *scale_out, float *scale_inv_out, uint32_t *amax_acc)
+    float *scale_out, float *scale_inv_out, uint32_t *amax_acc, int64_t block, int64_t n_blocks)
 {
     const float scale = DELAYED ? *amax : scale_from_amax(*amax);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (block == 0 && threadIdx.x == 0) {
         if (scale_out)
             *scale_out = scale;
         if (scale_inv_out)
@@ -276,8 +325,8 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
     uint32_t mx = 0;
     // DELAYED: a bounded grid walks the tiles (its one atomic per workgroup is then a few hundred
     // per tensor, not thousands); otherwise one tile per workgroup
-    const int64_t n_tiles = DELAYED ? tiles_x * ((rows + kQuantBigTile - 1) / kQuantBigTile) : (int64_t)blockIdx.x + 1;
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int64_t n_tiles = DELAYED ? tiles_x * ((rows + kQuantBigTile - 1) / kQuantBigTile) : block + 1;
+    for (int64_t tile = block; tile < n_tiles; tile += n_blocks) {
     const int64_t by = tile / tiles_x, bx = tile % tiles_x;
     const int64_t r0 = by * kQuantBigTile + (wave >> 1) * 128 + (lane >> 3) * 16;
     const int64_t c0 = bx * kQuantBigTile + (wave & 1) * 128 + (lane & 7) * 16;
@@ -327,6 +376,49 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
     // every lane reaches the one workgroup barrier of the amax commit
     if constexpr (DELAYED)
         quant_amax_commit(mx, amax_acc);
+}
+
+template <bool WITH_T, bool DELAYED>
+__global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
+    const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
+    const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
+    float *scale_out, float *scale_inv_out, uint32_t *amax_acc)
+{
+    quantize_e4m3_16x16_body<WITH_T, DELAYED>(x, rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out,
+                                              amax_acc, blockIdx.x, gridDim.x);
+}
+
+// Two tensors in one launch (activation and weight of a linear layer, each with its transposed
+// copy): workgroups [0, blocks0) cast the first, the rest the second.
+struct QuantTensor {
+    const uint16_t *x;
+    int64_t rows, cols, tiles_x;
+    const float *amax;
+    uint8_t *q, *qT;
+    float *scale_out, *scale_inv_out;
+};
+
+__global__ __launch_bounds__(kQuantThreads) void quantize2_e4m3_16x16_kernel(QuantTensor t0, int64_t blocks0,
+                                                                             QuantTensor t1)
+{
+    const bool first = (int64_t)blockIdx.x < blocks0;
+    const QuantTensor &t = first ? t0 : t1;
+    quantize_e4m3_16x16_body<true, false>(t.x, t.rows, t.cols, t.tiles_x, t.amax, t.q, t.qT, t.scale_out,
+                                          t.scale_inv_out, nullptr,
+                                          first ? (int64_t)blockIdx.x : (int64_t)blockIdx.x - blocks0, 1);
+}
+
+hipError_t launch_quantize2_e4m3(const void *x0_bf16, int64_t rows0, int64_t cols0, const float *amax0, uint8_t *q0,
+                                 uint8_t *q0T, float *scale0, float *scale0_inv, const void *x1_bf16,
+                                 int64_t rows1, int64_t cols1, const float *amax1, uint8_t *q1, uint8_t *q1T,
+                                 float *scale1, float *scale1_inv, hipStream_t s)
+{
+    auto tiles = [](int64_t v) { return (v + kQuantBigTile - 1) / kQuantBigTile; };
+    QuantTensor t0{(const uint16_t *)x0_bf16, rows0, cols0, tiles(cols0), amax0, q0, q0T, scale0, scale0_inv};
+    QuantTensor t1{(const uint16_t *)x1_bf16, rows1, cols1, tiles(cols1), amax1, q1, q1T, scale1, scale1_inv};
+    const int64_t b0 = tiles(rows0) * tiles(cols0), b1 = tiles(rows1) * tiles(cols1);
+    hipLaunchKernelGGL(quantize2_e4m3_16x16_kernel, dim3((unsigned)(b0 + b1)), dim3(kQuantThreads), 0, s, t0, b0, t1);
+    return hipGetLastError();
 }
 
 template <bool DELAYED>

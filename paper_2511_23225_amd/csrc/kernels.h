@@ -10,6 +10,14 @@ namespace tweo {
 
 hipError_t launch_fill_u32(uint32_t *p, int n, uint32_t v, hipStream_t s);
 hipError_t launch_amax(const void *x_bf16, int64_t n, float *amax_zeroed, hipStream_t s);
+// two tensors (element counts multiples of 8) in one launch
+hipError_t launch_amax2(const void *x0_bf16, int64_t n0, float *amax0_zeroed, const void *x1_bf16, int64_t n1,
+                        float *amax1_zeroed, hipStream_t s);
+// two tensors (rows and cols multiples of 16), each with its transposed copy, in one launch
+hipError_t launch_quantize2_e4m3(const void *x0_bf16, int64_t rows0, int64_t cols0, const float *amax0, uint8_t *q0,
+                                 uint8_t *q0T, float *scale0, float *scale0_inv, const void *x1_bf16,
+                                 int64_t rows1, int64_t cols1, const float *amax1, uint8_t *q1, uint8_t *q1T,
+                                 float *scale1, float *scale1_inv, hipStream_t s);
 hipError_t launch_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
                                 uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
                                 hipStream_t s);
@@ -48,6 +56,10 @@ hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s);
 size_t stream_k_workspace_bytes();
 void set_stream_k(bool on);
 bool stream_k_enabled();
+
+// Measurement hook: the next `pairs` GEMM kernel launches record events[2i] at their start and
+// events[2i+1] at their end (hipEvent_t handles); false if pairs is out of range.
+bool set_profile_events(void *const *events, int pairs);
 
 // Tile-shape override for benchmarking sweeps: 0 = heuristic.
 void set_gemm_tile_override(int variant);
