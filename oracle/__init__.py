@@ -44,6 +44,10 @@ def lib():
         L.orc_e4m3_decode.argtypes = [ctypes.c_uint8]
         L.orc_e4m3_encode.restype = ctypes.c_uint8
         L.orc_e4m3_encode.argtypes = [ctypes.c_float]
+        L.orc_e5m2_decode.restype = ctypes.c_double
+        L.orc_e5m2_decode.argtypes = [ctypes.c_uint8]
+        L.orc_e5m2_encode.restype = ctypes.c_uint8
+        L.orc_e5m2_encode.argtypes = [ctypes.c_float]
         L.orc_amax_bf16.restype = ctypes.c_float
         L.orc_penalty_sum.restype = ctypes.c_double
         L.orc_num_threads.restype = ctypes.c_int
@@ -86,6 +90,14 @@ def e4m3_encode(v):
     return int(lib().orc_e4m3_encode(ctypes.c_float(float(v))))
 
 
+def e5m2_decode(b):
+    return float(lib().orc_e5m2_decode(int(b)))
+
+
+def e5m2_encode(v):
+    return int(lib().orc_e5m2_encode(ctypes.c_float(float(v))))
+
+
 def amax_bf16(x):
     x = _c(x, np.uint16)
     return np.float32(lib().orc_amax_bf16(_p(x, _u16), _i64(x.size)))
@@ -95,6 +107,23 @@ def scale_from_amax(amax):
     s, si = _f32(), _f32()
     lib().orc_scale_from_amax(_f32(float(amax)), ctypes.byref(s), ctypes.byref(si))
     return np.float32(s.value), np.float32(si.value)
+
+
+def scale_from_amax_e5m2(amax):
+    s, si = _f32(), _f32()
+    lib().orc_scale_from_amax_e5m2(_f32(float(amax)), ctypes.byref(s), ctypes.byref(si))
+    return np.float32(s.value), np.float32(si.value)
+
+
+def quantize_e5m2(x, scale, transpose=True):
+    x = _c(x, np.uint16)
+    assert x.ndim == 2
+    r, c = x.shape
+    q = np.empty((r, c), np.uint8)
+    qT = np.empty((c, r), np.uint8) if transpose else None
+    lib().orc_quantize_e5m2(_p(x, _u16), _i64(r), _i64(c), _f32(float(scale)), _p(q, _u8),
+                            _p(qT, _u8))
+    return q, qT
 
 
 def quantize_e4m3(x, scale, transpose=True):
@@ -136,8 +165,8 @@ def fp8_linear_fwd(xq, wq, sx_inv, sw_inv, residual=None, rows=None, want_abs=Tr
     return y, ya, yb
 
 
-def fp8_linear_dgrad(dyq, wq, sdy_inv, sw_inv, rows=None, want_abs=True):
-    """dX rows (all m, or those in `rows`): (dx64, dxabs)."""
+def fp8_linear_dgrad(dyq, wq, sdy_inv, sw_inv, rows=None, want_abs=True, dy_e5m2=False):
+    """dX rows (all m, or those in `rows`): (dx64, dxabs).  dy_e5m2: dyq holds E5M2 codes."""
     dyq, wq = _c(dyq, np.uint8), _c(wq, np.uint8)
     M, N = dyq.shape
     N2, K = wq.shape
@@ -146,14 +175,14 @@ def fp8_linear_dgrad(dyq, wq, sdy_inv, sw_inv, rows=None, want_abs=True):
     R = nr if rows is not None else M
     dx = np.empty((R, K), np.float64)
     da = np.empty((R, K), np.float64) if want_abs else None
-    lib().orc_fp8_linear_dgrad(_p(dyq, _u8), _p(wq, _u8), _i64(M), _i64(N), _i64(K),
-                               _f32(float(sdy_inv)), _f32(float(sw_inv)), _p(rows, _i64),
-                               _i64(nr), _p(dx, _f64), _p(da, _f64))
+    lib().orc_fp8_linear_dgrad_fmt(_p(dyq, _u8), _p(wq, _u8), _i64(M), _i64(N), _i64(K),
+                                   _f32(float(sdy_inv)), _f32(float(sw_inv)), _p(rows, _i64),
+                                   _i64(nr), _p(dx, _f64), _p(da, _f64), ctypes.c_int(1 if dy_e5m2 else 0))
     return dx, da
 
 
-def fp8_linear_wgrad(dyq, xq, sdy_inv, sx_inv, rows=None, want_abs=True):
-    """dW rows (all n, or those in `rows`): (dw64, dwabs)."""
+def fp8_linear_wgrad(dyq, xq, sdy_inv, sx_inv, rows=None, want_abs=True, dy_e5m2=False):
+    """dW rows (all n, or those in `rows`): (dw64, dwabs).  dy_e5m2: dyq holds E5M2 codes."""
     dyq, xq = _c(dyq, np.uint8), _c(xq, np.uint8)
     M, N = dyq.shape
     M2, K = xq.shape
@@ -162,9 +191,9 @@ def fp8_linear_wgrad(dyq, xq, sdy_inv, sx_inv, rows=None, want_abs=True):
     R = nr if rows is not None else N
     dw = np.empty((R, K), np.float64)
     da = np.empty((R, K), np.float64) if want_abs else None
-    lib().orc_fp8_linear_wgrad(_p(dyq, _u8), _p(xq, _u8), _i64(M), _i64(N), _i64(K),
-                               _f32(float(sdy_inv)), _f32(float(sx_inv)), _p(rows, _i64),
-                               _i64(nr), _p(dw, _f64), _p(da, _f64))
+    lib().orc_fp8_linear_wgrad_fmt(_p(dyq, _u8), _p(xq, _u8), _i64(M), _i64(N), _i64(K),
+                                   _f32(float(sdy_inv)), _f32(float(sx_inv)), _p(rows, _i64),
+                                   _i64(nr), _p(dw, _f64), _p(da, _f64), ctypes.c_int(1 if dy_e5m2 else 0))
     return dw, da
 
 

@@ -111,6 +111,54 @@ uint8_t orc_e4m3_encode(float v)
     return sign | (uint8_t)code;
 }
 
+/*
+ * E5M2, the gradient format of the HYBRID recipe the paper trained with
+ * (Sec. 4.3: "Format.HYBRID (E4M3/E5M2)"): 1 sign, 5 exponent (bias 15), 2
+ * mantissa bits, IEEE-like: exponent 31 is Inf (mantissa 0) or NaN; largest
+ * finite magnitude 1.75 * 2^15 = 57344, smallest subnormal 2^-16.
+ */
+double orc_e5m2_decode(uint8_t b)
+{
+    int s = b >> 7, e = (b >> 2) & 31, m = b & 3;
+    double mag;
+    if (e == 31)
+        mag = m == 0 ? INFINITY : NAN;
+    else if (e == 0)
+        mag = ldexp((double)m / 4.0, -14);
+    else
+        mag = ldexp(1.0 + (double)m / 4.0, e - 15);
+    return s ? -mag : mag;
+}
+
+/*
+ * Round a binary32 to the nearest E5M2 value, ties to the even mantissa,
+ * saturating at +-57344 like the E4M3 cast (a training cast never produces Inf;
+ * the paper is silent: same reading).  NaN maps to a NaN code.  Same grid
+ * argument as for E4M3 with spacing 2^(E-2) and 2^-16 below 2^-14.
+ */
+uint8_t orc_e5m2_encode(float v)
+{
+    uint32_t u;
+    memcpy(&u, &v, sizeof u);
+    uint8_t sign = (u >> 31) ? 0x80 : 0x00;
+    if (isnan(v))
+        return sign | 0x7F;
+    double a = fabs((double)v);
+    if (a >= 57344.0)
+        return sign | 0x7B;
+    if (a == 0.0)
+        return sign;
+    int ex;
+    (void)frexp(a, &ex);
+    int E = ex - 1;
+    if (E < -14)
+        E = -14;
+    double spacing = ldexp(1.0, E - 2);
+    double r = nearbyint(a / spacing); /* 0..4 in the subnormal band, 4..8 in a normal binade */
+    int code = ((E + 14) << 2) + (int)r;
+    return sign | (uint8_t)code;
+}
+
 /* ------------------------------------------------------------------ amax */
 
 /*
@@ -151,6 +199,34 @@ void orc_scale_from_amax(float amax, float *scale, float *scale_inv)
     *scale_inv = 1.0f / s;
 }
 
+/* The same for the E5M2 range: scale = 57344 / amax. */
+void orc_scale_from_amax_e5m2(float amax, float *scale, float *scale_inv)
+{
+    float s;
+    if (!(amax > 0.0f) || isinf(amax) || isnan(amax)) {
+        s = 1.0f;
+    } else {
+        s = 57344.0f / amax;
+        if (isinf(s))
+            s = 3.402823466e+38f;
+    }
+    *scale = s;
+    *scale_inv = 1.0f / s;
+}
+
+void orc_quantize_e5m2(const uint16_t *x, int64_t rows, int64_t cols, float scale,
+                       uint8_t *q, uint8_t *qT)
+{
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) {
+            volatile float prod = orc_bf16_to_f32(x[r * cols + c]) * scale;
+            uint8_t b = orc_e5m2_encode(prod);
+            q[r * cols + c] = b;
+            if (qT)
+                qT[c * rows + r] = b;
+        }
+}
+
 /*
  * q[r,c] = e4m3( fp32(x[r,c]) * scale ): one fp32 multiply, then the rounding
  * above.  qT (optional) is the same bytes transposed, qT[c,r] = q[r,c].
@@ -174,6 +250,12 @@ static void decode_table(double *t)
 {
     for (int b = 0; b < 256; ++b)
         t[b] = orc_e4m3_decode((uint8_t)b);
+}
+
+static void decode_table_fmt(double *t, int e5m2)
+{
+    for (int b = 0; b < 256; ++b)
+        t[b] = e5m2 ? orc_e5m2_decode((uint8_t)b) : orc_e4m3_decode((uint8_t)b);
 }
 
 /*
@@ -223,13 +305,28 @@ void orc_fp8_linear_fwd(const uint8_t *xq, const uint8_t *wq, const uint16_t *re
  * Data gradient: dX[m,k] = (sum_n dec(dYq[m,n]) dec(Wq[n,k])) * sdy_inv * sw_inv.
  * Operands are the untransposed tensors; rows_idx selects rows m.
  */
+void orc_fp8_linear_dgrad_fmt(const uint8_t *dyq, const uint8_t *wq,
+                              int64_t M, int64_t N, int64_t K, float sdy_inv, float sw_inv,
+                              const int64_t *rows_idx, int64_t n_rows,
+                              double *dx64, double *dxabs, int dy_e5m2);
+
 void orc_fp8_linear_dgrad(const uint8_t *dyq, const uint8_t *wq,
                           int64_t M, int64_t N, int64_t K, float sdy_inv, float sw_inv,
                           const int64_t *rows_idx, int64_t n_rows,
                           double *dx64, double *dxabs)
 {
-    double t[256];
+    orc_fp8_linear_dgrad_fmt(dyq, wq, M, N, K, sdy_inv, sw_inv, rows_idx, n_rows, dx64, dxabs, 0);
+}
+
+/* dy_e5m2 != 0: the output gradient is in E5M2 codes (HYBRID format), the weights stay E4M3. */
+void orc_fp8_linear_dgrad_fmt(const uint8_t *dyq, const uint8_t *wq,
+                              int64_t M, int64_t N, int64_t K, float sdy_inv, float sw_inv,
+                              const int64_t *rows_idx, int64_t n_rows,
+                              double *dx64, double *dxabs, int dy_e5m2)
+{
+    double t[256], tg[256];
     decode_table(t);
+    decode_table_fmt(tg, dy_e5m2);
     int64_t R = rows_idx ? n_rows : M;
     double alpha = (double)sdy_inv * (double)sw_inv;
 #pragma omp parallel for schedule(static)
@@ -243,7 +340,7 @@ void orc_fp8_linear_dgrad(const uint8_t *dyq, const uint8_t *wq,
                 aab[k] = 0.0;
         }
         for (int64_t n = 0; n < N; ++n) { /* n ascending for every (m,k) */
-            double g = t[dyq[m * N + n]];
+            double g = tg[dyq[m * N + n]];
             for (int64_t k = 0; k < K; ++k) {
                 double p = g * t[wq[n * K + k]];
                 acc[k] += p;
@@ -263,13 +360,27 @@ void orc_fp8_linear_dgrad(const uint8_t *dyq, const uint8_t *wq,
  * Weight gradient: dW[n,k] = (sum_m dec(dYq[m,n]) dec(Xq[m,k])) * sdy_inv * sx_inv.
  * rows_idx selects rows n of dW.
  */
+void orc_fp8_linear_wgrad_fmt(const uint8_t *dyq, const uint8_t *xq,
+                              int64_t M, int64_t N, int64_t K, float sdy_inv, float sx_inv,
+                              const int64_t *rows_idx, int64_t n_rows,
+                              double *dw64, double *dwabs, int dy_e5m2);
+
 void orc_fp8_linear_wgrad(const uint8_t *dyq, const uint8_t *xq,
                           int64_t M, int64_t N, int64_t K, float sdy_inv, float sx_inv,
                           const int64_t *rows_idx, int64_t n_rows,
                           double *dw64, double *dwabs)
 {
-    double t[256];
+    orc_fp8_linear_wgrad_fmt(dyq, xq, M, N, K, sdy_inv, sx_inv, rows_idx, n_rows, dw64, dwabs, 0);
+}
+
+void orc_fp8_linear_wgrad_fmt(const uint8_t *dyq, const uint8_t *xq,
+                              int64_t M, int64_t N, int64_t K, float sdy_inv, float sx_inv,
+                              const int64_t *rows_idx, int64_t n_rows,
+                              double *dw64, double *dwabs, int dy_e5m2)
+{
+    double t[256], tg[256];
     decode_table(t);
+    decode_table_fmt(tg, dy_e5m2);
     int64_t R = rows_idx ? n_rows : N;
     double alpha = (double)sdy_inv * (double)sx_inv;
 #pragma omp parallel for schedule(static)
@@ -283,7 +394,7 @@ void orc_fp8_linear_wgrad(const uint8_t *dyq, const uint8_t *xq,
                 aab[k] = 0.0;
         }
         for (int64_t m = 0; m < M; ++m) { /* m ascending for every (n,k) */
-            double g = t[dyq[m * N + n]];
+            double g = tg[dyq[m * N + n]];
             for (int64_t k = 0; k < K; ++k) {
                 double p = g * t[xq[m * K + k]];
                 acc[k] += p;
