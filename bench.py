@@ -133,17 +133,29 @@ def time_elementwise(tw, torch, L, iters=20):
 
 
 def time_w8a8(tw, torch, synth, dev, iters=20):
-    """W8A8 INT8 inference GEMM at the 7B qkv shape (K=4096, N=12288) for M in {1,16,64,4096}."""
-    import numpy as np
+    """W8A8 INT8 inference GEMM at the 7B qkv shape (K=4096, N=12288) for M in {1,16,64,4096}, on
+    the workload's own statistics (N(0,1) activations clipped at 20, N(0,0.02) weights, per-tensor
+    static steps amax/127): what the codes look like decides the clock the matrix pipe sustains."""
     res = {}
     K, N = 4096, 12288
-    wq = torch.randint(-127, 128, (N, K), dtype=torch.int8, device=dev)
+    up = lambda b: torch.from_numpy(b.view("int16")).to(dev).view(torch.bfloat16)
+
+    def quant(t):
+        amax = float(t.float().abs().max())
+        q = torch.empty(t.shape, dtype=torch.int8, device=dev)
+        tw.tweo_quantize_i8(t, 127.0 / amax, q)
+        return q, amax / 127.0
+
+    wq = None
     for M in (1, 16, 64, 4096):
-        xq = torch.randint(-127, 128, (M, K), dtype=torch.int8, device=dev)
+        x, w = synth.w8a8_inputs(0, M)
+        if wq is None:
+            wq, step_w = quant(up(w))
+        xq, step_x = quant(up(x))
         y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
         ws = torch.empty(tw.tweo_workspace_bytes(tw.TWEO_OP_W8A8_LINEAR, M, N, K), dtype=torch.uint8,
                          device=dev)
-        fn = lambda: tw.tweo_w8a8_linear(xq, wq, 1e-4, y, ws)
+        fn = lambda: tw.tweo_w8a8_linear(xq, wq, step_x * step_w, y, ws)
         for _ in range(3):
             fn()
         s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
