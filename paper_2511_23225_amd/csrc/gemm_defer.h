@@ -38,6 +38,7 @@
 // A fragment of row i+1 is read while row i multiplies, the B fragment j of the
 // next K slab is read right after its last use in the current slab.
 #pragma once
+#include <utility>
 #include "gemm_common.h"
 
 namespace tweo {
@@ -67,11 +68,31 @@ struct DeferTile {
     // its last MFMA in slot SLAB + b and its first MFMA of the next tile in slot SLOTS + b: the
     // conversions are spread over the slots SLAB + 2 .. SLOTS + NB - 2.
     static constexpr int convert_slot(int h) { return SLAB + 2 + h * (2 * NB - 3) / (2 * NB); }
+    // Slots of a stage that issue an operand load, and the slots left for the write-out: a
+    // 16-byte-per-lane store of 32 different rows keeps the address unit busy for as long as four
+    // operand loads, so the two are kept apart.
+    __host__ __device__ __attribute__((always_inline)) static constexpr bool load_slot(int t)
+    {
+        return t < NA / 2 || (t >= SLAB && t < SLAB + NBP) || (t >= SLOTS - 4 && t < SLOTS - 4 + NA / 2);
+    }
+    static constexpr int FREE = SLOTS - NA - NBP;         // slots without a load, per stage
+    __host__ __device__ __attribute__((always_inline)) static constexpr int clamp(int v, int hi) { return v < 0 ? 0 : (v > hi ? hi : v); }
+    __host__ __device__ __attribute__((always_inline)) static constexpr int free_index(int t)                // how many of them lie before slot t
+    {
+        return t - clamp(t, NA / 2) - clamp(t - SLAB, NBP) - clamp(t - (SLOTS - 4), NA / 2);
+    }
 };
 
 // PMODE: 4 = TWEO penalty with p = 4 (the paper's setting), 0 = none.  D: number of stages of
 // the next tile over which the write-out of a tile is spread (3, 7 or 15; needs K >= 128 * (D + 1):
 // the tile's last stage, which converts its own blocks, takes no part in it).
+// calls f(integral_constant<int, 0>), f(integral_constant<int, 1>), ... in order
+template <typename F, int... Is>
+__device__ __forceinline__ void for_each_constant(std::integer_sequence<int, Is...>, F &f)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+
 template <bool INT8, int PMODE, int D, int MT>
 __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
 {
@@ -344,24 +365,24 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
     // micro-steps are dealt evenly over the slots of the first D stages, from slot 2 on.  FIRST: a
     // tile starts (1: the workgroup's first tile, 2: a later one, which also converts the last
     // half blocks of its predecessor).  LAST: a tile ends: its blocks are converted as they finish.
-    constexpr int W = D * T::SLOTS - 2;
+    constexpr int W = D * T::FREE;
+    // The slot number is a compile-time constant of each slot's body (the bodies are stamped out
+    // from an integer sequence): which pieces a slot carries is decided by the front end, not
+    // left to constant propagation through unrolled loops.
     auto stage = [&](auto dr_c, auto first_c, auto last_c) {
         constexpr int DR = decltype(dr_c)::value, FIRST = decltype(first_c)::value;
         constexpr bool LAST = decltype(last_c)::value;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-            for (int i = 0; i < MT; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int t = kk * T::SLAB + i * 4 + j;
-                    if (t == T::SLAB) {
+        auto slot_body = [&](auto t_c) {
+                {
+                    constexpr int t = decltype(t_c)::value;
+                    constexpr int kk = t / T::SLAB, i = (t % T::SLAB) / 4, j = t % 4;
+                    if constexpr (t == T::SLAB) {
                         // every wave has read the B half of this stage (its slab-1 fragments were
                         // requested in the last four slots of slab 0): the half can be refilled
                         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                         block_barrier();
                     }
-                    if (t == T::SLOTS - 4) {
+                    if constexpr (t == T::SLOTS - 4) {
                         // every LDS read of this stage has been issued: wait for them and for this
                         // wave's share of the next stage (everything but the eight B pieces of the
                         // stage after next, the youngest loads), then publish
@@ -369,31 +390,31 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
                         block_barrier();
                         flip_stage();
                     }
-                    if (FIRST != 0 && kk == 0)
+                    if constexpr (FIRST != 0 && kk == 0)
                         mfma_first(kk, i, j);
                     else
                         mfma(kk, i, j);
-                    if (j == 0) {
-                        if (i < MT - 1)
+                    if constexpr (j == 0) {
+                        if constexpr (i < MT - 1)
                             load_a(fa[(kk * MT + i + 1) & 1], kk, i + 1);
                         else
                             load_a(fa[((kk ^ 1) * MT) & 1], kk ^ 1, 0);  // next slab (after the flip: next stage)
                     }
-                    if (i == MT - 1)
+                    if constexpr (i == MT - 1)
                         load_b(fb[j], kk ^ 1, j);
                     // operand stream, at most one piece per slot: A of the next stage (second
                     // half of its pieces) in the first slots, B of the stage after next right
                     // behind the first barrier (which released its buffer half), A of the stage
                     // after next (first half) behind the second barrier
-                    if (t < T::NA / 2) {
+                    if constexpr (t < T::NA / 2) {
                         dma_piece_a(T::NA / 2 + t);
-                        if (t == T::NA / 2 - 1)
+                        if constexpr (t == T::NA / 2 - 1)
                             stream_advance(sa, false);
-                    } else if (t >= T::SLAB && t < T::SLAB + T::NBP) {
+                    } else if constexpr (t >= T::SLAB && t < T::SLAB + T::NBP) {
                         dma_piece_b(t - T::SLAB);
-                        if (t == T::SLAB + T::NBP - 1)
+                        if constexpr (t == T::SLAB + T::NBP - 1)
                             stream_advance(sb, true);
-                    } else if (t >= T::SLOTS - 4 && t < T::SLOTS - 4 + T::NA / 2) {
+                    } else if constexpr (t >= T::SLOTS - 4 && t < T::SLOTS - 4 + T::NA / 2) {
                         dma_piece_a(t - (T::SLOTS - 4));
                     }
                     // conversion of the tile that ends here / ended in the previous stage
@@ -402,20 +423,22 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
                         if ((LAST && T::convert_slot(h) == t) || (FIRST == 2 && T::convert_slot(h) == t + T::SLOTS))
                             convert_half(h);
                     // write-out of the previous tile
-                    if (DR >= 0) {
-                        const int w = DR * T::SLOTS + t - 2;
-                        if (w >= 0 && w < W) {
-                            const int q_lo = (w * T::DRAIN_STEPS + W - 1) / W;
-                            const int q_hi = ((w + 1) * T::DRAIN_STEPS + W - 1) / W;
-                            static_assert(T::DRAIN_STEPS <= 2 * W, "at most two micro-steps per slot");
-                            if (q_lo < q_hi)
-                                drain_step(q_lo);
-                            if (q_lo + 1 < q_hi)
-                                drain_step(q_lo + 1);
-                        }
+                    if constexpr (DR >= 0 && !T::load_slot(t)) {
+                        constexpr int w = DR * T::FREE + T::free_index(t);
+                        constexpr int q_lo = (w * T::DRAIN_STEPS + W - 1) / W;
+                        constexpr int q_hi = ((w + 1) * T::DRAIN_STEPS + W - 1) / W;
+                        static_assert(T::DRAIN_STEPS <= 3 * W, "at most three micro-steps per slot");
+                        if constexpr (q_lo < q_hi)
+                            drain_step(q_lo);
+                        if constexpr (q_lo + 1 < q_hi)
+                            drain_step(q_lo + 1);
+                        if constexpr (q_lo + 2 < q_hi)
+                            drain_step(q_lo + 2);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
+        };
+        for_each_constant(std::make_integer_sequence<int, T::SLOTS>{}, slot_body);
     };
     using std::integral_constant;
     using std::true_type;
