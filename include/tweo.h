@@ -96,6 +96,17 @@ tweo_status tweo_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, c
                                void *stream);
 
 /*
+ * The same cast into E5M2, the gradient format of the HYBRID recipe the paper
+ * trained with (Sec. 4.3: E4M3 for activations and weights, E5M2 for
+ * gradients): scale = 57344 / *amax with the same guards, q = e5m2(fp32(x) *
+ * scale), round to nearest even, saturating at +-57344 (a cast never produces
+ * an infinity), NaN -> a NaN code.  Arguments and errors as tweo_quantize_e4m3.
+ */
+tweo_status tweo_quantize_e5m2(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
+                               uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
+                               void *stream);
+
+/*
  * Delayed scaling, the form of per-tensor scaling the paper trained with
  * (Sec. 4.3: one scale per tensor, amax history of length 16): the cast of step
  * t uses scale_t = 448 / max(amax_{t-16} .. amax_{t-1}), fixed before the tensor
@@ -162,6 +173,17 @@ tweo_status tweo_fp8_linear_bwd(const uint8_t *dyq, const uint8_t *dyqT, const f
                                 const float *sx_inv, int64_t M, int64_t N, int64_t K,
                                 void *dx_bf16, void *dw_bf16, void *workspace,
                                 size_t workspace_bytes, void *stream);
+
+/*
+ * The same backward GEMMs with the gradient in E5M2 (HYBRID recipe, Sec. 4.3):
+ * dyq / dyqT hold E5M2 codes (tweo_quantize_e5m2), wqT / xqT E4M3 codes.
+ * Arguments, layouts and errors as tweo_fp8_linear_bwd.
+ */
+tweo_status tweo_fp8_linear_bwd_hybrid(const uint8_t *dyq, const uint8_t *dyqT, const float *sdy_inv,
+                                       const uint8_t *wqT, const float *sw_inv, const uint8_t *xqT,
+                                       const float *sx_inv, int64_t M, int64_t N, int64_t K,
+                                       void *dx_bf16, void *dw_bf16, void *workspace,
+                                       size_t workspace_bytes, void *stream);
 
 /*
  * Gradient of the TWEO penalty, added to the incoming output gradient before it
@@ -235,6 +257,12 @@ tweo_status tweo_fp8_linear_bwd_bf16(const void *dy_bf16, const tweo_fp8_saved *
                                      int64_t N, int64_t K, uint8_t *dyq, uint8_t *dyqT,
                                      void *dx_bf16, void *dw_bf16, void *workspace,
                                      size_t workspace_bytes, void *stream);
+
+/* The same with dy cast to E5M2 (HYBRID recipe, Sec. 4.3). */
+tweo_status tweo_fp8_linear_bwd_bf16_hybrid(const void *dy_bf16, const tweo_fp8_saved *saved, int64_t M,
+                                            int64_t N, int64_t K, uint8_t *dyq, uint8_t *dyqT,
+                                            void *dx_bf16, void *dw_bf16, void *workspace,
+                                            size_t workspace_bytes, void *stream);
 
 /*
  * Tuning hook for benchmarks and tests: forces the GEMM kernel variant.

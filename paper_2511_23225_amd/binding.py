@@ -20,7 +20,8 @@ EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quan
            "tweo_fp8_linear_fwd", "tweo_fp8_linear_bwd", "tweo_quantize_i8", "tweo_w8a8_linear",
            "tweo_fp8_linear_fwd_bf16", "tweo_fp8_linear_bwd_bf16", "tweo_set_gemm_tile",
            "tweo_set_stream_k", "tweo_penalty_grad_inject", "tweo_delayed_state_bytes",
-           "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed", "tweo_profile_gemm_launches")
+           "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed", "tweo_profile_gemm_launches",
+           "tweo_quantize_e5m2", "tweo_fp8_linear_bwd_hybrid", "tweo_fp8_linear_bwd_bf16_hybrid")
 
 
 class TweoError(RuntimeError):
@@ -58,15 +59,18 @@ def load():
     L.tweo_status_string.argtypes = [ctypes.c_int]
     L.tweo_amax.argtypes = [vp, i64, vp, vp]
     L.tweo_quantize_e4m3.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp]
+    L.tweo_quantize_e5m2.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp]
     L.tweo_fp8_linear_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp,
                                       ctypes.POINTER(PenaltyCfg), vp, vp, sz, vp]
     L.tweo_fp8_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
+    L.tweo_fp8_linear_bwd_hybrid.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
     L.tweo_quantize_i8.argtypes = [vp, i64, f32, vp, vp]
     L.tweo_w8a8_linear.argtypes = [vp, vp, i64, i64, i64, f32, vp, vp, sz, vp]
     L.tweo_fp8_linear_fwd_bf16.argtypes = [vp, vp, vp, i64, i64, i64, vp, ctypes.POINTER(PenaltyCfg),
                                            vp, ctypes.POINTER(Fp8Saved), vp, sz, vp]
     L.tweo_fp8_linear_bwd_bf16.argtypes = [vp, ctypes.POINTER(Fp8Saved), i64, i64, i64, vp, vp, vp,
                                            vp, vp, sz, vp]
+    L.tweo_fp8_linear_bwd_bf16_hybrid.argtypes = L.tweo_fp8_linear_bwd_bf16.argtypes
     L.tweo_set_gemm_tile.argtypes = [ctypes.c_int]
     L.tweo_set_stream_k.argtypes = [ctypes.c_int]
     L.tweo_profile_gemm_launches.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
@@ -166,6 +170,13 @@ def tweo_quantize_e4m3(x_bf16, amax, q, qT=None, scale_out=None, scale_inv_out=N
            "tweo_quantize_e4m3")
 
 
+def tweo_quantize_e5m2(x_bf16, amax, q, qT=None, scale_out=None, scale_inv_out=None):
+    rows, cols = x_bf16.shape
+    _check(load().tweo_quantize_e5m2(_ptr(x_bf16), rows, cols, _ptr(amax), _ptr(q), _ptr(qT),
+                                     _ptr(scale_out), _ptr(scale_inv_out), _stream()),
+           "tweo_quantize_e5m2")
+
+
 def tweo_fp8_linear_fwd(xq, sx_inv, wq, sw_inv, y_bf16, residual_bf16=None, pen=None,
                         penalty_sum=None, workspace=None):
     M, K = xq.shape
@@ -182,6 +193,14 @@ def tweo_fp8_linear_bwd(dyq, dyqT, sdy_inv, wqT, sw_inv, xqT, sx_inv, M, N, K, d
     _check(load().tweo_fp8_linear_bwd(_ptr(dyq), _ptr(dyqT), _ptr(sdy_inv), _ptr(wqT), _ptr(sw_inv),
                                       _ptr(xqT), _ptr(sx_inv), M, N, K, _ptr(dx_bf16), _ptr(dw_bf16),
                                       wp, wb, _stream()), "tweo_fp8_linear_bwd")
+
+
+def tweo_fp8_linear_bwd_hybrid(dyq, dyqT, sdy_inv, wqT, sw_inv, xqT, sx_inv, M, N, K, dx_bf16=None,
+                               dw_bf16=None, workspace=None):
+    wp, wb = _ws(workspace)
+    _check(load().tweo_fp8_linear_bwd_hybrid(_ptr(dyq), _ptr(dyqT), _ptr(sdy_inv), _ptr(wqT), _ptr(sw_inv),
+                                             _ptr(xqT), _ptr(sx_inv), M, N, K, _ptr(dx_bf16), _ptr(dw_bf16),
+                                             wp, wb, _stream()), "tweo_fp8_linear_bwd_hybrid")
 
 
 def tweo_quantize_i8(x_bf16, inv_step, out):
@@ -219,3 +238,12 @@ def tweo_fp8_linear_bwd_bf16(dy_bf16, saved, K, dyq, dyqT, dx_bf16=None, dw_bf16
     _check(load().tweo_fp8_linear_bwd_bf16(_ptr(dy_bf16), ctypes.byref(saved), M, N, K, _ptr(dyq),
                                            _ptr(dyqT), _ptr(dx_bf16), _ptr(dw_bf16), wp, wb,
                                            _stream()), "tweo_fp8_linear_bwd_bf16")
+
+
+def tweo_fp8_linear_bwd_bf16_hybrid(dy_bf16, saved, K, dyq, dyqT, dx_bf16=None, dw_bf16=None,
+                                    workspace=None):
+    M, N = dy_bf16.shape
+    wp, wb = _ws(workspace)
+    _check(load().tweo_fp8_linear_bwd_bf16_hybrid(_ptr(dy_bf16), ctypes.byref(saved), M, N, K, _ptr(dyq),
+                                                  _ptr(dyqT), _ptr(dx_bf16), _ptr(dw_bf16), wp, wb,
+                                                  _stream()), "tweo_fp8_linear_bwd_bf16_hybrid")

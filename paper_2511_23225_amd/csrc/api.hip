@@ -144,6 +144,19 @@ tweo_status tweo_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, c
                                            scale_inv_out, (hipStream_t)stream));
 }
 
+tweo_status tweo_quantize_e5m2(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
+                               uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
+                               void *stream)
+{
+    if (!x_bf16 || !amax || !q || rows <= 0 || cols <= 0 || !aligned16(x_bf16) || !aligned16(q) ||
+        (qT && !aligned16(qT)))
+        return TWEO_ERR_INVALID_ARG;
+    if (cols % 8 != 0 || rows > kMaxDim || cols > kMaxDim)
+        return TWEO_ERR_UNSUPPORTED;
+    return hip_status(launch_quantize_e5m2(x_bf16, rows, cols, amax, q, qT, scale_out,
+                                           scale_inv_out, (hipStream_t)stream));
+}
+
 size_t tweo_delayed_state_bytes(void) { return TWEO_DELAYED_STATE_WORDS * sizeof(float); }
 
 tweo_status tweo_delayed_state_init(void *state, void *stream)
@@ -207,11 +220,11 @@ tweo_status tweo_fp8_linear_fwd(const uint8_t *xq, const float *sx_inv, const ui
     return hip_status(e);
 }
 
-tweo_status tweo_fp8_linear_bwd(const uint8_t *dyq, const uint8_t *dyqT, const float *sdy_inv,
-                                const uint8_t *wqT, const float *sw_inv, const uint8_t *xqT,
-                                const float *sx_inv, int64_t M, int64_t N, int64_t K,
-                                void *dx_bf16, void *dw_bf16, void *workspace,
-                                size_t workspace_bytes, void *stream)
+static tweo_status fp8_linear_bwd_impl(const uint8_t *dyq, const uint8_t *dyqT, const float *sdy_inv,
+                                       const uint8_t *wqT, const float *sw_inv, const uint8_t *xqT,
+                                       const float *sx_inv, int64_t M, int64_t N, int64_t K,
+                                       void *dx_bf16, void *dw_bf16, void *workspace,
+                                       size_t workspace_bytes, void *stream, bool dy_e5m2)
 {
     if (M <= 0 || N <= 0 || K <= 0 || !sdy_inv || (!dx_bf16 && !dw_bf16))
         return TWEO_ERR_INVALID_ARG;
@@ -233,6 +246,7 @@ tweo_status tweo_fp8_linear_bwd(const uint8_t *dyq, const uint8_t *dyqT, const f
         a.s0 = sdy_inv;
         a.s1 = sw_inv;
         a.out = dx_bf16;
+        a.a_e5m2 = dy_e5m2;
         attach_stream_k(a, workspace, workspace_bytes, 256);
         hipError_t e = launch_fp8_gemm(a, s);
         if (e != hipSuccess)
@@ -248,12 +262,33 @@ tweo_status tweo_fp8_linear_bwd(const uint8_t *dyq, const uint8_t *dyqT, const f
         a.s0 = sdy_inv;
         a.s1 = sx_inv;
         a.out = dw_bf16;
+        a.a_e5m2 = dy_e5m2;
         attach_stream_k(a, workspace, workspace_bytes, 256);
         hipError_t e = launch_fp8_gemm(a, s);
         if (e != hipSuccess)
             return TWEO_ERR_HIP;
     }
     return TWEO_OK;
+}
+
+tweo_status tweo_fp8_linear_bwd(const uint8_t *dyq, const uint8_t *dyqT, const float *sdy_inv,
+                                const uint8_t *wqT, const float *sw_inv, const uint8_t *xqT,
+                                const float *sx_inv, int64_t M, int64_t N, int64_t K,
+                                void *dx_bf16, void *dw_bf16, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    return fp8_linear_bwd_impl(dyq, dyqT, sdy_inv, wqT, sw_inv, xqT, sx_inv, M, N, K, dx_bf16, dw_bf16,
+                               workspace, workspace_bytes, stream, false);
+}
+
+tweo_status tweo_fp8_linear_bwd_hybrid(const uint8_t *dyq, const uint8_t *dyqT, const float *sdy_inv,
+                                       const uint8_t *wqT, const float *sw_inv, const uint8_t *xqT,
+                                       const float *sx_inv, int64_t M, int64_t N, int64_t K,
+                                       void *dx_bf16, void *dw_bf16, void *workspace,
+                                       size_t workspace_bytes, void *stream)
+{
+    return fp8_linear_bwd_impl(dyq, dyqT, sdy_inv, wqT, sw_inv, xqT, sx_inv, M, N, K, dx_bf16, dw_bf16,
+                               workspace, workspace_bytes, stream, true);
 }
 
 tweo_status tweo_penalty_grad_inject(const void *dy_bf16, const void *a_bf16, int64_t n,
@@ -339,10 +374,10 @@ tweo_status tweo_fp8_linear_fwd_bf16(const void *x_bf16, const void *w_bf16,
                                pen, penalty_sum, workspace, workspace_bytes, stream);
 }
 
-tweo_status tweo_fp8_linear_bwd_bf16(const void *dy_bf16, const tweo_fp8_saved *saved, int64_t M,
-                                     int64_t N, int64_t K, uint8_t *dyq, uint8_t *dyqT,
-                                     void *dx_bf16, void *dw_bf16, void *workspace,
-                                     size_t workspace_bytes, void *stream)
+static tweo_status fp8_linear_bwd_bf16_impl(const void *dy_bf16, const tweo_fp8_saved *saved, int64_t M,
+                                            int64_t N, int64_t K, uint8_t *dyq, uint8_t *dyqT,
+                                            void *dx_bf16, void *dw_bf16, void *workspace,
+                                            size_t workspace_bytes, void *stream, bool dy_e5m2)
 {
     if (!dy_bf16 || !saved || !saved->xqT || !saved->wqT || !saved->scalars || !dyq || !dyqT ||
         M <= 0 || N <= 0 || K <= 0 || !aligned16(dy_bf16) || !aligned16(dyq) || !aligned16(dyqT))
@@ -355,11 +390,30 @@ tweo_status tweo_fp8_linear_bwd_bf16(const void *dy_bf16, const tweo_fp8_saved *
     if (e == hipSuccess)
         e = launch_amax(dy_bf16, M * N, sc + 6, s);
     if (e == hipSuccess)
-        e = launch_quantize_e4m3(dy_bf16, M, N, sc + 6, dyq, dyqT, sc + 7, sc + 8, s);
+        e = dy_e5m2 ? launch_quantize_e5m2(dy_bf16, M, N, sc + 6, dyq, dyqT, sc + 7, sc + 8, s)
+                    : launch_quantize_e4m3(dy_bf16, M, N, sc + 6, dyq, dyqT, sc + 7, sc + 8, s);
     if (e != hipSuccess)
         return TWEO_ERR_HIP;
-    return tweo_fp8_linear_bwd(dyq, dyqT, sc + 8, saved->wqT, sc + 5, saved->xqT, sc + 2, M, N, K,
-                               dx_bf16, dw_bf16, workspace, workspace_bytes, stream);
+    return fp8_linear_bwd_impl(dyq, dyqT, sc + 8, saved->wqT, sc + 5, saved->xqT, sc + 2, M, N, K,
+                               dx_bf16, dw_bf16, workspace, workspace_bytes, stream, dy_e5m2);
+}
+
+tweo_status tweo_fp8_linear_bwd_bf16(const void *dy_bf16, const tweo_fp8_saved *saved, int64_t M,
+                                     int64_t N, int64_t K, uint8_t *dyq, uint8_t *dyqT,
+                                     void *dx_bf16, void *dw_bf16, void *workspace,
+                                     size_t workspace_bytes, void *stream)
+{
+    return fp8_linear_bwd_bf16_impl(dy_bf16, saved, M, N, K, dyq, dyqT, dx_bf16, dw_bf16, workspace,
+                                    workspace_bytes, stream, false);
+}
+
+tweo_status tweo_fp8_linear_bwd_bf16_hybrid(const void *dy_bf16, const tweo_fp8_saved *saved, int64_t M,
+                                            int64_t N, int64_t K, uint8_t *dyq, uint8_t *dyqT,
+                                            void *dx_bf16, void *dw_bf16, void *workspace,
+                                            size_t workspace_bytes, void *stream)
+{
+    return fp8_linear_bwd_bf16_impl(dy_bf16, saved, M, N, K, dyq, dyqT, dx_bf16, dw_bf16, workspace,
+                                    workspace_bytes, stream, true);
 }
 
 }  // extern "C"

@@ -31,18 +31,20 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, b);
 }
 
-// Per-tensor scale into the E4M3 range (Sec. 4.3; +-448 from Sec. 1): 448/amax as one
-// IEEE fp32 division; amax of 0 / Inf / NaN -> 1; overflow -> FLT_MAX.
-__device__ __forceinline__ float scale_from_amax(float amax)
+// Per-tensor scale into an 8-bit float range (Sec. 4.3; E4M3: +-448 from Sec. 1, E5M2: +-57344):
+// range/amax as one IEEE fp32 division; amax of 0 / Inf / NaN -> 1; overflow -> FLT_MAX.
+__device__ __forceinline__ float scale_from_amax_range(float amax, float range)
 {
     float s = 1.0f;
     if (amax > 0.0f && amax < __builtin_inff()) {
-        s = 448.0f / amax;
+        s = range / amax;
         if (s == __builtin_inff())
             s = 3.402823466e+38f;
     }
     return s;
 }
+
+__device__ __forceinline__ float scale_from_amax(float amax) { return scale_from_amax_range(amax, 448.0f); }
 
 template <typename T>
 __device__ __forceinline__ T wave_reduce_sum(T v)

@@ -197,6 +197,35 @@ __device__ __forceinline__ uint32_t cvt4_e4m3(float a, float b, float c, float d
     return (uint32_t)r;
 }
 
+// E5M2, the gradient format of the HYBRID recipe (Sec. 4.3): same cast with the range +-57344.
+__device__ __forceinline__ float sat_e5m2(float v)
+{
+    float c = __builtin_amdgcn_fmed3f(v, -57344.0f, 57344.0f);
+    return v != v ? v : c;
+}
+
+__device__ __forceinline__ uint32_t cvt4_e5m2(float a, float b, float c, float d)
+{
+    int r = __builtin_amdgcn_cvt_pk_bf8_f32(sat_e5m2(a), sat_e5m2(b), 0, false);
+    r = __builtin_amdgcn_cvt_pk_bf8_f32(sat_e5m2(c), sat_e5m2(d), r, true);
+    return (uint32_t)r;
+}
+
+template <bool E5M2>
+__device__ __forceinline__ uint32_t cvt4_f8(float a, float b, float c, float d)
+{
+    if constexpr (E5M2)
+        return cvt4_e5m2(a, b, c, d);
+    else
+        return cvt4_e4m3(a, b, c, d);
+}
+
+template <bool E5M2>
+__device__ __forceinline__ float scale_f8(float amax)
+{
+    return scale_from_amax_range(amax, E5M2 ? 57344.0f : 448.0f);
+}
+
 // rows a,b,c,d (one dword = 4 bytes each) -> columns t0..t3 of the 4x4 byte matrix
 __device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d,
                                                    uint32_t &t0, uint32_t &t1, uint32_t &t2,
@@ -234,13 +263,13 @@ __device__ __forceinline__ void quant_amax_commit(uint32_t m, uint32_t *amax_acc
     }
 }
 
-template <bool WITH_T, bool DELAYED>
+template <bool WITH_T, bool DELAYED, bool E5M2 = false>
 __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
     const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
     const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
     float *scale_out, float *scale_inv_out, uint32_t *amax_acc)
 {
-    const float scale = DELAYED ? *amax : scale_from_amax(*amax);
+    const float scale = DELAYED ? *amax : scale_f8<E5M2>(*amax);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         if (scale_out)
             *scale_out = scale;
@@ -271,9 +300,9 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
     uint32_t lo[8], hi[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        lo[i] = cvt4_e4m3(bf16lo_to_f32(in[i].x) * scale, bf16hi_to_f32(in[i].x) * scale,
+        lo[i] = cvt4_f8<E5M2>(bf16lo_to_f32(in[i].x) * scale, bf16hi_to_f32(in[i].x) * scale,
                           bf16lo_to_f32(in[i].y) * scale, bf16hi_to_f32(in[i].y) * scale);
-        hi[i] = cvt4_e4m3(bf16lo_to_f32(in[i].z) * scale, bf16hi_to_f32(in[i].z) * scale,
+        hi[i] = cvt4_f8<E5M2>(bf16lo_to_f32(in[i].z) * scale, bf16hi_to_f32(in[i].z) * scale,
                           bf16lo_to_f32(in[i].w) * scale, bf16hi_to_f32(in[i].w) * scale);
         if (r0 + i < rows)
             *(uint2 *)(q + (r0 + i) * cols + c0) = make_uint2(lo[i], hi[i]);
@@ -308,13 +337,13 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
 // workgroup 256x256.
 constexpr int kQuantBigTile = 256;
 
-template <bool WITH_T, bool DELAYED>
+template <bool WITH_T, bool DELAYED, bool E5M2 = false>
 __device__ __forceinline__ void quantize_e4m3_16x16_body(
     const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
     const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
     float *scale_out, float *scale_inv_out, uint32_t *amax_acc, int64_t block, int64_t n_blocks)
 {
-    const float scale = DELAYED ? *amax : scale_from_amax(*amax);
+    const float scale = DELAYED ? *amax : scale_f8<E5M2>(*amax);
     if (block == 0 && threadIdx.x == 0) {
         if (scale_out)
             *scale_out = scale;
@@ -350,9 +379,9 @@ __device__ __forceinline__ void quantize_e4m3_16x16_body(
 #pragma unroll
             for (int w = 0; w < 2; ++w) {
                 const uint4 v = in[i][w];
-                qd[r][2 * w] = cvt4_e4m3(bf16lo_to_f32(v.x) * scale, bf16hi_to_f32(v.x) * scale,
+                qd[r][2 * w] = cvt4_f8<E5M2>(bf16lo_to_f32(v.x) * scale, bf16hi_to_f32(v.x) * scale,
                                          bf16lo_to_f32(v.y) * scale, bf16hi_to_f32(v.y) * scale);
-                qd[r][2 * w + 1] = cvt4_e4m3(bf16lo_to_f32(v.z) * scale, bf16hi_to_f32(v.z) * scale,
+                qd[r][2 * w + 1] = cvt4_f8<E5M2>(bf16lo_to_f32(v.z) * scale, bf16hi_to_f32(v.z) * scale,
                                              bf16lo_to_f32(v.w) * scale, bf16hi_to_f32(v.w) * scale);
             }
             *(uint4 *)(q + (r0 + r) * cols + c0) = make_uint4(qd[r][0], qd[r][1], qd[r][2], qd[r][3]);
@@ -378,13 +407,13 @@ __device__ __forceinline__ void quantize_e4m3_16x16_body(
         quant_amax_commit(mx, amax_acc);
 }
 
-template <bool WITH_T, bool DELAYED>
+template <bool WITH_T, bool DELAYED, bool E5M2 = false>
 __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
     const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
     const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
     float *scale_out, float *scale_inv_out, uint32_t *amax_acc)
 {
-    quantize_e4m3_16x16_body<WITH_T, DELAYED>(x, rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out,
+    quantize_e4m3_16x16_body<WITH_T, DELAYED, E5M2>(x, rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out,
                                               amax_acc, blockIdx.x, gridDim.x);
 }
 
@@ -421,7 +450,7 @@ hipError_t launch_quantize2_e4m3(const void *x0_bf16, int64_t rows0, int64_t col
     return hipGetLastError();
 }
 
-template <bool DELAYED>
+template <bool DELAYED, bool E5M2 = false>
 static hipError_t launch_quantize_e4m3_impl(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
                                             uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
                                             uint32_t *amax_acc, hipStream_t s)
@@ -435,11 +464,11 @@ static hipError_t launch_quantize_e4m3_impl(const void *x_bf16, int64_t rows, in
             n_wg = 1024;
         const dim3 grid((unsigned)n_wg);
         if (qT)
-            hipLaunchKernelGGL((quantize_e4m3_16x16_kernel<true, DELAYED>), grid, block, 0, s,
+            hipLaunchKernelGGL((quantize_e4m3_16x16_kernel<true, DELAYED, E5M2>), grid, block, 0, s,
                                (const uint16_t *)x_bf16, rows, cols, tiles_x, amax, q, qT, scale_out,
                                scale_inv_out, amax_acc);
         else
-            hipLaunchKernelGGL((quantize_e4m3_16x16_kernel<false, DELAYED>), grid, block, 0, s,
+            hipLaunchKernelGGL((quantize_e4m3_16x16_kernel<false, DELAYED, E5M2>), grid, block, 0, s,
                                (const uint16_t *)x_bf16, rows, cols, tiles_x, amax, q, qT, scale_out,
                                scale_inv_out, amax_acc);
         return hipGetLastError();
@@ -448,10 +477,10 @@ static hipError_t launch_quantize_e4m3_impl(const void *x_bf16, int64_t rows, in
     const int64_t tiles_y = (rows + kQuantTileRows - 1) / kQuantTileRows;
     const dim3 grid((unsigned)(tiles_x * tiles_y));
     if (qT)
-        hipLaunchKernelGGL((quantize_e4m3_kernel<true, DELAYED>), grid, block, 0, s, (const uint16_t *)x_bf16,
+        hipLaunchKernelGGL((quantize_e4m3_kernel<true, DELAYED, E5M2>), grid, block, 0, s, (const uint16_t *)x_bf16,
                            rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out, amax_acc);
     else
-        hipLaunchKernelGGL((quantize_e4m3_kernel<false, DELAYED>), grid, block, 0, s, (const uint16_t *)x_bf16,
+        hipLaunchKernelGGL((quantize_e4m3_kernel<false, DELAYED, E5M2>), grid, block, 0, s, (const uint16_t *)x_bf16,
                            rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out, amax_acc);
     return hipGetLastError();
 }
@@ -462,6 +491,14 @@ hipError_t launch_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, 
 {
     return launch_quantize_e4m3_impl<false>(x_bf16, rows, cols, amax, q, qT, scale_out, scale_inv_out,
                                             nullptr, s);
+}
+
+hipError_t launch_quantize_e5m2(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
+                                uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
+                                hipStream_t s)
+{
+    return launch_quantize_e4m3_impl<false, true>(x_bf16, rows, cols, amax, q, qT, scale_out,
+                                                  scale_inv_out, nullptr, s);
 }
 
 // ---------------------------------------------------------------------------

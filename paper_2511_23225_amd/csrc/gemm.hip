@@ -266,7 +266,7 @@ __device__ __forceinline__ void epilogue(const GemmDev &g, ACC (&acc)[T::MT][T::
 #undef TWEO_EPI
 }
 
-template <typename T, bool INT8>
+template <typename T, bool INT8, bool A_E5M2 = false>
 __global__ __launch_bounds__(T::THREADS) void gemm_nt_kernel(GemmDev g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -362,8 +362,9 @@ __global__ __launch_bounds__(T::THREADS) void gemm_nt_kernel(GemmDev g)
 #pragma unroll
                     for (int j = 0; j < T::NT; ++j)
                         // first operand -> register-distributed index (n), second -> lane index (m)
+                        // source formats: the first (B) always E4M3, the second (A) E4M3 or E5M2
                         acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            fb[j], fa[i], acc[i][j], 0, 0, 0, 0, 0, 0);
+                            fb[j], fa[i], acc[i][j], 0, A_E5M2 ? 1 : 0, 0, 0, 0, 0);
             }
         } else {
 #pragma unroll
@@ -1309,7 +1310,7 @@ int fp8_gemm_partials(const GemmArgs &a)
     return (int)(((a.M + kVariantBM[v] - 1) / kVariantBM[v]) * ((a.N + kVariantBN[v] - 1) / kVariantBN[v]));
 }
 
-template <typename T, bool INT8, bool DMA>
+template <typename T, bool INT8, bool DMA, bool A_E5M2 = false>
 static hipError_t launch_tile(const GemmArgs &a, hipStream_t s)
 {
     static bool attr_done = false;  // per instantiation
@@ -1317,7 +1318,7 @@ static hipError_t launch_tile(const GemmArgs &a, hipStream_t s)
     if constexpr (DMA)
         kern = (const void *)gemm_nt_dma_kernel<T, INT8>;
     else
-        kern = (const void *)gemm_nt_kernel<T, INT8>;
+        kern = (const void *)gemm_nt_kernel<T, INT8, A_E5M2>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            T::LDS_BYTES);
@@ -1345,7 +1346,7 @@ static hipError_t launch_tile(const GemmArgs &a, hipStream_t s)
     if constexpr (DMA)
         launch_gemm_kernel(gemm_nt_dma_kernel<T, INT8>, grid, block, T::LDS_BYTES, s, g);
     else
-        launch_gemm_kernel(gemm_nt_kernel<T, INT8>, grid, block, T::LDS_BYTES, s, g);
+        launch_gemm_kernel(gemm_nt_kernel<T, INT8, A_E5M2>, grid, block, T::LDS_BYTES, s, g);
     return hipGetLastError();
 }
 
@@ -1426,13 +1427,13 @@ static hipError_t launch_stream(const GemmArgs &a, hipStream_t s)
     return launch_stream_inst<T, INT8, WG_PER_CU, false>(a, s, grid, 0);
 }
 
-template <bool INT8, int PMODE, int D, int MT>
+template <bool INT8, int PMODE, int D, int MT, bool A_E5M2 = false>
 static hipError_t launch_defer_inst(const GemmArgs &a, hipStream_t s)
 {
     using T = DeferTile<MT>;
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_defer_kernel<INT8, PMODE, D, MT>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_defer_kernel<INT8, PMODE, D, MT, A_E5M2>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
         if (e != hipSuccess)
             return e;
@@ -1455,7 +1456,7 @@ static hipError_t launch_defer_inst(const GemmArgs &a, hipStream_t s)
     g.tiles_m = (int)((a.M + T::BM - 1) / T::BM);
     g.tiles_n = (int)(a.N / T::BN);
     const int grid = defer_workgroups(a.M, a.N, T::BM);
-    launch_gemm_kernel(gemm_nt_defer_kernel<INT8, PMODE, D, MT>, dim3((unsigned)grid), dim3(T::THREADS), T::LDS_BYTES, s, g);
+    launch_gemm_kernel(gemm_nt_defer_kernel<INT8, PMODE, D, MT, A_E5M2>, dim3((unsigned)grid), dim3(T::THREADS), T::LDS_BYTES, s, g);
     return hipGetLastError();
 }
 
@@ -1504,7 +1505,32 @@ static hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     }
 }
 
-hipError_t launch_fp8_gemm(const GemmArgs &a, hipStream_t s) { return launch_gemm<false>(a, s); }
+// E5M2 A operand (gradient GEMMs of the HYBRID recipe; no penalty, no residual): the deferred
+// kernel where it applies, else the register-staged kernel.
+static hipError_t launch_fp8_gemm_e5m2(const GemmArgs &a, hipStream_t s)
+{
+    if (a.p != 0 || a.residual != nullptr)
+        return hipErrorInvalidValue;
+    const int v = resolve_variant(a);
+    if (v == 15) {
+        const int64_t kt = a.K / 128;
+        if (kt >= 16)
+            return launch_defer_inst<false, 0, 15, 4, true>(a, s);
+        return kt >= 8 ? launch_defer_inst<false, 0, 7, 4, true>(a, s) : launch_defer_inst<false, 0, 3, 4, true>(a, s);
+    }
+    if (v == 16)
+        return launch_defer_inst<false, 0, 15, 3, true>(a, s);
+    if (a.M * a.N <= 128 * 128 * 16)
+        return launch_tile<T64x64, false, false, true>(a, s);
+    if (a.M * a.N <= 1024 * 1024)
+        return launch_tile<T128x128, false, false, true>(a, s);
+    return launch_tile<T256x256, false, false, true>(a, s);
+}
+
+hipError_t launch_fp8_gemm(const GemmArgs &a, hipStream_t s)
+{
+    return a.a_e5m2 ? launch_fp8_gemm_e5m2(a, s) : launch_gemm<false>(a, s);
+}
 template <int NBLK, int MB, int UNROLL, int WAVES, bool IL>
 static hipError_t launch_skinny(const GemmArgs &a, hipStream_t s)
 {

@@ -93,7 +93,9 @@ __device__ __forceinline__ void for_each_constant(std::integer_sequence<int, Is.
     (f(std::integral_constant<int, Is>{}), ...);
 }
 
-template <bool INT8, int PMODE, int D, int MT>
+// A_E5M2 (FP8 only): the A operand holds E5M2 codes (the gradient of the HYBRID recipe, Sec. 4.3);
+// B is always E4M3.  The MFMA takes the format of each source from a modifier.
+template <bool INT8, int PMODE, int D, int MT, bool A_E5M2 = false>
 __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
 {
     using T = DeferTile<MT>;
@@ -239,7 +241,10 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
                          : "+a"(acc[i][j])
                          : "v"(b0), "v"(a0), "v"(b1), "v"(a1));
         } else {
-            asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[j]), "v"(fa[ab]));
+            if constexpr (A_E5M2)
+                asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0 blgp:1" : "+a"(acc[i][j]) : "v"(fb[j]), "v"(fa[ab]));
+            else
+                asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[j]), "v"(fa[ab]));
         }
     };
     // first MFMA of a block in a tile: accumulates onto zero
@@ -254,7 +259,10 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
                          : "=&a"(acc[i][j])
                          : "v"(b0), "v"(a0), "v"(b1), "v"(a1));
         } else {
-            asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, 0" : "=&a"(acc[i][j]) : "v"(fb[j]), "v"(fa[ab]));
+            if constexpr (A_E5M2)
+                asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, 0 blgp:1" : "=&a"(acc[i][j]) : "v"(fb[j]), "v"(fa[ab]));
+            else
+                asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, 0" : "=&a"(acc[i][j]) : "v"(fb[j]), "v"(fa[ab]));
         }
     };
 

@@ -21,6 +21,10 @@ hipError_t launch_quantize2_e4m3(const void *x0_bf16, int64_t rows0, int64_t col
 hipError_t launch_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
                                 uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
                                 hipStream_t s);
+// the same cast into E5M2 (range +-57344), the gradient format of the HYBRID recipe
+hipError_t launch_quantize_e5m2(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
+                                uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
+                                hipStream_t s);
 hipError_t launch_delayed_state_init(void *state, hipStream_t s);
 hipError_t launch_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
                                         int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s);
@@ -43,6 +47,7 @@ struct GemmArgs {
     float inv_tau;          // 1 / (tau + eps)
     int p;                  // penalty power; 0 = no penalty
     float *partials;        // one fp32 per workgroup when p != 0
+    bool a_e5m2;            // FP8 only: A holds E5M2 codes (B is always E4M3)
     void *sk_workspace;     // stream-K scratch (256-byte aligned) or nullptr: then no stream-K
     size_t sk_workspace_bytes;
 };

@@ -1,0 +1,139 @@
+"""GPU parity of the HYBRID recipe's gradient path (Sec. 4.3: E4M3 activations and weights, E5M2
+gradients): E5M2 quantize-cast bit-exact against the CPU oracle, dgrad / wgrad with E5M2 dY within
+the FP8 GEMM tolerance, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2511_23225_amd as tw
+from paper_2511_23225_amd import synth
+from gpu_util import DEV, to_dev_bf16, to_dev, bf16_bits, scalar_f32, workspace, check_gemm
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def is_nan_code(q):
+    return ((q & 0x7C) == 0x7C) & ((q & 0x03) != 0)
+
+
+def gpu_quantize_e5m2(x_dev, amax_dev, transpose=True):
+    r, c = x_dev.shape
+    q = torch.empty((r, c), dtype=torch.uint8, device=DEV)
+    qT = torch.empty((c, r), dtype=torch.uint8, device=DEV) if transpose else None
+    s, si = scalar_f32(), scalar_f32()
+    tw.tweo_quantize_e5m2(x_dev, amax_dev, q, qT, s, si)
+    return q, qT, s, si
+
+
+def test_quantize_e5m2_all_bf16_patterns_times_scales():
+    # every bf16 bit pattern, for scales that exercise flush, subnormal, normal, saturate
+    allx = np.arange(65536, dtype=np.uint32).astype(np.uint16).reshape(256, 256)
+    amaxes = [57344.0, 1.0, 9873.0, 3.0e4, 0.013, 1e-30, 3.0e38, 57344.0 * 8, 5000.0, 0.0, np.inf, np.nan]
+    xd = to_dev_bf16(allx)
+    for amax in amaxes:
+        say("quantize e5m2 all patterns, amax=%r" % amax)
+        q, qT, s, si = gpu_quantize_e5m2(xd, scalar_f32(amax))
+        scale, scale_inv = oracle.scale_from_amax_e5m2(np.float32(amax))
+        assert s.cpu().numpy()[0] == scale and si.cpu().numpy()[0] == scale_inv
+        want, wantT = oracle.quantize_e5m2(allx, scale)
+        got, gotT = q.cpu().numpy(), qT.cpu().numpy()
+        nan = is_nan_code(want)
+        assert np.array_equal(is_nan_code(got), nan)  # NaN -> a NaN code (which one is unpinned)
+        assert np.array_equal(got[~nan], want[~nan])
+        assert np.array_equal(gotT, got.T)
+        assert not (((got & 0x7F) == 0x7C) & ~nan).any()  # a cast never produces an infinity
+
+
+@pytest.mark.parametrize("shape", [(8, 8), (24, 40), (100, 72), (256, 512), (1000, 1024), (16, 65536)])
+def test_quantize_e5m2_shapes(shape):
+    r, c = shape
+    say("quantize e5m2 shape %dx%d" % shape)
+    rng = np.random.default_rng(r * 131 + c)
+    x = synth.f32_to_bf16_bits((rng.standard_normal((r, c)) * np.exp(rng.uniform(-8, 3, (r, c)))).astype(np.float32))
+    amax = oracle.amax_bf16(x)
+    q, qT, _, _ = gpu_quantize_e5m2(to_dev_bf16(x), scalar_f32(amax))
+    scale, _ = oracle.scale_from_amax_e5m2(amax)
+    want, wantT = oracle.quantize_e5m2(x, scale)
+    assert np.array_equal(q.cpu().numpy(), want) and np.array_equal(qT.cpu().numpy(), wantT)
+    assert (want & 0x7F).max() == 0x7B  # the element that attains amax saturates the range
+
+
+def oracle_e4m3(x):
+    s, si = oracle.scale_from_amax(oracle.amax_bf16(x))
+    q, qT = oracle.quantize_e4m3(x, s)
+    return q, qT, si
+
+
+def oracle_e5m2(x):
+    s, si = oracle.scale_from_amax_e5m2(oracle.amax_bf16(x))
+    q, qT = oracle.quantize_e5m2(x, s)
+    return q, qT, si
+
+
+# tiny (64x64 tiles), ragged, mid-sized (register-staged 128 / 256 tiles), whole-tile shapes for
+# the deferred-epilogue kernel (dgrad: rows M, contraction N; wgrad: rows N, contraction M) with
+# one and with several tiles per workgroup, and a long contraction that takes the 192-row tiles
+HYBRID_CASES = [
+    (0, 0, 64, 64, 48, 0),
+    (1, 0, 208, 264, 144, 0),
+    (0, 0, 256, 512, 512, 0),
+    (3, 0, 1024, 1024, 1024, 0),
+    (3, 1, 4352, 2048, 4096, 0),
+    (3, 2, 2304, 512, 4608, 15),
+    (1, 1, 2048, 768, 2304, 16),
+]
+
+
+@pytest.mark.parametrize("case", HYBRID_CASES)
+def test_bwd_hybrid(case):
+    cfg, gi, M, K, N, tile = case
+    say("bwd hybrid cfg=%d M=%d K=%d N=%d tile=%d" % (cfg, M, K, N, tile))
+    x, w, dy = synth.fp8_linear_inputs(cfg, gi, M=M, K=K, N=N)
+    xq, xqT, sxi = oracle_e4m3(x)
+    wq, wqT, swi = oracle_e4m3(w)
+    dyq, dyqT, sdyi = oracle_e5m2(dy)
+    dx_ref, dx_abs = oracle.fp8_linear_dgrad(dyq, wq, sdyi, swi, dy_e5m2=True)
+    dw_ref, dw_abs = oracle.fp8_linear_wgrad(dyq, xq, sdyi, sxi, dy_e5m2=True)
+    dx = torch.full((M, K), float('nan'), dtype=torch.bfloat16, device=DEV)
+    dw = torch.full((N, K), float('nan'), dtype=torch.bfloat16, device=DEV)
+    tw.tweo_set_gemm_tile(tile)
+    try:
+        tw.tweo_fp8_linear_bwd_hybrid(to_dev(dyq), to_dev(dyqT), scalar_f32(sdyi), to_dev(wqT),
+                                      scalar_f32(swi), to_dev(xqT), scalar_f32(sxi), M, N, K, dx, dw,
+                                      workspace(tw.TWEO_OP_FP8_LINEAR_BWD, M, N, K))
+        torch.cuda.synchronize()
+    finally:
+        tw.tweo_set_gemm_tile(0)
+    check_gemm(bf16_bits(dx), dx_ref, dx_abs, N, "dgrad")
+    check_gemm(bf16_bits(dw), dw_ref, dw_abs, M, "wgrad")
+
+
+def test_hybrid_whole_backward_from_bf16():
+    cfg, gi, M, K, N = 0, 0, 256, 512, 512
+    say("hybrid bf16 path M=%d K=%d N=%d" % (M, K, N))
+    x, w, dy = synth.fp8_linear_inputs(cfg, gi)
+    u8 = lambda *s: torch.empty(s, dtype=torch.uint8, device=DEV)
+    xq, xqT, wq, wqT, dyq, dyqT = u8(M, K), u8(K, M), u8(N, K), u8(K, N), u8(M, N), u8(N, M)
+    sc = torch.zeros(16, dtype=torch.float32, device=DEV)
+    saved = tw.make_saved(xq, xqT, wq, wqT, sc)
+    y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    dx = torch.full((M, K), float('nan'), dtype=torch.bfloat16, device=DEV)
+    dw = torch.full((N, K), float('nan'), dtype=torch.bfloat16, device=DEV)
+    ws = workspace(tw.TWEO_OP_FP8_LINEAR_FWD_BF16, M, N, K)
+    tw.tweo_fp8_linear_fwd_bf16(to_dev_bf16(x), to_dev_bf16(w), y, saved, workspace=ws)
+    tw.tweo_fp8_linear_bwd_bf16_hybrid(to_dev_bf16(dy), saved, K, dyq, dyqT, dx, dw, ws)
+    torch.cuda.synchronize()
+    oxq, _, sxi = oracle_e4m3(x)
+    owq, _, swi = oracle_e4m3(w)
+    odyq, odyqT, sdyi = oracle_e5m2(dy)
+    assert np.array_equal(dyq.cpu().numpy(), odyq) and np.array_equal(dyqT.cpu().numpy(), odyqT)
+    assert sc.cpu().numpy()[8] == sdyi
+    dx_ref, dx_abs = oracle.fp8_linear_dgrad(odyq, owq, sdyi, swi, dy_e5m2=True)
+    dw_ref, dw_abs = oracle.fp8_linear_wgrad(odyq, oxq, sdyi, sxi, dy_e5m2=True)
+    check_gemm(bf16_bits(dx), dx_ref, dx_abs, N, "dgrad")
+    check_gemm(bf16_bits(dw), dw_ref, dw_abs, M, "wgrad")
