@@ -277,3 +277,30 @@ def w8a8_linear(xq, wq, alpha, want_acc=False):
         lib().orc_w8a8_linear(_p(xq, _i8), _p(wq, _i8), _i64(M), _i64(N), _i64(K),
                               _f32(float(alpha)), _p(y, _u16), _p(acc, _i32))
     return (y, acc) if want_acc else y
+
+
+def quantize_i8_rows(x, eps=0.0):
+    """Row-granular AbsMax (Sec. 4.4, Eq. 4: per-token activations, per-channel weights)."""
+    x = _c(x, np.uint16)
+    rows, cols = x.shape
+    q = np.empty((rows, cols), np.int8)
+    step = np.empty(rows, np.float32)
+    lib().orc_quantize_i8_rows(_p(x, _u16), _i64(rows), _i64(cols), _f32(float(eps)), _p(q, _i8),
+                               _p(step, _f32))
+    return q, step
+
+
+def w8a8_linear_scaled(xq, wq, sx, sw):
+    """y = bf16((fp32(acc) * sx[m]) * sw[n]); sx / sw of length 1 mean per-tensor steps."""
+    xq, wq = _c(xq, np.int8), _c(wq, np.int8)
+    M, K = xq.shape
+    N, K2 = wq.shape
+    assert K == K2
+    sx = _c(np.atleast_1d(sx), np.float32)
+    sw = _c(np.atleast_1d(sw), np.float32)
+    assert sx.size in (1, M) and sw.size in (1, N)
+    y = np.empty((M, N), np.uint16)
+    lib().orc_w8a8_linear_scaled(_p(xq, _i8), _p(wq, _i8), _i64(M), _i64(N), _i64(K), _p(sx, _f32),
+                                 _i64(0 if sx.size == 1 else 1), _p(sw, _f32),
+                                 _i64(0 if sw.size == 1 else 1), _p(y, _u16))
+    return y

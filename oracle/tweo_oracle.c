@@ -21,7 +21,9 @@
  * nearest-value search in exact rationals, a library cast for the in-range
  * part, the printed penalty values 0.0625 / 1 / 10000 (Sec. 3.3), integer
  * matmul by a library, adjoint identities between fwd/dgrad/wgrad, AbsMax
- * end points +-Q_8 (Sec. 4.4).  No function here is "parity unpinned"; the
+ * end points +-Q_8 (Sec. 4.4); for the row-granular INT8 functions exact
+ * rationals, row independence, power-of-two steps and a library matmul
+ * (tests/test_oracle_int8_rows.py).  No function here is "parity unpinned"; the
  * conventions the paper leaves open (NaN handling, zero amax, rounding mode of
  * "round") are listed where they are taken.
  */
@@ -527,6 +529,53 @@ void orc_w8a8_linear_small_m(const int8_t *xq, const int8_t *wq, int64_t M, int6
                 acc += (int32_t)xq[m * K + k] * (int32_t)wq[n * K + k];
             volatile float prod = (float)acc * alpha;
             y[m * N + n] = orc_f32_to_bf16(prod);
+        }
+}
+
+/*
+ * AbsMax quantisation at row granularity (Sec. 4.4, Eq. 4 with the "per-token"
+ * and "per-channel" choices of s): every row of a [rows, cols] matrix gets its
+ * own s_r = max_c |x_rc| + eps.  For activations a row is a token vector; for a
+ * weight stored [out, in] a row is an output channel.  As in the per-tensor
+ * case the division and the product with Q_8 are folded into one fp32 factor:
+ * inv_r = 127 / s_r (one fp32 division), X_q = round(x * inv_r) (one fp32
+ * multiply, round to nearest even), and the dequantisation step that Eq. 4
+ * applies afterwards is step_r = s_r / 127 (one fp32 division).  The maximum is
+ * taken on magnitude patterns (a NaN in a row poisons that row only: its step
+ * is NaN and its codes are 0).  A row of zeros with eps = 0 gives inv = inf,
+ * products NaN, codes 0 and step 0.
+ */
+void orc_quantize_i8_rows(const uint16_t *x, int64_t rows, int64_t cols, float eps, int8_t *q,
+                          float *step)
+{
+    for (int64_t r = 0; r < rows; ++r) {
+        volatile float s = orc_amax_bf16(x + r * cols, cols) + eps;
+        volatile float inv = 127.0f / s;
+        volatile float st = s / 127.0f;
+        orc_quantize_i8(x + r * cols, cols, inv, q + r * cols);
+        step[r] = st;
+    }
+}
+
+/*
+ * W8A8 linear with row-granular steps: acc[m,n] as above, then the two X_deq
+ * factors of Eq. 4 one after the other, y = bf16( (fp32(acc) * sx[m]) * sw[n] ):
+ * sx is per token (stride 1) or per tensor (stride 0), sw per output channel
+ * (stride 1) or per tensor (stride 0).  Two fp32 multiplies in this order.
+ */
+void orc_w8a8_linear_scaled(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N, int64_t K,
+                            const float *sx, int64_t sx_stride, const float *sw,
+                            int64_t sw_stride, uint16_t *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t m = 0; m < M; ++m) {
+            int32_t acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int32_t)xq[m * K + k] * (int32_t)wq[n * K + k];
+            volatile float t = (float)acc * sx[m * sx_stride];
+            volatile float u = t * sw[n * sw_stride];
+            y[m * N + n] = orc_f32_to_bf16(u);
         }
 }
 
