@@ -221,6 +221,43 @@ tweo_status tweo_w8a8_linear(const int8_t *xq, const int8_t *wq, int64_t M, int6
                              void *stream);
 
 /*
+ * AbsMax INT8 quantisation with one s per row (Sec. 4.4 Eq. 4 at the "per-token"
+ * granularity for activations [tokens, features] and at the "per-channel"
+ * granularity for weights [out, in]), computed from the data in the same call:
+ *   s_r = max_c |x[r,c]| + eps            (fp32)
+ *   q[r,c] = clamp( rne( fp32(x[r,c]) * (127 / s_r) ), -127, 127 )
+ *   step_out[r] = s_r / 127               (the factor X_deq applies to q)
+ * 127 / s_r and s_r / 127 are single fp32 divisions.  A NaN in a row gives that
+ * row step NaN and codes 0; a row of zeros with eps = 0 gives step 0 and codes 0.
+ *   x_bf16 [rows, cols] device, 16-byte aligned, cols % 8 == 0; q int8
+ *   [rows, cols] device, 16-byte aligned; step_out fp32 [rows] device.
+ * Errors: TWEO_ERR_INVALID_ARG (null, misaligned, eps negative or NaN),
+ * TWEO_ERR_UNSUPPORTED (cols % 8 != 0, a dimension above 2^24).
+ */
+tweo_status tweo_quantize_i8_rows(const void *x_bf16, int64_t rows, int64_t cols, float eps,
+                                  int8_t *q, float *step_out, void *stream);
+
+/*
+ * W8A8 linear with finer step granularities (Sec. 4.4: per-token activations
+ * "K", per-channel weights "C", combined freely with per-tensor "T"):
+ *   y[m,n] = bf16( ( fp32( sum_k xq[m,k] wq[n,k] ) * x_step[m or 0] ) * w_step[n or 0] )
+ * exact int32 accumulation, then two fp32 multiplies in this order.
+ *   x_step: device fp32 [M] when x_step_per_token = 1, [1] when 0;
+ *   w_step: device fp32 [N] when w_step_per_channel = 1, [1] when 0.
+ *   xq [M,K], wq [N,K] int8 device, 16-byte aligned, K % 16 == 0; y_bf16 [M,N]
+ *   device, 16-byte aligned, N % 8 == 0.  Needs no workspace.
+ * Bit-exact for every M.  Large shapes run on the general tiled kernels, not on
+ * the fastest per-tensor one: finer granularity costs throughput, as the paper
+ * says of it.
+ * Errors: TWEO_ERR_INVALID_ARG (null, misaligned, a flag other than 0 / 1),
+ * TWEO_ERR_UNSUPPORTED (shape rules above).
+ */
+tweo_status tweo_w8a8_linear_scaled(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N,
+                                    int64_t K, const float *x_step, int x_step_per_token,
+                                    const float *w_step, int w_step_per_channel, void *y_bf16,
+                                    void *stream);
+
+/*
  * State a forward pass leaves for the backward pass: the quantized operands,
  * their transposes and the per-tensor scalars.  All members are device
  * pointers to caller-owned buffers.

@@ -21,7 +21,8 @@ EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quan
            "tweo_fp8_linear_fwd_bf16", "tweo_fp8_linear_bwd_bf16", "tweo_set_gemm_tile",
            "tweo_set_stream_k", "tweo_penalty_grad_inject", "tweo_delayed_state_bytes",
            "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed", "tweo_profile_gemm_launches",
-           "tweo_quantize_e5m2", "tweo_fp8_linear_bwd_hybrid", "tweo_fp8_linear_bwd_bf16_hybrid")
+           "tweo_quantize_e5m2", "tweo_fp8_linear_bwd_hybrid", "tweo_fp8_linear_bwd_bf16_hybrid",
+           "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled")
 
 
 class TweoError(RuntimeError):
@@ -66,6 +67,8 @@ def load():
     L.tweo_fp8_linear_bwd_hybrid.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
     L.tweo_quantize_i8.argtypes = [vp, i64, f32, vp, vp]
     L.tweo_w8a8_linear.argtypes = [vp, vp, i64, i64, i64, f32, vp, vp, sz, vp]
+    L.tweo_quantize_i8_rows.argtypes = [vp, i64, i64, f32, vp, vp, vp]
+    L.tweo_w8a8_linear_scaled.argtypes = [vp, vp, i64, i64, i64, vp, ctypes.c_int, vp, ctypes.c_int, vp, vp]
     L.tweo_fp8_linear_fwd_bf16.argtypes = [vp, vp, vp, i64, i64, i64, vp, ctypes.POINTER(PenaltyCfg),
                                            vp, ctypes.POINTER(Fp8Saved), vp, sz, vp]
     L.tweo_fp8_linear_bwd_bf16.argtypes = [vp, ctypes.POINTER(Fp8Saved), i64, i64, i64, vp, vp, vp,
@@ -214,6 +217,24 @@ def tweo_w8a8_linear(xq, wq, alpha, y_bf16, workspace=None):
     wp, wb = _ws(workspace)
     _check(load().tweo_w8a8_linear(_ptr(xq), _ptr(wq), M, N, K, float(alpha), _ptr(y_bf16), wp, wb,
                                    _stream()), "tweo_w8a8_linear")
+
+
+def tweo_quantize_i8_rows(x_bf16, eps, q, step_out):
+    rows, cols = x_bf16.shape
+    _check(load().tweo_quantize_i8_rows(_ptr(x_bf16), rows, cols, float(eps), _ptr(q), _ptr(step_out),
+                                        _stream()), "tweo_quantize_i8_rows")
+
+
+def tweo_w8a8_linear_scaled(xq, wq, x_step, w_step, y_bf16):
+    """x_step holds M steps (per token) or 1 (per tensor); w_step N (per channel) or 1."""
+    M, K = xq.shape
+    N = wq.shape[0]
+    if x_step.numel() not in (1, M) or w_step.numel() not in (1, N):
+        raise ValueError("step vectors must have 1 or M / N elements")
+    _check(load().tweo_w8a8_linear_scaled(_ptr(xq), _ptr(wq), M, N, K, _ptr(x_step),
+                                          1 if x_step.numel() > 1 else 0,
+                                          _ptr(w_step), 1 if w_step.numel() > 1 else 0, _ptr(y_bf16),
+                                          _stream()), "tweo_w8a8_linear_scaled")
 
 
 def make_saved(xq, xqT, wq, wqT, scalars):

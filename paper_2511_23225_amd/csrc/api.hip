@@ -338,6 +338,42 @@ tweo_status tweo_w8a8_linear(const int8_t *xq, const int8_t *wq, int64_t M, int6
     return hip_status(launch_i8_gemm(a, (hipStream_t)stream));
 }
 
+tweo_status tweo_quantize_i8_rows(const void *x_bf16, int64_t rows, int64_t cols, float eps, int8_t *q,
+                                  float *step_out, void *stream)
+{
+    if (!x_bf16 || !q || !step_out || rows <= 0 || cols <= 0 || !aligned16(x_bf16) || !aligned16(q) ||
+        !(eps >= 0.0f))
+        return TWEO_ERR_INVALID_ARG;
+    if (cols % 8 != 0 || rows > kMaxDim || cols > kMaxDim)
+        return TWEO_ERR_UNSUPPORTED;
+    return hip_status(launch_quantize_i8_rows(x_bf16, rows, cols, eps, q, step_out, (hipStream_t)stream));
+}
+
+tweo_status tweo_w8a8_linear_scaled(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N, int64_t K,
+                                    const float *x_step, int x_step_per_token, const float *w_step,
+                                    int w_step_per_channel, void *y_bf16, void *stream)
+{
+    if (!xq || !wq || !y_bf16 || !x_step || !w_step || M <= 0 || N <= 0 || K <= 0 || !aligned16(xq) ||
+        !aligned16(wq) || !aligned16(y_bf16) || (x_step_per_token != 0 && x_step_per_token != 1) ||
+        (w_step_per_channel != 0 && w_step_per_channel != 1))
+        return TWEO_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || K % 16 != 0 || N % 8 != 0)
+        return TWEO_ERR_UNSUPPORTED;
+    GemmArgs a{};
+    a.A = (const uint8_t *)xq;
+    a.B = (const uint8_t *)wq;
+    a.M = M;
+    a.N = N;
+    a.K = K;
+    a.alpha = 1.0f;
+    a.out = y_bf16;
+    a.row_step = x_step;
+    a.row_step_stride = x_step_per_token;
+    a.col_step = w_step;
+    a.col_step_stride = w_step_per_channel;
+    return hip_status(launch_i8_gemm(a, (hipStream_t)stream));
+}
+
 tweo_status tweo_fp8_linear_fwd_bf16(const void *x_bf16, const void *w_bf16,
                                      const void *residual_bf16, int64_t M, int64_t N, int64_t K,
                                      void *y_bf16, const tweo_penalty_cfg *pen,

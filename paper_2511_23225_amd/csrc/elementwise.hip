@@ -620,6 +620,87 @@ hipError_t launch_quantize_i8(const void *x_bf16, int64_t n, float inv_step, int
 }
 
 // ---------------------------------------------------------------------------
+// Row-granular AbsMax INT8 (Sec. 4.4 Eq. 4 with one s per token vector or per output channel):
+// s_r = max_c |x_rc| + eps, q = clamp(rne(x * (127 / s_r)), +-127), step_r = s_r / 127.
+// TPR lanes share a row (one wave for short rows, four for long ones); the first four 16-byte
+// pieces of each lane stay in registers between the maximum and the rounding, so rows of up to
+// 32*TPR elements are read from memory once; longer rows read the rest a second time (from L2).
+// 3 B/element + 4 B/row.
+constexpr int kQrowThreads = 256;
+constexpr int kQrowCached = 4;
+
+template <int TPR>
+__global__ __launch_bounds__(kQrowThreads) void quantize_i8_rows_kernel(const uint4 *__restrict__ x, int64_t rows,
+                                                                        int vec_per_row, float eps,
+                                                                        uint2 *__restrict__ q,
+                                                                        float *__restrict__ step)
+{
+    constexpr int RPB = kQrowThreads / TPR;
+    const int t = threadIdx.x % TPR;
+    const int64_t row_raw = (int64_t)blockIdx.x * RPB + threadIdx.x / TPR;
+    const bool live = row_raw < rows;  // uniform over a wave: TPR is a multiple of the wave size
+    const int64_t row = live ? row_raw : rows - 1;
+    const uint4 *xr = x + row * vec_per_row;
+    uint4 c[kQrowCached];
+    uint32_t m = 0;
+#pragma unroll
+    for (int u = 0; u < kQrowCached; ++u) {
+        const int i = t + u * TPR;
+        c[u] = make_uint4(0u, 0u, 0u, 0u);
+        if (i < vec_per_row) {
+            c[u] = xr[i];
+            m = pk_absmax4(m, c[u]);
+        }
+    }
+    for (int i = t + kQrowCached * TPR; i < vec_per_row; i += TPR)
+        m = pk_absmax4(m, xr[i]);
+    uint32_t r = (m & 0xFFFFu) > (m >> 16) ? (m & 0xFFFFu) : (m >> 16);
+    r = wave_reduce_max_u32(r);
+    if constexpr (TPR > kWave) {
+        static_assert(TPR == kQrowThreads, "a long row takes the whole workgroup");
+        __shared__ uint32_t red[kQrowThreads / kWave];
+        if ((threadIdx.x & (kWave - 1)) == 0)
+            red[threadIdx.x / kWave] = r;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kQrowThreads / kWave; ++w)
+            r = red[w] > r ? red[w] : r;
+    }
+    const float s = __uint_as_float(r << 16) + eps;
+    const float inv = 127.0f / s;
+    if (!live)
+        return;
+    if (t == 0)
+        step[row] = s / 127.0f;
+    uint2 *qr = q + row * vec_per_row;
+#pragma unroll
+    for (int u = 0; u < kQrowCached; ++u) {
+        const int i = t + u * TPR;
+        if (i < vec_per_row)
+            qr[i] = make_uint2(q_i8x4(c[u].x, c[u].y, inv), q_i8x4(c[u].z, c[u].w, inv));
+    }
+    for (int i = t + kQrowCached * TPR; i < vec_per_row; i += TPR) {
+        const uint4 v = xr[i];
+        qr[i] = make_uint2(q_i8x4(v.x, v.y, inv), q_i8x4(v.z, v.w, inv));
+    }
+}
+
+hipError_t launch_quantize_i8_rows(const void *x_bf16, int64_t rows, int64_t cols, float eps, int8_t *q,
+                                   float *step, hipStream_t s)
+{
+    const int vec = (int)(cols / 8);
+    if (vec <= kWave * kQrowCached) {
+        const int64_t blocks = (rows + kQrowThreads / kWave - 1) / (kQrowThreads / kWave);
+        hipLaunchKernelGGL(quantize_i8_rows_kernel<kWave>, dim3((unsigned)blocks), dim3(kQrowThreads), 0, s,
+                           (const uint4 *)x_bf16, rows, vec, eps, (uint2 *)q, step);
+    } else {
+        hipLaunchKernelGGL(quantize_i8_rows_kernel<kQrowThreads>, dim3((unsigned)rows), dim3(kQrowThreads), 0, s,
+                           (const uint4 *)x_bf16, rows, vec, eps, (uint2 *)q, step);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Penalty-gradient injection (the derivative of the loss of Sec. 3.3 with
 // respect to the penalised activation, added to the incoming output gradient):
 //   out = bf16( dy + coef * sign(a) * (|a| / (tau+eps))^(p-1) ),

@@ -119,6 +119,18 @@ __device__ __forceinline__ void epilogue_impl(const GemmDev &g, ACC (&acc)[T::MT
     const bool n_ok = n0 + rd_seg * 8 < g.N;
     const bool has_res = RES < 0 ? g.residual != nullptr : RES != 0;
     const bool has_pen = PMODE < 0 ? g.p != 0 : PMODE != 0;
+    // dequantisation steps per row / column (INT8, general form only): this lane's eight columns
+    // are the same in every pass; alpha is 1 then
+    const bool has_vec = INT8 && RES < 0 && g.rs != nullptr;
+    float cstep[8] = {1.0f, 1.0f, 1.0f, 1.0f, 1.0f, 1.0f, 1.0f, 1.0f};
+    if (has_vec) {
+        alpha = 1.0f;
+        if (n_ok) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+                cstep[r] = g.cs[(int64_t)(n0 + rd_seg * 8 + r) * g.cs_stride];
+        }
+    }
     if constexpr (RES == 0 && INTERIOR && PMODE >= 0) {
         // Fast path: round to bf16 in the MFMA layout, stage packed values (half the LDS bytes),
         // two bands in flight.
@@ -184,6 +196,12 @@ __device__ __forceinline__ void epilogue_impl(const GemmDev &g, ACC (&acc)[T::MT
             if (INTERIOR || (row_u < rows_left && n_ok)) {
                 const int64_t row_off = (int64_t)row_u * g.N * 2;
                 float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                if (has_vec) {
+                    const float rstep = g.rs[(int64_t)(m0 + row_u + rd_row) * g.rs_stride];
+#pragma unroll
+                    for (int r = 0; r < 8; ++r)
+                        v[r] = (v[r] * rstep) * cstep[r];
+                }
                 if (has_res) {
                     const uint4 rr = *(const uint4 *)(res_base + row_off + lane_off);
                     v[0] += bf16lo_to_f32(rr.x);
@@ -253,9 +271,12 @@ __device__ __forceinline__ void epilogue(const GemmDev &g, ACC (&acc)[T::MT][T::
 {
     const bool interior = (tm + 1) * T::BM <= g.M && (tn + 1) * T::BN <= g.N;
     const bool res = g.residual != nullptr;
+    const bool vec = INT8 && g.rs != nullptr;  // step vectors: the general form below applies them
 #define TWEO_EPI(PM, RS, IN) \
     epilogue_impl<T, INT8, PM, RS, IN>(g, acc, smem, tm, tn, wm, wn, lane, wave, tid, partial_index, band_hook)
-    if (interior && g.p == 4 && !res)
+    if (vec)
+        TWEO_EPI(-1, -1, false);
+    else if (interior && g.p == 4 && !res)
         TWEO_EPI(4, 0, true);
     else if (interior && g.p == 4)
         TWEO_EPI(4, 1, true);
@@ -1052,11 +1073,18 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
 // with v_mfma_i32_16x16x64_i8 (operands loaded straight from global memory in
 // the MFMA lane layout: row = lane%16, 16 bytes at k = 16*(lane/16)), and the 8
 // partial int32 tiles are added through LDS - exact, so the result is the same
-// bits as any other summation order.  y = bf16(fp32(acc) * alpha) (Sec. 4.4).
-template <int NBLK, int MB, int UNROLL, int WAVES, bool IL>
+// bits as any other summation order.  y = bf16(fp32(acc) * alpha) (Sec. 4.4), or with VEC
+// y = bf16((fp32(acc) * rs[m]) * cs[n]): dequantisation steps per token and per output channel.
+struct StepVectors {
+    const float *rs, *cs;
+    int rs_stride, cs_stride;
+};
+
+template <int NBLK, int MB, int UNROLL, int WAVES, bool IL, bool VEC>
 __global__ __launch_bounds__(WAVES * 64) void w8a8_skinny_kernel(const int8_t *__restrict__ X,
                                                           const int8_t *__restrict__ W, int M, int N,
-                                                          int K, float alpha, uint16_t *__restrict__ Y)
+                                                          int K, float alpha, StepVectors sv,
+                                                          uint16_t *__restrict__ Y)
 {
     constexpr int STEP = 64;
     __shared__ v4i red[WAVES][MB][kWave];
@@ -1131,10 +1159,19 @@ __global__ __launch_bounds__(WAVES * 64) void w8a8_skinny_kernel(const int8_t *_
                 sum += red[w][b][l];
             const int m = b * 16 + (l & 15), n = n0 + a * 16 + 4 * (l >> 4);
             if (m < M && n < N) {
-                const uint2 packed =
-                    make_uint2(pack_bf16x2((float)sum[0] * alpha, (float)sum[1] * alpha),
-                               pack_bf16x2((float)sum[2] * alpha, (float)sum[3] * alpha));
-                *(uint2 *)(Y + (int64_t)m * N + n) = packed;
+                float y[4];
+                if constexpr (VEC) {
+                    const float rstep = sv.rs[(int64_t)m * sv.rs_stride];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        y[v] = ((float)sum[v] * rstep) * sv.cs[(int64_t)(n + v) * sv.cs_stride];
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        y[v] = (float)sum[v] * alpha;
+                }
+                *(uint2 *)(Y + (int64_t)m * N + n) =
+                    make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
             }
         }
     }
@@ -1283,13 +1320,13 @@ static int pick_variant(int64_t M, int64_t N, int64_t K)
 static bool defer_ok(const GemmArgs &a)
 {
     return a.M % 256 == 0 && a.N % 256 == 0 && a.K % 128 == 0 && a.K >= 512 && a.residual == nullptr &&
-           (a.p == 0 || a.p == 4) && a.N <= ((int64_t)1 << 22);
+           a.row_step == nullptr && (a.p == 0 || a.p == 4) && a.N <= ((int64_t)1 << 22);
 }
 
 static bool defer192_ok(const GemmArgs &a)
 {
     return a.N % 256 == 0 && a.K % 128 == 0 && a.K >= 2048 && a.residual == nullptr &&
-           (a.p == 0 || a.p == 4) && a.N <= ((int64_t)1 << 22);
+           a.row_step == nullptr && (a.p == 0 || a.p == 4) && a.N <= ((int64_t)1 << 22);
 }
 
 static int resolve_variant(const GemmArgs &a)
@@ -1340,6 +1377,10 @@ static hipError_t launch_tile(const GemmArgs &a, hipStream_t s)
     g.inv_tau = a.inv_tau;
     g.p = a.p;
     g.partials = a.partials;
+    g.rs = a.row_step;
+    g.cs = a.col_step;
+    g.rs_stride = a.row_step_stride;
+    g.cs_stride = a.col_step_stride;
     g.tiles_m = (int)((a.M + T::BM - 1) / T::BM);
     g.tiles_n = (int)((a.N + T::BN - 1) / T::BN);
     const dim3 grid((unsigned)(g.tiles_m * g.tiles_n)), block(T::THREADS);
@@ -1394,6 +1435,10 @@ static hipError_t launch_stream_inst(const GemmArgs &a, hipStream_t s, int grid,
     g.inv_tau = a.inv_tau;
     g.p = a.p;
     g.partials = a.partials;
+    g.rs = a.row_step;
+    g.cs = a.col_step;
+    g.rs_stride = a.row_step_stride;
+    g.cs_stride = a.col_step_stride;
     g.tiles_m = (int)((a.M + T::BM - 1) / T::BM);
     g.tiles_n = (int)((a.N + T::BN - 1) / T::BN);
     g.sk_full_rounds = full_rounds;
@@ -1453,6 +1498,10 @@ static hipError_t launch_defer_inst(const GemmArgs &a, hipStream_t s)
     g.inv_tau = a.inv_tau;
     g.p = a.p;
     g.partials = a.partials;
+    g.rs = a.row_step;
+    g.cs = a.col_step;
+    g.rs_stride = a.row_step_stride;
+    g.cs_stride = a.col_step_stride;
     g.tiles_m = (int)((a.M + T::BM - 1) / T::BM);
     g.tiles_n = (int)(a.N / T::BN);
     const int grid = defer_workgroups(a.M, a.N, T::BM);
@@ -1535,8 +1584,15 @@ template <int NBLK, int MB, int UNROLL, int WAVES, bool IL>
 static hipError_t launch_skinny(const GemmArgs &a, hipStream_t s)
 {
     const unsigned grid = (unsigned)((a.N + 16 * NBLK - 1) / (16 * NBLK));
-    launch_gemm_kernel(w8a8_skinny_kernel<NBLK, MB, UNROLL, WAVES, IL>, dim3(grid), dim3(WAVES * 64), 0, s, (const int8_t *)a.A,
-                       (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, (uint16_t *)a.out);
+    const StepVectors sv{a.row_step, a.col_step, a.row_step_stride, a.col_step_stride};
+    if (a.row_step != nullptr)
+        launch_gemm_kernel(w8a8_skinny_kernel<NBLK, MB, UNROLL, WAVES, IL, true>, dim3(grid), dim3(WAVES * 64), 0, s,
+                           (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
+                           (uint16_t *)a.out);
+    else
+        launch_gemm_kernel(w8a8_skinny_kernel<NBLK, MB, UNROLL, WAVES, IL, false>, dim3(grid), dim3(WAVES * 64), 0, s,
+                           (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
+                           (uint16_t *)a.out);
     return hipGetLastError();
 }
 

@@ -23,6 +23,10 @@ struct GemmDev {
     int sk_full_rounds;
     void *sk_partials;
     uint32_t *sk_counters;
+    // INT8 only, both or neither: dequantisation steps per output row / column (stride 1) or per
+    // tensor (stride 0); then y = bf16((fp32(acc) * rs[m*rs_stride]) * cs[n*cs_stride])
+    const float *rs, *cs;
+    int rs_stride, cs_stride;
 };
 
 // raster of tile ids: groups of 8 tile rows, column-major inside a group

@@ -30,6 +30,9 @@ hipError_t launch_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_
                                         int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s);
 hipError_t launch_quantize_i8(const void *x_bf16, int64_t n, float inv_step, int8_t *out,
                               hipStream_t s);
+// Row-granular AbsMax INT8: q [rows, cols] and one dequantisation step per row (cols % 8 == 0).
+hipError_t launch_quantize_i8_rows(const void *x_bf16, int64_t rows, int64_t cols, float eps, int8_t *q,
+                                   float *step, hipStream_t s);
 hipError_t launch_penalty_finish(const float *partials, int n, double *out, hipStream_t s);
 hipError_t launch_penalty_grad_inject(const void *dy_bf16, const void *a_bf16, int64_t n, float inv_tau,
                                       float coef, int p, void *out_bf16, hipStream_t s);
@@ -50,6 +53,10 @@ struct GemmArgs {
     bool a_e5m2;            // FP8 only: A holds E5M2 codes (B is always E4M3)
     void *sk_workspace;     // stream-K scratch (256-byte aligned) or nullptr: then no stream-K
     size_t sk_workspace_bytes;
+    // INT8 only, both or neither: device vectors of dequantisation steps, per row of A (stride 1)
+    // or one for all (stride 0), likewise per row of B; alpha is ignored when they are given
+    const float *row_step, *col_step;
+    int row_step_stride, col_step_stride;
 };
 
 // Number of fp32 penalty partials the FP8 GEMM writes for these arguments.
