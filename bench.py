@@ -156,7 +156,10 @@ def time_w8a8(tw, torch, synth, dev, iters=20):
         ws = torch.empty(tw.tweo_workspace_bytes(tw.TWEO_OP_W8A8_LINEAR, M, N, K), dtype=torch.uint8,
                          device=dev)
         fn = lambda: tw.tweo_w8a8_linear(xq, wq, step_x * step_w, y, ws)
-        for _ in range(3):
+        # the compute-bound shape is timed at the clock the chip settles at under load: it takes
+        # some 20 ms of work to get there from the idle state the small shapes leave behind
+        n_warm = 3 if M <= 64 else 100
+        for _ in range(n_warm):
             fn()
         s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         s.record()
@@ -168,6 +171,47 @@ def time_w8a8(tw, torch, synth, dev, iters=20):
         bytes_ = M * K + N * K + 2 * M * N
         res["M=%d" % M] = {"us": round(ms * 1e3, 2), "TOP/s": round(2.0 * M * N * K / ms / 1e9, 2),
                            "GB/s": round(bytes_ / ms / 1e6, 1)}
+
+        def kernel_us(fn):
+            # the kernel's own start-to-end time (events recorded by the launch itself): the
+            # back-to-back figure above includes what the host needs per call
+            ev = GemmEvents(torch, tw)
+            ev.arm(8, 0.0)  # as many as the hook holds at a time
+            for _ in range(8):
+                fn()
+            torch.cuda.synchronize()
+            d = sorted(ev.durations_ms())
+            return d[len(d) // 2] * 1e3
+
+        ku = kernel_us(fn)
+        res["M=%d" % M]["kernel_us"] = round(ku, 2)
+        res["M=%d" % M]["kernel_GB/s"] = round(bytes_ / ku / 1e3, 1)
+        # the finer granularities of Sec. 4.4 on the same codes: per-token steps found on the fly
+        # (quantise kernel timed with the GEMM), per-channel weight steps
+        xb = up(x)
+        xq2 = torch.empty((M, K), dtype=torch.int8, device=dev)
+        sx = torch.empty((M,), dtype=torch.float32, device=dev)
+        sw = torch.full((N,), step_w, dtype=torch.float32, device=dev)
+
+        def timed(fn):
+            for _ in range(n_warm):
+                fn()
+            s.record()
+            for _ in range(iters):
+                fn()
+            e.record()
+            torch.cuda.synchronize()
+            return s.elapsed_time(e) / iters
+
+        ms_q = timed(lambda: tw.tweo_quantize_i8_rows(xb, 1e-6, xq2, sx))
+        ms_g = timed(lambda: tw.tweo_w8a8_linear_scaled(xq2, wq, sx, sw, y))
+        ku_g = kernel_us(lambda: tw.tweo_w8a8_linear_scaled(xq2, wq, sx, sw, y))
+        res["M=%d" % M]["W(C)A(K)"] = {"quantize_rows_us": round(ms_q * 1e3, 2),
+                                       "quantize_rows_GB/s": round(3.0 * M * K / ms_q / 1e6, 1),
+                                       "gemm_us": round(ms_g * 1e3, 2),
+                                       "gemm_TOP/s": round(2.0 * M * N * K / ms_g / 1e9, 2),
+                                       "gemm_GB/s": round((bytes_ + 4 * (M + N)) / ms_g / 1e6, 1),
+                                       "gemm_kernel_us": round(ku_g, 2)}
     return res
 
 
