@@ -1177,6 +1177,109 @@ __global__ __launch_bounds__(WAVES * 64) void w8a8_skinny_kernel(const int8_t *_
     }
 }
 
+// The same contraction for K short enough that a workgroup can keep its whole share of X in
+// registers: wave w owns the 64-byte K steps w, w+WAVES, ... (at most XC of them) and loads
+// their X fragments once; the workgroup then walks over 16-row blocks of W (block ids
+// blockIdx.x, +gridDim.x, ...), so X crosses the L2 -> CU path once per workgroup instead of
+// once per 16 weight rows, and the next block's weights are in flight while this block's
+// partial tiles are added through LDS.  Same arithmetic, same bits.
+template <int MB, int WAVES, int XC, int DEPTH, bool VEC>
+__global__ __launch_bounds__(WAVES * 64) void w8a8_skinny_resident_kernel(const int8_t *__restrict__ X,
+                                                                   const int8_t *__restrict__ W, int M, int N,
+                                                                   int K, float alpha, StepVectors sv,
+                                                                   uint16_t *__restrict__ Y)
+{
+    constexpr int STEP = 64;
+    __shared__ v4i red[WAVES][MB][kWave];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int r16 = lane & 15, kc = lane >> 4;
+    const int steps = K / STEP;  // <= XC * WAVES (checked by the host)
+    const int blocks = (N + 15) / 16;
+    // k offset of this wave's u-th step; steps past the end re-read step `wave % steps` with a
+    // zero X fragment, so their products vanish
+    int koff[XC];
+    v4i xf[XC][MB];
+#pragma unroll
+    for (int u = 0; u < XC; ++u) {
+        const int su = wave + u * WAVES;
+        const bool ok = su < steps;
+        koff[u] = (ok ? su : wave % steps) * STEP + kc * 16;
+#pragma unroll
+        for (int b = 0; b < MB; ++b) {
+            int m = b * 16 + r16;
+            m = m < M ? m : M - 1;
+            const v4i v = *(const v4i *)(X + (int64_t)m * K + koff[u]);
+            xf[u][b] = ok ? v : v4i{0, 0, 0, 0};
+        }
+    }
+    auto load_w = [&](int blk, v4i(&wf)[XC]) {
+        int n = blk * 16 + r16;
+        n = n < N ? n : N - 1;  // rows past N: duplicates, never stored
+        const int8_t *wp = W + (int64_t)n * K;
+#pragma unroll
+        for (int u = 0; u < XC; ++u)
+            wf[u] = *(const v4i *)(wp + koff[u]);
+    };
+    // DEPTH blocks of weights in flight: block i+DEPTH-1 is requested before block i is multiplied
+    v4i wf[DEPTH][XC];
+    const int grid = gridDim.x;
+    int blk = blockIdx.x;
+#pragma unroll
+    for (int d = 0; d < DEPTH - 1; ++d)
+        if (blk + d * grid < blocks)
+            load_w(blk + d * grid, wf[d]);
+    while (blk < blocks) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            if (blk >= blocks)
+                break;
+            const int ahead = blk + (DEPTH - 1) * grid;
+            if (ahead < blocks)
+                load_w(ahead, wf[(d + DEPTH - 1) % DEPTH]);
+            v4i acc[MB];
+#pragma unroll
+            for (int b = 0; b < MB; ++b)
+                acc[b] = v4i{0, 0, 0, 0};
+#pragma unroll
+            for (int u = 0; u < XC; ++u)
+#pragma unroll
+                for (int b = 0; b < MB; ++b)
+                    // first operand -> register index (n), second -> lane%16 (m)
+                    acc[b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[d][u], xf[u][b], acc[b], 0, 0, 0);
+#pragma unroll
+            for (int b = 0; b < MB; ++b)
+                red[wave][b][lane] = acc[b];
+            __syncthreads();
+            // acc[v] of lane l is C[n = 4*(l/16) + v, m = l%16] of its 16x16 block
+            for (int t = tid; t < MB * kWave; t += WAVES * kWave) {
+                const int b = t / kWave, l = t % kWave;
+                v4i sum = red[0][b][l];
+#pragma unroll
+                for (int w = 1; w < WAVES; ++w)
+                    sum += red[w][b][l];
+                const int m = b * 16 + (l & 15), n = blk * 16 + 4 * (l >> 4);
+                if (m < M && n < N) {
+                    float y[4];
+                    if constexpr (VEC) {
+                        const float rstep = sv.rs[(int64_t)m * sv.rs_stride];
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            y[v] = ((float)sum[v] * rstep) * sv.cs[(int64_t)(n + v) * sv.cs_stride];
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            y[v] = (float)sum[v] * alpha;
+                    }
+                    *(uint2 *)(Y + (int64_t)m * N + n) =
+                        make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+                }
+            }
+            __syncthreads();  // red is rewritten by the next block
+            blk += grid;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // host side
 
@@ -1596,8 +1699,41 @@ static hipError_t launch_skinny(const GemmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+
+template <int MB, int WAVES, int XC, int DEPTH>
+static hipError_t launch_skinny_resident(const GemmArgs &a, hipStream_t s, int wg_per_cu)
+{
+    const int blocks = (int)((a.N + 15) / 16);
+    int grid = num_cus() * wg_per_cu;
+    if (grid > blocks)
+        grid = blocks;
+    const StepVectors sv{a.row_step, a.col_step, a.row_step_stride, a.col_step_stride};
+    if (a.row_step != nullptr)
+        launch_gemm_kernel(w8a8_skinny_resident_kernel<MB, WAVES, XC, DEPTH, true>, dim3((unsigned)grid), dim3(WAVES * 64), 0,
+                           s, (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
+                           (uint16_t *)a.out);
+    else
+        launch_gemm_kernel(w8a8_skinny_resident_kernel<MB, WAVES, XC, DEPTH, false>, dim3((unsigned)grid), dim3(WAVES * 64), 0,
+                           s, (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
+                           (uint16_t *)a.out);
+    return hipGetLastError();
+}
+
 hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s)
 {
+    // 4 <= M <= 64, K within what a workgroup's registers hold of X, several 16-row blocks of W per
+    // workgroup to walk over.  Measured at K = 4096, N = 12288: 10.3 / 11.1 / 13.1 / 17.3 us for
+    // M = 4 / 16 / 32 / 64 against 10.9 / 13.5 / 18.5 / 19.4 for the per-block kernel below, which
+    // stays ahead for M = 1 (9.4 against 10.0: a single row of X costs nothing to re-read).  More
+    // waves, a second workgroup per CU or a third block in flight were all slower.
+    if (g_tile_override == 0 && a.M >= 4 && a.M <= 64 && a.K % 64 == 0 && a.K <= 64 * 8 * 8 && a.N % 4 == 0 &&
+        a.N >= 16 * 2 * num_cus()) {
+        if (a.M <= 16)
+            return launch_skinny_resident<1, 8, 8, 2>(a, s, 1);
+        if (a.M <= 32)
+            return launch_skinny_resident<2, 8, 8, 2>(a, s, 1);
+        return launch_skinny_resident<4, 8, 8, 2>(a, s, 1);
+    }
     // small M: weight-streaming kernel (forced variants keep the tiled kernels, for tests)
     if (g_tile_override == 0 && a.M <= 64 && a.K % 64 == 0 && a.N % 4 == 0) {
         // measured on the 7B shapes: enough workgroups to cover the CUs matters more than the

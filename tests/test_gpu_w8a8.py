@@ -64,6 +64,24 @@ def test_w8a8_deferred_epilogue_kernel_bit_exact(shape):
     assert np.array_equal(bf16_bits(y), oracle.w8a8_linear(oxq, owq, alpha))
 
 
+@pytest.mark.parametrize("shape", [(4, 4096, 8192), (16, 1024, 8200), (17, 2048, 8192), (33, 4096, 12288),
+                                   (64, 64, 8192), (48, 640, 16384), (64, 4096, 8192), (5, 192, 8200)])
+def test_w8a8_resident_activation_kernel_bit_exact(shape):
+    # 4 <= M <= 64, K <= 4096, N >= 8192: the weight-streaming kernel that keeps X in registers and
+    # walks over blocks of weight rows; ragged M and N, K steps fewer than / not a multiple of the waves
+    M, K, N = shape
+    say("w8a8 resident M=%d K=%d N=%d" % (M, K, N))
+    x, w = synth.w8a8_inputs(0, M, K=K, N=N)
+    ax, aw = oracle.amax_bf16(x), oracle.amax_bf16(w)
+    inv_x, inv_w = np.float32(127.0) / ax, np.float32(127.0) / aw
+    alpha = (ax / np.float32(127.0)) * (aw / np.float32(127.0))
+    oxq, owq = oracle.quantize_i8(x, inv_x), oracle.quantize_i8(w, inv_w)
+    y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)  # poisoned
+    tw.tweo_w8a8_linear(to_dev(oxq), to_dev(owq), alpha, y, workspace(tw.TWEO_OP_W8A8_LINEAR, M, N, K))
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_bits(y), oracle.w8a8_linear(oxq, owq, alpha))
+
+
 def test_w8a8_stream_k_bit_exact():
     # 64 tiles, long K, K-split switched on: int32 partial accumulators are added exactly, so the
     # result is the same bits as the plain schedule's and the oracle's

@@ -108,7 +108,7 @@ def quantised(M, K, N, gran):
 # kernels on ragged and whole-tile shapes
 @pytest.mark.parametrize("gran", GRAN)
 @pytest.mark.parametrize("shape", [(1, 4096, 264), (16, 1024, 512), (17, 1024, 200), (32, 640, 136),
-                                   (48, 4096, 520), (64, 2048, 136), (64, 4096, 8192), (8, 4096, 8192),
+                                   (48, 4096, 520), (64, 2048, 136), (64, 4096, 8192), (8, 4096, 8192), (20, 640, 8200),
                                    (200, 512, 392), (512, 768, 256), (1024, 1024, 1024)])
 def test_scaled_linear_bit_exact(shape, gran):
     M, K, N = shape
