@@ -57,7 +57,10 @@ enum {
 
 /* Bytes of device workspace the given operation can use for these sizes (a
  * multiple of 256; never 0).  The workspace needs no initialisation and may be
- * reused by the next call on the same stream.  It has two parts: the TWEO
+ * reused by the next call on the same stream.  For the two *_BF16 operations
+ * it starts with 4 KB that are always required (the amax launch leaves one
+ * maximum per workgroup there and the cast launch reduces them, so nothing has
+ * to be cleared and no atomic is used).  Then two parts: the TWEO
  * penalty partial sums of a forward call (a few KB, required whenever a penalty
  * is asked for: less is TWEO_ERR_WORKSPACE), then - only after
  * tweo_set_stream_k(1) - scratch that lets a GEMM whose tile count does not fill
@@ -278,6 +281,9 @@ typedef struct {
  * (with transposes, kept in `saved`), the FP8 GEMM and the fused penalty -
  * i.e. every step of a per-tensor FP8 linear under current scaling (Sec. 4.3)
  * plus Sec. 3.3's penalty.  M % 16 == 0, N % 16 == 0, K % 16 == 0.
+ * workspace: required, 16-byte aligned, at least the first 4 KB of
+ * tweo_workspace_bytes(TWEO_OP_FP8_LINEAR_FWD_BF16, ...) (plus the penalty part
+ * when a penalty is asked for), else TWEO_ERR_WORKSPACE.
  */
 tweo_status tweo_fp8_linear_fwd_bf16(const void *x_bf16, const void *w_bf16,
                                      const void *residual_bf16, int64_t M, int64_t N, int64_t K,
@@ -288,7 +294,9 @@ tweo_status tweo_fp8_linear_fwd_bf16(const void *x_bf16, const void *w_bf16,
 /*
  * Whole backward path from a bf16 output gradient: amax(dy), quantize-cast of
  * dy (and its transpose) into dyq [M,N] / dyqT [N,M], then dgrad and wgrad on
- * the operands saved by the forward pass.
+ * the operands saved by the forward pass.  workspace: required, 16-byte
+ * aligned, at least 4 KB (tweo_workspace_bytes(TWEO_OP_FP8_LINEAR_BWD_BF16, ...)),
+ * else TWEO_ERR_WORKSPACE.
  */
 tweo_status tweo_fp8_linear_bwd_bf16(const void *dy_bf16, const tweo_fp8_saved *saved, int64_t M,
                                      int64_t N, int64_t K, uint8_t *dyq, uint8_t *dyqT,

@@ -88,17 +88,22 @@ inline bool stream_k_candidate(int64_t rows, int64_t cols, int64_t contraction)
     return stream_k_enabled() && contraction >= 2048 && rows >= 256 && cols >= 256;
 }
 
+// head of the workspace of the bf16 entry points: two runs of kAmaxPartialsMax workgroup maxima
+constexpr size_t kAmaxScratchBytes = 2 * kAmaxPartialsMax * sizeof(uint32_t);
+
 size_t tweo_workspace_bytes(int op, int64_t M, int64_t N, int64_t K)
 {
     if (M <= 0 || N <= 0 || K <= 0)
         return 256;
     switch (op) {
     case TWEO_OP_FP8_LINEAR_FWD:
-    case TWEO_OP_FP8_LINEAR_FWD_BF16:
         return penalty_bytes(M, N) + (stream_k_candidate(M, N, K) ? stream_k_workspace_bytes() : 0);
+    case TWEO_OP_FP8_LINEAR_FWD_BF16:  // the workgroup maxima of the amax launch in front
+        return kAmaxScratchBytes + tweo_workspace_bytes(TWEO_OP_FP8_LINEAR_FWD, M, N, K);
     case TWEO_OP_FP8_LINEAR_BWD:
-    case TWEO_OP_FP8_LINEAR_BWD_BF16:
         return 256 + (stream_k_candidate(M, K, N) || stream_k_candidate(N, K, M) ? stream_k_workspace_bytes() : 0);
+    case TWEO_OP_FP8_LINEAR_BWD_BF16:
+        return kAmaxScratchBytes + tweo_workspace_bytes(TWEO_OP_FP8_LINEAR_BWD, M, N, K);
     case TWEO_OP_W8A8_LINEAR:
         return 256 + (stream_k_candidate(M, N, K) ? stream_k_workspace_bytes() : 0);
     default:
@@ -392,22 +397,25 @@ tweo_status tweo_fp8_linear_fwd_bf16(const void *x_bf16, const void *w_bf16,
     tweo_status st = check_penalty(pen, penalty_sum, inv_tau, p);
     if (st != TWEO_OK)
         return st;
-    if (p != 0 && (!workspace || workspace_bytes < penalty_bytes(M, N)))
+    if (!workspace || !aligned16(workspace) ||
+        workspace_bytes < kAmaxScratchBytes + (p != 0 ? penalty_bytes(M, N) : 0))
         return TWEO_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     float *sc = saved->scalars;
-    hipError_t e = launch_fill_u32((uint32_t *)sc, 6, 0u, s);
     // activation and weight share one amax launch and one cast launch (a kernel of its own for
-    // the small weight tensor is mostly launch and tail latency)
-    if (e == hipSuccess)
-        e = launch_amax2(x_bf16, M * K, sc + 0, w_bf16, N * K, sc + 3, s);
+    // the small weight tensor is mostly launch and tail latency); the amax launch leaves one
+    // maximum per workgroup, the cast launch reduces them: nothing to clear, no atomics
+    uint32_t *px = (uint32_t *)workspace, *pw = px + kAmaxPartialsMax;
+    int nx = 0, nw = 0;
+    hipError_t e = launch_amax2_partials(x_bf16, M * K, px, &nx, w_bf16, N * K, pw, &nw, s);
     if (e == hipSuccess)
         e = launch_quantize2_e4m3(x_bf16, M, K, sc + 0, saved->xq, saved->xqT, sc + 1, sc + 2, w_bf16, N, K,
-                                  sc + 3, saved->wq, saved->wqT, sc + 4, sc + 5, s);
+                                  sc + 3, saved->wq, saved->wqT, sc + 4, sc + 5, s, px, nx, pw, nw);
     if (e != hipSuccess)
         return TWEO_ERR_HIP;
     return tweo_fp8_linear_fwd(saved->xq, sc + 2, saved->wq, sc + 5, residual_bf16, M, N, K, y_bf16,
-                               pen, penalty_sum, workspace, workspace_bytes, stream);
+                               pen, penalty_sum, (uint8_t *)workspace + kAmaxScratchBytes,
+                               workspace_bytes - kAmaxScratchBytes, stream);
 }
 
 static tweo_status fp8_linear_bwd_bf16_impl(const void *dy_bf16, const tweo_fp8_saved *saved, int64_t M,
@@ -420,18 +428,20 @@ static tweo_status fp8_linear_bwd_bf16_impl(const void *dy_bf16, const tweo_fp8_
         return TWEO_ERR_INVALID_ARG;
     if (!dims_ok(M, N, K) || M % 16 != 0 || N % 16 != 0 || K % 16 != 0)
         return TWEO_ERR_UNSUPPORTED;
+    if (!workspace || !aligned16(workspace) || workspace_bytes < kAmaxScratchBytes)
+        return TWEO_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     float *sc = saved->scalars;
-    hipError_t e = launch_fill_u32((uint32_t *)(sc + 6), 3, 0u, s);
+    uint32_t *pdy = (uint32_t *)workspace;
+    int ndy = 0;
+    hipError_t e = launch_amax_partials(dy_bf16, M * N, pdy, &ndy, s);
     if (e == hipSuccess)
-        e = launch_amax(dy_bf16, M * N, sc + 6, s);
-    if (e == hipSuccess)
-        e = dy_e5m2 ? launch_quantize_e5m2(dy_bf16, M, N, sc + 6, dyq, dyqT, sc + 7, sc + 8, s)
-                    : launch_quantize_e4m3(dy_bf16, M, N, sc + 6, dyq, dyqT, sc + 7, sc + 8, s);
+        e = launch_quantize_f8_from_partials(dy_bf16, M, N, pdy, ndy, dy_e5m2, sc + 6, dyq, dyqT, sc + 7, sc + 8, s);
     if (e != hipSuccess)
         return TWEO_ERR_HIP;
     return fp8_linear_bwd_impl(dyq, dyqT, sc + 8, saved->wqT, sc + 5, saved->xqT, sc + 2, M, N, K,
-                               dx_bf16, dw_bf16, workspace, workspace_bytes, stream, dy_e5m2);
+                               dx_bf16, dw_bf16, (uint8_t *)workspace + kAmaxScratchBytes,
+                               workspace_bytes - kAmaxScratchBytes, stream, dy_e5m2);
 }
 
 tweo_status tweo_fp8_linear_bwd_bf16(const void *dy_bf16, const tweo_fp8_saved *saved, int64_t M,

@@ -51,7 +51,11 @@ __device__ __forceinline__ uint32_t pk_absmax4(uint32_t m, uint4 v)
 // eight 16-byte loads in flight per lane (measured: ~30 % more bandwidth than a
 // grid-stride walk, whose concurrent streams are megabytes apart).
 constexpr int kAmaxUnroll = 8;
+constexpr int kAmaxMaxPartials = kAmaxPartialsMax;  // workgroups of one amax launch (one per CU)
 
+// PARTIAL: workgroup b stores its maximum to out[b] (no atomic, nothing to clear beforehand);
+// the consumer takes the maximum over the workgroups (quantize kernels below).
+template <bool PARTIAL = false>
 __device__ __forceinline__ void amax_body(const uint4 *__restrict__ x, int64_t n_vec, int64_t per_block,
                                           int block, const uint16_t *__restrict__ tail, int n_tail,
                                           uint32_t *out)
@@ -86,30 +90,36 @@ __device__ __forceinline__ void amax_body(const uint4 *__restrict__ x, int64_t n
         // bf16 magnitude widened to the fp32 pattern.  The result only grows, so a workgroup
         // whose maximum is already covered skips the atomic (they serialise on one address).
         const uint32_t mine = r << 16;
-        if (mine > __atomic_load_n(out, __ATOMIC_RELAXED))
-            atomicMax(out, mine);
+        if constexpr (PARTIAL) {
+            out[block] = mine;
+        } else {
+            if (mine > __atomic_load_n(out, __ATOMIC_RELAXED))
+                atomicMax(out, mine);
+        }
     }
 }
 
+template <bool PARTIAL>
 __global__ __launch_bounds__(kAmaxThreads) void amax_kernel(const uint4 *__restrict__ x,
                                                             int64_t n_vec, int64_t per_block,
                                                             const uint16_t *__restrict__ tail,
                                                             int n_tail, uint32_t *out)
 {
-    amax_body(x, n_vec, per_block, (int)blockIdx.x, tail, n_tail, out);
+    amax_body<PARTIAL>(x, n_vec, per_block, (int)blockIdx.x, tail, n_tail, out);
 }
 
 // Two tensors in one launch (the activation and the weight of a linear layer): workgroups
 // [0, blocks0) reduce the first, the rest the second.  Element counts are multiples of 8.
+template <bool PARTIAL>
 __global__ __launch_bounds__(kAmaxThreads) void amax2_kernel(const uint4 *__restrict__ x0, int64_t n_vec0,
                                                              int64_t per_block0, int blocks0, uint32_t *out0,
                                                              const uint4 *__restrict__ x1, int64_t n_vec1,
                                                              int64_t per_block1, uint32_t *out1)
 {
     if ((int)blockIdx.x < blocks0)
-        amax_body(x0, n_vec0, per_block0, (int)blockIdx.x, nullptr, 0, out0);
+        amax_body<PARTIAL>(x0, n_vec0, per_block0, (int)blockIdx.x, nullptr, 0, out0);
     else
-        amax_body(x1, n_vec1, per_block1, (int)blockIdx.x - blocks0, nullptr, 0, out1);
+        amax_body<PARTIAL>(x1, n_vec1, per_block1, (int)blockIdx.x - blocks0, nullptr, 0, out1);
 }
 
 static int amax_cus()
@@ -122,12 +132,15 @@ static int amax_cus()
             cus = v;
         else
             cus = 256;
+        if (cus > kAmaxMaxPartials)
+            cus = kAmaxMaxPartials;
     }
     return cus;
 }
 
-hipError_t launch_amax2(const void *x0_bf16, int64_t n0, float *amax0_zeroed, const void *x1_bf16, int64_t n1,
-                        float *amax1_zeroed, hipStream_t s)
+static hipError_t launch_amax2_impl(const void *x0_bf16, int64_t n0, float *amax0_zeroed, const void *x1_bf16,
+                                    int64_t n1, float *amax1_zeroed, bool partial, int *blocks0, int *blocks1,
+                                    hipStream_t s)
 {
     // the workgroups of one wave over the CUs are shared out in proportion to the tensor sizes
     const int cus = amax_cus();
@@ -143,13 +156,38 @@ hipError_t launch_amax2(const void *x0_bf16, int64_t n0, float *amax0_zeroed, co
         b0 = (v0 + chunk - 1) / chunk;
     if (b1 > (v1 + chunk - 1) / chunk)
         b1 = (v1 + chunk - 1) / chunk;
-    hipLaunchKernelGGL(amax2_kernel, dim3((unsigned)(b0 + b1)), dim3(kAmaxThreads), 0, s, (const uint4 *)x0_bf16, v0,
-                       (v0 + b0 - 1) / b0, (int)b0, (uint32_t *)amax0_zeroed, (const uint4 *)x1_bf16, v1,
-                       (v1 + b1 - 1) / b1, (uint32_t *)amax1_zeroed);
+    if (partial)
+        hipLaunchKernelGGL(amax2_kernel<true>, dim3((unsigned)(b0 + b1)), dim3(kAmaxThreads), 0, s,
+                           (const uint4 *)x0_bf16, v0, (v0 + b0 - 1) / b0, (int)b0, (uint32_t *)amax0_zeroed,
+                           (const uint4 *)x1_bf16, v1, (v1 + b1 - 1) / b1, (uint32_t *)amax1_zeroed);
+    else
+        hipLaunchKernelGGL(amax2_kernel<false>, dim3((unsigned)(b0 + b1)), dim3(kAmaxThreads), 0, s,
+                           (const uint4 *)x0_bf16, v0, (v0 + b0 - 1) / b0, (int)b0, (uint32_t *)amax0_zeroed,
+                           (const uint4 *)x1_bf16, v1, (v1 + b1 - 1) / b1, (uint32_t *)amax1_zeroed);
+    if (blocks0)
+        *blocks0 = (int)b0;
+    if (blocks1)
+        *blocks1 = (int)b1;
     return hipGetLastError();
 }
 
-hipError_t launch_amax(const void *x_bf16, int64_t n, float *amax_zeroed, hipStream_t s)
+hipError_t launch_amax2(const void *x0_bf16, int64_t n0, float *amax0_zeroed, const void *x1_bf16, int64_t n1,
+                        float *amax1_zeroed, hipStream_t s)
+{
+    return launch_amax2_impl(x0_bf16, n0, amax0_zeroed, x1_bf16, n1, amax1_zeroed, false, nullptr, nullptr, s);
+}
+
+// One maximum per workgroup into partials0[0 .. *blocks0) and partials1[0 .. *blocks1) (each at most
+// kAmaxMaxPartials): nothing to clear, no atomics.
+hipError_t launch_amax2_partials(const void *x0_bf16, int64_t n0, uint32_t *partials0, int *blocks0,
+                                 const void *x1_bf16, int64_t n1, uint32_t *partials1, int *blocks1, hipStream_t s)
+{
+    return launch_amax2_impl(x0_bf16, n0, (float *)partials0, x1_bf16, n1, (float *)partials1, true, blocks0,
+                             blocks1, s);
+}
+
+static hipError_t launch_amax_impl(const void *x_bf16, int64_t n, float *amax_zeroed, bool partial, int *blocks_out,
+                                   hipStream_t s)
 {
     const int64_t n_vec = n / 8;
     const int n_tail = (int)(n % 8);
@@ -161,10 +199,27 @@ hipError_t launch_amax(const void *x_bf16, int64_t n, float *amax_zeroed, hipStr
     if (blocks > cus)
         blocks = cus;
     const int64_t per_block = (n_vec + blocks - 1) / blocks;
-    hipLaunchKernelGGL(amax_kernel, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, s,
-                       (const uint4 *)x_bf16, n_vec, per_block,
-                       (const uint16_t *)x_bf16 + n_vec * 8, n_tail, (uint32_t *)amax_zeroed);
+    if (partial)
+        hipLaunchKernelGGL(amax_kernel<true>, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, s,
+                           (const uint4 *)x_bf16, n_vec, per_block, (const uint16_t *)x_bf16 + n_vec * 8, n_tail,
+                           (uint32_t *)amax_zeroed);
+    else
+        hipLaunchKernelGGL(amax_kernel<false>, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, s,
+                           (const uint4 *)x_bf16, n_vec, per_block, (const uint16_t *)x_bf16 + n_vec * 8, n_tail,
+                           (uint32_t *)amax_zeroed);
+    if (blocks_out)
+        *blocks_out = (int)blocks;
     return hipGetLastError();
+}
+
+hipError_t launch_amax(const void *x_bf16, int64_t n, float *amax_zeroed, hipStream_t s)
+{
+    return launch_amax_impl(x_bf16, n, amax_zeroed, false, nullptr, s);
+}
+
+hipError_t launch_amax_partials(const void *x_bf16, int64_t n, uint32_t *partials, int *blocks, hipStream_t s)
+{
+    return launch_amax_impl(x_bf16, n, (float *)partials, true, blocks, s);
 }
 
 // ---------------------------------------------------------------------------
@@ -341,9 +396,31 @@ template <bool WITH_T, bool DELAYED, bool E5M2 = false>
 __device__ __forceinline__ void quantize_e4m3_16x16_body(
     const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
     const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
-    float *scale_out, float *scale_inv_out, uint32_t *amax_acc, int64_t block, int64_t n_blocks)
+    float *scale_out, float *scale_inv_out, uint32_t *amax_acc, int64_t block, int64_t n_blocks,
+    const uint32_t *__restrict__ amax_partials = nullptr, int n_partials = 0, float *amax_store = nullptr)
 {
-    const float scale = DELAYED ? *amax : scale_f8<E5M2>(*amax);
+    float amax_v;
+    if (amax_partials != nullptr) {  // uniform: the maxima of the amax launch's workgroups
+        __shared__ uint32_t pred[kQuantThreads / kWave];
+        uint32_t m = 0;
+        for (int i = threadIdx.x; i < n_partials; i += kQuantThreads) {
+            const uint32_t v = amax_partials[i];
+            m = v > m ? v : m;
+        }
+        m = wave_reduce_max_u32(m);
+        if ((threadIdx.x & (kWave - 1)) == 0)
+            pred[threadIdx.x / kWave] = m;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kQuantThreads / kWave; ++w)
+            m = pred[w] > m ? pred[w] : m;
+        amax_v = __uint_as_float(m);
+        if (block == 0 && threadIdx.x == 0)
+            *amax_store = amax_v;
+    } else {
+        amax_v = *amax;
+    }
+    const float scale = DELAYED ? amax_v : scale_f8<E5M2>(amax_v);
     if (block == 0 && threadIdx.x == 0) {
         if (scale_out)
             *scale_out = scale;
@@ -411,10 +488,12 @@ template <bool WITH_T, bool DELAYED, bool E5M2 = false>
 __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
     const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
     const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
-    float *scale_out, float *scale_inv_out, uint32_t *amax_acc)
+    float *scale_out, float *scale_inv_out, uint32_t *amax_acc, const uint32_t *__restrict__ amax_partials,
+    int n_partials, float *amax_store)
 {
     quantize_e4m3_16x16_body<WITH_T, DELAYED, E5M2>(x, rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out,
-                                              amax_acc, blockIdx.x, gridDim.x);
+                                              amax_acc, blockIdx.x, gridDim.x, amax_partials, n_partials,
+                                              amax_store);
 }
 
 // Two tensors in one launch (activation and weight of a linear layer, each with its transposed
@@ -425,6 +504,9 @@ struct QuantTensor {
     const float *amax;
     uint8_t *q, *qT;
     float *scale_out, *scale_inv_out;
+    const uint32_t *amax_partials;  // or nullptr: then *amax is the maximum
+    int n_partials;
+    float *amax_store;
 };
 
 __global__ __launch_bounds__(kQuantThreads) void quantize2_e4m3_16x16_kernel(QuantTensor t0, int64_t blocks0,
@@ -434,17 +516,21 @@ __global__ __launch_bounds__(kQuantThreads) void quantize2_e4m3_16x16_kernel(Qua
     const QuantTensor &t = first ? t0 : t1;
     quantize_e4m3_16x16_body<true, false>(t.x, t.rows, t.cols, t.tiles_x, t.amax, t.q, t.qT, t.scale_out,
                                           t.scale_inv_out, nullptr,
-                                          first ? (int64_t)blockIdx.x : (int64_t)blockIdx.x - blocks0, 1);
+                                          first ? (int64_t)blockIdx.x : (int64_t)blockIdx.x - blocks0, 1,
+                                          t.amax_partials, t.n_partials, t.amax_store);
 }
 
-hipError_t launch_quantize2_e4m3(const void *x0_bf16, int64_t rows0, int64_t cols0, const float *amax0, uint8_t *q0,
+hipError_t launch_quantize2_e4m3(const void *x0_bf16, int64_t rows0, int64_t cols0, float *amax0, uint8_t *q0,
                                  uint8_t *q0T, float *scale0, float *scale0_inv, const void *x1_bf16,
-                                 int64_t rows1, int64_t cols1, const float *amax1, uint8_t *q1, uint8_t *q1T,
-                                 float *scale1, float *scale1_inv, hipStream_t s)
+                                 int64_t rows1, int64_t cols1, float *amax1, uint8_t *q1, uint8_t *q1T,
+                                 float *scale1, float *scale1_inv, hipStream_t s, const uint32_t *partials0,
+                                 int n_partials0, const uint32_t *partials1, int n_partials1)
 {
     auto tiles = [](int64_t v) { return (v + kQuantBigTile - 1) / kQuantBigTile; };
-    QuantTensor t0{(const uint16_t *)x0_bf16, rows0, cols0, tiles(cols0), amax0, q0, q0T, scale0, scale0_inv};
-    QuantTensor t1{(const uint16_t *)x1_bf16, rows1, cols1, tiles(cols1), amax1, q1, q1T, scale1, scale1_inv};
+    QuantTensor t0{(const uint16_t *)x0_bf16, rows0, cols0, tiles(cols0), amax0, q0, q0T, scale0, scale0_inv,
+                   partials0, n_partials0, amax0};
+    QuantTensor t1{(const uint16_t *)x1_bf16, rows1, cols1, tiles(cols1), amax1, q1, q1T, scale1, scale1_inv,
+                   partials1, n_partials1, amax1};
     const int64_t b0 = tiles(rows0) * tiles(cols0), b1 = tiles(rows1) * tiles(cols1);
     hipLaunchKernelGGL(quantize2_e4m3_16x16_kernel, dim3((unsigned)(b0 + b1)), dim3(kQuantThreads), 0, s, t0, b0, t1);
     return hipGetLastError();
@@ -453,9 +539,13 @@ hipError_t launch_quantize2_e4m3(const void *x0_bf16, int64_t rows0, int64_t col
 template <bool DELAYED, bool E5M2 = false>
 static hipError_t launch_quantize_e4m3_impl(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
                                             uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
-                                            uint32_t *amax_acc, hipStream_t s)
+                                            uint32_t *amax_acc, hipStream_t s,
+                                            const uint32_t *amax_partials = nullptr, int n_partials = 0,
+                                            float *amax_store = nullptr)
 {
     const dim3 block(kQuantThreads);
+    if (amax_partials != nullptr && (rows % 16 != 0 || cols % 16 != 0))
+        return hipErrorInvalidValue;  // only the whole-block kernel reduces partial maxima
     if (rows % 16 == 0 && cols % 16 == 0) {
         const int64_t tiles_x = (cols + kQuantBigTile - 1) / kQuantBigTile;
         const int64_t tiles_y = (rows + kQuantBigTile - 1) / kQuantBigTile;
@@ -466,11 +556,11 @@ static hipError_t launch_quantize_e4m3_impl(const void *x_bf16, int64_t rows, in
         if (qT)
             hipLaunchKernelGGL((quantize_e4m3_16x16_kernel<true, DELAYED, E5M2>), grid, block, 0, s,
                                (const uint16_t *)x_bf16, rows, cols, tiles_x, amax, q, qT, scale_out,
-                               scale_inv_out, amax_acc);
+                               scale_inv_out, amax_acc, amax_partials, n_partials, amax_store);
         else
             hipLaunchKernelGGL((quantize_e4m3_16x16_kernel<false, DELAYED, E5M2>), grid, block, 0, s,
                                (const uint16_t *)x_bf16, rows, cols, tiles_x, amax, q, qT, scale_out,
-                               scale_inv_out, amax_acc);
+                               scale_inv_out, amax_acc, amax_partials, n_partials, amax_store);
         return hipGetLastError();
     }
     const int64_t tiles_x = (cols + kQuantTileCols - 1) / kQuantTileCols;
@@ -499,6 +589,20 @@ hipError_t launch_quantize_e5m2(const void *x_bf16, int64_t rows, int64_t cols, 
 {
     return launch_quantize_e4m3_impl<false, true>(x_bf16, rows, cols, amax, q, qT, scale_out,
                                                   scale_inv_out, nullptr, s);
+}
+
+// The cast fed by launch_amax_partials: the maximum over `n_partials` workgroup maxima is taken
+// by every workgroup of the cast itself and stored to *amax_out.  rows, cols multiples of 16.
+hipError_t launch_quantize_f8_from_partials(const void *x_bf16, int64_t rows, int64_t cols,
+                                            const uint32_t *amax_partials, int n_partials, bool e5m2,
+                                            float *amax_out, uint8_t *q, uint8_t *qT, float *scale_out,
+                                            float *scale_inv_out, hipStream_t s)
+{
+    if (e5m2)
+        return launch_quantize_e4m3_impl<false, true>(x_bf16, rows, cols, amax_out, q, qT, scale_out, scale_inv_out,
+                                                      nullptr, s, amax_partials, n_partials, amax_out);
+    return launch_quantize_e4m3_impl<false, false>(x_bf16, rows, cols, amax_out, q, qT, scale_out, scale_inv_out,
+                                                   nullptr, s, amax_partials, n_partials, amax_out);
 }
 
 // ---------------------------------------------------------------------------

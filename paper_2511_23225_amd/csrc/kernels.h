@@ -13,11 +13,26 @@ hipError_t launch_amax(const void *x_bf16, int64_t n, float *amax_zeroed, hipStr
 // two tensors (element counts multiples of 8) in one launch
 hipError_t launch_amax2(const void *x0_bf16, int64_t n0, float *amax0_zeroed, const void *x1_bf16, int64_t n1,
                         float *amax1_zeroed, hipStream_t s);
-// two tensors (rows and cols multiples of 16), each with its transposed copy, in one launch
-hipError_t launch_quantize2_e4m3(const void *x0_bf16, int64_t rows0, int64_t cols0, const float *amax0, uint8_t *q0,
+// two tensors (rows and cols multiples of 16), each with its transposed copy, in one launch; with
+// partials (from launch_amax2_partials) each workgroup first takes the maximum over them and
+// workgroup 0 stores it to *amax, else *amax is read
+hipError_t launch_quantize2_e4m3(const void *x0_bf16, int64_t rows0, int64_t cols0, float *amax0, uint8_t *q0,
                                  uint8_t *q0T, float *scale0, float *scale0_inv, const void *x1_bf16,
-                                 int64_t rows1, int64_t cols1, const float *amax1, uint8_t *q1, uint8_t *q1T,
-                                 float *scale1, float *scale1_inv, hipStream_t s);
+                                 int64_t rows1, int64_t cols1, float *amax1, uint8_t *q1, uint8_t *q1T,
+                                 float *scale1, float *scale1_inv, hipStream_t s,
+                                 const uint32_t *partials0 = nullptr, int n_partials0 = 0,
+                                 const uint32_t *partials1 = nullptr, int n_partials1 = 0);
+// amax without a cleared output and without atomics: one maximum (fp32 bit pattern) per workgroup
+// into partials[0 .. *blocks), at most kAmaxPartialsMax of them per tensor
+constexpr int kAmaxPartialsMax = 512;
+hipError_t launch_amax_partials(const void *x_bf16, int64_t n, uint32_t *partials, int *blocks, hipStream_t s);
+hipError_t launch_amax2_partials(const void *x0_bf16, int64_t n0, uint32_t *partials0, int *blocks0,
+                                 const void *x1_bf16, int64_t n1, uint32_t *partials1, int *blocks1, hipStream_t s);
+// the cast that consumes them (rows, cols multiples of 16); stores the maximum to *amax_out
+hipError_t launch_quantize_f8_from_partials(const void *x_bf16, int64_t rows, int64_t cols,
+                                            const uint32_t *amax_partials, int n_partials, bool e5m2,
+                                            float *amax_out, uint8_t *q, uint8_t *qT, float *scale_out,
+                                            float *scale_inv_out, hipStream_t s);
 hipError_t launch_quantize_e4m3(const void *x_bf16, int64_t rows, int64_t cols, const float *amax,
                                 uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
                                 hipStream_t s);
