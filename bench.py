@@ -49,7 +49,8 @@ class Layer:
         self.sc = torch.zeros(16, dtype=torch.float32, device=dev)
         self.saved = tw.make_saved(self.xq, self.xqT, self.wq, self.wqT, self.sc)
         self.S = torch.zeros(2, dtype=torch.float64, device=dev)
-        self.ws = torch.empty(tw.tweo_workspace_bytes(tw.TWEO_OP_FP8_LINEAR_FWD_BF16, M, N, K),
+        self.ws = torch.empty(max(tw.tweo_workspace_bytes(op, M, N, K) for op in
+                                  (tw.TWEO_OP_FP8_LINEAR_FWD_BF16, tw.TWEO_OP_FP8_LINEAR_BWD_BF16)),
                               dtype=torch.uint8, device=dev)
         self.flops = 6.0 * M * N * K
         # delayed-scaling states of the three scaled tensors (x, w, dy)
@@ -130,6 +131,29 @@ def time_elementwise(tw, torch, L, iters=20):
         out[name] = {"GB/s": round(n * bytes_per_elt / ms / 1e6, 1), "us": round(ms * 1e3, 2),
                      "MB": round(n * bytes_per_elt / 1e6, 1)}
     return out
+
+
+def time_penalty_cost(tw, torch, L, reps=24):
+    """What the fused penalty epilogue (Sec. 3.3) costs: the forward GEMM kernel of one layer on its
+    already quantised operands with and without the penalty, alternating, kernel start-to-end
+    events, medians."""
+    inv = lambda i: L.sc[i:i + 1]
+    t = {True: [], False: []}
+    for _ in range(reps // 8):
+        for with_pen in (True, False, False, True):
+            ev = GemmEvents(torch, tw)
+            ev.arm(2, 0.0)
+            for _ in range(2):
+                if with_pen:
+                    tw.tweo_fp8_linear_fwd(L.xq, inv(2), L.wq, inv(5), L.y, pen=PEN, penalty_sum=L.S,
+                                           workspace=L.ws)
+                else:
+                    tw.tweo_fp8_linear_fwd(L.xq, inv(2), L.wq, inv(5), L.y, workspace=L.ws)
+            torch.cuda.synchronize()
+            t[with_pen] += ev.durations_ms()
+    med = lambda v: sorted(v)[len(v) // 2] * 1e3
+    return {"layer": "%s %dx%dx%d" % (L.name, L.M, L.K, L.N), "fwd_with_penalty_us": round(med(t[True]), 2),
+            "fwd_without_us": round(med(t[False]), 2)}
 
 
 def time_w8a8(tw, torch, synth, dev, iters=20):
@@ -309,11 +333,11 @@ def main():
         print(json.dumps({"copy_bytes_each_way": n, "copies": max(1, a.steps)}), flush=True)
         return
     cfg = WORKLOADS[a.workload]
+    tw.tweo_set_stream_k(a.stream_k)  # before the workspaces are sized
     t0 = time.perf_counter()
     layers = [Layer(tw, torch, synth, cfg, gi, dev) for gi in range(len(synth.CONFIGS[cfg]["gemms"]))]
     log("inputs generated and uploaded in %.1f s" % (time.perf_counter() - t0))
     tw.tweo_set_gemm_tile(a.tile)
-    tw.tweo_set_stream_k(a.stream_k)
     step_flops = sum(L.flops for L in layers)
     host0 = layers[0].host
     for L in layers:
@@ -387,6 +411,7 @@ def main():
         big = max(layers, key=lambda L: L.M * L.K)
         out["elementwise"] = time_elementwise(tw, torch, big)
         out["elementwise"]["peak_GB/s"] = HBM_PEAK_GBS
+        out["penalty_cost"] = time_penalty_cost(tw, torch, layers[0])
         del layers
         torch.cuda.empty_cache()
         out["w8a8_qkv_4096x12288"] = time_w8a8(tw, torch, synth, dev)

@@ -60,7 +60,8 @@ enum {
  * reused by the next call on the same stream.  For the two *_BF16 operations
  * it starts with 4 KB that are always required (the amax launch leaves one
  * maximum per workgroup there and the cast launch reduces them, so nothing has
- * to be cleared and no atomic is used).  Then two parts: the TWEO
+ * to be cleared and no atomic is used).  Then the parts of the plain
+ * operations: the TWEO
  * penalty partial sums of a forward call (a few KB, required whenever a penalty
  * is asked for: less is TWEO_ERR_WORKSPACE), then - only after
  * tweo_set_stream_k(1) - scratch that lets a GEMM whose tile count does not fill
@@ -68,7 +69,12 @@ enum {
  * per CU, 128 MB on a 256-CU device; only counted when a contraction of the
  * operation is at least 2048 long).  A caller that passes a workspace without
  * the second part gets the same results up to the fp32 summation order, from
- * the plain schedule. */
+ * the plain schedule.  The second part also serves, without any switch, a GEMM
+ * without penalty whose output has far fewer 256x256 tiles than the device has
+ * CUs under a contraction of 16384 or more (weight gradients of narrow layers
+ * over many tokens): several workgroups share a tile, each multiplies a run of
+ * K and stores fp32 sums here (runs x rows x cols x 4 bytes), a second launch
+ * adds the runs in index order - run-to-run identical results. */
 size_t tweo_workspace_bytes(int op, int64_t M, int64_t N, int64_t K);
 
 const char *tweo_status_string(tweo_status s);

@@ -1,6 +1,7 @@
 // C ABI of the library (include/tweo.h): argument validation and dispatch.
 // Nothing here allocates, frees or synchronises; everything is enqueued on the
 // caller's stream.
+#include <algorithm>
 #include "../../include/tweo.h"
 #include "kernels.h"
 
@@ -97,11 +98,14 @@ size_t tweo_workspace_bytes(int op, int64_t M, int64_t N, int64_t K)
         return 256;
     switch (op) {
     case TWEO_OP_FP8_LINEAR_FWD:
-        return penalty_bytes(M, N) + (stream_k_candidate(M, N, K) ? stream_k_workspace_bytes() : 0);
+        return penalty_bytes(M, N) + round256(std::max(stream_k_candidate(M, N, K) ? stream_k_workspace_bytes() : 0,
+                                                       fp8_gemm_ksplit_bytes(M, N, K)));
     case TWEO_OP_FP8_LINEAR_FWD_BF16:  // the workgroup maxima of the amax launch in front
         return kAmaxScratchBytes + tweo_workspace_bytes(TWEO_OP_FP8_LINEAR_FWD, M, N, K);
-    case TWEO_OP_FP8_LINEAR_BWD:
-        return 256 + (stream_k_candidate(M, K, N) || stream_k_candidate(N, K, M) ? stream_k_workspace_bytes() : 0);
+    case TWEO_OP_FP8_LINEAR_BWD:  // dgrad [M,K] over N, wgrad [N,K] over M
+        return 256 + round256(std::max({stream_k_candidate(M, K, N) || stream_k_candidate(N, K, M)
+                                            ? stream_k_workspace_bytes() : (size_t)0,
+                                        fp8_gemm_ksplit_bytes(M, K, N), fp8_gemm_ksplit_bytes(N, K, M)}));
     case TWEO_OP_FP8_LINEAR_BWD_BF16:
         return kAmaxScratchBytes + tweo_workspace_bytes(TWEO_OP_FP8_LINEAR_BWD, M, N, K);
     case TWEO_OP_W8A8_LINEAR:

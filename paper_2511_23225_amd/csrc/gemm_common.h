@@ -27,6 +27,11 @@ struct GemmDev {
     // tensor (stride 0); then y = bf16((fp32(acc) * rs[m*rs_stride]) * cs[n*cs_stride])
     const float *rs, *cs;
     int rs_stride, cs_stride;
+    // K split (register-staged FP8 kernel only): ksplit > 1 workgroups share a tile, workgroup
+    // `split` multiplies its run of K stages and stores the fp32 sums to
+    // ksplit_out[split][M][N]; a second kernel adds the runs in order and rounds
+    int ksplit;
+    float *ksplit_out;
 };
 
 // raster of tile ids: groups of 8 tile rows, column-major inside a group

@@ -79,6 +79,11 @@ int fp8_gemm_partials(const GemmArgs &a);
 hipError_t launch_fp8_gemm(const GemmArgs &a, hipStream_t s);
 hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s);
 
+// K split of tile-starved FP8 GEMMs (no penalty, no residual): number of runs (1 = none) and the
+// fp32 scratch they need; given through sk_workspace like the stream-K scratch, which it shares.
+int fp8_gemm_ksplit(int64_t M, int64_t N, int64_t K);
+size_t fp8_gemm_ksplit_bytes(int64_t M, int64_t N, int64_t K);
+
 // Bytes of stream-K scratch that let every shape use it on this device.
 size_t stream_k_workspace_bytes();
 void set_stream_k(bool on);

@@ -273,6 +273,41 @@ def test_bwd(case, tile):
     check_gemm(bf16_bits(dw), dw_ref, dw_abs, M, "wgrad")
 
 
+# outputs of a few 256x256 tiles under a very long contraction: the K split (several workgroups per
+# tile, fp32 runs added in order by a second kernel).  wgrad over 16384 tokens of a 768-wide layer
+# (8 runs), a ragged one whose last K stage is partial, a dgrad over a long N; each run twice.
+@pytest.mark.parametrize("case", [(1, 1, 16384, 768, 768), (3, 0, 16400, 264, 528), (0, 0, 256, 512, 16384)])
+def test_bwd_k_split(case):
+    cfg, gi, M, K, N = case
+    say("bwd K split cfg=%d M=%d K=%d N=%d" % (cfg, M, K, N))
+    x, w, dy = synth.fp8_linear_inputs(cfg, gi, M=M, K=K, N=N)
+    xq, xqT, sxi = oracle_quantized(x)
+    wq, wqT, swi = oracle_quantized(w)
+    dyq, dyqT, sdyi = oracle_quantized(dy)
+    dx_ref, dx_abs = oracle.fp8_linear_dgrad(dyq, wq, sdyi, swi)
+    dw_ref, dw_abs = oracle.fp8_linear_wgrad(dyq, xq, sdyi, sxi)
+    ws = workspace(tw.TWEO_OP_FP8_LINEAR_BWD, M, N, K)
+    assert ws.numel() >= 2 * 4 * min(M * K, N * K)  # the query asks for the runs' scratch
+    outs = []
+    for rep in range(2):
+        dx = torch.full((M, K), float('nan'), dtype=torch.bfloat16, device=DEV)
+        dw = torch.full((N, K), float('nan'), dtype=torch.bfloat16, device=DEV)
+        ws.fill_(0xFF)  # the scratch needs no initialisation: poison it
+        tw.tweo_fp8_linear_bwd(to_dev(dyq), to_dev(dyqT), scalar_f32(sdyi), to_dev(wqT),
+                               scalar_f32(swi), to_dev(xqT), scalar_f32(sxi), M, N, K, dx, dw, ws)
+        torch.cuda.synchronize()
+        outs.append((bf16_bits(dx), bf16_bits(dw)))
+    check_gemm(outs[0][0], dx_ref, dx_abs, N, "dgrad")
+    check_gemm(outs[0][1], dw_ref, dw_abs, M, "wgrad")
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])  # run to run
+    # without the scratch the plain schedule runs: same result within the same bounds
+    dw = torch.full((N, K), float('nan'), dtype=torch.bfloat16, device=DEV)
+    tw.tweo_fp8_linear_bwd(to_dev(dyq), to_dev(dyqT), scalar_f32(sdyi), to_dev(wqT), scalar_f32(swi),
+                           to_dev(xqT), scalar_f32(sxi), M, N, K, None, dw, None)
+    torch.cuda.synchronize()
+    check_gemm(bf16_bits(dw), dw_ref, dw_abs, M, "wgrad, plain schedule")
+
+
 def test_whole_path_from_bf16_and_determinism():
     cfg, gi, M, K, N = 0, 0, 256, 512, 512
     say("bf16 path M=%d K=%d N=%d" % (M, K, N))

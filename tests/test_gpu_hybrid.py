@@ -86,6 +86,7 @@ HYBRID_CASES = [
     (3, 1, 4352, 2048, 4096, 0),
     (3, 2, 2304, 512, 4608, 15),
     (1, 1, 2048, 768, 2304, 16),
+    (3, 0, 16400, 264, 528, 0),  # few tiles, long contraction: the K split with an E5M2 operand
 ]
 
 
