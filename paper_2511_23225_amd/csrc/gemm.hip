@@ -287,6 +287,29 @@ __device__ __forceinline__ void epilogue(const GemmDev &g, ACC (&acc)[T::MT][T::
 #undef TWEO_EPI
 }
 
+// K split: the fp32 sums of one run, straight from the MFMA layout.  Lane (l31, lh) holds row l31
+// and columns 8q + 4lh .. +3 of each 32x32 block (16-byte stores; the four q of a block complete
+// the row's 128-byte line).
+template <typename T, typename ACC>
+__device__ __forceinline__ void store_ksplit_run(const GemmDev &g, ACC (&acc)[T::MT][T::NT], int split, int tm,
+                                                 int tn, int wm, int wn, int l31, int lh)
+{
+    float *dst = g.ksplit_out + (int64_t)split * g.M * g.N;
+#pragma unroll
+    for (int i = 0; i < T::MT; ++i) {
+        const int m = tm * T::BM + wm * T::TM + i * 32 + l31;
+#pragma unroll
+        for (int j = 0; j < T::NT; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = tn * T::BN + wn * T::TN + j * 32 + 8 * q + 4 * lh;
+                if (m < g.M && n < g.N)
+                    *(v4f *)(dst + (int64_t)m * g.N + n) =
+                        v4f{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            }
+    }
+}
+
 template <typename T, bool INT8, bool A_E5M2 = false>
 __global__ __launch_bounds__(T::THREADS) void gemm_nt_kernel(GemmDev g)
 {
@@ -438,23 +461,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_nt_kernel(GemmDev g)
 
     if constexpr (!INT8) {
         if (g.ksplit > 1) {
-            // fp32 sums of this run, straight from the MFMA layout: lane (l31, lh) holds row l31
-            // and columns 8q + 4lh .. +3 of each 32x32 block (16-byte stores; the four q of a
-            // block complete the row's 128-byte line)
-            float *dst = g.ksplit_out + (int64_t)split * g.M * g.N;
-#pragma unroll
-            for (int i = 0; i < T::MT; ++i) {
-                const int m = tm * BM + wm * T::TM + i * 32 + l31;
-#pragma unroll
-                for (int j = 0; j < T::NT; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int n = tn * BN + wn * T::TN + j * 32 + 8 * q + 4 * lh;
-                        if (m < g.M && n < g.N)
-                            *(v4f *)(dst + (int64_t)m * g.N + n) =
-                                v4f{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                    }
-            }
+            store_ksplit_run<T>(g, acc, split, tm, tn, wm, wn, l31, lh);
             return;
         }
     }
@@ -500,12 +507,21 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_dma_kernel(GemmDev
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int wm = wave / T::WN, wn = wave % T::WN;
     int tm, tn;
-    tile_of_workgroup(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
+    // with a K split the grid is ksplit runs of the tile grid: run `split` takes K stages
+    // [split * stages / ksplit, (split + 1) * stages / ksplit)
+    const int n_tiles = g.tiles_m * g.tiles_n;
+    const int split = g.ksplit > 1 ? (int)blockIdx.x / n_tiles : 0;
+    tile_of_workgroup((int)blockIdx.x - split * n_tiles, g.tiles_m, g.tiles_n, tm, tn);
+    int kt = g.K / T::BK, kt_begin = 0;
+    if (g.ksplit > 1) {
+        kt_begin = (int)((int64_t)split * kt / g.ksplit);
+        kt = (int)((int64_t)(split + 1) * kt / g.ksplit) - kt_begin;
+    }
 
     // ---- DMA addressing -----------------------------------------------------
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
-    const uint8_t *Ag = g.A + (int64_t)tm * T::BM * g.K;
-    const uint8_t *Bg = g.B + (int64_t)tn * T::BN * g.K;
+    const uint8_t *Ag = g.A + (int64_t)tm * T::BM * g.K + (int64_t)kt_begin * T::BK;
+    const uint8_t *Bg = g.B + (int64_t)tn * T::BN * g.K + (int64_t)kt_begin * T::BK;
     const int a_rows = g.M - tm * T::BM, b_rows = g.N - tn * T::BN;
     uint32_t a_voff[T::A_DMA], b_voff[T::B_DMA];
 #pragma unroll
@@ -587,7 +603,6 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_dma_kernel(GemmDev
 
     // ---- pipeline ---------------------------------------------------------------
     // Invariant at the top of iteration s: stages <= s+NS-2 have been issued.
-    const int kt = g.K / T::BK;
 #pragma unroll
     for (int s = 0; s < T::NS - 1; ++s)
         if (s < kt)
@@ -640,6 +655,12 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_dma_kernel(GemmDev
         tail_step(s, fr[0], fr[1]);
         if (s + 1 < kt)
             tail_step(s + 1, fr[1], fr[0]);
+    }
+    if constexpr (!INT8) {
+        if (g.ksplit > 1) {
+            store_ksplit_run<T>(g, acc, split, tm, tn, wm, wn, l31, lh);
+            return;
+        }
     }
     block_barrier();  // every wave is done reading the stages before they are reused
     NoBandHook no_hook;
@@ -1716,15 +1737,16 @@ static hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 // K split for outputs with far fewer tiles than CUs and a very long contraction (weight gradients
 // of narrow layers: 2304x768 over 50432 tokens is 27 tiles): `splits` workgroups per 256x256
 // tile, each at least 16 stages long, fp32 runs to scratch, one reduce launch.  1 = no split.
-// Measured: 349 -> 136 us for that shape; at a contraction of 8192 the scratch traffic and the
-// second launch eat the gain (40 -> 46 us), hence the 16384 floor.
+// Measured: 349 -> 117 us for that shape, 104 -> 94 us for 2048x2048 over 16384 (64 tiles, the
+// limit taken); at a contraction of 8192 the scratch traffic and the second launch eat the gain
+// (40 -> 46 us), hence the 16384 floor.
 int fp8_gemm_ksplit(int64_t M, int64_t N, int64_t K)
 {
     if (g_tile_override != 0)
         return 1;
     const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256), k_tiles = (K + kBK - 1) / kBK;
     const int64_t cus = num_cus();
-    if (tiles * 4 >= cus || k_tiles < 128)
+    if (tiles * 4 > cus || k_tiles < 128)
         return 1;
     int64_t splits = cus / tiles;
     if (splits > k_tiles / 16)
@@ -1740,14 +1762,21 @@ size_t fp8_gemm_ksplit_bytes(int64_t M, int64_t N, int64_t K)
     return splits > 1 ? (size_t)splits * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
-template <bool A_E5M2>
+// DMA: the direct-to-LDS kernel on 64-byte stages (K % 64 == 0, E4M3 operands), else the
+// register-staged one.
+template <bool A_E5M2, bool DMA>
 static hipError_t launch_ksplit(const GemmArgs &a, hipStream_t s, int splits)
 {
-    using T = T256x256;
+    using T = typename std::conditional<DMA, D256x256w8, T256x256>::type;
+    static_assert(!(DMA && A_E5M2), "the direct-to-LDS kernel takes E4M3 operands only");
+    const void *kern;
+    if constexpr (DMA)
+        kern = (const void *)gemm_nt_dma_kernel<T, false>;
+    else
+        kern = (const void *)gemm_nt_kernel<T, false, A_E5M2>;
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_kernel<T, false, A_E5M2>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
         if (e != hipSuccess)
             return e;
         attr_done = true;
@@ -1775,15 +1804,22 @@ static hipError_t launch_ksplit(const GemmArgs &a, hipStream_t s, int splits)
         e1 = g_prof_events[2 * g_prof_next + 1];
         ++g_prof_next;
     }
-    if (e0 != nullptr) {
-        hipExtLaunchKernelGGL((gemm_nt_kernel<T, false, A_E5M2>), grid, block, T::LDS_BYTES, s, e0, nullptr, 0, g);
+    auto launch_first = [&](auto kernel) {
+        if (e0 != nullptr)
+            hipExtLaunchKernelGGL(kernel, grid, block, T::LDS_BYTES, s, e0, nullptr, 0, g);
+        else
+            hipLaunchKernelGGL(kernel, grid, block, T::LDS_BYTES, s, g);
+    };
+    if constexpr (DMA)
+        launch_first(gemm_nt_dma_kernel<T, false>);
+    else
+        launch_first(gemm_nt_kernel<T, false, A_E5M2>);
+    if (e1 != nullptr)
         hipExtLaunchKernelGGL(splitk_reduce_kernel, rgrid, dim3(256), 0, s, nullptr, e1, 0,
                               (const float *)g.ksplit_out, splits, mn, a.s0, a.s1, (uint16_t *)a.out);
-    } else {
-        hipLaunchKernelGGL((gemm_nt_kernel<T, false, A_E5M2>), grid, block, T::LDS_BYTES, s, g);
+    else
         hipLaunchKernelGGL(splitk_reduce_kernel, rgrid, dim3(256), 0, s, (const float *)g.ksplit_out, splits, mn, a.s0,
                            a.s1, (uint16_t *)a.out);
-    }
     return hipGetLastError();
 }
 
@@ -1815,7 +1851,11 @@ hipError_t launch_fp8_gemm(const GemmArgs &a, hipStream_t s)
         const int splits = fp8_gemm_ksplit(a.M, a.N, a.K);
         if (splits > 1 && a.sk_workspace != nullptr && ((uintptr_t)a.sk_workspace & 15u) == 0 &&
             a.sk_workspace_bytes >= (size_t)splits * (size_t)a.M * (size_t)a.N * sizeof(float))
-            return a.a_e5m2 ? launch_ksplit<true>(a, s, splits) : launch_ksplit<false>(a, s, splits);
+        {
+            if (a.a_e5m2)
+                return launch_ksplit<true, false>(a, s, splits);
+            return a.K % 64 == 0 ? launch_ksplit<false, true>(a, s, splits) : launch_ksplit<false, false>(a, s, splits);
+        }
     }
     return a.a_e5m2 ? launch_fp8_gemm_e5m2(a, s) : launch_gemm<false>(a, s);
 }
