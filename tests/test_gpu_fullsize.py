@@ -28,7 +28,11 @@ def run_layer(x, w, dy, M, K, N, residual=None):
              sc=torch.full((16,), -1.0, dtype=torch.float32, device=DEV),
              S=torch.zeros(2, dtype=torch.float64, device=DEV))
     saved = tw.make_saved(t["xq"], t["xqT"], t["wq"], t["wqT"], t["sc"])
-    ws = workspace(tw.TWEO_OP_FP8_LINEAR_FWD_BF16, M, N, K)
+    # one workspace for both directions, as bench.py sizes it (the backward one includes the
+    # scratch of a K-split weight gradient where the shape calls for one)
+    ws = torch.empty(max(tw.tweo_workspace_bytes(op, M, N, K) for op in
+                         (tw.TWEO_OP_FP8_LINEAR_FWD_BF16, tw.TWEO_OP_FP8_LINEAR_BWD_BF16)),
+                     dtype=torch.uint8, device=DEV)
     tw.tweo_fp8_linear_fwd_bf16(to_dev_bf16(x), to_dev_bf16(w), t["y"], saved,
                                 residual_bf16=None if residual is None else to_dev_bf16(residual),
                                 pen=PEN, penalty_sum=t["S"], workspace=ws)
@@ -64,6 +68,7 @@ CASES = [  # (cfg, gemm index, full oracle for the forward + penalty?)
     (2, 1, False),   # ViT fc1 50432x768x3072 (channel outliers)
     (2, 2, False),   # ViT fc2 50432x3072x768
     (3, 0, False),   # LLaMA qkv 16384x2048x6144
+    (3, 1, False),   # LLaMA o 16384x2048x2048 (its weight gradient: 64 tiles, K split)
     (3, 4, False),   # LLaMA down 16384x5632x2048
 ]
 
