@@ -1473,6 +1473,14 @@ static int pick_variant(int64_t M, int64_t N, int64_t K)
             }
             if (c13 < best)
                 v = 13;
+            // few K stages per tile: the big tiles' fixed cost per tile (fill, write-out) weighs
+            // more than the model's rounds say (8192x2304, K = 768: 26 us against 31 us measured)
+            if (v == 14 && K < 1024 && c13 < 1.2 * c14)
+                v = 13;
+            // a single round of 128x128 tiles under a long contraction: the non-persistent
+            // kernel with its four-stage ring is 10-15 % ahead (weight gradients of narrow layers)
+            if (v == 13 && K >= 4096 && K % 64 == 0 && tiles(128, 128) <= (int64_t)(2 * cus))
+                v = 8;
             // The deferred-epilogue kernel (one wave per SIMD, operand halves refilled behind
             // their own barriers) is the faster 256x256 kernel whenever every CU gets a tile.
             if (v == 11 && M % 256 == 0 && N % 256 == 0 && K % 128 == 0 && K >= 512 &&
