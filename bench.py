@@ -379,7 +379,7 @@ def main():
                    "gemms": ["%s %dx%dx%d" % (L.name, L.M, L.K, L.N) for L in layers],
                    "flop_per_step": step_flops, "penalty": "tau=3 p=4 eps=1e-6, fused",
                    "tile": a.tile},
-        "roofline": {"bound": "mfma", "kernel": "gemm_nt_defer_kernel / gemm_nt_stream_kernel (fp8 fwd, dgrad, wgrad)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_nt_defer_kernel (fp8 fwd, dgrad, wgrad; tile-starved ones: other variants or a K split)",
                      "achieved": round(gemm_tflops, 2), "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tflops / FP8_PEAK_TFLOPS, 4),
                      "traffic": profiled_traffic(a.workload) if a.tile == 0 else None,
