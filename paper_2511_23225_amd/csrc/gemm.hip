@@ -1249,11 +1249,14 @@ __global__ __launch_bounds__(WAVES * 64) void w8a8_skinny_resident_kernel(const 
     const int blocks = (N + 15) / 16;
     // k offset of this wave's u-th step; steps past the end re-read step `wave % steps` with a
     // zero X fragment, so their products vanish
+    // Workgroups start at different steps (rotation by workgroup index): they all read the same
+    // X, and in the same order they would all queue at the same L2 channel at the same time.
     int koff[XC];
     v4i xf[XC][MB];
+    const int rot = (int)(blockIdx.x % XC);
 #pragma unroll
     for (int u = 0; u < XC; ++u) {
-        const int su = wave + u * WAVES;
+        const int su = wave + ((u + rot) % XC) * WAVES;
         const bool ok = su < steps;
         koff[u] = (ok ? su : wave % steps) * STEP + kc * 16;
 #pragma unroll
