@@ -230,12 +230,29 @@ def time_w8a8(tw, torch, synth, dev, iters=20):
         ms_q = timed(lambda: tw.tweo_quantize_i8_rows(xb, 1e-6, xq2, sx))
         ms_g = timed(lambda: tw.tweo_w8a8_linear_scaled(xq2, wq, sx, sw, y))
         ku_g = kernel_us(lambda: tw.tweo_w8a8_linear_scaled(xq2, wq, sx, sw, y))
+        # the decode step (per-token quantise + GEMM) as one HIP graph: what the pair costs once
+        # the host's per-call time is out of the way
+        graph_us = None
+        if M <= 64:
+            pair = lambda: (tw.tweo_quantize_i8_rows(xb, 1e-6, xq2, sx), tw.tweo_w8a8_linear_scaled(xq2, wq, sx, sw, y))
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                pair()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(10):
+                    pair()
+            graph_us = timed(graph.replay) * 1e3 / 10
         res["M=%d" % M]["W(C)A(K)"] = {"quantize_rows_us": round(ms_q * 1e3, 2),
                                        "quantize_rows_GB/s": round(3.0 * M * K / ms_q / 1e6, 1),
                                        "gemm_us": round(ms_g * 1e3, 2),
                                        "gemm_TOP/s": round(2.0 * M * N * K / ms_g / 1e9, 2),
                                        "gemm_GB/s": round((bytes_ + 4 * (M + N)) / ms_g / 1e6, 1),
-                                       "gemm_kernel_us": round(ku_g, 2)}
+                                       "gemm_kernel_us": round(ku_g, 2),
+                                       "quantize_plus_gemm_in_graph_us": None if graph_us is None else round(graph_us, 2)}
     return res
 
 
