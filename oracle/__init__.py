@@ -304,3 +304,19 @@ def w8a8_linear_scaled(xq, wq, sx, sw):
                                  _i64(0 if sx.size == 1 else 1), _p(sw, _f32),
                                  _i64(0 if sw.size == 1 else 1), _p(y, _u16))
     return y
+
+
+def w8a8_linear_scaled_i8out(xq, wq, sx, sw, inv_step_out):
+    """INT8 output for a quantised residual stream: clamp(rne(((fp32(acc)*sx[m])*sw[n]) * inv_step_out))."""
+    xq, wq = _c(xq, np.int8), _c(wq, np.int8)
+    M, K = xq.shape
+    N, K2 = wq.shape
+    assert K == K2
+    sx = _c(np.atleast_1d(sx), np.float32)
+    sw = _c(np.atleast_1d(sw), np.float32)
+    assert sx.size in (1, M) and sw.size in (1, N)
+    yq = np.empty((M, N), np.int8)
+    lib().orc_w8a8_linear_scaled_i8out(_p(xq, _i8), _p(wq, _i8), _i64(M), _i64(N), _i64(K), _p(sx, _f32),
+                                       _i64(0 if sx.size == 1 else 1), _p(sw, _f32),
+                                       _i64(0 if sw.size == 1 else 1), _f32(float(inv_step_out)), _p(yq, _i8))
+    return yq

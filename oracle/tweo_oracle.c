@@ -579,6 +579,41 @@ void orc_w8a8_linear_scaled(const int8_t *xq, const int8_t *wq, int64_t M, int64
         }
 }
 
+/*
+ * The same linear with an INT8 output for a quantised residual stream (Sec. 4.4, Table 4 "Res.?
+ * Yes": the activation that leaves the layer is itself stored in 8 bits, with a static
+ * per-tensor s): Eq. 4 applied to the fp32 result, X_q = round(y / s_out * Q_8) with the two
+ * factors folded into inv_step_out = 127 / s_out by the caller.  Readings: the fp32 value
+ * (fp32(acc) * sx[m]) * sw[n] is quantised directly, without rounding it to bf16 first; one more
+ * fp32 multiply, round to nearest even, saturation to +-127, NaN -> 0, as in orc_quantize_i8.
+ */
+void orc_w8a8_linear_scaled_i8out(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N, int64_t K,
+                                  const float *sx, int64_t sx_stride, const float *sw,
+                                  int64_t sw_stride, float inv_step_out, int8_t *yq)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t m = 0; m < M; ++m) {
+            int32_t acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int32_t)xq[m * K + k] * (int32_t)wq[n * K + k];
+            volatile float t = (float)acc * sx[m * sx_stride];
+            volatile float u = t * sw[n * sw_stride];
+            volatile float prod = u * inv_step_out;
+            float r = nearbyintf(prod);
+            int v;
+            if (isnan(r))
+                v = 0;
+            else if (r > 127.0f)
+                v = 127;
+            else if (r < -127.0f)
+                v = -127;
+            else
+                v = (int)r;
+            yq[m * N + n] = (int8_t)v;
+        }
+}
+
 int orc_num_threads(void)
 {
     int n = 1;

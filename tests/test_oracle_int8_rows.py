@@ -139,3 +139,40 @@ def test_scaled_linear_per_tensor_steps_reduce_to_the_static_path():
     sx, sw = ax / F32(127.0), aw / F32(127.0)
     assert np.array_equal(oracle.w8a8_linear_scaled(xq, wq, [sx], [sw]),
                           oracle.w8a8_linear_scaled(xq, wq, np.full(16, sx, F32), np.full(64, sw, F32)))
+
+
+def test_i8out_power_of_two_steps_against_exact_rationals():
+    rng = np.random.default_rng(8)
+    xq = rng.integers(-127, 128, (5, 64), dtype=np.int8)
+    wq = rng.integers(-127, 128, (9, 64), dtype=np.int8)
+    ex, ew = rng.integers(-10, -6, 5), rng.integers(-9, -5, 9)
+    sx, sw = np.exp2(ex).astype(np.float32), np.exp2(ew).astype(np.float32)
+    inv = F32(127.0) / F32(3.0)                     # s_out = 3: a non-trivial fp32 factor
+    yq = oracle.w8a8_linear_scaled_i8out(xq, wq, sx, sw, inv)
+    acc = int_ref(xq, wq)
+    for m in range(5):
+        for n in range(9):
+            # acc * 2^a * 2^b is exact in fp32 (|acc| < 2^24); then one fp32 multiply, then the rounding
+            y = F32(float(Fraction(int(acc[m, n])) * Fraction(2) ** int(ex[m]) * Fraction(2) ** int(ew[n])))
+            want = frac_round_half_even(Fraction(float(y * inv)))
+            assert yq[m, n] == max(-127, min(127, want)), (m, n)
+    assert np.abs(yq).max() == 127 and (np.abs(yq) < 127).any()  # both the saturated and the open range occur
+
+
+def test_i8out_is_eq4_applied_to_the_linear_output():
+    x, w = synth.w8a8_inputs(1, 12, K=512, N=48)
+    xq, sx = oracle.quantize_i8_rows(x, 1e-6)
+    wq, sw = oracle.quantize_i8_rows(w, 1e-6)
+    exact = int_ref(xq, wq) * sx.astype(np.float64)[:, None] * sw.astype(np.float64)[None, :]
+    s_out = F32(np.abs(exact).max())                # static AbsMax of the layer's output
+    yq = oracle.w8a8_linear_scaled_i8out(xq, wq, sx, sw, F32(127.0) / s_out)
+    # X_deq = X_q / Q_8 * s is within half a step of the real output (plus three fp32 roundings)
+    step = float(s_out) / 127.0
+    assert np.abs(yq.astype(np.float64) * step - exact).max() <= 0.5 * step * (1 + 1e-4)
+    i = np.unravel_index(np.argmax(np.abs(exact)), exact.shape)
+    assert abs(int(yq[i])) == 127 and np.sign(yq[i]) == np.sign(exact[i])
+    # a step that is too small saturates, symmetric, never -128
+    tiny = oracle.w8a8_linear_scaled_i8out(xq, wq, sx, sw, F32(1e9))
+    assert set(np.unique(tiny)).issubset({-127, 0, 127})
+    # the transposed problem transposes the result
+    assert np.array_equal(oracle.w8a8_linear_scaled_i8out(wq, xq, sw, sx, F32(127.0) / s_out), yq.T)
