@@ -267,6 +267,21 @@ tweo_status tweo_w8a8_linear_scaled(const int8_t *xq, const int8_t *wq, int64_t 
                                     void *stream);
 
 /*
+ * The same linear with an INT8 result, for a pipeline whose residual stream is
+ * itself quantised (Sec. 4.4, the "Res.? Yes" rows of the residual-stream
+ * table): Eq. 4 with a static per-tensor s_out applied to the fp32 result,
+ *   yq[m,n] = clamp( rne( ((fp32(acc) * x_step[m or 0]) * w_step[n or 0]) * inv_step_out ), -127, 127 ),
+ * inv_step_out = 127 / s_out computed once by the caller; the fp32 value is not
+ * rounded to bf16 in between; NaN -> 0.  yq int8 [M,N] device, 16-byte aligned;
+ * everything else as tweo_w8a8_linear_scaled.  Errors as there, plus
+ * TWEO_ERR_INVALID_ARG for a NaN inv_step_out.
+ */
+tweo_status tweo_w8a8_linear_scaled_i8out(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N,
+                                          int64_t K, const float *x_step, int x_step_per_token,
+                                          const float *w_step, int w_step_per_channel,
+                                          float inv_step_out, int8_t *yq, void *stream);
+
+/*
  * State a forward pass leaves for the backward pass: the quantized operands,
  * their transposes and the per-tensor scalars.  All members are device
  * pointers to caller-owned buffers.

@@ -22,7 +22,7 @@ EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quan
            "tweo_set_stream_k", "tweo_penalty_grad_inject", "tweo_delayed_state_bytes",
            "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed", "tweo_profile_gemm_launches",
            "tweo_quantize_e5m2", "tweo_fp8_linear_bwd_hybrid", "tweo_fp8_linear_bwd_bf16_hybrid",
-           "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled")
+           "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled", "tweo_w8a8_linear_scaled_i8out")
 
 
 class TweoError(RuntimeError):
@@ -69,6 +69,7 @@ def load():
     L.tweo_w8a8_linear.argtypes = [vp, vp, i64, i64, i64, f32, vp, vp, sz, vp]
     L.tweo_quantize_i8_rows.argtypes = [vp, i64, i64, f32, vp, vp, vp]
     L.tweo_w8a8_linear_scaled.argtypes = [vp, vp, i64, i64, i64, vp, ctypes.c_int, vp, ctypes.c_int, vp, vp]
+    L.tweo_w8a8_linear_scaled_i8out.argtypes = [vp, vp, i64, i64, i64, vp, ctypes.c_int, vp, ctypes.c_int, f32, vp, vp]
     L.tweo_fp8_linear_fwd_bf16.argtypes = [vp, vp, vp, i64, i64, i64, vp, ctypes.POINTER(PenaltyCfg),
                                            vp, ctypes.POINTER(Fp8Saved), vp, sz, vp]
     L.tweo_fp8_linear_bwd_bf16.argtypes = [vp, ctypes.POINTER(Fp8Saved), i64, i64, i64, vp, vp, vp,
@@ -235,6 +236,18 @@ def tweo_w8a8_linear_scaled(xq, wq, x_step, w_step, y_bf16):
                                           1 if x_step.numel() > 1 else 0,
                                           _ptr(w_step), 1 if w_step.numel() > 1 else 0, _ptr(y_bf16),
                                           _stream()), "tweo_w8a8_linear_scaled")
+
+
+def tweo_w8a8_linear_scaled_i8out(xq, wq, x_step, w_step, inv_step_out, yq):
+    """INT8 result with the static step 1 / inv_step_out * 127 (quantised residual stream)."""
+    M, K = xq.shape
+    N = wq.shape[0]
+    if x_step.numel() not in (1, M) or w_step.numel() not in (1, N):
+        raise ValueError("step vectors must have 1 or M / N elements")
+    _check(load().tweo_w8a8_linear_scaled_i8out(_ptr(xq), _ptr(wq), M, N, K, _ptr(x_step),
+                                                1 if x_step.numel() > 1 else 0, _ptr(w_step),
+                                                1 if w_step.numel() > 1 else 0, float(inv_step_out), _ptr(yq),
+                                                _stream()), "tweo_w8a8_linear_scaled_i8out")
 
 
 def make_saved(xq, xqT, wq, wqT, scalars):

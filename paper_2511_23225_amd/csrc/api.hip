@@ -358,9 +358,10 @@ tweo_status tweo_quantize_i8_rows(const void *x_bf16, int64_t rows, int64_t cols
     return hip_status(launch_quantize_i8_rows(x_bf16, rows, cols, eps, q, step_out, (hipStream_t)stream));
 }
 
-tweo_status tweo_w8a8_linear_scaled(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N, int64_t K,
-                                    const float *x_step, int x_step_per_token, const float *w_step,
-                                    int w_step_per_channel, void *y_bf16, void *stream)
+static tweo_status w8a8_linear_scaled_impl(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N, int64_t K,
+                                           const float *x_step, int x_step_per_token, const float *w_step,
+                                           int w_step_per_channel, void *y_bf16, bool out_i8, float out_inv_step,
+                                           void *stream)
 {
     if (!xq || !wq || !y_bf16 || !x_step || !w_step || M <= 0 || N <= 0 || K <= 0 || !aligned16(xq) ||
         !aligned16(wq) || !aligned16(y_bf16) || (x_step_per_token != 0 && x_step_per_token != 1) ||
@@ -380,7 +381,27 @@ tweo_status tweo_w8a8_linear_scaled(const int8_t *xq, const int8_t *wq, int64_t 
     a.row_step_stride = x_step_per_token;
     a.col_step = w_step;
     a.col_step_stride = w_step_per_channel;
+    a.out_i8 = out_i8;
+    a.out_inv_step = out_inv_step;
     return hip_status(launch_i8_gemm(a, (hipStream_t)stream));
+}
+
+tweo_status tweo_w8a8_linear_scaled(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N, int64_t K,
+                                    const float *x_step, int x_step_per_token, const float *w_step,
+                                    int w_step_per_channel, void *y_bf16, void *stream)
+{
+    return w8a8_linear_scaled_impl(xq, wq, M, N, K, x_step, x_step_per_token, w_step, w_step_per_channel, y_bf16,
+                                   false, 0.0f, stream);
+}
+
+tweo_status tweo_w8a8_linear_scaled_i8out(const int8_t *xq, const int8_t *wq, int64_t M, int64_t N, int64_t K,
+                                          const float *x_step, int x_step_per_token, const float *w_step,
+                                          int w_step_per_channel, float inv_step_out, int8_t *yq, void *stream)
+{
+    if (!(inv_step_out == inv_step_out))
+        return TWEO_ERR_INVALID_ARG;
+    return w8a8_linear_scaled_impl(xq, wq, M, N, K, x_step, x_step_per_token, w_step, w_step_per_channel, yq, true,
+                                   inv_step_out, stream);
 }
 
 tweo_status tweo_fp8_linear_fwd_bf16(const void *x_bf16, const void *w_bf16,

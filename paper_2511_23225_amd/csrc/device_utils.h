@@ -46,6 +46,16 @@ __device__ __forceinline__ float scale_from_amax_range(float amax, float range)
 
 __device__ __forceinline__ float scale_from_amax(float amax) { return scale_from_amax_range(amax, 448.0f); }
 
+// Eq. 4 rounding to INT8: clamp(rne(v * inv_step), +-127), NaN -> 0; the low byte of the result
+__device__ __forceinline__ uint32_t round_to_i8(float v, float inv_step)
+{
+    const float prod = v * inv_step;
+    float r = __builtin_rintf(prod);  // v_rndne_f32: ties to even
+    r = __builtin_amdgcn_fmed3f(r, -127.0f, 127.0f);
+    r = (prod != prod) ? 0.0f : r;
+    return (uint32_t)(int)r & 0xFFu;
+}
+
 template <typename T>
 __device__ __forceinline__ T wave_reduce_sum(T v)
 {

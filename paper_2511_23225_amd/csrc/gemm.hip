@@ -213,6 +213,16 @@ __device__ __forceinline__ void epilogue_impl(const GemmDev &g, ACC (&acc)[T::MT
                     v[6] += bf16lo_to_f32(rr.w);
                     v[7] += bf16hi_to_f32(rr.w);
                 }
+                if (has_vec && g.out_i8) {  // INT8 output: one byte per element, no penalty
+                    uint32_t lo4 = 0, hi4 = 0;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        lo4 |= round_to_i8(v[r], g.out_inv_step) << (8 * r);
+                        hi4 |= round_to_i8(v[4 + r], g.out_inv_step) << (8 * r);
+                    }
+                    *(uint2 *)((uint8_t *)g.out + (base_off + row_off + (int64_t)lane_off) / 2) = make_uint2(lo4, hi4);
+                    continue;
+                }
                 const uint4 packed = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
                                                 pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
                 *(uint4 *)(out_base + row_off + lane_off) = packed;
@@ -1130,6 +1140,8 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
 struct StepVectors {
     const float *rs, *cs;
     int rs_stride, cs_stride;
+    int out_i8;  // Y holds int8 = clamp(rne(y * out_inv_step), +-127) instead of bf16
+    float out_inv_step;
 };
 
 template <int NBLK, int MB, int UNROLL, int WAVES, bool IL, bool VEC>
@@ -1217,6 +1229,12 @@ __global__ __launch_bounds__(WAVES * 64) void w8a8_skinny_kernel(const int8_t *_
 #pragma unroll
                     for (int v = 0; v < 4; ++v)
                         y[v] = ((float)sum[v] * rstep) * sv.cs[(int64_t)(n + v) * sv.cs_stride];
+                    if (sv.out_i8) {
+                        *(uint32_t *)((uint8_t *)Y + (int64_t)m * N + n) =
+                            round_to_i8(y[0], sv.out_inv_step) | (round_to_i8(y[1], sv.out_inv_step) << 8) |
+                            (round_to_i8(y[2], sv.out_inv_step) << 16) | (round_to_i8(y[3], sv.out_inv_step) << 24);
+                        continue;
+                    }
                 } else {
 #pragma unroll
                     for (int v = 0; v < 4; ++v)
@@ -1320,6 +1338,12 @@ __global__ __launch_bounds__(WAVES * 64) void w8a8_skinny_resident_kernel(const 
 #pragma unroll
                         for (int v = 0; v < 4; ++v)
                             y[v] = ((float)sum[v] * rstep) * sv.cs[(int64_t)(n + v) * sv.cs_stride];
+                        if (sv.out_i8) {
+                            *(uint32_t *)((uint8_t *)Y + (int64_t)m * N + n) =
+                                round_to_i8(y[0], sv.out_inv_step) | (round_to_i8(y[1], sv.out_inv_step) << 8) |
+                                (round_to_i8(y[2], sv.out_inv_step) << 16) | (round_to_i8(y[3], sv.out_inv_step) << 24);
+                            continue;
+                        }
                     } else {
 #pragma unroll
                         for (int v = 0; v < 4; ++v)
@@ -1566,6 +1590,8 @@ static hipError_t launch_tile(const GemmArgs &a, hipStream_t s)
     g.cs = a.col_step;
     g.rs_stride = a.row_step_stride;
     g.cs_stride = a.col_step_stride;
+    g.out_i8 = a.out_i8 ? 1 : 0;
+    g.out_inv_step = a.out_inv_step;
     g.ksplit = 1;
     g.ksplit_out = nullptr;
     g.tiles_m = (int)((a.M + T::BM - 1) / T::BM);
@@ -1626,6 +1652,8 @@ static hipError_t launch_stream_inst(const GemmArgs &a, hipStream_t s, int grid,
     g.cs = a.col_step;
     g.rs_stride = a.row_step_stride;
     g.cs_stride = a.col_step_stride;
+    g.out_i8 = a.out_i8 ? 1 : 0;
+    g.out_inv_step = a.out_inv_step;
     g.ksplit = 1;
     g.ksplit_out = nullptr;
     g.tiles_m = (int)((a.M + T::BM - 1) / T::BM);
@@ -1691,6 +1719,8 @@ static hipError_t launch_defer_inst(const GemmArgs &a, hipStream_t s)
     g.cs = a.col_step;
     g.rs_stride = a.row_step_stride;
     g.cs_stride = a.col_step_stride;
+    g.out_i8 = a.out_i8 ? 1 : 0;
+    g.out_inv_step = a.out_inv_step;
     g.ksplit = 1;
     g.ksplit_out = nullptr;
     g.tiles_m = (int)((a.M + T::BM - 1) / T::BM);
@@ -1874,7 +1904,7 @@ template <int NBLK, int MB, int UNROLL, int WAVES, bool IL>
 static hipError_t launch_skinny(const GemmArgs &a, hipStream_t s)
 {
     const unsigned grid = (unsigned)((a.N + 16 * NBLK - 1) / (16 * NBLK));
-    const StepVectors sv{a.row_step, a.col_step, a.row_step_stride, a.col_step_stride};
+    const StepVectors sv{a.row_step, a.col_step, a.row_step_stride, a.col_step_stride, a.out_i8 ? 1 : 0, a.out_inv_step};
     if (a.row_step != nullptr)
         launch_gemm_kernel(w8a8_skinny_kernel<NBLK, MB, UNROLL, WAVES, IL, true>, dim3(grid), dim3(WAVES * 64), 0, s,
                            (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
@@ -1894,7 +1924,7 @@ static hipError_t launch_skinny_resident(const GemmArgs &a, hipStream_t s, int w
     int grid = num_cus() * wg_per_cu;
     if (grid > blocks)
         grid = blocks;
-    const StepVectors sv{a.row_step, a.col_step, a.row_step_stride, a.col_step_stride};
+    const StepVectors sv{a.row_step, a.col_step, a.row_step_stride, a.col_step_stride, a.out_i8 ? 1 : 0, a.out_inv_step};
     if (a.row_step != nullptr)
         launch_gemm_kernel(w8a8_skinny_resident_kernel<MB, WAVES, XC, DEPTH, true>, dim3((unsigned)grid), dim3(WAVES * 64), 0,
                            s, (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,

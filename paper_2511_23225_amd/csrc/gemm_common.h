@@ -27,6 +27,9 @@ struct GemmDev {
     // tensor (stride 0); then y = bf16((fp32(acc) * rs[m*rs_stride]) * cs[n*cs_stride])
     const float *rs, *cs;
     int rs_stride, cs_stride;
+    // with step vectors only: out holds int8 [M,N] = clamp(rne(y * out_inv_step), +-127) instead of bf16
+    int out_i8;
+    float out_inv_step;
     // K split (register-staged FP8 kernel only): ksplit > 1 workgroups share a tile, workgroup
     // `split` multiplies its run of K stages and stores the fp32 sums to
     // ksplit_out[split][M][N]; a second kernel adds the runs in order and rounds

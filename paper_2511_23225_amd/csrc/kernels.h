@@ -72,6 +72,9 @@ struct GemmArgs {
     // or one for all (stride 0), likewise per row of B; alpha is ignored when they are given
     const float *row_step, *col_step;
     int row_step_stride, col_step_stride;
+    // with step vectors only: `out` is int8 [M,N], the fp32 result times out_inv_step rounded to INT8
+    bool out_i8;
+    float out_inv_step;
 };
 
 // Number of fp32 penalty partials the FP8 GEMM writes for these arguments.

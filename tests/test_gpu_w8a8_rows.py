@@ -161,3 +161,25 @@ def test_error_paths():
     y = torch.zeros((8, 8), dtype=torch.bfloat16, device=DEV)
     with pytest.raises(ValueError):
         tw.tweo_w8a8_linear_scaled(q, q, st[:3], st, y)
+
+
+# INT8 output for a quantised residual stream: the weight-streaming kernels (per-block and
+# resident-X), the tiled kernels on ragged and whole-tile shapes; steps that leave most values in
+# range, and one that saturates
+@pytest.mark.parametrize("gran", ["KC", "TT"])
+@pytest.mark.parametrize("shape", [(1, 4096, 264), (17, 1024, 200), (64, 2048, 136), (64, 4096, 8192), (8, 4096, 8192),
+                                   (200, 512, 392), (1024, 1024, 1024)])
+def test_scaled_linear_int8_output_bit_exact(shape, gran):
+    M, K, N = shape
+    say("w8a8 int8 out M=%d K=%d N=%d %s" % (M, K, N, gran))
+    xq, wq, sx, sw = quantised(M, K, N, gran)
+    ref = synth.bf16_bits_to_f32(oracle.w8a8_linear_scaled(xq, wq, sx, sw))
+    s_out = np.float32(np.abs(ref).max())
+    for inv in (np.float32(127.0) / s_out, np.float32(127.0) / (s_out / np.float32(16.0))):
+        yq = torch.full((M, N), 99, dtype=torch.int8, device=DEV)  # poisoned
+        tw.tweo_w8a8_linear_scaled_i8out(to_dev(xq), to_dev(wq), to_dev(np.atleast_1d(sx).astype(np.float32)),
+                                         to_dev(np.atleast_1d(sw).astype(np.float32)), inv, yq)
+        torch.cuda.synchronize()
+        want = oracle.w8a8_linear_scaled_i8out(xq, wq, sx, sw, inv)
+        assert np.array_equal(yq.cpu().numpy(), want)
+        assert np.abs(want).max() == 127
