@@ -70,16 +70,18 @@ CASES = [  # (cfg, gemm index, full oracle for the forward + penalty?)
     (3, 0, False),   # LLaMA qkv 16384x2048x6144
     (3, 1, False),   # LLaMA o 16384x2048x2048 (its weight gradient: 64 tiles, K split)
     (3, 4, False),   # LLaMA down 16384x5632x2048
+    (2, 0, False, 18912),  # ViT qkv at 96 images: 18912 tokens, not a multiple of any tile height
+    (2, 2, False, 18912),  # ViT fc2 likewise (long K forward, ragged rows in dgrad, ragged contraction in wgrad)
 ]
 
 
 @pytest.mark.parametrize("case", CASES)
 def test_full_size_layer(case):
-    cfg, gi, full = case
+    cfg, gi, full = case[:3]
     g = synth.CONFIGS[cfg]["gemms"][gi]
-    M, K, N = g.M, g.K, g.N
+    M, K, N = (case[3] if len(case) > 3 else g.M), g.K, g.N
     say("full size cfg=%d %s M=%d K=%d N=%d" % (cfg, g.name, M, K, N))
-    x, w, dy = synth.fp8_linear_inputs(cfg, gi)
+    x, w, dy = synth.fp8_linear_inputs(cfg, gi, M=M)
     residual = synth.residual_input(cfg, gi, M, N) if g.name in ("fc2", "down", "proj") else None
     t = run_layer(x, w, dy, M, K, N, residual)
     say("  gpu done")
