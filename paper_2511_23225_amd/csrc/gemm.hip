@@ -1492,14 +1492,35 @@ static int pick_variant(int64_t M, int64_t N, int64_t K)
             const double c11 = cost(256, 256, cus, 1.0);
             const double c13 = cost(128, 128, 2 * cus, 0.425);
             const double c14 = cost(192, 256, cus, 0.97);
+            // The deferred-epilogue kernel (one wave per SIMD, operand halves refilled behind
+            // their own barriers) where the shape allows it: ahead of the 8-wave kernel by 15 %
+            // when a tile's write-out has 15 stages to hide under, by nothing at 6 stages.
+            const int64_t kt = K / 128;
+            const bool e15 = M % 256 == 0 && N % 256 == 0 && K % 128 == 0 && K >= 512 && tiles(256, 256) >= (int64_t)cus;
+            const bool e16 = N % 256 == 0 && K % 128 == 0 && K >= 2048;
+            const double gain = kt >= 16 ? 1.15 : (kt >= 8 ? 1.08 : 1.0);
+            const double c15 = e15 ? cost(256, 256, cus, gain) : 1e300;
+            const double c16 = e16 ? cost(192, 256, cus, 0.97 * gain) : 1e300;
             v = 11;
             double best = c11;
             if (c14 < best) {
                 v = 14;
                 best = c14;
             }
+            if (c15 < best) {
+                v = 15;
+                best = c15;
+            }
+            if (c16 < best) {
+                v = 16;
+                best = c16;
+            }
             if (c13 < best)
                 v = 13;
+            if (v == 11 && e15)
+                v = 15;
+            if (v == 14 && e16)
+                v = 16;
             // few K stages per tile: the big tiles' fixed cost per tile (fill, write-out) weighs
             // more than the model's rounds say (8192x2304, K = 768: 26 us against 31 us measured)
             if (v == 14 && K < 1024 && c13 < 1.2 * c14)
@@ -1508,13 +1529,6 @@ static int pick_variant(int64_t M, int64_t N, int64_t K)
             // kernel with its four-stage ring is 10-15 % ahead (weight gradients of narrow layers)
             if (v == 13 && K >= 4096 && K % 64 == 0 && tiles(128, 128) <= (int64_t)(2 * cus))
                 v = 8;
-            // The deferred-epilogue kernel (one wave per SIMD, operand halves refilled behind
-            // their own barriers) is the faster 256x256 kernel whenever every CU gets a tile.
-            if (v == 11 && M % 256 == 0 && N % 256 == 0 && K % 128 == 0 && K >= 512 &&
-                tiles(256, 256) >= (int64_t)cus)
-                v = 15;
-            if (v == 14 && N % 256 == 0 && K % 128 == 0 && K >= 2048)
-                v = 16;
         }
     }
     if (v >= 11 && K % 128 != 0)  // the persistent kernels need whole 128-byte stages
