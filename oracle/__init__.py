@@ -220,9 +220,13 @@ class DelayedScaling:
 
     LENGTH = 16
 
-    def __init__(self):
+    def __init__(self, e5m2=False):
         self.history = []          # most recent last, at most LENGTH entries
         self.next_scale = np.float32(1.0)
+        # the gradient tensors of the HYBRID recipe are cast to E5M2 (Sec. 4.3): same history, the
+        # scale maps into +-57344 and the cast is the E5M2 one
+        self._scale = scale_from_amax_e5m2 if e5m2 else scale_from_amax
+        self._quantize = quantize_e5m2 if e5m2 else quantize_e4m3
 
     def _max(self):
         # maximum on the magnitude bit patterns, like amax itself (NaN above Inf above finite)
@@ -234,14 +238,14 @@ class DelayedScaling:
         a = np.float32(amax_bf16(x_bf16))
         if not self.history:                      # bootstrap
             self.history.append(a)
-            used, used_inv = scale_from_amax(self._max())
+            used, used_inv = self._scale(self._max())
         else:
             used = self.next_scale
             used_inv = np.float32(1.0) / np.float32(used)
             self.history.append(a)
         self.history = self.history[-self.LENGTH:]
-        self.next_scale = np.float32(scale_from_amax(self._max())[0])
-        qq, qqT = quantize_e4m3(x_bf16, used, transpose=transpose)
+        self.next_scale = np.float32(self._scale(self._max())[0])
+        qq, qqT = self._quantize(x_bf16, used, transpose=transpose)
         return qq, qqT, np.float32(used), np.float32(used_inv)
 
 

@@ -7,6 +7,7 @@ import numpy as np
 import torch
 
 import oracle
+from paper_2511_23225_amd import synth
 
 
 def exact_table():
@@ -131,3 +132,32 @@ def test_gradient_gemms_with_e5m2_dy_match_exact_rationals():
         for k in range(K):
             ex = sum(TABLE[int(dyq[m, n])] * e4[int(xq[m, k])] for m in range(M)) * Fraction(float(sdy)) * Fraction(float(sx))
             assert abs(dw[n, k] - float(ex)) <= 1e-12 * max(1.0, abs(float(ex)))
+
+
+def _tensor_with_amax(amax, seed, shape=(16, 32)):
+    rng = np.random.default_rng(seed)
+    v = (rng.uniform(-0.5, 0.5, shape) * amax).astype(np.float32)
+    v[0, 0] = amax
+    return synth.f32_to_bf16_bits(v)
+
+
+def test_delayed_scaling_with_e5m2_gradients():
+    # HYBRID + delayed scaling as the paper ran it (Sec. 4.3): the same 16-deep window, the scale
+    # maps into +-57344, the bytes are E5M2 codes of x * scale
+    d = oracle.DelayedScaling(e5m2=True)
+    amaxes = [2.0] * 3 + [512.0] + [2.0] * 20
+    used = []
+    for t, a in enumerate(amaxes):
+        x = _tensor_with_amax(a, t)
+        q, qT, s, si = d.cast(x)
+        used.append(float(s))
+        assert np.array_equal(qT, q.T)
+        assert np.float32(si) == np.float32(1.0) / np.float32(s)
+        assert np.array_equal(q, oracle.quantize_e5m2(x, np.float32(s))[0])
+    assert used[0] == used[1] == used[2] == used[3] == 57344.0 / 2.0
+    assert all(u == 57344.0 / 512.0 for u in used[4:20]) and all(u == 57344.0 / 2.0 for u in used[20:])
+    # a spike the history has not seen saturates at the largest finite code, never inf
+    d = oracle.DelayedScaling(e5m2=True)
+    d.cast(_tensor_with_amax(1.0, 0))
+    q, _, s, _ = d.cast(_tensor_with_amax(64.0, 1))
+    assert float(s) == 57344.0 and (q[0, 0] & 0x7F) == 0x7B and not ((q & 0x7F) == 0x7C).any()
