@@ -70,19 +70,22 @@ def run_step(tw, layers, ev=None):
         tw.tweo_fp8_linear_bwd_bf16(L.dy, L.saved, L.K, L.dyq, L.dyqT, L.dx, L.dw, L.ws)
 
 
-def run_step_delayed(tw, layers, bootstrap=False):
+def run_step_delayed(tw, layers, bootstrap=False, hybrid=False):
     """The same step with the paper's delayed scaling (Sec. 4.3): every tensor is cast in one
-    pass with the scale its amax history fixed beforehand; no separate amax pass."""
+    pass with the scale its amax history fixed beforehand; no separate amax pass.  hybrid: the
+    gradient is cast to E5M2 as in the paper's HYBRID recipe."""
     inv = tw.DELAYED_USED_SCALE_INV
+    cast_dy = tw.tweo_quantize_e5m2_delayed if hybrid else tw.tweo_quantize_e4m3_delayed
+    bwd = tw.tweo_fp8_linear_bwd_hybrid if hybrid else tw.tweo_fp8_linear_bwd
     for L in layers:
         sx, sw, sdy = L.st
         tw.tweo_quantize_e4m3_delayed(L.x, sx, L.xq, L.xqT, bootstrap=bootstrap)
         tw.tweo_quantize_e4m3_delayed(L.w, sw, L.wq, L.wqT, bootstrap=bootstrap)
         tw.tweo_fp8_linear_fwd(L.xq, sx[inv:inv + 1], L.wq, sw[inv:inv + 1], L.y, pen=PEN, penalty_sum=L.S,
                                workspace=L.ws)
-        tw.tweo_quantize_e4m3_delayed(L.dy, sdy, L.dyq, L.dyqT, bootstrap=bootstrap)
-        tw.tweo_fp8_linear_bwd(L.dyq, L.dyqT, sdy[inv:inv + 1], L.wqT, sw[inv:inv + 1], L.xqT,
-                               sx[inv:inv + 1], L.M, L.N, L.K, L.dx, L.dw, L.ws)
+        cast_dy(L.dy, sdy, L.dyq, L.dyqT, bootstrap=bootstrap)
+        bwd(L.dyq, L.dyqT, sdy[inv:inv + 1], L.wqT, sw[inv:inv + 1], L.xqT,
+            sx[inv:inv + 1], L.M, L.N, L.K, L.dx, L.dw, L.ws)
 
 
 class GemmEvents:
@@ -425,6 +428,20 @@ def main():
         ms_d = (time.perf_counter() - t0) * 1e3 / a.steps
         out["delayed_scaling_history16"] = {"ms_per_step": round(ms_d, 4),
                                             "TFLOP/s": round(step_flops / (ms_d * 1e-3) / 1e12, 2)}
+        # the paper's recipe in full: delayed scaling and E5M2 gradients (fresh gradient states)
+        for L in layers:
+            tw.tweo_delayed_state_init(L.st[2])
+        run_step_delayed(tw, layers, bootstrap=True, hybrid=True)
+        for _ in range(2):
+            run_step_delayed(tw, layers, hybrid=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            run_step_delayed(tw, layers, hybrid=True)
+        torch.cuda.synchronize()
+        ms_h = (time.perf_counter() - t0) * 1e3 / a.steps
+        out["delayed_scaling_hybrid_e5m2_gradients"] = {"ms_per_step": round(ms_h, 4),
+                                                        "TFLOP/s": round(step_flops / (ms_h * 1e-3) / 1e12, 2)}
         big = max(layers, key=lambda L: L.M * L.K)
         out["elementwise"] = time_elementwise(tw, torch, big)
         out["elementwise"]["peak_GB/s"] = HBM_PEAK_GBS

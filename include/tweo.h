@@ -146,6 +146,10 @@ size_t tweo_delayed_state_bytes(void);
 tweo_status tweo_delayed_state_init(void *state, void *stream);
 tweo_status tweo_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
                                        int bootstrap, uint8_t *q, uint8_t *qT, void *stream);
+/* The same for a tensor that is cast to E5M2 (the gradients of the HYBRID recipe,
+ * Sec. 4.3): scale = 57344 / max(history), saturation at +-57344, a state of its own. */
+tweo_status tweo_quantize_e5m2_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
+                                       int bootstrap, uint8_t *q, uint8_t *qT, void *stream);
 
 /*
  * FP8 linear forward with the TWEO penalty fused into the epilogue

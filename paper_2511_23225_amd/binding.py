@@ -22,7 +22,7 @@ EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quan
            "tweo_set_stream_k", "tweo_penalty_grad_inject", "tweo_delayed_state_bytes",
            "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed", "tweo_profile_gemm_launches",
            "tweo_quantize_e5m2", "tweo_fp8_linear_bwd_hybrid", "tweo_fp8_linear_bwd_bf16_hybrid",
-           "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled", "tweo_w8a8_linear_scaled_i8out")
+           "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled", "tweo_w8a8_linear_scaled_i8out", "tweo_quantize_e5m2_delayed")
 
 
 class TweoError(RuntimeError):
@@ -82,6 +82,7 @@ def load():
     L.tweo_delayed_state_bytes.restype = ctypes.c_size_t
     L.tweo_delayed_state_init.argtypes = [vp, vp]
     L.tweo_quantize_e4m3_delayed.argtypes = [vp, i64, i64, vp, ctypes.c_int, vp, vp, vp]
+    L.tweo_quantize_e5m2_delayed.argtypes = [vp, i64, i64, vp, ctypes.c_int, vp, vp, vp]
     L.tweo_penalty_grad_inject.argtypes = [vp, vp, i64, ctypes.POINTER(PenaltyCfg), ctypes.c_float, vp, vp]
     for name in EXPORTS:
         if name not in ("tweo_workspace_bytes", "tweo_status_string", "tweo_delayed_state_bytes"):
@@ -161,6 +162,12 @@ def tweo_quantize_e4m3_delayed(x_bf16, state, q, qT=None, bootstrap=False):
     rows, cols = x_bf16.shape
     _check(load().tweo_quantize_e4m3_delayed(_ptr(x_bf16), rows, cols, _ptr(state), 1 if bootstrap else 0,
                                              _ptr(q), _ptr(qT), _stream()), "tweo_quantize_e4m3_delayed")
+
+
+def tweo_quantize_e5m2_delayed(x_bf16, state, q, qT=None, bootstrap=False):
+    rows, cols = x_bf16.shape
+    _check(load().tweo_quantize_e5m2_delayed(_ptr(x_bf16), rows, cols, _ptr(state), 1 if bootstrap else 0,
+                                             _ptr(q), _ptr(qT), _stream()), "tweo_quantize_e5m2_delayed")
 
 
 def tweo_amax(x_bf16, amax_out):
@@ -247,7 +254,7 @@ def tweo_w8a8_linear_scaled_i8out(xq, wq, x_step, w_step, inv_step_out, yq):
     _check(load().tweo_w8a8_linear_scaled_i8out(_ptr(xq), _ptr(wq), M, N, K, _ptr(x_step),
                                                 1 if x_step.numel() > 1 else 0, _ptr(w_step),
                                                 1 if w_step.numel() > 1 else 0, float(inv_step_out), _ptr(yq),
-                                                _stream()), "tweo_w8a8_linear_scaled_i8out")
+                                                _stream()), "tweo_w8a8_linear_scaled_i8out", "tweo_quantize_e5m2_delayed")
 
 
 def make_saved(xq, xqT, wq, wqT, scalars):

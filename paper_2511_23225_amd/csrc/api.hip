@@ -187,6 +187,18 @@ tweo_status tweo_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t
                                                    (hipStream_t)stream));
 }
 
+tweo_status tweo_quantize_e5m2_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
+                                       int bootstrap, uint8_t *q, uint8_t *qT, void *stream)
+{
+    if (!x_bf16 || !state || !q || rows <= 0 || cols <= 0 || !aligned16(x_bf16) || !aligned16(q) ||
+        !aligned16(state) || (qT && !aligned16(qT)))
+        return TWEO_ERR_INVALID_ARG;
+    if (cols % 8 != 0 || rows > kMaxDim || cols > kMaxDim)
+        return TWEO_ERR_UNSUPPORTED;
+    return hip_status(launch_quantize_e5m2_delayed(x_bf16, rows, cols, state, bootstrap != 0, q, qT,
+                                                   (hipStream_t)stream));
+}
+
 tweo_status tweo_fp8_linear_fwd(const uint8_t *xq, const float *sx_inv, const uint8_t *wq,
                                 const float *sw_inv, const void *residual_bf16, int64_t M,
                                 int64_t N, int64_t K, void *y_bf16, const tweo_penalty_cfg *pen,

@@ -622,7 +622,7 @@ __global__ void delayed_state_init_kernel(uint32_t *st)
 
 // Consumes the accumulated amax: remembers the scale that was just used, pushes the amax into
 // the ring, derives the next scale, clears the accumulator.  One thread.
-__global__ void delayed_state_update_kernel(uint32_t *st, int bootstrap)
+__global__ void delayed_state_update_kernel(uint32_t *st, int bootstrap, float range)
 {
     if (threadIdx.x != 0 || blockIdx.x != 0)
         return;
@@ -637,7 +637,7 @@ __global__ void delayed_state_update_kernel(uint32_t *st, int bootstrap)
     uint32_t m = 0;
     for (int k = 0; k < 16; ++k)
         m = st[k] > m ? st[k] : m;  // magnitude patterns order like unsigned integers (NaN on top)
-    const float scale = scale_from_amax(bits_to_f32(m));
+    const float scale = scale_from_amax_range(bits_to_f32(m), range);  // 448 (E4M3) or 57344 (E5M2)
     st[17] = f32_to_bits(scale);
     st[18] = f32_to_bits(1.0f / scale);
     st[19] = (uint32_t)pos;
@@ -655,29 +655,43 @@ hipError_t launch_delayed_state_init(void *state, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
-                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s)
+template <bool E5M2>
+static hipError_t launch_quantize_f8_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
+                                             int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s)
 {
     float *st = (float *)state;
+    const float range = E5M2 ? 57344.0f : 448.0f;
     hipError_t e;
     if (bootstrap) {
         // empty history: this tensor's own amax makes the scale (two passes, once)
         e = launch_amax(x_bf16, rows * cols, st + 16, s);
         if (e != hipSuccess)
             return e;
-        hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 1);
+        hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 1, range);
         e = hipGetLastError();
         if (e != hipSuccess)
             return e;
-        return launch_quantize_e4m3_impl<true>(x_bf16, rows, cols, st + 21, q, qT, nullptr, nullptr,
-                                               (uint32_t *)st + 24, s);  // amax goes to a spare word
+        return launch_quantize_e4m3_impl<true, E5M2>(x_bf16, rows, cols, st + 21, q, qT, nullptr, nullptr,
+                                                     (uint32_t *)st + 24, s);  // amax goes to a spare word
     }
-    e = launch_quantize_e4m3_impl<true>(x_bf16, rows, cols, st + 17, q, qT, nullptr, nullptr,
-                                        (uint32_t *)st + 16, s);
+    e = launch_quantize_e4m3_impl<true, E5M2>(x_bf16, rows, cols, st + 17, q, qT, nullptr, nullptr,
+                                              (uint32_t *)st + 16, s);
     if (e != hipSuccess)
         return e;
-    hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 0);
+    hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 0, range);
     return hipGetLastError();
+}
+
+hipError_t launch_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
+                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s)
+{
+    return launch_quantize_f8_delayed<false>(x_bf16, rows, cols, state, bootstrap, q, qT, s);
+}
+
+hipError_t launch_quantize_e5m2_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
+                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s)
+{
+    return launch_quantize_f8_delayed<true>(x_bf16, rows, cols, state, bootstrap, q, qT, s);
 }
 
 // ---------------------------------------------------------------------------

@@ -43,6 +43,9 @@ hipError_t launch_quantize_e5m2(const void *x_bf16, int64_t rows, int64_t cols, 
 hipError_t launch_delayed_state_init(void *state, hipStream_t s);
 hipError_t launch_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
                                         int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s);
+// the same for a tensor cast to E5M2 (gradients of the HYBRID recipe): scale = 57344 / max(history)
+hipError_t launch_quantize_e5m2_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
+                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s);
 hipError_t launch_quantize_i8(const void *x_bf16, int64_t n, float inv_step, int8_t *out,
                               hipStream_t s);
 // Row-granular AbsMax INT8: q [rows, cols] and one dequantisation step per row (cols % 8 == 0).

@@ -138,3 +138,36 @@ def test_hybrid_whole_backward_from_bf16():
     dw_ref, dw_abs = oracle.fp8_linear_wgrad(odyq, oxq, sdyi, sxi, dy_e5m2=True)
     check_gemm(bf16_bits(dx), dx_ref, dx_abs, N, "dgrad")
     check_gemm(bf16_bits(dw), dw_ref, dw_abs, M, "wgrad")
+
+
+@pytest.mark.parametrize("shape", [(256, 512), (200, 136), (1024, 768)])
+def test_delayed_scaling_sequence_e5m2(shape):
+    # the gradient tensors under the paper's own recipe (Sec. 4.3: HYBRID formats, delayed scaling
+    # with an amax history of 16): 20 steps with a spike and an all-zero step, bytes and the
+    # scales in the state bit-exact against the oracle
+    rows, cols = shape
+    say("delayed scaling, E5M2", shape)
+    ref = oracle.DelayedScaling(e5m2=True)
+    state = torch.full((tw.DELAYED_STATE_WORDS,), -7.0, dtype=torch.float32, device=DEV)
+    tw.tweo_delayed_state_init(state)
+    q = torch.empty((rows, cols), dtype=torch.uint8, device=DEV)
+    qT = torch.empty((cols, rows), dtype=torch.uint8, device=DEV)
+    rng = np.random.default_rng(rows + 3 * cols)
+    for step in range(20):
+        v = (rng.standard_normal((rows, cols)) * (1.0 + 0.1 * step)).astype(np.float32)
+        if step == 3:
+            v[rng.integers(rows), rng.integers(cols)] = -4321.0
+        if step == 7:
+            v[:] = 0.0
+        x = synth.f32_to_bf16_bits(v)
+        oq, oqT, used, used_inv = ref.cast(x)
+        q.fill_(0x55)
+        qT.fill_(0x55)
+        tw.tweo_quantize_e5m2_delayed(to_dev_bf16(x), state, q, qT, bootstrap=(step == 0))
+        torch.cuda.synchronize()
+        st = state.cpu().numpy()
+        assert np.array_equal(q.cpu().numpy(), oq), step
+        assert np.array_equal(qT.cpu().numpy(), oqT), step
+        assert st[tw.DELAYED_USED_SCALE].view(np.uint32) == np.float32(used).view(np.uint32), step
+        assert st[tw.DELAYED_USED_SCALE_INV].view(np.uint32) == np.float32(used_inv).view(np.uint32), step
+        assert st[tw.DELAYED_NEXT_SCALE].view(np.uint32) == np.float32(ref.next_scale).view(np.uint32), step
