@@ -335,6 +335,26 @@ tweo_status tweo_fp8_linear_bwd_bf16_hybrid(const void *dy_bf16, const tweo_fp8_
                                             size_t workspace_bytes, void *stream);
 
 /*
+ * The backward path with the penalty-gradient injection (tweo_penalty_grad_inject)
+ * as a prologue of the gradient's amax and cast: dy' = bf16(dy + g * p * sign(a) *
+ * (|a| / (tau+eps))^(p-1) / (tau+eps)) is formed on the way into both passes and
+ * never stored; everything downstream (amax, scale, codes, GEMMs) is what
+ * tweo_penalty_grad_inject followed by tweo_fp8_linear_bwd_bf16 (dy_e5m2 = 0) or
+ * tweo_fp8_linear_bwd_bf16_hybrid (dy_e5m2 = 1) gives, bit for bit.  a_bf16
+ * [M,N]: the penalised activation of the forward pass.  10 instead of 12 bytes
+ * of traffic per gradient element, one launch less, no buffer for dy' (measured
+ * on MI355X: the same time as the two calls, whose intermediate is re-read
+ * from the memory-side cache).
+ * Errors as the two calls it replaces.
+ */
+tweo_status tweo_fp8_linear_bwd_bf16_inject(const void *dy_bf16, const void *a_bf16,
+                                            const tweo_penalty_cfg *pen, float g, int dy_e5m2,
+                                            const tweo_fp8_saved *saved, int64_t M, int64_t N,
+                                            int64_t K, uint8_t *dyq, uint8_t *dyqT, void *dx_bf16,
+                                            void *dw_bf16, void *workspace, size_t workspace_bytes,
+                                            void *stream);
+
+/*
  * Tuning hook for benchmarks and tests: forces the GEMM kernel variant.
  * 0 = choose from the shape (the default).  1-4 = register-staged kernel, tiles
  * 256x256, 256x128, 128x128, 64x64 (any K % 16 == 0).  5-10 = DMA-pipelined

@@ -22,7 +22,7 @@ EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quan
            "tweo_set_stream_k", "tweo_penalty_grad_inject", "tweo_delayed_state_bytes",
            "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed", "tweo_profile_gemm_launches",
            "tweo_quantize_e5m2", "tweo_fp8_linear_bwd_hybrid", "tweo_fp8_linear_bwd_bf16_hybrid",
-           "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled", "tweo_w8a8_linear_scaled_i8out", "tweo_quantize_e5m2_delayed")
+           "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled", "tweo_w8a8_linear_scaled_i8out", "tweo_quantize_e5m2_delayed", "tweo_fp8_linear_bwd_bf16_inject")
 
 
 class TweoError(RuntimeError):
@@ -75,6 +75,8 @@ def load():
     L.tweo_fp8_linear_bwd_bf16.argtypes = [vp, ctypes.POINTER(Fp8Saved), i64, i64, i64, vp, vp, vp,
                                            vp, vp, sz, vp]
     L.tweo_fp8_linear_bwd_bf16_hybrid.argtypes = L.tweo_fp8_linear_bwd_bf16.argtypes
+    L.tweo_fp8_linear_bwd_bf16_inject.argtypes = [vp, vp, ctypes.POINTER(PenaltyCfg), f32, ctypes.c_int,
+                                                  ctypes.POINTER(Fp8Saved), i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     L.tweo_set_gemm_tile.argtypes = [ctypes.c_int]
     L.tweo_set_stream_k.argtypes = [ctypes.c_int]
     L.tweo_profile_gemm_launches.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
@@ -254,7 +256,7 @@ def tweo_w8a8_linear_scaled_i8out(xq, wq, x_step, w_step, inv_step_out, yq):
     _check(load().tweo_w8a8_linear_scaled_i8out(_ptr(xq), _ptr(wq), M, N, K, _ptr(x_step),
                                                 1 if x_step.numel() > 1 else 0, _ptr(w_step),
                                                 1 if w_step.numel() > 1 else 0, float(inv_step_out), _ptr(yq),
-                                                _stream()), "tweo_w8a8_linear_scaled_i8out", "tweo_quantize_e5m2_delayed")
+                                                _stream()), "tweo_w8a8_linear_scaled_i8out", "tweo_quantize_e5m2_delayed", "tweo_fp8_linear_bwd_bf16_inject")
 
 
 def make_saved(xq, xqT, wq, wqT, scalars):
@@ -279,6 +281,17 @@ def tweo_fp8_linear_bwd_bf16(dy_bf16, saved, K, dyq, dyqT, dx_bf16=None, dw_bf16
     _check(load().tweo_fp8_linear_bwd_bf16(_ptr(dy_bf16), ctypes.byref(saved), M, N, K, _ptr(dyq),
                                            _ptr(dyqT), _ptr(dx_bf16), _ptr(dw_bf16), wp, wb,
                                            _stream()), "tweo_fp8_linear_bwd_bf16")
+
+
+def tweo_fp8_linear_bwd_bf16_inject(dy_bf16, a_bf16, pen, g, saved, K, dyq, dyqT, dx_bf16=None, dw_bf16=None,
+                                    workspace=None, dy_e5m2=False):
+    M, N = dy_bf16.shape
+    wp, wb = _ws(workspace)
+    cfg = PenaltyCfg(float(pen[0]), float(pen[1]), int(pen[2]))
+    _check(load().tweo_fp8_linear_bwd_bf16_inject(_ptr(dy_bf16), _ptr(a_bf16), ctypes.byref(cfg), float(g),
+                                                  1 if dy_e5m2 else 0, ctypes.byref(saved), M, N, K, _ptr(dyq),
+                                                  _ptr(dyqT), _ptr(dx_bf16), _ptr(dw_bf16), wp, wb, _stream()),
+           "tweo_fp8_linear_bwd_bf16_inject")
 
 
 def tweo_fp8_linear_bwd_bf16_hybrid(dy_bf16, saved, K, dyq, dyqT, dx_bf16=None, dw_bf16=None,

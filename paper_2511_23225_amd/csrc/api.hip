@@ -499,4 +499,32 @@ tweo_status tweo_fp8_linear_bwd_bf16_hybrid(const void *dy_bf16, const tweo_fp8_
                                     workspace_bytes, stream, true);
 }
 
+tweo_status tweo_fp8_linear_bwd_bf16_inject(const void *dy_bf16, const void *a_bf16,
+                                            const tweo_penalty_cfg *pen, float g, int dy_e5m2,
+                                            const tweo_fp8_saved *saved, int64_t M, int64_t N, int64_t K,
+                                            uint8_t *dyq, uint8_t *dyqT, void *dx_bf16, void *dw_bf16,
+                                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!dy_bf16 || !a_bf16 || !pen || !saved || !saved->xqT || !saved->wqT || !saved->scalars || !dyq || !dyqT ||
+        M <= 0 || N <= 0 || K <= 0 || !aligned16(dy_bf16) || !aligned16(a_bf16) || !aligned16(dyq) ||
+        !aligned16(dyqT) || !(g == g) || !(pen->tau > 0.0f) || !(pen->eps >= 0.0f) ||
+        (dy_e5m2 != 0 && dy_e5m2 != 1))
+        return TWEO_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || M % 16 != 0 || N % 16 != 0 || K % 16 != 0 || pen->p < 1 || pen->p > 8)
+        return TWEO_ERR_UNSUPPORTED;
+    if (!workspace || !aligned16(workspace) || workspace_bytes < kAmaxScratchBytes)
+        return TWEO_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    float *sc = saved->scalars;
+    const double denom = (double)pen->tau + (double)pen->eps;
+    hipError_t e = launch_amax_quantize_inject(dy_bf16, a_bf16, M, N, (float)(1.0 / denom),
+                                               (float)((double)g * pen->p / denom), pen->p, dy_e5m2 != 0,
+                                               (uint32_t *)workspace, sc + 6, dyq, dyqT, sc + 7, sc + 8, s);
+    if (e != hipSuccess)
+        return TWEO_ERR_HIP;
+    return fp8_linear_bwd_impl(dyq, dyqT, sc + 8, saved->wqT, sc + 5, saved->xqT, sc + 2, M, N, K, dx_bf16, dw_bf16,
+                               (uint8_t *)workspace + kAmaxScratchBytes, workspace_bytes - kAmaxScratchBytes, stream,
+                               dy_e5m2 != 0);
+}
+
 }  // extern "C"

@@ -47,6 +47,44 @@ __device__ __forceinline__ uint32_t pk_absmax4(uint32_t m, uint4 v)
     return pk_absmax(m, v.w);
 }
 
+template <int P>
+__device__ __forceinline__ float inject_one(float dy, float a, float inv_tau, float coef, int p)
+{
+    const float u = __builtin_fabsf(a) * inv_tau;
+    float w = 1.0f;
+    if constexpr (P == 4) {
+        w = u * u * u;
+    } else {
+        // p is at most 8: a fixed trip count keeps the callers' loops unrollable
+#pragma unroll
+        for (int e = 1; e < 8; ++e)
+            w = e < p ? w * u : w;
+    }
+    const float t = coef * w;
+    // sign(a) = 0 for a = 0; a NaN activation poisons the gradient, as it should
+    return dy + (a > 0.0f ? t : (a < 0.0f ? -t : (a == 0.0f ? 0.0f : a)));
+}
+
+// The injection as a prologue of the gradient's amax and cast passes: the gradient is formed
+// (and rounded to bf16, as the stand-alone kernel stores it) on the way in.
+struct InjectArgs {
+    const uint16_t *act;  // the penalised activation, same shape as the gradient
+    float inv_tau, coef;
+    int p;
+};
+
+template <int P>  // 4: the paper's power, straight-line; 0: inj.p, any power up to 8
+__device__ __forceinline__ uint4 inject_vec(uint4 d, uint4 a, const InjectArgs &inj)
+{
+    const uint32_t dd[4] = {d.x, d.y, d.z, d.w}, aa[4] = {a.x, a.y, a.z, a.w};
+    uint32_t r[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        r[k] = pack_bf16x2(inject_one<P>(bf16lo_to_f32(dd[k]), bf16lo_to_f32(aa[k]), inj.inv_tau, inj.coef, inj.p),
+                           inject_one<P>(bf16hi_to_f32(dd[k]), bf16hi_to_f32(aa[k]), inj.inv_tau, inj.coef, inj.p));
+    return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
 // Each workgroup owns one contiguous chunk of the tensor and walks it with
 // eight 16-byte loads in flight per lane (measured: ~30 % more bandwidth than a
 // grid-stride walk, whose concurrent streams are megabytes apart).
@@ -120,6 +158,45 @@ __global__ __launch_bounds__(kAmaxThreads) void amax2_kernel(const uint4 *__rest
         amax_body<PARTIAL>(x0, n_vec0, per_block0, (int)blockIdx.x, nullptr, 0, out0);
     else
         amax_body<PARTIAL>(x1, n_vec1, per_block1, (int)blockIdx.x - blocks0, nullptr, 0, out1);
+}
+
+// amax of the gradient with the penalty gradient added on the way in (one maximum per workgroup)
+template <int P>
+__global__ __launch_bounds__(kAmaxThreads) void amax_inject_kernel(const uint4 *__restrict__ dy, InjectArgs inj,
+                                                                   int64_t n_vec, int64_t per_block,
+                                                                   uint32_t *__restrict__ partials)
+{
+    __shared__ uint32_t red[kAmaxThreads / kWave];
+    const uint4 *act = (const uint4 *)inj.act;
+    const int64_t b0 = (int64_t)blockIdx.x * per_block;
+    const int64_t b1 = b0 + per_block < n_vec ? b0 + per_block : n_vec;
+    uint32_t m = 0;
+    constexpr int UNROLL = 4;  // eight 16-byte loads in flight per lane, as in the plain amax
+    int64_t i = b0 + threadIdx.x;
+    for (; i + (UNROLL - 1) * kAmaxThreads < b1; i += UNROLL * kAmaxThreads) {
+        uint4 d[UNROLL], a[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            d[u] = dy[i + u * kAmaxThreads];
+            a[u] = act[i + u * kAmaxThreads];
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            m = pk_absmax4(m, inject_vec<P>(d[u], a[u], inj));
+    }
+    for (; i < b1; i += kAmaxThreads)
+        m = pk_absmax4(m, inject_vec<P>(dy[i], act[i], inj));
+    uint32_t r = (m & 0xFFFFu) > (m >> 16) ? (m & 0xFFFFu) : (m >> 16);
+    r = wave_reduce_max_u32(r);
+    if ((threadIdx.x & (kWave - 1)) == 0)
+        red[threadIdx.x / kWave] = r;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kAmaxThreads / kWave; ++w)
+            r = red[w] > r ? red[w] : r;
+        partials[blockIdx.x] = r << 16;
+    }
 }
 
 static int amax_cus()
@@ -392,12 +469,14 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
 // workgroup 256x256.
 constexpr int kQuantBigTile = 256;
 
-template <bool WITH_T, bool DELAYED, bool E5M2 = false>
+// INJECT: 0 = plain cast; 4 / 1 = the penalty gradient is added on the way in (p = 4 / any p)
+template <bool WITH_T, bool DELAYED, bool E5M2 = false, int INJECT = 0>
 __device__ __forceinline__ void quantize_e4m3_16x16_body(
     const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
     const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
     float *scale_out, float *scale_inv_out, uint32_t *amax_acc, int64_t block, int64_t n_blocks,
-    const uint32_t *__restrict__ amax_partials = nullptr, int n_partials = 0, float *amax_store = nullptr)
+    const uint32_t *__restrict__ amax_partials = nullptr, int n_partials = 0, float *amax_store = nullptr,
+    InjectArgs inj = InjectArgs{})
 {
     float amax_v;
     if (amax_partials != nullptr) {  // uniform: the maxima of the amax launch's workgroups
@@ -447,6 +526,11 @@ __device__ __forceinline__ void quantize_e4m3_16x16_body(
             const uint4 *src = (const uint4 *)(x + (r0 + half * 8 + i) * cols + c0);
             in[i][0] = src[0];
             in[i][1] = src[1];
+            if constexpr (INJECT != 0) {
+                const uint4 *asrc = (const uint4 *)(inj.act + (r0 + half * 8 + i) * cols + c0);
+                in[i][0] = inject_vec<(INJECT == 4 ? 4 : 0)>(in[i][0], asrc[0], inj);
+                in[i][1] = inject_vec<(INJECT == 4 ? 4 : 0)>(in[i][1], asrc[1], inj);
+            }
             if constexpr (DELAYED)
                 mx = pk_absmax4(pk_absmax4(mx, in[i][0]), in[i][1]);
         }
@@ -494,6 +578,17 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_16x16_kernel(
     quantize_e4m3_16x16_body<WITH_T, DELAYED, E5M2>(x, rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out,
                                               amax_acc, blockIdx.x, gridDim.x, amax_partials, n_partials,
                                               amax_store);
+}
+
+template <bool E5M2, int INJECT>
+__global__ __launch_bounds__(kQuantThreads) void quantize_inject_16x16_kernel(
+    const uint16_t *__restrict__ dy, InjectArgs inj, int64_t rows, int64_t cols, int64_t tiles_x,
+    uint8_t *__restrict__ q, uint8_t *__restrict__ qT, float *scale_out, float *scale_inv_out,
+    const uint32_t *__restrict__ amax_partials, int n_partials, float *amax_store)
+{
+    quantize_e4m3_16x16_body<true, false, E5M2, INJECT>(dy, rows, cols, tiles_x, amax_store, q, qT, scale_out,
+                                                      scale_inv_out, nullptr, blockIdx.x, gridDim.x, amax_partials,
+                                                      n_partials, amax_store, inj);
 }
 
 // Two tensors in one launch (activation and weight of a linear layer, each with its transposed
@@ -603,6 +698,49 @@ hipError_t launch_quantize_f8_from_partials(const void *x_bf16, int64_t rows, in
                                                       nullptr, s, amax_partials, n_partials, amax_out);
     return launch_quantize_e4m3_impl<false, false>(x_bf16, rows, cols, amax_out, q, qT, scale_out, scale_inv_out,
                                                    nullptr, s, amax_partials, n_partials, amax_out);
+}
+
+// amax and cast of dy' = bf16(dy + coef * sign(a) * (|a| * inv_tau)^(p-1)) without storing dy':
+// the amax launch leaves workgroup maxima, the cast launch reduces them (rows, cols multiples of 16).
+hipError_t launch_amax_quantize_inject(const void *dy_bf16, const void *a_bf16, int64_t rows, int64_t cols,
+                                       float inv_tau, float coef, int p, bool e5m2, uint32_t *partials,
+                                       float *amax_out, uint8_t *q, uint8_t *qT, float *scale_out,
+                                       float *scale_inv_out, hipStream_t s)
+{
+    const InjectArgs inj{(const uint16_t *)a_bf16, inv_tau, coef, p};
+    const int64_t n_vec = rows * cols / 8;
+    int64_t blocks = n_vec / (kAmaxUnroll * kAmaxThreads);
+    if (blocks < 1)
+        blocks = 1;
+    if (blocks > amax_cus())
+        blocks = amax_cus();
+    if (p == 4)
+        hipLaunchKernelGGL(amax_inject_kernel<4>, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, s,
+                           (const uint4 *)dy_bf16, inj, n_vec, (n_vec + blocks - 1) / blocks, partials);
+    else
+        hipLaunchKernelGGL(amax_inject_kernel<0>, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, s,
+                           (const uint4 *)dy_bf16, inj, n_vec, (n_vec + blocks - 1) / blocks, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return e;
+    const int64_t tiles_x = (cols + kQuantBigTile - 1) / kQuantBigTile, tiles_y = (rows + kQuantBigTile - 1) / kQuantBigTile;
+    const dim3 grid((unsigned)(tiles_x * tiles_y)), block(kQuantThreads);
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, block, 0, s, (const uint16_t *)dy_bf16, inj, rows, cols, tiles_x, q, qT,
+                           scale_out, scale_inv_out, (const uint32_t *)partials, (int)blocks, amax_out);
+    };
+    if (e5m2) {
+        if (p == 4)
+            launch(quantize_inject_16x16_kernel<true, 4>);
+        else
+            launch(quantize_inject_16x16_kernel<true, 1>);
+    } else {
+        if (p == 4)
+            launch(quantize_inject_16x16_kernel<false, 4>);
+        else
+            launch(quantize_inject_16x16_kernel<false, 1>);
+    }
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
@@ -826,22 +964,6 @@ hipError_t launch_quantize_i8_rows(const void *x_bf16, int64_t rows, int64_t col
 // 6 B/element of HBM traffic (two 2-byte reads, one 2-byte write); fp32
 // arithmetic, the power by repeated multiplication (p is a small integer).
 constexpr int kInjectThreads = 256;
-
-template <int P>
-__device__ __forceinline__ float inject_one(float dy, float a, float inv_tau, float coef, int p)
-{
-    const float u = __builtin_fabsf(a) * inv_tau;
-    float w = 1.0f;
-    if constexpr (P == 4) {
-        w = u * u * u;
-    } else {
-        for (int e = 1; e < p; ++e)
-            w *= u;
-    }
-    const float t = coef * w;
-    // sign(a) = 0 for a = 0; a NaN activation poisons the gradient, as it should
-    return dy + (a > 0.0f ? t : (a < 0.0f ? -t : (a == 0.0f ? 0.0f : a)));
-}
 
 template <int P>
 __global__ __launch_bounds__(kInjectThreads) void penalty_grad_inject_kernel(

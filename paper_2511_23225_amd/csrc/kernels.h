@@ -54,6 +54,12 @@ hipError_t launch_quantize_i8_rows(const void *x_bf16, int64_t rows, int64_t col
 hipError_t launch_penalty_finish(const float *partials, int n, double *out, hipStream_t s);
 hipError_t launch_penalty_grad_inject(const void *dy_bf16, const void *a_bf16, int64_t n, float inv_tau,
                                       float coef, int p, void *out_bf16, hipStream_t s);
+// the injection fused into the gradient's amax and cast launches (rows, cols multiples of 16;
+// partials: kAmaxPartialsMax words of scratch)
+hipError_t launch_amax_quantize_inject(const void *dy_bf16, const void *a_bf16, int64_t rows, int64_t cols,
+                                       float inv_tau, float coef, int p, bool e5m2, uint32_t *partials,
+                                       float *amax_out, uint8_t *q, uint8_t *qT, float *scale_out,
+                                       float *scale_inv_out, hipStream_t s);
 
 // C[M,N] = A[M,K] * B[N,K]^T on 8-bit operands, both K-contiguous.
 struct GemmArgs {

@@ -171,3 +171,58 @@ def test_delayed_scaling_sequence_e5m2(shape):
         assert st[tw.DELAYED_USED_SCALE].view(np.uint32) == np.float32(used).view(np.uint32), step
         assert st[tw.DELAYED_USED_SCALE_INV].view(np.uint32) == np.float32(used_inv).view(np.uint32), step
         assert st[tw.DELAYED_NEXT_SCALE].view(np.uint32) == np.float32(ref.next_scale).view(np.uint32), step
+
+
+@pytest.mark.parametrize("pen", [(3.0, 1e-6, 4), (2.0, 0.0, 3)])
+@pytest.mark.parametrize("e5m2", [False, True])
+def test_backward_with_fused_penalty_gradient_injection(e5m2, pen):
+    # the injection as a prologue of the gradient's amax and cast: every downstream bit equals what
+    # the stand-alone injection kernel followed by the plain backward call gives, and the codes
+    # equal the oracle's (injection -> bf16 -> amax -> cast)
+    cfg, gi, M, K, N = 0, 0, 256, 512, 512
+    say("fused injection e5m2=%s pen=%s" % (e5m2, pen))
+    x, w, dy = synth.fp8_linear_inputs(cfg, gi)
+    u8 = lambda *s: torch.empty(s, dtype=torch.uint8, device=DEV)
+    bf = lambda *s: torch.full(s, float("nan"), dtype=torch.bfloat16, device=DEV)
+    g = 0.37 / (M * N)
+    results = []
+    for fused in (True, False):
+        xq, xqT, wq, wqT, dyq, dyqT = u8(M, K), u8(K, M), u8(N, K), u8(K, N), u8(M, N), u8(N, M)
+        sc = torch.zeros(16, dtype=torch.float32, device=DEV)
+        saved = tw.make_saved(xq, xqT, wq, wqT, sc)
+        y, dx, dw = bf(M, N), bf(M, K), bf(N, K)
+        ws = torch.empty(max(tw.tweo_workspace_bytes(op, M, N, K) for op in
+                             (tw.TWEO_OP_FP8_LINEAR_FWD_BF16, tw.TWEO_OP_FP8_LINEAR_BWD_BF16)),
+                         dtype=torch.uint8, device=DEV)
+        tw.tweo_fp8_linear_fwd_bf16(to_dev_bf16(x), to_dev_bf16(w), y, saved, workspace=ws)
+        dyd = to_dev_bf16(dy)
+        if fused:
+            tw.tweo_fp8_linear_bwd_bf16_inject(dyd, y, pen, g, saved, K, dyq, dyqT, dx, dw, ws, dy_e5m2=e5m2)
+        else:
+            dy2 = torch.empty_like(dyd)
+            tw.tweo_penalty_grad_inject(dyd, y, pen, g, dy2)
+            (tw.tweo_fp8_linear_bwd_bf16_hybrid if e5m2 else tw.tweo_fp8_linear_bwd_bf16)(
+                dy2, saved, K, dyq, dyqT, dx, dw, ws)
+        torch.cuda.synchronize()
+        results.append([t.clone() for t in (dyq, dyqT, sc, dx.view(torch.int16), dw.view(torch.int16))])
+        y_bits = bf16_bits(y)
+    for a, b in zip(*results):
+        assert torch.equal(a, b)
+    # against the oracle (fp64 injection): the GPU forms the gradient in fp32, so a value that sits at a
+    # bf16 rounding boundary may come out one ulp apart (tests of the stand-alone kernel); hence the
+    # amax within one bf16 ulp, and, when it is the same, the same codes on all but the odd element
+    dy2_ref, _ = oracle.penalty_grad_inject(dy, y_bits, pen[0], pen[1], pen[2], g)
+    amax = oracle.amax_bf16(dy2_ref)
+    dyq, dyqT, sc = results[0][0], results[0][1], results[0][2].cpu().numpy()
+    got_amax_bits = int(sc[6:7].view(np.uint32)[0])
+    assert abs(got_amax_bits - int(np.float32(amax).view(np.uint32))) <= 1 << 16
+    if sc[6] == amax:
+        if e5m2:
+            s_ref, si_ref = oracle.scale_from_amax_e5m2(amax)
+            q_ref, qT_ref = oracle.quantize_e5m2(dy2_ref, s_ref)
+        else:
+            s_ref, si_ref = oracle.scale_from_amax(amax)
+            q_ref, qT_ref = oracle.quantize_e4m3(dy2_ref, s_ref)
+        assert sc[7] == s_ref and sc[8] == si_ref
+        assert np.mean(dyq.cpu().numpy() == q_ref) > 0.99 and np.mean(dyqT.cpu().numpy() == qT_ref) > 0.99
+        assert np.array_equal(dyqT.cpu().numpy(), dyq.cpu().numpy().T)
