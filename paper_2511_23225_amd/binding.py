@@ -22,7 +22,8 @@ EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quan
            "tweo_set_stream_k", "tweo_penalty_grad_inject", "tweo_delayed_state_bytes",
            "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed", "tweo_profile_gemm_launches",
            "tweo_quantize_e5m2", "tweo_fp8_linear_bwd_hybrid", "tweo_fp8_linear_bwd_bf16_hybrid",
-           "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled", "tweo_w8a8_linear_scaled_i8out", "tweo_quantize_e5m2_delayed", "tweo_fp8_linear_bwd_bf16_inject")
+           "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled", "tweo_w8a8_linear_scaled_i8out",
+           "tweo_quantize_e5m2_delayed", "tweo_fp8_linear_bwd_bf16_inject")
 
 
 class TweoError(RuntimeError):
@@ -256,7 +257,7 @@ def tweo_w8a8_linear_scaled_i8out(xq, wq, x_step, w_step, inv_step_out, yq):
     _check(load().tweo_w8a8_linear_scaled_i8out(_ptr(xq), _ptr(wq), M, N, K, _ptr(x_step),
                                                 1 if x_step.numel() > 1 else 0, _ptr(w_step),
                                                 1 if w_step.numel() > 1 else 0, float(inv_step_out), _ptr(yq),
-                                                _stream()), "tweo_w8a8_linear_scaled_i8out", "tweo_quantize_e5m2_delayed", "tweo_fp8_linear_bwd_bf16_inject")
+                                                _stream()), "tweo_w8a8_linear_scaled_i8out")
 
 
 def make_saved(xq, xqT, wq, wqT, scalars):
