@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the per-tensor FP8 linear hot path (fwd + bwd, fused TWEO penalty) on one MI355X.
 
-A step = one pass over every linear layer of the workload's Transformer block, each from its
+A step = one pass over every linear layer of the workload's Transformer block (all forwards, then
+the backwards in reverse order, as a training step runs them), each from its
 bf16 operands: amax(X), amax(W), E4M3 casts (+ transposes), FP8 forward GEMM with the penalty
 epilogue, amax(dY), cast of dY, dgrad GEMM, wgrad GEMM.  Inputs are synthetic (seeded), resident
 in HBM before the timed region.  Prints ONE JSON line.
@@ -61,10 +62,12 @@ def run_step(tw, layers, ev=None):
     """The whole path through the two bf16 entry points: amax and casts of X and W, forward GEMM
     with the penalty epilogue and its finishing sum; amax and cast of dY, dgrad and wgrad GEMMs.
     `ev`: the three GEMM kernels of every layer record their own start and end events."""
+    # the order of a training step: every forward, then the backwards from the last layer down
     for L in layers:
         if ev is not None:
             ev.arm(1, 2.0 * L.M * L.N * L.K)
         tw.tweo_fp8_linear_fwd_bf16(L.x, L.w, L.y, L.saved, pen=PEN, penalty_sum=L.S, workspace=L.ws)
+    for L in reversed(layers):
         if ev is not None:
             ev.arm(2, 2.0 * L.M * L.N * L.K)
         tw.tweo_fp8_linear_bwd_bf16(L.dy, L.saved, L.K, L.dyq, L.dyqT, L.dx, L.dw, L.ws)
@@ -381,8 +384,12 @@ def main():
     for li, L in enumerate(layers):
         fl = 2.0 * L.M * L.N * L.K
         parts = []
-        for k, name in enumerate(("fwd", "dgrad", "wgrad")):
-            d = [dur[j] for j in range(len(dur)) if j % per_step == 3 * li + k]
+        nl = len(layers)
+        # order of the launches inside a step: the forwards of layers 0..n-1, then (dgrad, wgrad) of
+        # layers n-1..0
+        where = {"fwd": li, "dgrad": nl + 2 * (nl - 1 - li), "wgrad": nl + 2 * (nl - 1 - li) + 1}
+        for name in ("fwd", "dgrad", "wgrad"):
+            d = [dur[j] for j in range(len(dur)) if j % per_step == where[name]]
             parts.append("%s %7.1f us %5.0f TFLOP/s" % (name, 1e3 * sum(d) / len(d), fl / (sum(d) / len(d)) / 1e9))
         log("  %-5s %s" % (L.name, "   ".join(parts)))
     n_gemm_launches = len(dur)
