@@ -86,6 +86,8 @@ def run_step_delayed(tw, layers, bootstrap=False, hybrid=False):
         tw.tweo_quantize_e4m3_delayed(L.w, sw, L.wq, L.wqT, bootstrap=bootstrap)
         tw.tweo_fp8_linear_fwd(L.xq, sx[inv:inv + 1], L.wq, sw[inv:inv + 1], L.y, pen=PEN, penalty_sum=L.S,
                                workspace=L.ws)
+    for L in reversed(layers):
+        sx, sw, sdy = L.st
         cast_dy(L.dy, sdy, L.dyq, L.dyqT, bootstrap=bootstrap)
         bwd(L.dyq, L.dyqT, sdy[inv:inv + 1], L.wqT, sw[inv:inv + 1], L.xqT,
             sx[inv:inv + 1], L.M, L.N, L.K, L.dx, L.dw, L.ws)
