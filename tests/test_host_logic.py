@@ -72,3 +72,14 @@ def test_argument_checks_return_before_any_launch():
     assert L.tweo_set_gemm_tile(99) == INV and L.tweo_set_gemm_tile(0) == tw.TWEO_OK
     for code in range(5):
         assert tw.status_string(code)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
