@@ -157,3 +157,39 @@ def test_full_size_w8a8(gi, M):
         rs = rows_sample(M, 48, gi)
         want = oracle.w8a8_linear(np.ascontiguousarray(oxq[rs]), owq, alpha)
         assert np.array_equal(bf16_bits(y[torch.from_numpy(rs).to(DEV)]), want)
+
+
+@pytest.mark.parametrize("M", [16, 64, 4096])
+@pytest.mark.parametrize("gi", [0, 3])  # qkv 4096 -> 12288 and down 11008 -> 4096
+def test_full_size_w8a8_finer_granularities(gi, M):
+    # W8(C)A8(K) at the 7B shapes: per-token quantisation on the GPU (all bytes and steps compared),
+    # per-channel weights, bf16 and INT8 outputs (all rows for M <= 64, sampled rows for M = 4096)
+    g = synth.CONFIGS[4]["gemms"][gi]
+    K, N = g.K, g.N
+    say("full size w8a8 W(C)A(K) %s M=%d K=%d N=%d" % (g.name, M, K, N))
+    x, w = synth.w8a8_inputs(gi, M)
+    xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
+    wq = torch.empty((N, K), dtype=torch.int8, device=DEV)
+    sx = torch.empty((M,), dtype=torch.float32, device=DEV)
+    sw = torch.empty((N,), dtype=torch.float32, device=DEV)
+    tw.tweo_quantize_i8_rows(to_dev_bf16(x), 1e-6, xq, sx)
+    tw.tweo_quantize_i8_rows(to_dev_bf16(w), 1e-6, wq, sw)
+    oxq, osx = oracle.quantize_i8_rows(x, 1e-6)
+    owq, osw = oracle.quantize_i8_rows(w, 1e-6)
+    assert np.array_equal(xq.cpu().numpy(), oxq) and np.array_equal(wq.cpu().numpy(), owq)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), osx.view(np.uint32))
+    assert np.array_equal(sw.cpu().numpy().view(np.uint32), osw.view(np.uint32))
+    y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+    yq = torch.full((M, N), 99, dtype=torch.int8, device=DEV)
+    inv_out = np.float32(127.0) / np.float32(2.0)  # a static output step that clips the tails
+    tw.tweo_w8a8_linear_scaled(xq, wq, sx, sw, y)
+    tw.tweo_w8a8_linear_scaled_i8out(xq, wq, sx, sw, inv_out, yq)
+    torch.cuda.synchronize()
+    rs = np.arange(M) if M <= 64 else rows_sample(M, 48, gi)
+    sel = torch.from_numpy(rs).to(DEV)
+    want = oracle.w8a8_linear_scaled(np.ascontiguousarray(oxq[rs]), owq, np.ascontiguousarray(osx[rs]), osw)
+    want_q = oracle.w8a8_linear_scaled_i8out(np.ascontiguousarray(oxq[rs]), owq, np.ascontiguousarray(osx[rs]), osw,
+                                             inv_out)
+    assert np.array_equal(bf16_bits(y[sel]), want)
+    assert np.array_equal(yq[sel].cpu().numpy(), want_q)
+    assert 0 < np.mean(np.abs(want_q) == 127) < 0.5  # some saturate, most do not
