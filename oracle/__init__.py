@@ -51,6 +51,8 @@ def lib():
         L.orc_amax_bf16.restype = ctypes.c_float
         L.orc_penalty_sum.restype = ctypes.c_double
         L.orc_num_threads.restype = ctypes.c_int
+        L.orc_f64_to_bf16.restype = ctypes.c_uint16
+        L.orc_f64_to_bf16.argtypes = [ctypes.c_double]
         _lib = L
     return _lib
 
@@ -324,3 +326,31 @@ def w8a8_linear_scaled_i8out(xq, wq, sx, sw, inv_step_out):
                                        _i64(0 if sx.size == 1 else 1), _p(sw, _f32),
                                        _i64(0 if sw.size == 1 else 1), _f32(float(inv_step_out)), _p(yq, _i8))
     return yq
+
+
+def f64_to_bf16_scalar(v):
+    return int(lib().orc_f64_to_bf16(ctypes.c_double(float(v))))
+
+
+def residual_add_bf16(x, r):
+    """h = bf16(x + r): the residual-stream update in front of a normalisation."""
+    x, r = _c(x, np.uint16), _c(r, np.uint16)
+    assert x.shape == r.shape
+    h = np.empty(x.shape, np.uint16)
+    lib().orc_residual_add_bf16(_p(x, _u16), _p(r, _u16), _i64(x.size), _p(h, _u16))
+    return h
+
+
+def layernorm(h, gamma, beta=None, eps=1e-5):
+    """Row-wise LayerNorm in fp64 (Sec. 4.3: LayerNorm runs under FP8 too): (y64, y_bf16)."""
+    h, gamma = _c(h, np.uint16), _c(gamma, np.uint16)
+    rows, cols = h.shape
+    assert gamma.shape == (cols,)
+    if beta is not None:
+        beta = _c(beta, np.uint16)
+        assert beta.shape == (cols,)
+    y64 = np.empty((rows, cols), np.float64)
+    yb = np.empty((rows, cols), np.uint16)
+    lib().orc_layernorm(_p(h, _u16), _p(gamma, _u16), _p(beta, _u16), _i64(rows), _i64(cols),
+                        _f64(float(eps)), _p(y64, _f64), _p(yb, _u16))
+    return y64, yb

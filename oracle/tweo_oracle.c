@@ -23,7 +23,9 @@
  * matmul by a library, adjoint identities between fwd/dgrad/wgrad, AbsMax
  * end points +-Q_8 (Sec. 4.4); for the row-granular INT8 functions exact
  * rationals, row independence, power-of-two steps and a library matmul
- * (tests/test_oracle_int8_rows.py).  No function here is "parity unpinned"; the
+ * (tests/test_oracle_int8_rows.py); for LayerNorm closed forms (constant and
+ * two-valued rows), invariances, exact rationals and a library layer norm in
+ * fp64 (tests/test_oracle_layernorm.py).  No function here is "parity unpinned"; the
  * conventions the paper leaves open (NaN handling, zero amax, rounding mode of
  * "round") are listed where they are taken.
  */
@@ -612,6 +614,89 @@ void orc_w8a8_linear_scaled_i8out(const int8_t *xq, const int8_t *wq, int64_t M,
                 v = (int)r;
             yq[m * N + n] = (int8_t)v;
         }
+}
+
+/* ------------------------------------------------- LayerNorm under FP8 */
+
+/*
+ * binary64 -> bf16 in ONE rounding (to nearest, ties to even), so that a value
+ * computed in fp64 is not rounded twice on its way to bf16.  The bf16 grid in
+ * the binade [2^E, 2^(E+1)) has spacing 2^(E-7); below the smallest normal
+ * 2^-126 the spacing stays 2^-133.  A result of 2^128 or more is +-Inf.
+ */
+uint16_t orc_f64_to_bf16(double v)
+{
+    if (isnan(v))
+        return 0x7FC0;
+    uint16_t sign = signbit(v) ? 0x8000 : 0;
+    double a = fabs(v);
+    if (a == 0.0)
+        return sign;
+    if (isinf(a))
+        return sign | 0x7F80;
+    int ex;
+    (void)frexp(a, &ex);
+    int E = ex - 1; /* floor(log2 a) */
+    if (E < -126)
+        E = -126;
+    double r = nearbyint(ldexp(a, 7 - E)); /* 128..256 in a normal binade, 0..128 below */
+    if (E > 127 || (E == 127 && r >= 256.0))
+        return sign | 0x7F80;
+    /* first pattern of binade E is (E+127)<<7 and corresponds to r = 128; a carry to r = 256
+     * lands on the next binade's first pattern by the same formula */
+    uint32_t pattern = (uint32_t)((E + 126) << 7) + (uint32_t)r;
+    return sign | (uint16_t)pattern;
+}
+
+/*
+ * The residual-stream update in front of a normalisation: h = bf16(x + r).
+ * The sum of two bf16 values is exact in fp64; it is rounded to bf16 once.
+ */
+void orc_residual_add_bf16(const uint16_t *x, const uint16_t *r, int64_t n, uint16_t *h)
+{
+    for (int64_t i = 0; i < n; ++i)
+        h[i] = orc_f64_to_bf16((double)orc_bf16_to_f32(x[i]) + (double)orc_bf16_to_f32(r[i]));
+}
+
+/*
+ * LayerNorm of each row of h[rows, cols] (Sec. 4.3: the paper runs the
+ * LayerNorm components under FP8 as well, i.e. the normalised activation is
+ * what the per-tensor cast of the next linear layer consumes).  The paper gives
+ * no formula; the standard definition is taken:
+ *   mu = mean_c h[r,c],  var = mean_c (h[r,c] - mu)^2   (biased),
+ *   y[r,c] = (h[r,c] - mu) / sqrt(var + eps) * gamma[c] + beta[c],
+ * everything in fp64; gamma, beta are bf16 parameters (beta may be NULL = 0).
+ * y64 receives the fp64 values, y_bf16 their single rounding to bf16 (the
+ * activation as the model stores it and as the FP8 cast reads it).
+ */
+void orc_layernorm(const uint16_t *h, const uint16_t *gamma, const uint16_t *beta, int64_t rows,
+                   int64_t cols, double eps, double *y64, uint16_t *y_bf16)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const uint16_t *hr = h + r * cols;
+        double sum = 0.0;
+        for (int64_t c = 0; c < cols; ++c)
+            sum += (double)orc_bf16_to_f32(hr[c]);
+        double mu = sum / (double)cols;
+        double ss = 0.0;
+        for (int64_t c = 0; c < cols; ++c) {
+            double d = (double)orc_bf16_to_f32(hr[c]) - mu;
+            ss += d * d;
+        }
+        double var = ss / (double)cols;
+        double rstd = 1.0 / sqrt(var + eps);
+        for (int64_t c = 0; c < cols; ++c) {
+            double d = (double)orc_bf16_to_f32(hr[c]) - mu;
+            double y = d * rstd * (double)orc_bf16_to_f32(gamma[c]);
+            if (beta)
+                y += (double)orc_bf16_to_f32(beta[c]);
+            if (y64)
+                y64[r * cols + c] = y;
+            if (y_bf16)
+                y_bf16[r * cols + c] = orc_f64_to_bf16(y);
+        }
+    }
 }
 
 int orc_num_threads(void)
