@@ -119,57 +119,92 @@ class GemmEvents:
         return [s.elapsed_time(e) for s, e in self.pairs]
 
 
-def time_elementwise(tw, torch, L, iters=20):
-    """GB/s of the amax and quantize passes on this layer's largest activation (algorithmic bytes)."""
+def time_elementwise(tw, torch, L, peers, iters=20):
+    """GB/s of the amax and quantize passes on this layer's largest activation (algorithmic bytes).
+    warm: the same tensor again and again (184 MB: it stays in the 256 MB memory-side cache, so
+    this is NOT an HBM figure).  cold: the passes rotate over `peers` + this tensor, at least
+    four distinct tensors of the same shape whose total is several times the cache, with
+    output buffers rotating too, so that every byte comes from / goes to HBM."""
     out = {}
     n = L.M * L.K
-    for name, fn, bytes_per_elt in (
-            ("amax", lambda: tw.tweo_amax(L.x, L.sc[0:1]), 2.0),
-            ("quantize_e4m3_T", lambda: tw.tweo_quantize_e4m3(L.x, L.sc[0:1], L.xq, L.xqT), 4.0),
-            ("quantize_e4m3", lambda: tw.tweo_quantize_e4m3(L.x, L.sc[0:1], L.xq, None), 3.0)):
-        for _ in range(3):
-            fn()
-        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        s.record()
-        for _ in range(iters):
-            fn()
-        e.record()
-        torch.cuda.synchronize()
-        ms = s.elapsed_time(e) / iters
-        out[name] = {"GB/s": round(n * bytes_per_elt / ms / 1e6, 1), "us": round(ms * 1e3, 2),
-                     "MB": round(n * bytes_per_elt / 1e6, 1)}
+    xs = [L.x] + peers
+    assert len(xs) >= 3 and all(t.numel() == n for t in xs)
+    qs = [torch.empty((L.M, L.K), dtype=torch.uint8, device=L.x.device) for _ in xs]
+    qTs = [torch.empty((L.K, L.M), dtype=torch.uint8, device=L.x.device) for _ in xs]
+    xs = [t.view(L.M, L.K) for t in xs]
+    am = torch.zeros(4 * len(xs), dtype=torch.float32, device=L.x.device)
+    for i, t in enumerate(xs):
+        tw.tweo_amax(t, am[4 * i:4 * i + 1])
+    passes = (
+        ("amax", lambda i: tw.tweo_amax(xs[i], am[4 * i:4 * i + 1]), 2.0),
+        ("quantize_e4m3_T", lambda i: tw.tweo_quantize_e4m3(xs[i], am[4 * i:4 * i + 1], qs[i], qTs[i]), 4.0),
+        ("quantize_e4m3", lambda i: tw.tweo_quantize_e4m3(xs[i], am[4 * i:4 * i + 1], qs[i], None), 3.0))
+    for name, fn, bytes_per_elt in passes:
+        res = {"MB": round(n * bytes_per_elt / 1e6, 1)}
+        for mode, pick in (("warm", lambda k: 0), ("cold", lambda k: k % len(xs))):
+            for k in range(len(xs)):
+                fn(pick(k))
+            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s.record()
+            for k in range(iters):
+                fn(pick(k))
+            e.record()
+            torch.cuda.synchronize()
+            ms = s.elapsed_time(e) / iters
+            res[mode] = {"GB/s": round(n * bytes_per_elt / ms / 1e6, 1), "us": round(ms * 1e3, 2),
+                         "frac_of_hbm_peak": round(n * bytes_per_elt / ms / 1e6 / HBM_PEAK_GBS, 3)}
+        out[name] = res
+    out["note"] = "cold = rotation over %d distinct %.0f MB tensors (HBM); warm = one tensor (memory-side cache)" % (
+        len(xs), n * 2 / 1e6)
     return out
 
 
 def time_penalty_cost(tw, torch, L, reps=24):
-    """What the fused penalty epilogue (Sec. 3.3) costs: the forward GEMM kernel of one layer on its
-    already quantised operands with and without the penalty, alternating, kernel start-to-end
-    events, medians."""
+    """What the fused penalty (Sec. 3.3) costs on one layer's forward GEMM, operands already
+    quantised, with and without, alternating, medians.  Two clocks: the GEMM kernel's own
+    start-to-end events (the epilogue arithmetic only), and stream events around batches of
+    calls (everything the penalty adds: the epilogue and the finishing launch)."""
     inv = lambda i: L.sc[i:i + 1]
+
+    def call(with_pen):
+        if with_pen:
+            tw.tweo_fp8_linear_fwd(L.xq, inv(2), L.wq, inv(5), L.y, pen=PEN, penalty_sum=L.S, workspace=L.ws)
+        else:
+            tw.tweo_fp8_linear_fwd(L.xq, inv(2), L.wq, inv(5), L.y, workspace=L.ws)
+
     t = {True: [], False: []}
+    tc = {True: [], False: []}
     for _ in range(reps // 8):
         for with_pen in (True, False, False, True):
             ev = GemmEvents(torch, tw)
             ev.arm(2, 0.0)
             for _ in range(2):
-                if with_pen:
-                    tw.tweo_fp8_linear_fwd(L.xq, inv(2), L.wq, inv(5), L.y, pen=PEN, penalty_sum=L.S,
-                                           workspace=L.ws)
-                else:
-                    tw.tweo_fp8_linear_fwd(L.xq, inv(2), L.wq, inv(5), L.y, workspace=L.ws)
+                call(with_pen)
             torch.cuda.synchronize()
             t[with_pen] += ev.durations_ms()
+            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s.record()
+            for _ in range(8):
+                call(with_pen)
+            e.record()
+            torch.cuda.synchronize()
+            tc[with_pen].append(s.elapsed_time(e) / 8)
     med = lambda v: sorted(v)[len(v) // 2] * 1e3
-    return {"layer": "%s %dx%dx%d" % (L.name, L.M, L.K, L.N), "fwd_with_penalty_us": round(med(t[True]), 2),
-            "fwd_without_us": round(med(t[False]), 2)}
+    return {"layer": "%s %dx%dx%d" % (L.name, L.M, L.K, L.N),
+            "gemm_kernel_with_penalty_us": round(med(t[True]), 2), "gemm_kernel_without_us": round(med(t[False]), 2),
+            "call_with_penalty_us": round(med(tc[True]), 2), "call_without_us": round(med(tc[False]), 2),
+            "note": "call_* = back-to-back calls timed by stream events, finishing launch of the penalty included"}
 
 
-def time_w8a8(tw, torch, synth, dev, iters=20):
-    """W8A8 INT8 inference GEMM at the 7B qkv shape (K=4096, N=12288) for M in {1,16,64,4096}, on
-    the workload's own statistics (N(0,1) activations clipped at 20, N(0,0.02) weights, per-tensor
-    static steps amax/127): what the codes look like decides the clock the matrix pipe sustains."""
+def time_w8a8(tw, torch, synth, dev, iters=20, copies=8):
+    """W8A8 INT8 inference GEMMs at the 7B shapes (Sec. 4.4): qkv 4096->12288, gate and up
+    4096->11008, down 11008->4096, for M in {1, 16, 64, 4096}, on the workload's own statistics
+    (N(0,1) activations clipped at 20, N(0,0.02) weights, per-tensor static steps amax/127).
+    M <= 64 is bound by streaming the weights: a decode step reads each layer's weights once, so
+    the figure that counts is COLD - the call rotates over `copies` distinct weight matrices
+    (row-rotated copies of the quantised weights, 360-400 MB in total against 256 MB of
+    memory-side cache); the warm figure (one 45-50 MB matrix, cache resident) is printed beside it."""
     res = {}
-    K, N = 4096, 12288
     up = lambda b: torch.from_numpy(b.view("int16")).to(dev).view(torch.bfloat16)
 
     def quant(t):
@@ -178,89 +213,97 @@ def time_w8a8(tw, torch, synth, dev, iters=20):
         tw.tweo_quantize_i8(t, 127.0 / amax, q)
         return q, amax / 127.0
 
-    wq = None
-    for M in (1, 16, 64, 4096):
-        x, w = synth.w8a8_inputs(0, M)
-        if wq is None:
-            wq, step_w = quant(up(w))
-        xq, step_x = quant(up(x))
-        y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
-        ws = torch.empty(tw.tweo_workspace_bytes(tw.TWEO_OP_W8A8_LINEAR, M, N, K), dtype=torch.uint8,
-                         device=dev)
-        fn = lambda: tw.tweo_w8a8_linear(xq, wq, step_x * step_w, y, ws)
-        # the compute-bound shape is timed at the clock the chip settles at under load: it takes
-        # some 20 ms of work to get there from the idle state the small shapes leave behind
-        n_warm = 3 if M <= 64 else 100
-        for _ in range(n_warm):
-            fn()
-        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    def kernel_us(fns):
+        # the kernels' own start-to-end times (events recorded by the launches themselves)
+        d = []
+        for lo in range(0, len(fns), 8):  # as many as the hook holds at a time
+            ev = GemmEvents(torch, tw)
+            ev.arm(len(fns[lo:lo + 8]), 0.0)
+            for fn in fns[lo:lo + 8]:
+                fn()
+            torch.cuda.synchronize()
+            d += ev.durations_ms()
+        d = sorted(d)
+        return d[len(d) // 2] * 1e3
+
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def stream_us(fns, n_warm):
+        for k in range(n_warm):
+            fns[k % len(fns)]()
         s.record()
-        for _ in range(iters):
-            fn()
+        for k in range(iters):
+            fns[k % len(fns)]()
         e.record()
         torch.cuda.synchronize()
-        ms = s.elapsed_time(e) / iters
-        bytes_ = M * K + N * K + 2 * M * N
-        res["M=%d" % M] = {"us": round(ms * 1e3, 2), "TOP/s": round(2.0 * M * N * K / ms / 1e9, 2),
-                           "GB/s": round(bytes_ / ms / 1e6, 1)}
+        return s.elapsed_time(e) / iters * 1e3
 
-        def kernel_us(fn):
-            # the kernel's own start-to-end time (events recorded by the launch itself): the
-            # back-to-back figure above includes what the host needs per call
-            ev = GemmEvents(torch, tw)
-            ev.arm(8, 0.0)  # as many as the hook holds at a time
-            for _ in range(8):
-                fn()
-            torch.cuda.synchronize()
-            d = sorted(ev.durations_ms())
-            return d[len(d) // 2] * 1e3
-
-        ku = kernel_us(fn)
-        res["M=%d" % M]["kernel_us"] = round(ku, 2)
-        res["M=%d" % M]["kernel_GB/s"] = round(bytes_ / ku / 1e3, 1)
-        # the finer granularities of Sec. 4.4 on the same codes: per-token steps found on the fly
-        # (quantise kernel timed with the GEMM), per-channel weight steps
-        xb = up(x)
-        xq2 = torch.empty((M, K), dtype=torch.int8, device=dev)
-        sx = torch.empty((M,), dtype=torch.float32, device=dev)
-        sw = torch.full((N,), step_w, dtype=torch.float32, device=dev)
-
-        def timed(fn):
-            for _ in range(n_warm):
-                fn()
-            s.record()
-            for _ in range(iters):
-                fn()
-            e.record()
-            torch.cuda.synchronize()
-            return s.elapsed_time(e) / iters
-
-        ms_q = timed(lambda: tw.tweo_quantize_i8_rows(xb, 1e-6, xq2, sx))
-        ms_g = timed(lambda: tw.tweo_w8a8_linear_scaled(xq2, wq, sx, sw, y))
-        ku_g = kernel_us(lambda: tw.tweo_w8a8_linear_scaled(xq2, wq, sx, sw, y))
-        # the decode step (per-token quantise + GEMM) as one HIP graph: what the pair costs once
-        # the host's per-call time is out of the way
-        graph_us = None
-        if M <= 64:
-            pair = lambda: (tw.tweo_quantize_i8_rows(xb, 1e-6, xq2, sx), tw.tweo_w8a8_linear_scaled(xq2, wq, sx, sw, y))
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                pair()
-            torch.cuda.current_stream().wait_stream(side)
-            torch.cuda.synchronize()
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=side):
-                for _ in range(10):
-                    pair()
-            graph_us = timed(graph.replay) * 1e3 / 10
-        res["M=%d" % M]["W(C)A(K)"] = {"quantize_rows_us": round(ms_q * 1e3, 2),
-                                       "quantize_rows_GB/s": round(3.0 * M * K / ms_q / 1e6, 1),
-                                       "gemm_us": round(ms_g * 1e3, 2),
-                                       "gemm_TOP/s": round(2.0 * M * N * K / ms_g / 1e9, 2),
-                                       "gemm_GB/s": round((bytes_ + 4 * (M + N)) / ms_g / 1e6, 1),
-                                       "gemm_kernel_us": round(ku_g, 2),
-                                       "quantize_plus_gemm_in_graph_us": None if graph_us is None else round(graph_us, 2)}
+    for gi, g in enumerate(synth.CONFIGS[4]["gemms"]):
+        K, N = g.K, g.N
+        shape = {}
+        wqs = None
+        for M in (1, 16, 64, 4096):
+            x, w = synth.w8a8_inputs(gi, M, with_w=wqs is None)
+            if wqs is None:
+                wq, step_w = quant(up(w))
+                wqs = [wq] + [torch.roll(wq, 16 * 37 * (c + 1), 0) for c in range(copies - 1)]
+            xq, step_x = quant(up(x))
+            ys = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in range(copies if M <= 64 else 1)]
+            ws = torch.empty(tw.tweo_workspace_bytes(tw.TWEO_OP_W8A8_LINEAR, M, N, K), dtype=torch.uint8, device=dev)
+            bytes_ = M * K + N * K + 2 * M * N
+            call = lambda c: (lambda: tw.tweo_w8a8_linear(xq, wqs[c], step_x * step_w, ys[c % len(ys)], ws))
+            r = {}
+            if M <= 64:
+                warm, cold = [call(0)] * 8, [call(c) for c in range(copies)]
+                stream_us(cold, copies)
+                r["cold_kernel_us"] = round(kernel_us(cold + cold), 2)
+                r["cold_GB/s"] = round(bytes_ / r["cold_kernel_us"] / 1e3, 1)
+                r["cold_frac_of_hbm_peak"] = round(r["cold_GB/s"] / HBM_PEAK_GBS, 3)
+                r["cold_call_us"] = round(stream_us(cold, copies), 2)
+                stream_us(warm, 3)
+                r["warm_kernel_us"] = round(kernel_us(warm), 2)
+                r["warm_GB/s"] = round(bytes_ / r["warm_kernel_us"] / 1e3, 1)
+            else:
+                # the compute-bound shape is timed at the clock the chip settles at under load: it
+                # takes some 20 ms of work to get there from the idle state the small shapes leave
+                us = stream_us([call(0)], 100)
+                r["us"] = round(us, 2)
+                r["TOP/s"] = round(2.0 * M * N * K / us / 1e6, 2)
+                r["frac_of_int8_peak"] = round(2.0 * M * N * K / us / 1e6 / INT8_PEAK_TOPS, 3)
+            shape["M=%d" % M] = r
+            if gi == 0:
+                # the finer granularities of Sec. 4.4 on the same codes: per-token steps found on the
+                # fly (quantise kernel timed with the GEMM), per-channel weight steps
+                xb = up(x)
+                xq2 = torch.empty((M, K), dtype=torch.int8, device=dev)
+                sx = torch.empty((M,), dtype=torch.float32, device=dev)
+                sw = torch.full((N,), step_w, dtype=torch.float32, device=dev)
+                n_warm = 3 if M <= 64 else 50
+                us_q = stream_us([lambda: tw.tweo_quantize_i8_rows(xb, 1e-6, xq2, sx)], n_warm)
+                gemm = [(lambda c: (lambda: tw.tweo_w8a8_linear_scaled(xq2, wqs[c], sx, sw, ys[c % len(ys)])))(c)
+                        for c in range(copies if M <= 64 else 1)]
+                us_g = stream_us(gemm, n_warm)
+                fine = {"quantize_rows_us": round(us_q, 2), "gemm_call_us_cold": round(us_g, 2),
+                        "gemm_kernel_us_cold": round(kernel_us(gemm + gemm), 2)}
+                if M <= 64:
+                    # the decode step (per-token quantise + GEMM) as one HIP graph: what the pair costs
+                    # once the host's per-call time is out of the way (cold weights: the graph
+                    # holds one pair per weight copy)
+                    pairs = lambda: [(tw.tweo_quantize_i8_rows(xb, 1e-6, xq2, sx), f()) for f in gemm]
+                    side = torch.cuda.Stream()
+                    side.wait_stream(torch.cuda.current_stream())
+                    with torch.cuda.stream(side):
+                        pairs()
+                    torch.cuda.current_stream().wait_stream(side)
+                    torch.cuda.synchronize()
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph, stream=side):
+                        pairs()
+                    fine["quantize_plus_gemm_in_graph_us_cold"] = round(stream_us([graph.replay], 2) / len(gemm), 2)
+                r["W(C)A(K)"] = fine
+        res["%s %d->%d" % (g.name, K, N)] = shape
+        del wqs
+        torch.cuda.empty_cache()
     return res
 
 
@@ -316,6 +359,37 @@ def profiled_traffic(workload):
 
 
 EVENT_EVERY = 4
+
+
+def time_workload(tw, torch, synth, cfg, dev, steps, warmup):
+    """ms per step, end-to-end TFLOP/s and GEMM-kernel TFLOP/s of another workload (same step)."""
+    layers = [Layer(tw, torch, synth, cfg, gi, dev) for gi in range(len(synth.CONFIGS[cfg]["gemms"]))]
+    for L in layers:
+        L.host = None
+    flops = sum(L.flops for L in layers)
+    for _ in range(warmup):
+        run_step(tw, layers)
+    torch.cuda.synchronize()
+    ev = GemmEvents(torch, tw)
+    t0 = time.perf_counter()
+    for i in range(steps):
+        run_step(tw, layers, ev if i % EVENT_EVERY == 0 else None)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    # a few more steps timed by stream events: at sub-millisecond steps the host's launch time shows in the wall clock
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
+    for _ in range(steps):
+        run_step(tw, layers)
+    e.record()
+    torch.cuda.synchronize()
+    gemm_ms = sum(ev.durations_ms())
+    return {"workload": synth.CONFIGS[cfg]["name"], "ms_per_step": round(ms, 4),
+            "ms_per_step_stream_events": round(s.elapsed_time(e) / steps, 4),
+            "TFLOP/s": round(flops / ms / 1e9, 2),
+            "gemm_TFLOP/s": round(sum(ev.flops) / gemm_ms / 1e9, 2),
+            "gemm_frac_of_fp8_peak": round(sum(ev.flops) / gemm_ms / 1e9 / FP8_PEAK_TFLOPS, 4),
+            "gemm_launches": len(ev.pairs)}
 
 
 def main():
@@ -412,6 +486,8 @@ def main():
                      "achieved": round(gemm_tflops, 2), "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tflops / FP8_PEAK_TFLOPS, 4),
                      "traffic": profiled_traffic(a.workload) if a.tile == 0 else None,
+                     "traffic_source": "committed rocprofv3 --pmc summary of this command "
+                                       "(profiles/fp8_gemm_llama_block_pmc_traffic.txt), not measured by this run",
                      "algorithmic_bytes_per_launch": round(
                          sum((L.M * L.K + L.N * L.K + 2 * L.M * L.N) + (L.M * L.N + L.N * L.K + 2 * L.M * L.K)
                              + (L.M * L.N + L.M * L.K + 2 * L.N * L.K) for L in layers) / (3.0 * len(layers))),
@@ -452,12 +528,20 @@ def main():
         out["delayed_scaling_hybrid_e5m2_gradients"] = {"ms_per_step": round(ms_h, 4),
                                                         "TFLOP/s": round(step_flops / (ms_h * 1e-3) / 1e12, 2)}
         big = max(layers, key=lambda L: L.M * L.K)
-        out["elementwise"] = time_elementwise(tw, torch, big)
+        peers = [L.y for L in layers if L is not big and L.y.numel() == big.x.numel()]
+        while len(peers) < 3:
+            peers.append(torch.roll(big.x.view(-1), 12345 * (len(peers) + 1)).view_as(big.x))
+        out["elementwise"] = time_elementwise(tw, torch, big, peers)
         out["elementwise"]["peak_GB/s"] = HBM_PEAK_GBS
+        del peers
         out["penalty_cost"] = time_penalty_cost(tw, torch, layers[0])
-        del layers
+        del layers, big
         torch.cuda.empty_cache()
-        out["w8a8_qkv_4096x12288"] = time_w8a8(tw, torch, synth, dev)
+        out["w8a8_7b"] = time_w8a8(tw, torch, synth, dev)
+        out["other_workloads"] = {}
+        for name in ("gpt2", "vit", "single"):
+            if name != a.workload:
+                out["other_workloads"][name] = time_workload(tw, torch, synth, WORKLOADS[name], dev, a.steps, a.warmup)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(synth, cfg, host0)
     print(json.dumps(out), flush=True)

@@ -426,7 +426,8 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
             mx = pk_absmax4(mx, in[i]);
     }
     if constexpr (DELAYED)
-        quant_amax_commit(mx, amax_acc);
+        if (amax_acc != nullptr)  // uniform over the grid
+            quant_amax_commit(mx, amax_acc);
     if (!active)
         return;
     uint32_t lo[8], hi[8];
@@ -563,9 +564,11 @@ __device__ __forceinline__ void quantize_e4m3_16x16_body(
         }
     }
     }
-    // every lane reaches the one workgroup barrier of the amax commit
+    // every lane reaches the one workgroup barrier of the amax commit (amax_acc is uniform over
+    // the grid; nullptr = the caller already has this tensor's amax)
     if constexpr (DELAYED)
-        quant_amax_commit(mx, amax_acc);
+        if (amax_acc != nullptr)
+            quant_amax_commit(mx, amax_acc);
 }
 
 template <bool WITH_T, bool DELAYED, bool E5M2 = false>
@@ -809,8 +812,9 @@ static hipError_t launch_quantize_f8_delayed(const void *x_bf16, int64_t rows, i
         e = hipGetLastError();
         if (e != hipSuccess)
             return e;
+        // the history already holds this tensor's amax: the cast returns none
         return launch_quantize_e4m3_impl<true, E5M2>(x_bf16, rows, cols, st + 21, q, qT, nullptr, nullptr,
-                                                     (uint32_t *)st + 24, s);  // amax goes to a spare word
+                                                     nullptr, s);
     }
     e = launch_quantize_e4m3_impl<true, E5M2>(x_bf16, rows, cols, st + 17, q, qT, nullptr, nullptr,
                                               (uint32_t *)st + 16, s);

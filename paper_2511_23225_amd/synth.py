@@ -129,15 +129,16 @@ def residual_input(cfg, gemm_index, M, N):
     return f32_to_bf16_bits(normal((M, N), 1.0, _rng(cfg, 10 * gemm_index + 7)))
 
 
-def w8a8_inputs(gemm_index, M, K=None, N=None):
-    """bf16 X[M,K] ~ N(0,1) clipped to |x|<20 and bf16 W[N,K] ~ N(0,0.02) for the INT8 config."""
+def w8a8_inputs(gemm_index, M, K=None, N=None, with_w=True):
+    """bf16 X[M,K] ~ N(0,1) clipped to |x|<20 and bf16 W[N,K] ~ N(0,0.02) for the INT8 config
+    (with_w=False: W is None; it does not depend on M, so a caller that has it need not regenerate it)."""
     c = CONFIGS[4]
     g = c["gemms"][gemm_index]
     K, N = K or g.K, N or g.N
     rx, rw = _rng(4, 10 * gemm_index + 100 * (M % 97)), _rng(4, 10 * gemm_index + 1)
     x = np.clip(normal((M, K), 1.0, rx), -c["clip"], c["clip"])
-    w = normal((N, K), 0.02, rw)
-    return f32_to_bf16_bits(x), f32_to_bf16_bits(w)
+    w = normal((N, K), 0.02, rw) if with_w else None
+    return f32_to_bf16_bits(x), (f32_to_bf16_bits(w) if with_w else None)
 
 
 def gemm_flops(M, N, K):

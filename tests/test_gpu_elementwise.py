@@ -173,3 +173,40 @@ def test_delayed_scaling_sequence(shape):
         ring = np.sort(st[:16].view(np.uint32))[::-1][:len(ref.history)]
         want = np.sort(np.array(ref.history, np.float32).view(np.uint32))[::-1]
         assert np.array_equal(ring, want), step
+
+
+def test_delayed_scaling_state_checkpoint_and_restore():
+    # The 32-word state is the only state of the recipe (Sec. 4.3: amax history of length 16).
+    # Copy it to the host in the middle of a 20-step sequence, restore it into a fresh buffer and
+    # continue there: bytes and every state word equal the uninterrupted run and the oracle.
+    rows, cols = 256, 512
+    ref = oracle.DelayedScaling()
+    state = torch.full((tw.DELAYED_STATE_WORDS,), -7.0, dtype=torch.float32, device=DEV)
+    tw.tweo_delayed_state_init(state)
+    resumed = None
+    rng = np.random.default_rng(99)
+    q = torch.empty((rows, cols), dtype=torch.uint8, device=DEV)
+    qT = torch.empty((cols, rows), dtype=torch.uint8, device=DEV)
+    q2, qT2 = torch.empty_like(q), torch.empty_like(qT)
+    for step in range(20):
+        v = (rng.standard_normal((rows, cols)) * (1.0 + 0.3 * step)).astype(np.float32)
+        if step in (5, 12):
+            v[rng.integers(rows), rng.integers(cols)] = 2500.0 * (step - 4)
+        x = synth.f32_to_bf16_bits(v)
+        oq, oqT, used, used_inv = ref.cast(x)
+        tw.tweo_quantize_e4m3_delayed(to_dev_bf16(x), state, q, qT, bootstrap=(step == 0))
+        if resumed is not None:
+            tw.tweo_quantize_e4m3_delayed(to_dev_bf16(x), resumed, q2, qT2, bootstrap=False)
+        torch.cuda.synchronize()
+        assert np.array_equal(q.cpu().numpy(), oq) and np.array_equal(qT.cpu().numpy(), oqT), step
+        if resumed is not None:
+            assert torch.equal(q, q2) and torch.equal(qT, qT2), step
+            assert torch.equal(state.view(torch.int32), resumed.view(torch.int32)), step
+        if step == 9:
+            saved = state.cpu().numpy().copy()                  # the checkpoint: 128 bytes
+            assert saved.nbytes == tw.tweo_delayed_state_bytes()
+            resumed = torch.from_numpy(saved).to(DEV)           # a fresh buffer
+        st = state.cpu().numpy()
+        assert st[tw.DELAYED_USED_SCALE].view(np.uint32) == np.float32(used).view(np.uint32), step
+        assert st[tw.DELAYED_NEXT_SCALE].view(np.uint32) == np.float32(ref.next_scale).view(np.uint32), step
+        assert not st[23:].view(np.uint32).any()                # words beyond the documented ones stay 0
