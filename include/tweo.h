@@ -172,6 +172,28 @@ tweo_status tweo_fp8_linear_fwd(const uint8_t *xq, const float *sx_inv, const ui
                                 void *stream);
 
 /*
+ * tweo_fp8_linear_fwd for callers that cannot allocate device memory and have no
+ * workspace to pass (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): the same forward GEMM with the same fused penalty, the
+ * partial sums kept in a device array inside the library (tweo_static_scratch_bytes()
+ * = 1 MiB per GPU, held until the process ends) instead of a workspace.  Calls no
+ * hipMalloc / hipFree and no allocating routine; the array's device address is
+ * looked up once per device on the first call there.
+ *   Arguments, layouts, results and errors as tweo_fp8_linear_fwd, without the
+ *   workspace.  The results are the same bits.
+ *   Limit: with a penalty, ceil(M/64) * ceil(N/64) * 4 bytes must fit the array
+ *   (M * N up to about 10^9 elements), else TWEO_ERR_UNSUPPORTED.
+ *   Every call on a GPU uses that GPU's one array: calls that overlap in time on
+ *   one GPU (different streams, different threads) race on it.  Nothing in it has
+ *   to start at zero and nothing of an earlier call's contents is read.
+ */
+size_t tweo_static_scratch_bytes(void);
+tweo_status tweo_fp8_linear_fwd_static(const uint8_t *xq, const float *sx_inv, const uint8_t *wq,
+                                       const float *sw_inv, const void *residual_bf16, int64_t M,
+                                       int64_t N, int64_t K, void *y_bf16, const tweo_penalty_cfg *pen,
+                                       double *penalty_sum, void *stream);
+
+/*
  * FP8 linear backward (autograd of the layer above under the same recipe).
  *   dx[m,k] = bf16( (sum_n dec(dyq[m,n]) dec(wq[n,k])) * (*sdy_inv) * (*sw_inv) )
  *   dw[n,k] = bf16( (sum_m dec(dyq[m,n]) dec(xq[m,k])) * (*sdy_inv) * (*sx_inv) )

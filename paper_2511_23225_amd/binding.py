@@ -23,7 +23,8 @@ EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quan
            "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed", "tweo_profile_gemm_launches",
            "tweo_quantize_e5m2", "tweo_fp8_linear_bwd_hybrid", "tweo_fp8_linear_bwd_bf16_hybrid",
            "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled", "tweo_w8a8_linear_scaled_i8out",
-           "tweo_quantize_e5m2_delayed", "tweo_fp8_linear_bwd_bf16_inject")
+           "tweo_quantize_e5m2_delayed", "tweo_fp8_linear_bwd_bf16_inject",
+           "tweo_fp8_linear_fwd_static", "tweo_static_scratch_bytes")
 
 
 class TweoError(RuntimeError):
@@ -64,6 +65,10 @@ def load():
     L.tweo_quantize_e5m2.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp]
     L.tweo_fp8_linear_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp,
                                       ctypes.POINTER(PenaltyCfg), vp, vp, sz, vp]
+    L.tweo_fp8_linear_fwd_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp,
+                                             ctypes.POINTER(PenaltyCfg), vp, vp]
+    L.tweo_static_scratch_bytes.argtypes = []
+    L.tweo_static_scratch_bytes.restype = ctypes.c_size_t
     L.tweo_fp8_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
     L.tweo_fp8_linear_bwd_hybrid.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
     L.tweo_quantize_i8.argtypes = [vp, i64, f32, vp, vp]
@@ -88,7 +93,8 @@ def load():
     L.tweo_quantize_e5m2_delayed.argtypes = [vp, i64, i64, vp, ctypes.c_int, vp, vp, vp]
     L.tweo_penalty_grad_inject.argtypes = [vp, vp, i64, ctypes.POINTER(PenaltyCfg), ctypes.c_float, vp, vp]
     for name in EXPORTS:
-        if name not in ("tweo_workspace_bytes", "tweo_status_string", "tweo_delayed_state_bytes"):
+        if name not in ("tweo_workspace_bytes", "tweo_status_string", "tweo_delayed_state_bytes",
+                        "tweo_static_scratch_bytes"):
             getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -199,6 +205,18 @@ def tweo_fp8_linear_fwd(xq, sx_inv, wq, sw_inv, y_bf16, residual_bf16=None, pen=
     _check(load().tweo_fp8_linear_fwd(_ptr(xq), _ptr(sx_inv), _ptr(wq), _ptr(sw_inv),
                                       _ptr(residual_bf16), M, N, K, _ptr(y_bf16), _pen(pen),
                                       _ptr(penalty_sum), wp, wb, _stream()), "tweo_fp8_linear_fwd")
+
+
+def tweo_static_scratch_bytes():
+    return int(load().tweo_static_scratch_bytes())
+
+
+def tweo_fp8_linear_fwd_static(xq, sx_inv, wq, sw_inv, y_bf16, residual_bf16=None, pen=None, penalty_sum=None):
+    M, K = xq.shape
+    N = wq.shape[0]
+    _check(load().tweo_fp8_linear_fwd_static(_ptr(xq), _ptr(sx_inv), _ptr(wq), _ptr(sw_inv),
+                                             _ptr(residual_bf16), M, N, K, _ptr(y_bf16), _pen(pen),
+                                             _ptr(penalty_sum), _stream()), "tweo_fp8_linear_fwd_static")
 
 
 def tweo_fp8_linear_bwd(dyq, dyqT, sdy_inv, wqT, sw_inv, xqT, sx_inv, M, N, K, dx_bf16=None,

@@ -241,6 +241,60 @@ tweo_status tweo_fp8_linear_fwd(const uint8_t *xq, const float *sx_inv, const ui
     return hip_status(e);
 }
 
+// ---------------------------------------------------------------------------
+// The forward entry point for callers that cannot allocate: the penalty partial sums live in a
+// file-scope device array instead of a caller's workspace.  Each GPU holds its own copy of the
+// array at its own address; the address is looked up once per device (with that device current)
+// and kept.  Host code never uses the array's name for anything but that lookup.
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+tweo_status static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return TWEO_ERR_HIP;
+    void *p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (p == nullptr) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr)
+            return TWEO_ERR_HIP;
+        __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);  // every thread finds the same address
+    }
+    *out = p;
+    return TWEO_OK;
+}
+}  // namespace
+
+size_t tweo_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+tweo_status tweo_fp8_linear_fwd_static(const uint8_t *xq, const float *sx_inv, const uint8_t *wq,
+                                       const float *sw_inv, const void *residual_bf16, int64_t M,
+                                       int64_t N, int64_t K, void *y_bf16, const tweo_penalty_cfg *pen,
+                                       double *penalty_sum, void *stream)
+{
+    if (M <= 0 || N <= 0 || K <= 0)
+        return TWEO_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K))
+        return TWEO_ERR_UNSUPPORTED;
+    // the partial sums of this shape must fit the array (one fp32 per 64x64 block of the output)
+    const size_t need = penalty_bytes(M, N);
+    if (pen != nullptr && penalty_sum != nullptr && need > kStaticScratchBytes)
+        return TWEO_ERR_UNSUPPORTED;
+    void *ws = nullptr;
+    tweo_status st = static_scratch(&ws);
+    if (st != TWEO_OK)
+        return st;
+    // exactly the penalty part: no K-split or stream-K scratch is offered, so the plain schedule
+    // runs.  Every slot the finishing kernel reads is written by this call's GEMM: nothing of a
+    // previous call's contents is used and nothing needs clearing.
+    return tweo_fp8_linear_fwd(xq, sx_inv, wq, sw_inv, residual_bf16, M, N, K, y_bf16, pen, penalty_sum, ws,
+                               need < kStaticScratchBytes ? need : kStaticScratchBytes, stream);
+}
+
 static tweo_status fp8_linear_bwd_impl(const uint8_t *dyq, const uint8_t *dyqT, const float *sdy_inv,
                                        const uint8_t *wqT, const float *sw_inv, const uint8_t *xqT,
                                        const float *sx_inv, int64_t M, int64_t N, int64_t K,
