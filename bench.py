@@ -159,6 +159,49 @@ def time_elementwise(tw, torch, L, peers, iters=20):
     return out
 
 
+def time_layernorm(tw, torch, dev, rows=16384, cols=2048, copies=6, iters=24):
+    """LayerNorm -> E4M3 cast (+ transposed copy) of a residual stream of the workload's shape
+    (Sec. 4.3: LayerNorm runs under FP8 too), cold: the calls rotate over `copies` distinct
+    tensors (6 x 67 MB against 256 MB of memory-side cache).  Algorithmic bytes: 2 read + 1 + 1
+    written per element; beside it the plain amax + cast of the same tensors (the same bytes)."""
+    g = torch.Generator(device=dev)
+    g.manual_seed(7)
+    xs = [(torch.randn((rows, cols), device=dev, generator=g) * 3).to(torch.bfloat16) for _ in range(copies)]
+    gamma = (1 + 0.1 * torch.randn((cols,), device=dev, generator=g)).to(torch.bfloat16)
+    beta = (0.1 * torch.randn((cols,), device=dev, generator=g)).to(torch.bfloat16)
+    qs = [torch.empty((rows, cols), dtype=torch.uint8, device=dev) for _ in range(copies)]
+    qTs = [torch.empty((cols, rows), dtype=torch.uint8, device=dev) for _ in range(copies)]
+    ws = torch.empty(tw.tweo_workspace_bytes(tw.TWEO_OP_LAYERNORM_QUANTIZE, rows, 1, 1), dtype=torch.uint8, device=dev)
+    st = torch.zeros(tw.DELAYED_STATE_WORDS, dtype=torch.float32, device=dev)
+    am = torch.zeros(4, dtype=torch.float32, device=dev)
+    tw.tweo_delayed_state_init(st)
+    tw.tweo_layernorm_quantize_e4m3_delayed(xs[0], gamma, st, qs[0], ws, bootstrap=True, beta_bf16=beta, qT=qTs[0])
+
+    def plain(i):
+        tw.tweo_amax(xs[i], am[0:1])
+        tw.tweo_quantize_e4m3(xs[i], am[0:1], qs[i], qTs[i])
+
+    forms = (("layernorm_cast_current_scaling", lambda i: tw.tweo_layernorm_quantize_e4m3(
+                 xs[i], gamma, qs[i], ws, beta_bf16=beta, qT=qTs[i])),
+             ("layernorm_cast_delayed_scaling", lambda i: tw.tweo_layernorm_quantize_e4m3_delayed(
+                 xs[i], gamma, st, qs[i], ws, beta_bf16=beta, qT=qTs[i])),
+             ("amax_plus_cast_no_layernorm", plain))
+    out = {"tensor": "%dx%d bf16, %d copies" % (rows, cols, copies)}
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for name, fn in forms:
+        for k in range(copies):
+            fn(k)
+        s.record()
+        for k in range(iters):
+            fn(k % copies)
+        e.record()
+        torch.cuda.synchronize()
+        us = s.elapsed_time(e) / iters * 1e3
+        out[name] = {"us": round(us, 2), "GB/s": round(4.0 * rows * cols / us / 1e3, 1),
+                     "frac_of_hbm_peak": round(4.0 * rows * cols / us / 1e3 / HBM_PEAK_GBS, 3)}
+    return out
+
+
 def time_penalty_cost(tw, torch, L, reps=24):
     """What the fused penalty (Sec. 3.3) costs on one layer's forward GEMM, operands already
     quantised, with and without, alternating, medians.  Two clocks: the GEMM kernel's own
@@ -535,6 +578,7 @@ def main():
         out["elementwise"]["peak_GB/s"] = HBM_PEAK_GBS
         del peers
         out["penalty_cost"] = time_penalty_cost(tw, torch, layers[0])
+        out["layernorm"] = time_layernorm(tw, torch, dev)
         del layers, big
         torch.cuda.empty_cache()
         out["w8a8_7b"] = time_w8a8(tw, torch, synth, dev)

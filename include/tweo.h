@@ -52,7 +52,8 @@ enum {
     TWEO_OP_FP8_LINEAR_BWD = 1,
     TWEO_OP_W8A8_LINEAR = 2,
     TWEO_OP_FP8_LINEAR_FWD_BF16 = 3,
-    TWEO_OP_FP8_LINEAR_BWD_BF16 = 4
+    TWEO_OP_FP8_LINEAR_BWD_BF16 = 4,
+    TWEO_OP_LAYERNORM_QUANTIZE = 5 /* M = rows; N, K unused (pass 1) */
 };
 
 /* Bytes of device workspace the given operation can use for these sizes (a
@@ -150,6 +151,53 @@ tweo_status tweo_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t
  * Sec. 4.3): scale = 57344 / max(history), saturation at +-57344, a state of its own. */
 tweo_status tweo_quantize_e5m2_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
                                        int bootstrap, uint8_t *q, uint8_t *qT, void *stream);
+
+/*
+ * LayerNorm feeding the per-tensor FP8 cast (Sec. 4.3: the LayerNorm components
+ * run under FP8 together with the linear layers, so the normalised activation is
+ * what the next linear's cast consumes).  The paper gives no formula; the
+ * textbook row-wise normalisation is taken:
+ *   h[r,c]  = x[r,c]                      or, with a residual, bf16( x[r,c] + residual[r,c] )
+ *   mu_r    = mean_c h[r,c],  var_r = mean_c (h[r,c] - mu_r)^2        (biased)
+ *   y[r,c]  = bf16( (h[r,c] - mu_r) / sqrt(var_r + eps) * gamma[c] + beta[c] )
+ *   q[r,c]  = e4m3( fp32(y[r,c]) * scale ),  qT[c,r] = q[r,c]
+ * The statistics and the normalisation are computed in fp64 and y is rounded once
+ * to bf16: it is the activation as a model stores it, and amax, scale and codes
+ * are those tweo_amax + tweo_quantize_e4m3 give on that bf16 tensor.  The
+ * statistics themselves are never quantised.
+ *   tweo_layernorm_quantize_e4m3: current scaling, scale = 448 / max|y|.
+ *   tweo_layernorm_quantize_e4m3_delayed: delayed scaling on `state` as
+ *   tweo_quantize_e4m3_delayed (the tensor's amax enters the history).
+ *   x_bf16 [rows, cols]; rows % 16 == 0, cols % 16 == 0.
+ *   residual_bf16 [rows, cols] or NULL; with a residual h_out_bf16 [rows, cols]
+ *   is required and receives h (the updated residual stream); it may be x_bf16
+ *   or residual_bf16 themselves (in place).  Without one it is ignored.
+ *   gamma_bf16 [cols]; beta_bf16 [cols] or NULL (= 0); eps >= 0.
+ *   y_out_bf16 [rows, cols] or NULL (the normalised activation, if wanted).
+ *   q [rows, cols]; qT [cols, rows] or NULL; amax_out, scale_out, scale_inv_out:
+ *   one device fp32 each or NULL.
+ *   workspace: tweo_workspace_bytes(TWEO_OP_LAYERNORM_QUANTIZE, rows, 1, 1) bytes,
+ *   16-byte aligned (the row statistics, 16 bytes per row, and 2.3 KB of maxima),
+ *   else TWEO_ERR_WORKSPACE.  After the call it holds (mean, 1/sqrt(var+eps)) as
+ *   two doubles per row from byte 2304 on, which is what a backward pass needs.
+ * HBM traffic: the rows are read once from memory (2 B/element, + 2 + 2 with a
+ * residual); the later passes re-read them from the caches when the tensor fits
+ * there; 1 B/element written per copy of the codes.
+ * Errors: TWEO_ERR_INVALID_ARG (null, misaligned, negative or NaN eps, residual
+ * without h_out), TWEO_ERR_UNSUPPORTED (shape), TWEO_ERR_WORKSPACE.
+ */
+tweo_status tweo_layernorm_quantize_e4m3(const void *x_bf16, const void *residual_bf16,
+                                         const void *gamma_bf16, const void *beta_bf16, int64_t rows,
+                                         int64_t cols, float eps, void *h_out_bf16, void *y_out_bf16,
+                                         float *amax_out, uint8_t *q, uint8_t *qT, float *scale_out,
+                                         float *scale_inv_out, void *workspace, size_t workspace_bytes,
+                                         void *stream);
+tweo_status tweo_layernorm_quantize_e4m3_delayed(const void *x_bf16, const void *residual_bf16,
+                                                 const void *gamma_bf16, const void *beta_bf16,
+                                                 int64_t rows, int64_t cols, float eps, void *state,
+                                                 int bootstrap, void *h_out_bf16, void *y_out_bf16,
+                                                 uint8_t *q, uint8_t *qT, void *workspace,
+                                                 size_t workspace_bytes, void *stream);
 
 /*
  * FP8 linear forward with the TWEO penalty fused into the epilogue

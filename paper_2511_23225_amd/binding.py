@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_PKG, "libtweo_hip.so")
 
 TWEO_OK, TWEO_ERR_INVALID_ARG, TWEO_ERR_UNSUPPORTED, TWEO_ERR_WORKSPACE, TWEO_ERR_HIP = range(5)
 (TWEO_OP_FP8_LINEAR_FWD, TWEO_OP_FP8_LINEAR_BWD, TWEO_OP_W8A8_LINEAR, TWEO_OP_FP8_LINEAR_FWD_BF16,
- TWEO_OP_FP8_LINEAR_BWD_BF16) = range(5)
+ TWEO_OP_FP8_LINEAR_BWD_BF16, TWEO_OP_LAYERNORM_QUANTIZE) = range(6)
 
 EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quantize_e4m3",
            "tweo_fp8_linear_fwd", "tweo_fp8_linear_bwd", "tweo_quantize_i8", "tweo_w8a8_linear",
@@ -24,7 +24,8 @@ EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quan
            "tweo_quantize_e5m2", "tweo_fp8_linear_bwd_hybrid", "tweo_fp8_linear_bwd_bf16_hybrid",
            "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled", "tweo_w8a8_linear_scaled_i8out",
            "tweo_quantize_e5m2_delayed", "tweo_fp8_linear_bwd_bf16_inject",
-           "tweo_fp8_linear_fwd_static", "tweo_static_scratch_bytes")
+           "tweo_fp8_linear_fwd_static", "tweo_static_scratch_bytes",
+           "tweo_layernorm_quantize_e4m3", "tweo_layernorm_quantize_e4m3_delayed")
 
 
 class TweoError(RuntimeError):
@@ -67,6 +68,9 @@ def load():
                                       ctypes.POINTER(PenaltyCfg), vp, vp, sz, vp]
     L.tweo_fp8_linear_fwd_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp,
                                              ctypes.POINTER(PenaltyCfg), vp, vp]
+    L.tweo_layernorm_quantize_e4m3.argtypes = [vp, vp, vp, vp, i64, i64, f32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.tweo_layernorm_quantize_e4m3_delayed.argtypes = [vp, vp, vp, vp, i64, i64, f32, vp, ctypes.c_int, vp, vp, vp,
+                                                       vp, vp, sz, vp]
     L.tweo_static_scratch_bytes.argtypes = []
     L.tweo_static_scratch_bytes.restype = ctypes.c_size_t
     L.tweo_fp8_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
@@ -205,6 +209,29 @@ def tweo_fp8_linear_fwd(xq, sx_inv, wq, sw_inv, y_bf16, residual_bf16=None, pen=
     _check(load().tweo_fp8_linear_fwd(_ptr(xq), _ptr(sx_inv), _ptr(wq), _ptr(sw_inv),
                                       _ptr(residual_bf16), M, N, K, _ptr(y_bf16), _pen(pen),
                                       _ptr(penalty_sum), wp, wb, _stream()), "tweo_fp8_linear_fwd")
+
+
+def tweo_layernorm_quantize_e4m3(x_bf16, gamma_bf16, q, workspace, beta_bf16=None, residual_bf16=None, eps=1e-5,
+                                 h_out_bf16=None, y_out_bf16=None, amax_out=None, qT=None, scale_out=None,
+                                 scale_inv_out=None):
+    rows, cols = x_bf16.shape
+    wp, wb = _ws(workspace)
+    _check(load().tweo_layernorm_quantize_e4m3(_ptr(x_bf16), _ptr(residual_bf16), _ptr(gamma_bf16), _ptr(beta_bf16),
+                                               rows, cols, float(eps), _ptr(h_out_bf16), _ptr(y_out_bf16),
+                                               _ptr(amax_out), _ptr(q), _ptr(qT), _ptr(scale_out),
+                                               _ptr(scale_inv_out), wp, wb, _stream()),
+           "tweo_layernorm_quantize_e4m3")
+
+
+def tweo_layernorm_quantize_e4m3_delayed(x_bf16, gamma_bf16, state, q, workspace, bootstrap=False, beta_bf16=None,
+                                         residual_bf16=None, eps=1e-5, h_out_bf16=None, y_out_bf16=None, qT=None):
+    rows, cols = x_bf16.shape
+    wp, wb = _ws(workspace)
+    _check(load().tweo_layernorm_quantize_e4m3_delayed(_ptr(x_bf16), _ptr(residual_bf16), _ptr(gamma_bf16),
+                                                       _ptr(beta_bf16), rows, cols, float(eps), _ptr(state),
+                                                       1 if bootstrap else 0, _ptr(h_out_bf16), _ptr(y_out_bf16),
+                                                       _ptr(q), _ptr(qT), wp, wb, _stream()),
+           "tweo_layernorm_quantize_e4m3_delayed")
 
 
 def tweo_static_scratch_bytes():

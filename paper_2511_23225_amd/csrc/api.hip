@@ -110,6 +110,8 @@ size_t tweo_workspace_bytes(int op, int64_t M, int64_t N, int64_t K)
         return kAmaxScratchBytes + tweo_workspace_bytes(TWEO_OP_FP8_LINEAR_BWD, M, N, K);
     case TWEO_OP_W8A8_LINEAR:
         return 256 + (stream_k_candidate(M, N, K) ? stream_k_workspace_bytes() : 0);
+    case TWEO_OP_LAYERNORM_QUANTIZE:  // M rows (N, K unused)
+        return kAmaxPartialsMax * sizeof(uint32_t) + 256 + round256((size_t)M * 2 * sizeof(double));
     default:
         return 256;
     }
@@ -380,6 +382,63 @@ tweo_status tweo_penalty_grad_inject(const void *dy_bf16, const void *a_bf16, in
     return hip_status(launch_penalty_grad_inject(dy_bf16, a_bf16, n, (float)(1.0 / denom),
                                                  (float)((double)g * pen->p / denom), pen->p, out_bf16,
                                                  (hipStream_t)stream));
+}
+
+namespace {
+// workspace of the LayerNorm entry points: the amax launch's workgroup maxima, one spare fp32 slot
+// for the amax when the caller wants none, then two doubles per row
+constexpr size_t kLnHeadBytes = kAmaxPartialsMax * sizeof(uint32_t) + 256;
+inline size_t layernorm_bytes(int64_t rows) { return kLnHeadBytes + round256((size_t)rows * 2 * sizeof(double)); }
+
+tweo_status layernorm_quantize_impl(const void *x_bf16, const void *residual_bf16, const void *gamma_bf16,
+                                    const void *beta_bf16, int64_t rows, int64_t cols, float eps, void *state,
+                                    int bootstrap, void *h_out_bf16, void *y_out_bf16, float *amax_out, uint8_t *q,
+                                    uint8_t *qT, float *scale_out, float *scale_inv_out, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    if (!x_bf16 || !gamma_bf16 || !q || rows <= 0 || cols <= 0 || !aligned16(x_bf16) || !aligned16(gamma_bf16) ||
+        !aligned16(q) || (beta_bf16 && !aligned16(beta_bf16)) || (qT && !aligned16(qT)) ||
+        (y_out_bf16 && !aligned16(y_out_bf16)) || (state && !aligned16(state)) || !(eps >= 0.0f))
+        return TWEO_ERR_INVALID_ARG;
+    // a residual makes a new tensor h = x + r that the cast pass reads back: it needs a home
+    if (residual_bf16 && (!h_out_bf16 || !aligned16(residual_bf16) || !aligned16(h_out_bf16)))
+        return TWEO_ERR_INVALID_ARG;
+    if (rows % 16 != 0 || cols % 16 != 0 || rows > kMaxDim || cols > ((int64_t)1 << 24))
+        return TWEO_ERR_UNSUPPORTED;
+    if (!workspace || !aligned16(workspace) || workspace_bytes < layernorm_bytes(rows))
+        return TWEO_ERR_WORKSPACE;
+    uint32_t *partials = (uint32_t *)workspace;
+    float *spare = (float *)((uint8_t *)workspace + kAmaxPartialsMax * sizeof(uint32_t));
+    double *stats = (double *)((uint8_t *)workspace + kLnHeadBytes);
+    return hip_status(launch_layernorm_quantize(x_bf16, residual_bf16, gamma_bf16, beta_bf16, rows, cols, (double)eps,
+                                                h_out_bf16, y_out_bf16, q, qT, stats, partials,
+                                                amax_out ? amax_out : spare, scale_out, scale_inv_out, state,
+                                                bootstrap != 0, (hipStream_t)stream));
+}
+}  // namespace
+
+tweo_status tweo_layernorm_quantize_e4m3(const void *x_bf16, const void *residual_bf16, const void *gamma_bf16,
+                                         const void *beta_bf16, int64_t rows, int64_t cols, float eps,
+                                         void *h_out_bf16, void *y_out_bf16, float *amax_out, uint8_t *q, uint8_t *qT,
+                                         float *scale_out, float *scale_inv_out, void *workspace,
+                                         size_t workspace_bytes, void *stream)
+{
+    return layernorm_quantize_impl(x_bf16, residual_bf16, gamma_bf16, beta_bf16, rows, cols, eps, nullptr, 0, h_out_bf16,
+                                   y_out_bf16, amax_out, q, qT, scale_out, scale_inv_out, workspace, workspace_bytes,
+                                   stream);
+}
+
+tweo_status tweo_layernorm_quantize_e4m3_delayed(const void *x_bf16, const void *residual_bf16,
+                                                 const void *gamma_bf16, const void *beta_bf16, int64_t rows,
+                                                 int64_t cols, float eps, void *state, int bootstrap, void *h_out_bf16,
+                                                 void *y_out_bf16, uint8_t *q, uint8_t *qT, void *workspace,
+                                                 size_t workspace_bytes, void *stream)
+{
+    if (!state)
+        return TWEO_ERR_INVALID_ARG;
+    return layernorm_quantize_impl(x_bf16, residual_bf16, gamma_bf16, beta_bf16, rows, cols, eps, state, bootstrap,
+                                   h_out_bf16, y_out_bf16, nullptr, q, qT, nullptr, nullptr, workspace, workspace_bytes,
+                                   stream);
 }
 
 tweo_status tweo_quantize_i8(const void *x_bf16, int64_t n, float inv_step, int8_t *out,

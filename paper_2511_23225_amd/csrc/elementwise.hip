@@ -377,7 +377,7 @@ __device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint3
 // fixed before this tensor was seen and wants this tensor's amax back for the history: DELAYED
 // kernels read the scale itself from `amax`, and add the maximum magnitude pattern of what they
 // load to *amax_acc (one atomicMax per workgroup, skipped when already covered).
-__device__ __forceinline__ void quant_amax_commit(uint32_t m, uint32_t *amax_acc)
+__device__ __forceinline__ void quant_amax_commit(uint32_t m, uint32_t *amax_acc, bool atomic = true)
 {
     __shared__ uint32_t red[kQuantThreads / kWave];
     uint32_t r = (m & 0xFFFFu) > (m >> 16) ? (m & 0xFFFFu) : (m >> 16);
@@ -390,7 +390,9 @@ __device__ __forceinline__ void quant_amax_commit(uint32_t m, uint32_t *amax_acc
         for (int w = 1; w < kQuantThreads / kWave; ++w)
             r = red[w] > r ? red[w] : r;
         const uint32_t mine = r << 16;
-        if (mine > __atomic_load_n(amax_acc, __ATOMIC_RELAXED))
+        if (!atomic)
+            *amax_acc = mine;  // a slot of this workgroup's own
+        else if (mine > __atomic_load_n(amax_acc, __ATOMIC_RELAXED))
             atomicMax(amax_acc, mine);
     }
 }
@@ -463,6 +465,149 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------
+// LayerNorm in front of the cast (Sec. 4.3: the LayerNorm components run under FP8 with the linear
+// layers, i.e. the normalised activation is what the next linear's per-tensor cast consumes).
+// Textbook row-wise normalisation, biased variance; the value is rounded ONCE to bf16 (the stored
+// activation) and that bf16 value is what amax and the FP8 rounding see.  The arithmetic is fp64:
+// its instructions issue at the rate of fp32 ones on this chip and the passes are bound by memory,
+// so the stored bits do not depend on the summation order to any extent a test could see.
+struct LnArgs {
+    const double *stats;           // per row: mean, 1 / sqrt(var + eps)
+    const uint16_t *gamma, *beta;  // bf16 [cols]; beta may be nullptr
+};
+
+// fp64 -> fp32 with round-to-odd (truncate, then set the last bit if anything was lost): rounding
+// that result to bf16 with round-to-nearest-even is the single correct rounding of the fp64 value.
+__device__ __forceinline__ float f64_to_f32_round_odd(double v)
+{
+    float t = (float)v;
+    const double back = (double)t;
+    if (back != v && v == v) {
+        uint32_t tb = f32_to_bits(t);
+        if (__builtin_fabs(back) > __builtin_fabs(v))
+            tb -= 1u;  // one step towards zero (also from Inf to the largest finite value)
+        t = bits_to_f32(tb | 1u);
+    }
+    return t;
+}
+
+__device__ __forceinline__ float ln_one(float x, double mean, double rstd, float g, float b, bool has_beta)
+{
+#pragma clang fp contract(off)
+    const double d = (double)x - mean;
+    double y = (d * rstd) * (double)g;
+    if (has_beta)
+        y = y + (double)b;
+    return f64_to_f32_round_odd(y);
+}
+
+// eight elements of a row: x, gamma and beta as packed bf16 pairs -> packed bf16 pairs of y
+__device__ __forceinline__ uint4 ln_vec(uint4 x, double mean, double rstd, uint4 g, uint4 b, bool has_beta)
+{
+    const uint32_t xx[4] = {x.x, x.y, x.z, x.w}, gg[4] = {g.x, g.y, g.z, g.w}, bb[4] = {b.x, b.y, b.z, b.w};
+    uint32_t r[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        r[k] = pack_bf16x2(ln_one(bf16lo_to_f32(xx[k]), mean, rstd, bf16lo_to_f32(gg[k]), bf16lo_to_f32(bb[k]), has_beta),
+                           ln_one(bf16hi_to_f32(xx[k]), mean, rstd, bf16hi_to_f32(gg[k]), bf16hi_to_f32(bb[k]), has_beta));
+    return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
+// h = bf16(x + r) on eight elements: the fp32 sum of two bf16 values rounded to bf16 equals the
+// exact sum rounded once (the fp32 sum is exact unless the smaller term lies below the bf16
+// rounding position of the larger one by more than fp32 can hold, and then it decides nothing)
+__device__ __forceinline__ uint4 add_bf16x8(uint4 a, uint4 b)
+{
+    const uint32_t aa[4] = {a.x, a.y, a.z, a.w}, bb[4] = {b.x, b.y, b.z, b.w};
+    uint32_t r[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        r[k] = pack_bf16x2(bf16lo_to_f32(aa[k]) + bf16lo_to_f32(bb[k]), bf16hi_to_f32(aa[k]) + bf16hi_to_f32(bb[k]));
+    return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
+__device__ __forceinline__ double sum8_f64(uint4 v)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    double s = 0.0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        s += (double)bf16lo_to_f32(w[k]) + (double)bf16hi_to_f32(w[k]);
+    return s;
+}
+
+__device__ __forceinline__ double sumsq8_f64(uint4 v, double mean)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    double s = 0.0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const double d0 = (double)bf16lo_to_f32(w[k]) - mean, d1 = (double)bf16hi_to_f32(w[k]) - mean;
+        s += d0 * d0 + d1 * d1;
+    }
+    return s;
+}
+
+// Row statistics: one wave per row, the first kLnCached 16-byte pieces of every lane stay in
+// registers between the mean and the variance, so rows of up to 4096 elements are read from memory
+// once (2 B/element).  RESIDUAL: the row is h = bf16(x + r), stored to h_out on the way.
+constexpr int kLnThreads = 1024;
+constexpr int kLnCached = 8;
+
+template <bool RESIDUAL>
+__global__ __launch_bounds__(kLnThreads) void ln_stats_kernel(const uint4 *x, const uint4 *res, uint4 *h_out,
+                                                              int64_t rows, int vec_per_row, double eps,
+                                                              double *__restrict__ stats)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    constexpr int WAVES = kLnThreads / kWave;
+    const double n = (double)vec_per_row * 8.0;
+    for (int64_t row = (int64_t)blockIdx.x * WAVES + wave; row < rows; row += (int64_t)gridDim.x * WAVES) {
+        const uint4 *xr = x + row * vec_per_row;
+        const uint4 *rr = RESIDUAL ? res + row * vec_per_row : nullptr;
+        uint4 *hr = RESIDUAL ? h_out + row * vec_per_row : nullptr;
+        uint4 c[kLnCached];
+        double s = 0.0;
+#pragma unroll
+        for (int u = 0; u < kLnCached; ++u) {
+            const int i = lane + u * kWave;
+            c[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (i < vec_per_row) {
+                c[u] = xr[i];
+                if constexpr (RESIDUAL) {
+                    c[u] = add_bf16x8(c[u], rr[i]);
+                    hr[i] = c[u];
+                }
+                s += sum8_f64(c[u]);
+            }
+        }
+        for (int i = lane + kLnCached * kWave; i < vec_per_row; i += kWave) {
+            uint4 v = xr[i];
+            if constexpr (RESIDUAL) {
+                v = add_bf16x8(v, rr[i]);
+                hr[i] = v;
+            }
+            s += sum8_f64(v);
+        }
+        const double mean = wave_reduce_sum(s) / n;
+        double ss = 0.0;
+#pragma unroll
+        for (int u = 0; u < kLnCached; ++u)
+            if (lane + u * kWave < vec_per_row)
+                ss += sumsq8_f64(c[u], mean);
+        // h_out may be x or the residual itself (an in-place update of the stream): what this lane
+        // stored above is read back, not formed again
+        for (int i = lane + kLnCached * kWave; i < vec_per_row; i += kWave)
+            ss += sumsq8_f64(RESIDUAL ? hr[i] : xr[i], mean);
+        const double var = wave_reduce_sum(ss) / n;
+        if (lane == 0) {
+            stats[2 * row] = mean;
+            stats[2 * row + 1] = 1.0 / __builtin_sqrt(var + eps);
+        }
+    }
+}
+
 // Same cast for shapes with rows % 16 == 0 and cols % 16 == 0: a lane owns a
 // 16x16 block (two 16-byte loads per row), so q is written in 16-byte pieces
 // that 8 neighbouring lanes join into whole 128-byte lines, and - after sixteen
@@ -471,16 +616,22 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(
 constexpr int kQuantBigTile = 256;
 
 // INJECT: 0 = plain cast; 4 / 1 = the penalty gradient is added on the way in (p = 4 / any p)
-template <bool WITH_T, bool DELAYED, bool E5M2 = false, int INJECT = 0>
+// LN: the tensor that is cast is the LayerNorm of x (statistics precomputed per row).  AMAX_ONLY
+// (with DELAYED's bounded grid and tile loop): nothing is stored, workgroup b leaves the maximum
+// magnitude pattern of what it would have cast in amax_acc[b].
+template <bool WITH_T, bool DELAYED, bool E5M2 = false, int INJECT = 0, bool LN = false, bool AMAX_ONLY = false>
 __device__ __forceinline__ void quantize_e4m3_16x16_body(
     const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
     const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
     float *scale_out, float *scale_inv_out, uint32_t *amax_acc, int64_t block, int64_t n_blocks,
     const uint32_t *__restrict__ amax_partials = nullptr, int n_partials = 0, float *amax_store = nullptr,
-    InjectArgs inj = InjectArgs{})
+    InjectArgs inj = InjectArgs{}, LnArgs ln = LnArgs{}, uint16_t *__restrict__ y_out = nullptr)
 {
-    float amax_v;
-    if (amax_partials != nullptr) {  // uniform: the maxima of the amax launch's workgroups
+    static_assert(!AMAX_ONLY || DELAYED, "the amax-only pass walks the tiles with a bounded grid");
+    float amax_v = 0.0f;
+    if constexpr (AMAX_ONLY) {
+        // no scale needed
+    } else if (amax_partials != nullptr) {  // uniform: the maxima of the amax launch's workgroups
         __shared__ uint32_t pred[kQuantThreads / kWave];
         uint32_t m = 0;
         for (int i = threadIdx.x; i < n_partials; i += kQuantThreads) {
@@ -501,7 +652,7 @@ __device__ __forceinline__ void quantize_e4m3_16x16_body(
         amax_v = *amax;
     }
     const float scale = DELAYED ? amax_v : scale_f8<E5M2>(amax_v);
-    if (block == 0 && threadIdx.x == 0) {
+    if (!AMAX_ONLY && block == 0 && threadIdx.x == 0) {
         if (scale_out)
             *scale_out = scale;
         if (scale_inv_out)
@@ -519,6 +670,16 @@ __device__ __forceinline__ void quantize_e4m3_16x16_body(
     if (c0 >= cols || r0 >= rows)  // whole 16x16 blocks: in or out
         continue;
     uint32_t qd[16][4];
+    uint4 lg[2], lb[2];  // LN: gamma and beta of the lane's 16 columns
+    if constexpr (LN) {
+        lg[0] = ((const uint4 *)(ln.gamma + c0))[0];
+        lg[1] = ((const uint4 *)(ln.gamma + c0))[1];
+        lb[0] = lb[1] = make_uint4(0u, 0u, 0u, 0u);
+        if (ln.beta != nullptr) {
+            lb[0] = ((const uint4 *)(ln.beta + c0))[0];
+            lb[1] = ((const uint4 *)(ln.beta + c0))[1];
+        }
+    }
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         uint4 in[8][2];
@@ -527,6 +688,16 @@ __device__ __forceinline__ void quantize_e4m3_16x16_body(
             const uint4 *src = (const uint4 *)(x + (r0 + half * 8 + i) * cols + c0);
             in[i][0] = src[0];
             in[i][1] = src[1];
+            if constexpr (LN) {
+                const double mean = ln.stats[2 * (r0 + half * 8 + i)], rstd = ln.stats[2 * (r0 + half * 8 + i) + 1];
+                in[i][0] = ln_vec(in[i][0], mean, rstd, lg[0], lb[0], ln.beta != nullptr);
+                in[i][1] = ln_vec(in[i][1], mean, rstd, lg[1], lb[1], ln.beta != nullptr);
+                if (!AMAX_ONLY && y_out != nullptr) {
+                    uint4 *dst = (uint4 *)(y_out + (r0 + half * 8 + i) * cols + c0);
+                    dst[0] = in[i][0];
+                    dst[1] = in[i][1];
+                }
+            }
             if constexpr (INJECT != 0) {
                 const uint4 *asrc = (const uint4 *)(inj.act + (r0 + half * 8 + i) * cols + c0);
                 in[i][0] = inject_vec<(INJECT == 4 ? 4 : 0)>(in[i][0], asrc[0], inj);
@@ -535,6 +706,8 @@ __device__ __forceinline__ void quantize_e4m3_16x16_body(
             if constexpr (DELAYED)
                 mx = pk_absmax4(pk_absmax4(mx, in[i][0]), in[i][1]);
         }
+        if constexpr (AMAX_ONLY)
+            continue;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int r = half * 8 + i;
@@ -549,7 +722,7 @@ __device__ __forceinline__ void quantize_e4m3_16x16_body(
             *(uint4 *)(q + (r0 + r) * cols + c0) = make_uint4(qd[r][0], qd[r][1], qd[r][2], qd[r][3]);
         }
     }
-    if (WITH_T) {
+    if (WITH_T && !AMAX_ONLY) {
 #pragma unroll
         for (int C = 0; C < 4; ++C) {
             uint32_t t[4][4];  // t[R][k]: column 4C+k, rows 4R..4R+3
@@ -566,9 +739,25 @@ __device__ __forceinline__ void quantize_e4m3_16x16_body(
     }
     // every lane reaches the one workgroup barrier of the amax commit (amax_acc is uniform over
     // the grid; nullptr = the caller already has this tensor's amax)
-    if constexpr (DELAYED)
+    if constexpr (AMAX_ONLY)
+        quant_amax_commit(mx, amax_acc + block, false);
+    else if constexpr (DELAYED)
         if (amax_acc != nullptr)
             quant_amax_commit(mx, amax_acc);
+}
+
+// LayerNorm + cast (DELAYED: the scale is read from *amax, the tensor's amax goes to *amax_acc), or
+// the amax-only pass over the normalised tensor (one maximum per workgroup into amax_acc[])
+template <bool WITH_T, bool DELAYED, bool AMAX_ONLY>
+__global__ __launch_bounds__(kQuantThreads) void quantize_ln_16x16_kernel(
+    const uint16_t *__restrict__ x, LnArgs ln, int64_t rows, int64_t cols, int64_t tiles_x,
+    const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT, uint16_t *__restrict__ y_out,
+    float *scale_out, float *scale_inv_out, uint32_t *amax_acc, const uint32_t *__restrict__ amax_partials,
+    int n_partials, float *amax_store)
+{
+    quantize_e4m3_16x16_body<WITH_T, DELAYED, false, 0, true, AMAX_ONLY>(
+        x, rows, cols, tiles_x, amax, q, qT, scale_out, scale_inv_out, amax_acc, blockIdx.x, gridDim.x, amax_partials,
+        n_partials, amax_store, InjectArgs{}, ln, y_out);
 }
 
 template <bool WITH_T, bool DELAYED, bool E5M2 = false>
@@ -763,10 +952,17 @@ __global__ void delayed_state_init_kernel(uint32_t *st)
 
 // Consumes the accumulated amax: remembers the scale that was just used, pushes the amax into
 // the ring, derives the next scale, clears the accumulator.  One thread.
-__global__ void delayed_state_update_kernel(uint32_t *st, int bootstrap, float range)
+__global__ void delayed_state_update_kernel(uint32_t *st, int bootstrap, float range,
+                                            const uint32_t *partials = nullptr, int n_partials = 0)
 {
     if (threadIdx.x != 0 || blockIdx.x != 0)
         return;
+    if (partials != nullptr) {  // the tensor's amax arrives as one maximum per workgroup of an earlier launch
+        uint32_t m = 0;
+        for (int i = 0; i < n_partials; ++i)
+            m = partials[i] > m ? partials[i] : m;
+        st[16] = m;
+    }
     int pos = (int)st[19], filled = (int)st[20];
     if (!bootstrap) {  // a bootstrap cast has not happened yet: nothing was "used"
         st[21] = st[17];
@@ -808,7 +1004,8 @@ static hipError_t launch_quantize_f8_delayed(const void *x_bf16, int64_t rows, i
         e = launch_amax(x_bf16, rows * cols, st + 16, s);
         if (e != hipSuccess)
             return e;
-        hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 1, range);
+        hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 1, range,
+                           (const uint32_t *)nullptr, 0);
         e = hipGetLastError();
         if (e != hipSuccess)
             return e;
@@ -820,7 +1017,8 @@ static hipError_t launch_quantize_f8_delayed(const void *x_bf16, int64_t rows, i
                                               (uint32_t *)st + 16, s);
     if (e != hipSuccess)
         return e;
-    hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 0, range);
+    hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 0, range,
+                       (const uint32_t *)nullptr, 0);
     return hipGetLastError();
 }
 
@@ -834,6 +1032,84 @@ hipError_t launch_quantize_e5m2_delayed(const void *x_bf16, int64_t rows, int64_
                                         int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s)
 {
     return launch_quantize_f8_delayed<true>(x_bf16, rows, cols, state, bootstrap, q, qT, s);
+}
+
+// LayerNorm -> per-tensor E4M3 cast (Sec. 4.3).  Launches: row statistics (2 B/element from
+// memory; with a residual it also forms and stores h = bf16(x + r)); for current scaling, or for
+// the first call on a delayed-scaling state, an amax-only pass over the normalised tensor (it
+// re-reads the rows from the caches); then the cast, which normalises on the way in (re-read from
+// the caches, 1 B/element written per copy of the codes, + 2 B/element if y is wanted).
+// stats: 2 doubles per row; partials: kAmaxPartialsMax words.  rows, cols multiples of 16.
+hipError_t launch_layernorm_quantize(const void *x_bf16, const void *res_bf16, const void *gamma_bf16,
+                                     const void *beta_bf16, int64_t rows, int64_t cols, double eps, void *h_out,
+                                     void *y_out, uint8_t *q, uint8_t *qT, double *stats, uint32_t *partials,
+                                     float *amax_out, float *scale_out, float *scale_inv_out, void *state,
+                                     int bootstrap, hipStream_t s)
+{
+    const int vec = (int)(cols / 8);
+    constexpr int WAVES = kLnThreads / kWave;
+    int64_t sgrid = (rows + WAVES - 1) / WAVES;
+    if (sgrid > 2 * amax_cus())
+        sgrid = 2 * amax_cus();
+    if (res_bf16 != nullptr)
+        hipLaunchKernelGGL(ln_stats_kernel<true>, dim3((unsigned)sgrid), dim3(kLnThreads), 0, s, (const uint4 *)x_bf16,
+                           (const uint4 *)res_bf16, (uint4 *)h_out, rows, vec, eps, stats);
+    else
+        hipLaunchKernelGGL(ln_stats_kernel<false>, dim3((unsigned)sgrid), dim3(kLnThreads), 0, s, (const uint4 *)x_bf16,
+                           (const uint4 *)nullptr, (uint4 *)nullptr, rows, vec, eps, stats);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return e;
+    const uint16_t *src = (const uint16_t *)(res_bf16 != nullptr ? h_out : x_bf16);
+    const LnArgs ln{stats, (const uint16_t *)gamma_bf16, (const uint16_t *)beta_bf16};
+    const int64_t tiles_x = (cols + kQuantBigTile - 1) / kQuantBigTile, tiles_y = (rows + kQuantBigTile - 1) / kQuantBigTile;
+    const int64_t n_tiles = tiles_x * tiles_y;
+    const int64_t bounded = n_tiles < kAmaxMaxPartials ? n_tiles : kAmaxMaxPartials;
+    const dim3 block(kQuantThreads);
+    float *st = (float *)state;
+    const bool delayed = state != nullptr;
+    if (!delayed || bootstrap) {
+        hipLaunchKernelGGL((quantize_ln_16x16_kernel<false, true, true>), dim3((unsigned)bounded), block, 0, s, src, ln, rows,
+                           cols, tiles_x, (const float *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr,
+                           (uint16_t *)nullptr, (float *)nullptr, (float *)nullptr, partials, (const uint32_t *)nullptr, 0,
+                           (float *)nullptr);
+        if ((e = hipGetLastError()) != hipSuccess)
+            return e;
+    }
+    if (!delayed) {
+        if (qT)
+            hipLaunchKernelGGL((quantize_ln_16x16_kernel<true, false, false>), dim3((unsigned)n_tiles), block, 0, s, src, ln,
+                               rows, cols, tiles_x, (const float *)amax_out, q, qT, (uint16_t *)y_out, scale_out, scale_inv_out,
+                               (uint32_t *)nullptr, (const uint32_t *)partials, (int)bounded, amax_out);
+        else
+            hipLaunchKernelGGL((quantize_ln_16x16_kernel<false, false, false>), dim3((unsigned)n_tiles), block, 0, s, src, ln,
+                               rows, cols, tiles_x, (const float *)amax_out, q, qT, (uint16_t *)y_out, scale_out, scale_inv_out,
+                               (uint32_t *)nullptr, (const uint32_t *)partials, (int)bounded, amax_out);
+        return hipGetLastError();
+    }
+    if (bootstrap) {  // empty history: the tensor's own amax makes the scale
+        hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 1, 448.0f,
+                           (const uint32_t *)partials, (int)bounded);
+        if ((e = hipGetLastError()) != hipSuccess)
+            return e;
+    }
+    const float *scale_src = bootstrap ? st + 21 : st + 17;
+    uint32_t *acc = bootstrap ? nullptr : (uint32_t *)st + 16;
+    int64_t n_wg = n_tiles < 1024 ? n_tiles : 1024;
+    if (qT)
+        hipLaunchKernelGGL((quantize_ln_16x16_kernel<true, true, false>), dim3((unsigned)n_wg), block, 0, s, src, ln, rows, cols,
+                           tiles_x, scale_src, q, qT, (uint16_t *)y_out, (float *)nullptr, (float *)nullptr, acc,
+                           (const uint32_t *)nullptr, 0, (float *)nullptr);
+    else
+        hipLaunchKernelGGL((quantize_ln_16x16_kernel<false, true, false>), dim3((unsigned)n_wg), block, 0, s, src, ln, rows, cols,
+                           tiles_x, scale_src, q, qT, (uint16_t *)y_out, (float *)nullptr, (float *)nullptr, acc,
+                           (const uint32_t *)nullptr, 0, (float *)nullptr);
+    if ((e = hipGetLastError()) != hipSuccess)
+        return e;
+    if (!bootstrap)
+        hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 0, 448.0f,
+                           (const uint32_t *)nullptr, 0);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------

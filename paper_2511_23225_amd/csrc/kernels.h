@@ -46,6 +46,14 @@ hipError_t launch_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_
 // the same for a tensor cast to E5M2 (gradients of the HYBRID recipe): scale = 57344 / max(history)
 hipError_t launch_quantize_e5m2_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
                                         int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s);
+// LayerNorm of x (or of h = bf16(x + res), stored to h_out) followed by the per-tensor E4M3 cast of
+// the normalised tensor; state == nullptr: current scaling (amax_out required), else delayed
+// scaling on that state.  stats: 2 doubles per row, partials: kAmaxPartialsMax words of scratch.
+hipError_t launch_layernorm_quantize(const void *x_bf16, const void *res_bf16, const void *gamma_bf16,
+                                     const void *beta_bf16, int64_t rows, int64_t cols, double eps, void *h_out,
+                                     void *y_out, uint8_t *q, uint8_t *qT, double *stats, uint32_t *partials,
+                                     float *amax_out, float *scale_out, float *scale_inv_out, void *state,
+                                     int bootstrap, hipStream_t s);
 hipError_t launch_quantize_i8(const void *x_bf16, int64_t n, float inv_step, int8_t *out,
                               hipStream_t s);
 // Row-granular AbsMax INT8: q [rows, cols] and one dequantisation step per row (cols % 8 == 0).

@@ -1,0 +1,207 @@
+"""GPU parity of LayerNorm -> per-tensor E4M3 cast (current and delayed scaling), through the C ABI.
+
+The byte-parity rule: the GPU normalises in fp64 like the oracle, in a different summation order,
+so the two fp64 values of an element differ by a few 1e-16 relative.  The stored bf16 value, and
+with it amax, scale and every code, must be the oracle's bit for bit, except where the oracle's
+fp64 value lies within 1e-10 (relative) of a bf16 rounding boundary; such elements are counted,
+must differ by one bf16 step at most, and none is expected at these sizes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2511_23225_amd as tw
+from paper_2511_23225_amd import synth
+from gpu_util import DEV, to_dev_bf16, bf16_bits, scalar_f32
+
+pytestmark = pytest.mark.gpu
+HEAD = 512 * 4 + 256  # bytes in front of the row statistics in the workspace
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def make_inputs(rows, cols, seed, outliers=True, with_beta=True):
+    rng = np.random.default_rng(seed)
+    x = (rng.standard_normal((rows, cols)) * 3.0 + 0.5).astype(np.float32)
+    if outliers:  # a few extreme values, as in an untreated residual stream (Sec. 1)
+        k = max(1, rows * cols // 20000)
+        x.reshape(-1)[rng.choice(rows * cols, k, replace=False)] = rng.uniform(1000, 5000, k) * rng.choice([-1, 1], k)
+    r = rng.standard_normal((rows, cols)).astype(np.float32)
+    gamma = (1.0 + 0.1 * rng.standard_normal(cols)).astype(np.float32)
+    beta = (0.1 * rng.standard_normal(cols)).astype(np.float32) if with_beta else None
+    b = synth.f32_to_bf16_bits
+    return b(x), b(r), b(gamma), None if beta is None else b(beta)
+
+
+def boundary_distance(y64):
+    """Relative distance of each fp64 value to the nearest midpoint between adjacent bf16 values."""
+    a = np.abs(y64)
+    e = np.floor(np.log2(np.maximum(a, 1e-300)))
+    ulp = 2.0 ** (e - 7)
+    frac = a / ulp - np.floor(a / ulp)
+    return np.abs(frac - 0.5) * ulp / np.maximum(a, 1e-300)
+
+
+def check_y(got, want_bits, y64, what):
+    diff = got != want_bits
+    n = int(diff.sum())
+    if n:
+        assert np.all(boundary_distance(y64[diff]) < 1e-10), what
+        assert np.all(np.abs(got[diff].astype(np.int32) - want_bits[diff].astype(np.int32)) == 1), what
+        assert n <= 2, (what, n)
+    return diff
+
+
+def ws_for(rows):
+    return torch.full((tw.tweo_workspace_bytes(tw.TWEO_OP_LAYERNORM_QUANTIZE, rows, 1, 1),), 0xEE, dtype=torch.uint8,
+                      device=DEV)
+
+
+CASES = [(256, 768, True, True), (48, 2048, True, False), (592, 768, False, True), (64, 4096, True, True),
+         (32, 5632, True, True), (16, 16, False, False), (1024, 2048, True, True)]
+
+
+@pytest.mark.parametrize("with_residual", [False, True])
+@pytest.mark.parametrize("case", CASES)
+def test_layernorm_quantize_current_scaling(case, with_residual):
+    rows, cols, outliers, with_beta = case
+    eps = np.float32(1e-5)
+    say("layernorm current rows=%d cols=%d residual=%s" % (rows, cols, with_residual))
+    x, r, gamma, beta = make_inputs(rows, cols, rows + cols, outliers, with_beta)
+    h = oracle.residual_add_bf16(x, r) if with_residual else x
+    y64, yb = oracle.layernorm(h, gamma, beta, float(eps))
+    amax = oracle.amax_bf16(yb)
+    scale, scale_inv = oracle.scale_from_amax(amax)
+    oq, oqT = oracle.quantize_e4m3(yb, scale)
+
+    q = torch.full((rows, cols), 0x55, dtype=torch.uint8, device=DEV)
+    qT = torch.full((cols, rows), 0x55, dtype=torch.uint8, device=DEV)
+    y = torch.full((rows, cols), float("nan"), dtype=torch.bfloat16, device=DEV)
+    hd = torch.full((rows, cols), float("nan"), dtype=torch.bfloat16, device=DEV) if with_residual else None
+    am, sc, sci = scalar_f32(-1), scalar_f32(-1), scalar_f32(-1)
+    ws = ws_for(rows)
+    tw.tweo_layernorm_quantize_e4m3(to_dev_bf16(x), to_dev_bf16(gamma), q, ws,
+                                    beta_bf16=None if beta is None else to_dev_bf16(beta),
+                                    residual_bf16=to_dev_bf16(r) if with_residual else None, eps=eps, h_out_bf16=hd,
+                                    y_out_bf16=y, amax_out=am, qT=qT, scale_out=sc, scale_inv_out=sci)
+    torch.cuda.synchronize()
+    if with_residual:
+        assert np.array_equal(bf16_bits(hd), h)
+    flips = check_y(bf16_bits(y), yb, y64, "y")
+    if not flips.any():
+        assert am.cpu().numpy()[0].view(np.uint32) == np.float32(amax).view(np.uint32)
+        assert sc.cpu().numpy()[0].view(np.uint32) == np.float32(scale).view(np.uint32)
+        assert sci.cpu().numpy()[0].view(np.uint32) == np.float32(scale_inv).view(np.uint32)
+        assert np.array_equal(q.cpu().numpy(), oq)
+        assert np.array_equal(qT.cpu().numpy(), oqT)
+    # the row statistics a backward pass would use
+    st = ws[HEAD:HEAD + rows * 16].cpu().numpy().view(np.float64).reshape(rows, 2)
+    hv = synth.bf16_bits_to_f32(h).astype(np.float64)
+    assert np.allclose(st[:, 0], hv.mean(axis=1), rtol=1e-12, atol=1e-13)
+    assert np.allclose(st[:, 1], 1.0 / np.sqrt(hv.var(axis=1) + float(eps)), rtol=1e-12)
+    # codes alone (no y, no transposed copy, no scalars wanted): the same bytes
+    q2 = torch.full((rows, cols), 0x55, dtype=torch.uint8, device=DEV)
+    tw.tweo_layernorm_quantize_e4m3(to_dev_bf16(h), to_dev_bf16(gamma), q2, ws,
+                                    beta_bf16=None if beta is None else to_dev_bf16(beta), eps=eps)
+    torch.cuda.synchronize()
+    assert torch.equal(q, q2)
+
+
+def test_layernorm_residual_update_in_place():
+    rows, cols = 128, 5632  # rows longer than what a lane keeps in registers: the re-read path
+    x, r, gamma, beta = make_inputs(rows, cols, 5, True, True)
+    h = oracle.residual_add_bf16(x, r)
+    _, yb = oracle.layernorm(h, gamma, beta, 1e-6)
+    scale, _ = oracle.scale_from_amax(oracle.amax_bf16(yb))
+    oq, _ = oracle.quantize_e4m3(yb, scale, transpose=False)
+    xd = to_dev_bf16(x)
+    q = torch.empty((rows, cols), dtype=torch.uint8, device=DEV)
+    tw.tweo_layernorm_quantize_e4m3(xd, to_dev_bf16(gamma), q, ws_for(rows), beta_bf16=to_dev_bf16(beta),
+                                    residual_bf16=to_dev_bf16(r), eps=np.float32(1e-6), h_out_bf16=xd)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_bits(xd), h)
+    assert np.array_equal(q.cpu().numpy(), oq)
+
+
+@pytest.mark.parametrize("shape", [(256, 768), (64, 2048)])
+def test_layernorm_quantize_delayed_scaling_sequence(shape):
+    # 8 steps on one delayed-scaling state (Sec. 4.3: history of 16), the first one bootstrapping:
+    # codes, transposed codes and the state's scales against the oracle's recipe on the oracle's y
+    rows, cols = shape
+    eps = np.float32(1e-5)
+    ref = oracle.DelayedScaling()
+    state = torch.zeros(tw.DELAYED_STATE_WORDS, dtype=torch.float32, device=DEV)
+    tw.tweo_delayed_state_init(state)
+    q = torch.empty((rows, cols), dtype=torch.uint8, device=DEV)
+    qT = torch.empty((cols, rows), dtype=torch.uint8, device=DEV)
+    ws = ws_for(rows)
+    for step in range(8):
+        say("layernorm delayed", shape, step)
+        x, r, gamma, beta = make_inputs(rows, cols, 100 * step + rows, step == 3, True)
+        if step in (2, 5):   # gains that move the output's amax up and down
+            gamma = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(gamma) * np.float32(4.0 if step == 2 else 0.25))
+        y64, yb = oracle.layernorm(x, gamma, beta, float(eps))
+        oq, oqT, used, used_inv = ref.cast(yb)
+        y = torch.empty((rows, cols), dtype=torch.bfloat16, device=DEV)
+        tw.tweo_layernorm_quantize_e4m3_delayed(to_dev_bf16(x), to_dev_bf16(gamma), state, q, ws, bootstrap=(step == 0),
+                                                beta_bf16=to_dev_bf16(beta), eps=eps, y_out_bf16=y, qT=qT)
+        torch.cuda.synchronize()
+        flips = check_y(bf16_bits(y), yb, y64, "y")
+        assert not flips.any()
+        st = state.cpu().numpy()
+        assert st[tw.DELAYED_USED_SCALE].view(np.uint32) == np.float32(used).view(np.uint32), step
+        assert st[tw.DELAYED_USED_SCALE_INV].view(np.uint32) == np.float32(used_inv).view(np.uint32), step
+        assert st[tw.DELAYED_NEXT_SCALE].view(np.uint32) == np.float32(ref.next_scale).view(np.uint32), step
+        assert st[16] == 0.0 and not st[23:].view(np.uint32).any()
+        assert np.array_equal(q.cpu().numpy(), oq), step
+        assert np.array_equal(qT.cpu().numpy(), oqT), step
+
+
+@pytest.mark.parametrize("shape", [(16384, 2048), (18912, 768), (50432, 768)])
+def test_layernorm_quantize_full_size(shape):
+    # the residual streams of the LLaMA block (16384 tokens x 2048) and of the ViT block (256 and
+    # 96 images x 197 tokens x 768): every byte against the oracle
+    rows, cols = shape
+    eps = np.float32(1e-5)
+    say("layernorm full size", shape)
+    x, r, gamma, beta = make_inputs(rows, cols, rows, True, True)
+    h = oracle.residual_add_bf16(x, r)
+    y64, yb = oracle.layernorm(h, gamma, beta, float(eps))
+    scale, scale_inv = oracle.scale_from_amax(oracle.amax_bf16(yb))
+    oq, oqT = oracle.quantize_e4m3(yb, scale)
+    q = torch.empty((rows, cols), dtype=torch.uint8, device=DEV)
+    qT = torch.empty((cols, rows), dtype=torch.uint8, device=DEV)
+    y = torch.empty((rows, cols), dtype=torch.bfloat16, device=DEV)
+    hd = torch.empty((rows, cols), dtype=torch.bfloat16, device=DEV)
+    sci = scalar_f32(-1)
+    tw.tweo_layernorm_quantize_e4m3(to_dev_bf16(x), to_dev_bf16(gamma), q, ws_for(rows), beta_bf16=to_dev_bf16(beta),
+                                    residual_bf16=to_dev_bf16(r), eps=eps, h_out_bf16=hd, y_out_bf16=y, qT=qT,
+                                    scale_inv_out=sci)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_bits(hd), h)
+    flips = check_y(bf16_bits(y), yb, y64, "y")
+    say("  flips at rounding boundaries:", int(flips.sum()))
+    assert sci.cpu().numpy()[0].view(np.uint32) == np.float32(scale_inv).view(np.uint32)
+    gq, gqT = q.cpu().numpy(), qT.cpu().numpy()
+    assert np.array_equal(gq[~flips], oq[~flips])
+    assert np.array_equal(gqT[~flips.T], oqT[~flips.T])
+
+
+def test_layernorm_error_paths():
+    x = torch.zeros((16, 16), dtype=torch.bfloat16, device=DEV)
+    g = torch.ones((16,), dtype=torch.bfloat16, device=DEV)
+    q = torch.zeros((16, 16), dtype=torch.uint8, device=DEV)
+    with pytest.raises(tw.TweoError) as e:
+        tw.tweo_layernorm_quantize_e4m3(x, g, q, None)
+    assert e.value.status == tw.TWEO_ERR_WORKSPACE
+    with pytest.raises(tw.TweoError) as e:
+        tw.tweo_layernorm_quantize_e4m3(x, g, q, ws_for(16), residual_bf16=x)   # a residual needs h_out
+    assert e.value.status == tw.TWEO_ERR_INVALID_ARG
+    with pytest.raises(tw.TweoError) as e:
+        tw.tweo_layernorm_quantize_e4m3(x[:, :8].contiguous(), g[:8].contiguous(), q[:, :8].contiguous(), ws_for(16))
+    assert e.value.status == tw.TWEO_ERR_UNSUPPORTED
+    with pytest.raises(tw.TweoError) as e:
+        tw.tweo_layernorm_quantize_e4m3(x, g, q, ws_for(16), eps=-1.0)
+    assert e.value.status == tw.TWEO_ERR_INVALID_ARG

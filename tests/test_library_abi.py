@@ -39,7 +39,7 @@ def test_status_strings(lib):
 
 
 def test_workspace_bytes(lib):
-    for op in range(5):
+    for op in range(6):
         b = tw.tweo_workspace_bytes(op, 8192, 2304, 768)
         assert b >= 256 and b % 256 == 0
     assert tw.tweo_workspace_bytes(0, 16384, 6144, 2048) >= 4 * (16384 // 256) * (6144 // 256)
@@ -79,6 +79,23 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
     assert lib.tweo_quantize_i8(p, 16, float("nan"), p, None) == tw.TWEO_ERR_INVALID_ARG
     assert lib.tweo_w8a8_linear(p, p, 4, 16, 8, 1.0, p, None, 0, None) == tw.TWEO_ERR_UNSUPPORTED
     assert lib.tweo_w8a8_linear(p, None, 4, 16, 16, 1.0, p, None, 0, None) == tw.TWEO_ERR_INVALID_ARG
+    # LayerNorm -> cast: every check comes before the first launch
+    ln = lib.tweo_layernorm_quantize_e4m3
+    assert ln(p, None, p, None, 16, 16, 1e-5, None, None, None, p, None, None, None, None, 0, None) == \
+        tw.TWEO_ERR_WORKSPACE
+    assert ln(p, None, p, None, 16, 16, 1e-5, None, None, None, p, None, None, None, p, 64, None) == \
+        tw.TWEO_ERR_WORKSPACE
+    assert ln(p, None, None, None, 16, 16, 1e-5, None, None, None, p, None, None, None, p, 4096, None) == \
+        tw.TWEO_ERR_INVALID_ARG
+    assert ln(p, p, p, None, 16, 16, 1e-5, None, None, None, p, None, None, None, p, 4096, None) == \
+        tw.TWEO_ERR_INVALID_ARG      # a residual without a place for h
+    assert ln(p, None, p, None, 16, 24, 1e-5, None, None, None, p, None, None, None, p, 4096, None) == \
+        tw.TWEO_ERR_UNSUPPORTED
+    assert ln(p, None, p, None, 16, 16, float("nan"), None, None, None, p, None, None, None, p, 4096, None) == \
+        tw.TWEO_ERR_INVALID_ARG
+    assert lib.tweo_layernorm_quantize_e4m3_delayed(p, None, p, None, 16, 16, 1e-5, None, 0, None, None, p, None, p,
+                                                    4096, None) == tw.TWEO_ERR_INVALID_ARG   # no state
+    assert tw.tweo_workspace_bytes(tw.TWEO_OP_LAYERNORM_QUANTIZE, 16384, 1, 1) == 2304 + 16384 * 16
     assert lib.tweo_set_gemm_tile(99) == tw.TWEO_ERR_INVALID_ARG
     assert lib.tweo_set_gemm_tile(0) == tw.TWEO_OK
 
