@@ -74,23 +74,18 @@ def run_step(tw, layers, ev=None):
 
 
 def run_step_delayed(tw, layers, bootstrap=False, hybrid=False):
-    """The same step with the paper's delayed scaling (Sec. 4.3): every tensor is cast in one
-    pass with the scale its amax history fixed beforehand; no separate amax pass.  hybrid: the
-    gradient is cast to E5M2 as in the paper's HYBRID recipe."""
-    inv = tw.DELAYED_USED_SCALE_INV
-    cast_dy = tw.tweo_quantize_e5m2_delayed if hybrid else tw.tweo_quantize_e4m3_delayed
-    bwd = tw.tweo_fp8_linear_bwd_hybrid if hybrid else tw.tweo_fp8_linear_bwd
+    """The same step under the paper's own recipe (Sec. 4.3): delayed scaling, every tensor cast in
+    one pass with the scale its amax history fixed beforehand, no separate amax pass, through
+    tweo_fp8_linear_fwd_bf16_delayed / tweo_fp8_linear_bwd_bf16_delayed.  hybrid: the gradient is
+    cast to E5M2 as in the paper's HYBRID format."""
     for L in layers:
         sx, sw, sdy = L.st
-        tw.tweo_quantize_e4m3_delayed(L.x, sx, L.xq, L.xqT, bootstrap=bootstrap)
-        tw.tweo_quantize_e4m3_delayed(L.w, sw, L.wq, L.wqT, bootstrap=bootstrap)
-        tw.tweo_fp8_linear_fwd(L.xq, sx[inv:inv + 1], L.wq, sw[inv:inv + 1], L.y, pen=PEN, penalty_sum=L.S,
-                               workspace=L.ws)
+        tw.tweo_fp8_linear_fwd_bf16_delayed(L.x, L.w, L.y, L.saved, sx, sw, bootstrap=bootstrap, pen=PEN,
+                                            penalty_sum=L.S, workspace=L.ws)
     for L in reversed(layers):
         sx, sw, sdy = L.st
-        cast_dy(L.dy, sdy, L.dyq, L.dyqT, bootstrap=bootstrap)
-        bwd(L.dyq, L.dyqT, sdy[inv:inv + 1], L.wqT, sw[inv:inv + 1], L.xqT,
-            sx[inv:inv + 1], L.M, L.N, L.K, L.dx, L.dw, L.ws)
+        tw.tweo_fp8_linear_bwd_bf16_delayed(L.dy, L.saved, sdy, L.K, L.dyq, L.dyqT, L.dx, L.dw, L.ws,
+                                            bootstrap=bootstrap, dy_e5m2=hybrid)
 
 
 class GemmEvents:

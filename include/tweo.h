@@ -405,6 +405,32 @@ tweo_status tweo_fp8_linear_bwd_bf16_hybrid(const void *dy_bf16, const tweo_fp8_
                                             size_t workspace_bytes, void *stream);
 
 /*
+ * The two whole paths under the recipe the paper trained with (Sec. 4.3: per-tensor
+ * delayed scaling, amax history of 16, HYBRID formats): every tensor is read once,
+ * cast with the scale its history fixed beforehand, and its own amax joins the
+ * history (tweo_quantize_e4m3_delayed).  state_x, state_w, state_dy: one
+ * delayed-scaling state per scaled tensor (tweo_delayed_state_init), distinct;
+ * bootstrap != 0 on the first call on those states.  The activation and the weight
+ * share one cast launch and one state-update launch.  saved->scalars receives, as
+ * under current scaling, amax / scale used / its inverse of x (words 0-2), w (3-5)
+ * and, by the backward call, dy (6-8).  dy_e5m2 = 1 casts the gradient to E5M2
+ * (HYBRID), 0 to E4M3.  Shapes, workspace (that of tweo_fp8_linear_fwd /
+ * tweo_fp8_linear_bwd, optional unless a penalty or a K split needs it) and errors
+ * as tweo_fp8_linear_fwd_bf16 / tweo_fp8_linear_bwd_bf16.
+ */
+tweo_status tweo_fp8_linear_fwd_bf16_delayed(const void *x_bf16, const void *w_bf16,
+                                             const void *residual_bf16, int64_t M, int64_t N, int64_t K,
+                                             void *y_bf16, const tweo_penalty_cfg *pen,
+                                             double *penalty_sum, const tweo_fp8_saved *saved,
+                                             void *state_x, void *state_w, int bootstrap,
+                                             void *workspace, size_t workspace_bytes, void *stream);
+tweo_status tweo_fp8_linear_bwd_bf16_delayed(const void *dy_bf16, const tweo_fp8_saved *saved,
+                                             void *state_dy, int bootstrap, int dy_e5m2, int64_t M,
+                                             int64_t N, int64_t K, uint8_t *dyq, uint8_t *dyqT,
+                                             void *dx_bf16, void *dw_bf16, void *workspace,
+                                             size_t workspace_bytes, void *stream);
+
+/*
  * The backward path with the penalty-gradient injection (tweo_penalty_grad_inject)
  * as a prologue of the gradient's amax and cast: dy' = bf16(dy + g * p * sign(a) *
  * (|a| / (tau+eps))^(p-1) / (tau+eps)) is formed on the way into both passes and

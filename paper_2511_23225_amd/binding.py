@@ -25,7 +25,8 @@ EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quan
            "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled", "tweo_w8a8_linear_scaled_i8out",
            "tweo_quantize_e5m2_delayed", "tweo_fp8_linear_bwd_bf16_inject",
            "tweo_fp8_linear_fwd_static", "tweo_static_scratch_bytes",
-           "tweo_layernorm_quantize_e4m3", "tweo_layernorm_quantize_e4m3_delayed")
+           "tweo_layernorm_quantize_e4m3", "tweo_layernorm_quantize_e4m3_delayed",
+           "tweo_fp8_linear_fwd_bf16_delayed", "tweo_fp8_linear_bwd_bf16_delayed")
 
 
 class TweoError(RuntimeError):
@@ -71,6 +72,10 @@ def load():
     L.tweo_layernorm_quantize_e4m3.argtypes = [vp, vp, vp, vp, i64, i64, f32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.tweo_layernorm_quantize_e4m3_delayed.argtypes = [vp, vp, vp, vp, i64, i64, f32, vp, ctypes.c_int, vp, vp, vp,
                                                        vp, vp, sz, vp]
+    L.tweo_fp8_linear_fwd_bf16_delayed.argtypes = [vp, vp, vp, i64, i64, i64, vp, ctypes.POINTER(PenaltyCfg), vp,
+                                                   ctypes.POINTER(Fp8Saved), vp, vp, ctypes.c_int, vp, sz, vp]
+    L.tweo_fp8_linear_bwd_bf16_delayed.argtypes = [vp, ctypes.POINTER(Fp8Saved), vp, ctypes.c_int, ctypes.c_int, i64,
+                                                   i64, i64, vp, vp, vp, vp, vp, sz, vp]
     L.tweo_static_scratch_bytes.argtypes = []
     L.tweo_static_scratch_bytes.restype = ctypes.c_size_t
     L.tweo_fp8_linear_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
@@ -232,6 +237,27 @@ def tweo_layernorm_quantize_e4m3_delayed(x_bf16, gamma_bf16, state, q, workspace
                                                        1 if bootstrap else 0, _ptr(h_out_bf16), _ptr(y_out_bf16),
                                                        _ptr(q), _ptr(qT), wp, wb, _stream()),
            "tweo_layernorm_quantize_e4m3_delayed")
+
+
+def tweo_fp8_linear_fwd_bf16_delayed(x_bf16, w_bf16, y_bf16, saved, state_x, state_w, bootstrap=False,
+                                     residual_bf16=None, pen=None, penalty_sum=None, workspace=None):
+    M, K = x_bf16.shape
+    N = w_bf16.shape[0]
+    wp, wb = _ws(workspace)
+    _check(load().tweo_fp8_linear_fwd_bf16_delayed(_ptr(x_bf16), _ptr(w_bf16), _ptr(residual_bf16), M, N, K,
+                                                   _ptr(y_bf16), _pen(pen), _ptr(penalty_sum), ctypes.byref(saved),
+                                                   _ptr(state_x), _ptr(state_w), 1 if bootstrap else 0, wp, wb,
+                                                   _stream()), "tweo_fp8_linear_fwd_bf16_delayed")
+
+
+def tweo_fp8_linear_bwd_bf16_delayed(dy_bf16, saved, state_dy, K, dyq, dyqT, dx_bf16=None, dw_bf16=None,
+                                     workspace=None, bootstrap=False, dy_e5m2=False):
+    M, N = dy_bf16.shape
+    wp, wb = _ws(workspace)
+    _check(load().tweo_fp8_linear_bwd_bf16_delayed(_ptr(dy_bf16), ctypes.byref(saved), _ptr(state_dy),
+                                                   1 if bootstrap else 0, 1 if dy_e5m2 else 0, M, N, K, _ptr(dyq),
+                                                   _ptr(dyqT), _ptr(dx_bf16), _ptr(dw_bf16), wp, wb, _stream()),
+           "tweo_fp8_linear_bwd_bf16_delayed")
 
 
 def tweo_static_scratch_bytes():

@@ -612,6 +612,54 @@ tweo_status tweo_fp8_linear_bwd_bf16_hybrid(const void *dy_bf16, const tweo_fp8_
                                     workspace_bytes, stream, true);
 }
 
+tweo_status tweo_fp8_linear_fwd_bf16_delayed(const void *x_bf16, const void *w_bf16, const void *residual_bf16,
+                                             int64_t M, int64_t N, int64_t K, void *y_bf16,
+                                             const tweo_penalty_cfg *pen, double *penalty_sum,
+                                             const tweo_fp8_saved *saved, void *state_x, void *state_w,
+                                             int bootstrap, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x_bf16 || !w_bf16 || !y_bf16 || !saved || !saved->xq || !saved->xqT || !saved->wq || !saved->wqT ||
+        !saved->scalars || !state_x || !state_w || state_x == state_w || M <= 0 || N <= 0 || K <= 0 ||
+        !aligned16(x_bf16) || !aligned16(w_bf16) || !aligned16(saved->xq) || !aligned16(saved->xqT) ||
+        !aligned16(saved->wq) || !aligned16(saved->wqT) || !aligned16(saved->scalars) || !aligned16(state_x) ||
+        !aligned16(state_w))
+        return TWEO_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || M % 16 != 0 || N % 16 != 0 || K % 16 != 0)
+        return TWEO_ERR_UNSUPPORTED;
+    float *sc = saved->scalars;
+    // x and w share one cast launch and one state-update launch; the update leaves each tensor's
+    // amax, the scale its cast used and the inverse in the saved scalars (words 0-2 and 3-5)
+    hipError_t e = launch_quantize2_e4m3_delayed(x_bf16, M, K, state_x, saved->xq, saved->xqT, sc + 0, w_bf16, N, K,
+                                                 state_w, saved->wq, saved->wqT, sc + 3, bootstrap != 0,
+                                                 (hipStream_t)stream);
+    if (e != hipSuccess)
+        return TWEO_ERR_HIP;
+    return tweo_fp8_linear_fwd(saved->xq, sc + 2, saved->wq, sc + 5, residual_bf16, M, N, K, y_bf16, pen, penalty_sum,
+                               workspace, workspace_bytes, stream);
+}
+
+tweo_status tweo_fp8_linear_bwd_bf16_delayed(const void *dy_bf16, const tweo_fp8_saved *saved, void *state_dy,
+                                             int bootstrap, int dy_e5m2, int64_t M, int64_t N, int64_t K,
+                                             uint8_t *dyq, uint8_t *dyqT, void *dx_bf16, void *dw_bf16,
+                                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!dy_bf16 || !saved || !saved->xqT || !saved->wqT || !saved->scalars || !state_dy || !dyq || !dyqT ||
+        M <= 0 || N <= 0 || K <= 0 || !aligned16(dy_bf16) || !aligned16(dyq) || !aligned16(dyqT) ||
+        !aligned16(state_dy) || (dy_e5m2 != 0 && dy_e5m2 != 1))
+        return TWEO_ERR_INVALID_ARG;
+    if (!dims_ok(M, N, K) || M % 16 != 0 || N % 16 != 0 || K % 16 != 0)
+        return TWEO_ERR_UNSUPPORTED;
+    float *sc = saved->scalars;
+    hipError_t e = dy_e5m2 ? launch_quantize_e5m2_delayed(dy_bf16, M, N, state_dy, bootstrap != 0, dyq, dyqT,
+                                                          (hipStream_t)stream, sc + 6)
+                           : launch_quantize_e4m3_delayed(dy_bf16, M, N, state_dy, bootstrap != 0, dyq, dyqT,
+                                                          (hipStream_t)stream, sc + 6);
+    if (e != hipSuccess)
+        return TWEO_ERR_HIP;
+    return fp8_linear_bwd_impl(dyq, dyqT, sc + 8, saved->wqT, sc + 5, saved->xqT, sc + 2, M, N, K, dx_bf16, dw_bf16,
+                               workspace, workspace_bytes, stream, dy_e5m2 != 0);
+}
+
 tweo_status tweo_fp8_linear_bwd_bf16_inject(const void *dy_bf16, const void *a_bf16,
                                             const tweo_penalty_cfg *pen, float g, int dy_e5m2,
                                             const tweo_fp8_saved *saved, int64_t M, int64_t N, int64_t K,

@@ -477,41 +477,49 @@ struct LnArgs {
     const uint16_t *gamma, *beta;  // bf16 [cols]; beta may be nullptr
 };
 
-// fp64 -> fp32 with round-to-odd (truncate, then set the last bit if anything was lost): rounding
-// that result to bf16 with round-to-nearest-even is the single correct rounding of the fp64 value.
-__device__ __forceinline__ float f64_to_f32_round_odd(double v)
+// fp64 -> fp32 such that rounding the result to bf16 (round to nearest even) is the single correct
+// rounding of the fp64 value: the 29 mantissa bits that fp32 cannot hold are cut off and, if any
+// was set, the last bit that fp32 does hold is set ("round to odd"); the conversion is then exact,
+// and a value rounded to odd at 24 bits rounds to 8 bits like the original.  (Below the smallest
+// normal fp32, 1.2e-38, the conversion itself rounds again; a normalised activation is either an
+// exact zero or many orders of magnitude above that.)
+__device__ __forceinline__ float f64_to_f32_for_bf16(double v)
 {
-    float t = (float)v;
-    const double back = (double)t;
-    if (back != v && v == v) {
-        uint32_t tb = f32_to_bits(t);
-        if (__builtin_fabs(back) > __builtin_fabs(v))
-            tb -= 1u;  // one step towards zero (also from Inf to the largest finite value)
-        t = bits_to_f32(tb | 1u);
-    }
-    return t;
+    uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)b, cut = lo & 0x1FFFFFFFu;
+    const uint32_t lo2 = (lo & 0xE0000000u) | ((cut + 0x1FFFFFFFu) & 0x20000000u);
+    b = (b & 0xFFFFFFFF00000000ull) | lo2;
+    return (float)__builtin_bit_cast(double, b);
 }
 
-__device__ __forceinline__ float ln_one(float x, double mean, double rstd, float g, float b, bool has_beta)
+// eight elements of a row: y = (x - mean) * (rstd * gamma) + beta in fp64 (one rounding more or
+// less than the textbook order of operations: 1e-16 relative, far below anything a bf16 rounding
+// sees), as packed bf16 pairs.  g64 / b64: the eight columns' parameters, widened by the caller.
+__device__ __forceinline__ uint4 ln_vec(uint4 x, double mean, double rstd, const double (&g64)[8], const double (&b64)[8],
+                                        bool has_beta)
 {
-#pragma clang fp contract(off)
-    const double d = (double)x - mean;
-    double y = (d * rstd) * (double)g;
-    if (has_beta)
-        y = y + (double)b;
-    return f64_to_f32_round_odd(y);
-}
-
-// eight elements of a row: x, gamma and beta as packed bf16 pairs -> packed bf16 pairs of y
-__device__ __forceinline__ uint4 ln_vec(uint4 x, double mean, double rstd, uint4 g, uint4 b, bool has_beta)
-{
-    const uint32_t xx[4] = {x.x, x.y, x.z, x.w}, gg[4] = {g.x, g.y, g.z, g.w}, bb[4] = {b.x, b.y, b.z, b.w};
+    const uint32_t xx[4] = {x.x, x.y, x.z, x.w};
     uint32_t r[4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
-        r[k] = pack_bf16x2(ln_one(bf16lo_to_f32(xx[k]), mean, rstd, bf16lo_to_f32(gg[k]), bf16lo_to_f32(bb[k]), has_beta),
-                           ln_one(bf16hi_to_f32(xx[k]), mean, rstd, bf16hi_to_f32(gg[k]), bf16hi_to_f32(bb[k]), has_beta));
+    for (int k = 0; k < 4; ++k) {
+        const double d0 = (double)bf16lo_to_f32(xx[k]) - mean, d1 = (double)bf16hi_to_f32(xx[k]) - mean;
+        const double a0 = rstd * g64[2 * k], a1 = rstd * g64[2 * k + 1];
+        // without a beta nothing is added, so that a zero keeps the sign the product gives it
+        const double y0 = has_beta ? __builtin_fma(d0, a0, b64[2 * k]) : d0 * a0;
+        const double y1 = has_beta ? __builtin_fma(d1, a1, b64[2 * k + 1]) : d1 * a1;
+        r[k] = pack_bf16x2(f64_to_f32_for_bf16(y0), f64_to_f32_for_bf16(y1));
+    }
     return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
+__device__ __forceinline__ void widen8(uint4 v, double (&out)[8])
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        out[2 * k] = (double)bf16lo_to_f32(w[k]);
+        out[2 * k + 1] = (double)bf16hi_to_f32(w[k]);
+    }
 }
 
 // h = bf16(x + r) on eight elements: the fp32 sum of two bf16 values rounded to bf16 equals the
@@ -688,23 +696,38 @@ __device__ __forceinline__ void quantize_e4m3_16x16_body(
             const uint4 *src = (const uint4 *)(x + (r0 + half * 8 + i) * cols + c0);
             in[i][0] = src[0];
             in[i][1] = src[1];
-            if constexpr (LN) {
-                const double mean = ln.stats[2 * (r0 + half * 8 + i)], rstd = ln.stats[2 * (r0 + half * 8 + i) + 1];
-                in[i][0] = ln_vec(in[i][0], mean, rstd, lg[0], lb[0], ln.beta != nullptr);
-                in[i][1] = ln_vec(in[i][1], mean, rstd, lg[1], lb[1], ln.beta != nullptr);
-                if (!AMAX_ONLY && y_out != nullptr) {
-                    uint4 *dst = (uint4 *)(y_out + (r0 + half * 8 + i) * cols + c0);
-                    dst[0] = in[i][0];
-                    dst[1] = in[i][1];
-                }
-            }
             if constexpr (INJECT != 0) {
                 const uint4 *asrc = (const uint4 *)(inj.act + (r0 + half * 8 + i) * cols + c0);
                 in[i][0] = inject_vec<(INJECT == 4 ? 4 : 0)>(in[i][0], asrc[0], inj);
                 in[i][1] = inject_vec<(INJECT == 4 ? 4 : 0)>(in[i][1], asrc[1], inj);
             }
-            if constexpr (DELAYED)
+            if constexpr (DELAYED && !LN)
                 mx = pk_absmax4(pk_absmax4(mx, in[i][0]), in[i][1]);
+        }
+        if constexpr (LN) {
+            // normalise what was loaded, eight columns at a time (their widened parameters live
+            // only that long)
+#pragma unroll
+            for (int w = 0; w < 2; ++w) {
+                double g64[8], b64[8];
+                widen8(lg[w], g64);
+                widen8(lb[w], b64);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const double2 st = *(const double2 *)(ln.stats + 2 * (r0 + half * 8 + i));
+                    in[i][w] = ln_vec(in[i][w], st.x, st.y, g64, b64, ln.beta != nullptr);
+                    if constexpr (DELAYED)
+                        mx = pk_absmax4(mx, in[i][w]);
+                }
+            }
+            if (!AMAX_ONLY && y_out != nullptr) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    uint4 *dst = (uint4 *)(y_out + (r0 + half * 8 + i) * cols + c0);
+                    dst[0] = in[i][0];
+                    dst[1] = in[i][1];
+                }
+            }
         }
         if constexpr (AMAX_ONLY)
             continue;
@@ -951,24 +974,17 @@ __global__ void delayed_state_init_kernel(uint32_t *st)
 }
 
 // Consumes the accumulated amax: remembers the scale that was just used, pushes the amax into
-// the ring, derives the next scale, clears the accumulator.  One thread.
-__global__ void delayed_state_update_kernel(uint32_t *st, int bootstrap, float range,
-                                            const uint32_t *partials = nullptr, int n_partials = 0)
+// the ring, derives the next scale, clears the accumulator.  One thread.  sc_out (optional): three
+// fp32 of the caller's: this tensor's amax, the scale its cast uses / used, and its inverse.
+__device__ __forceinline__ void delayed_state_update(uint32_t *st, int bootstrap, float range, float *sc_out)
 {
-    if (threadIdx.x != 0 || blockIdx.x != 0)
-        return;
-    if (partials != nullptr) {  // the tensor's amax arrives as one maximum per workgroup of an earlier launch
-        uint32_t m = 0;
-        for (int i = 0; i < n_partials; ++i)
-            m = partials[i] > m ? partials[i] : m;
-        st[16] = m;
-    }
     int pos = (int)st[19], filled = (int)st[20];
     if (!bootstrap) {  // a bootstrap cast has not happened yet: nothing was "used"
         st[21] = st[17];
         st[22] = st[18];
     }
-    st[pos & 15] = st[16];
+    const uint32_t mine = st[16];
+    st[pos & 15] = mine;
     pos = (pos + 1) & 15;
     filled = filled < 16 ? filled + 1 : 16;
     uint32_t m = 0;
@@ -984,6 +1000,33 @@ __global__ void delayed_state_update_kernel(uint32_t *st, int bootstrap, float r
         st[21] = st[17];
         st[22] = st[18];
     }
+    if (sc_out != nullptr) {
+        sc_out[0] = bits_to_f32(mine);
+        sc_out[1] = bits_to_f32(st[21]);
+        sc_out[2] = bits_to_f32(st[22]);
+    }
+}
+
+__global__ void delayed_state_update_kernel(uint32_t *st, int bootstrap, float range,
+                                            const uint32_t *partials = nullptr, int n_partials = 0,
+                                            float *sc_out = nullptr)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0)
+        return;
+    if (partials != nullptr) {  // the tensor's amax arrives as one maximum per workgroup of an earlier launch
+        uint32_t m = 0;
+        for (int i = 0; i < n_partials; ++i)
+            m = partials[i] > m ? partials[i] : m;
+        st[16] = m;
+    }
+    delayed_state_update(st, bootstrap, range, sc_out);
+}
+
+// two states in one launch (the activation's and the weight's of a linear layer): block b, thread 0
+__global__ void delayed_state_update2_kernel(uint32_t *st0, float *sc0, uint32_t *st1, float *sc1, float range)
+{
+    if (threadIdx.x == 0)
+        delayed_state_update(blockIdx.x == 0 ? st0 : st1, 0, range, blockIdx.x == 0 ? sc0 : sc1);
 }
 
 hipError_t launch_delayed_state_init(void *state, hipStream_t s)
@@ -994,7 +1037,8 @@ hipError_t launch_delayed_state_init(void *state, hipStream_t s)
 
 template <bool E5M2>
 static hipError_t launch_quantize_f8_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
-                                             int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s)
+                                             int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s,
+                                             float *sc_out = nullptr)
 {
     float *st = (float *)state;
     const float range = E5M2 ? 57344.0f : 448.0f;
@@ -1005,7 +1049,7 @@ static hipError_t launch_quantize_f8_delayed(const void *x_bf16, int64_t rows, i
         if (e != hipSuccess)
             return e;
         hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 1, range,
-                           (const uint32_t *)nullptr, 0);
+                           (const uint32_t *)nullptr, 0, sc_out);
         e = hipGetLastError();
         if (e != hipSuccess)
             return e;
@@ -1018,20 +1062,71 @@ static hipError_t launch_quantize_f8_delayed(const void *x_bf16, int64_t rows, i
     if (e != hipSuccess)
         return e;
     hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 0, range,
-                       (const uint32_t *)nullptr, 0);
+                       (const uint32_t *)nullptr, 0, sc_out);
     return hipGetLastError();
 }
 
 hipError_t launch_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
-                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s)
+                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s, float *sc_out)
 {
-    return launch_quantize_f8_delayed<false>(x_bf16, rows, cols, state, bootstrap, q, qT, s);
+    return launch_quantize_f8_delayed<false>(x_bf16, rows, cols, state, bootstrap, q, qT, s, sc_out);
 }
 
 hipError_t launch_quantize_e5m2_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
-                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s)
+                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s, float *sc_out)
 {
-    return launch_quantize_f8_delayed<true>(x_bf16, rows, cols, state, bootstrap, q, qT, s);
+    return launch_quantize_f8_delayed<true>(x_bf16, rows, cols, state, bootstrap, q, qT, s, sc_out);
+}
+
+// The activation and the weight of a linear layer under delayed scaling in one cast launch and one
+// state-update launch (each tensor with its transposed copy; rows, cols multiples of 16).
+struct QuantTensorDelayed {
+    const uint16_t *x;
+    int64_t rows, cols, tiles_x;
+    const float *scale;
+    uint8_t *q, *qT;
+    uint32_t *amax_acc;
+};
+
+__global__ __launch_bounds__(kQuantThreads) void quantize2_delayed_16x16_kernel(QuantTensorDelayed t0, int64_t blocks0,
+                                                                                QuantTensorDelayed t1, int64_t blocks1)
+{
+    const bool first = (int64_t)blockIdx.x < blocks0;
+    const QuantTensorDelayed &t = first ? t0 : t1;
+    quantize_e4m3_16x16_body<true, true>(t.x, t.rows, t.cols, t.tiles_x, t.scale, t.q, t.qT, nullptr, nullptr, t.amax_acc,
+                                         first ? (int64_t)blockIdx.x : (int64_t)blockIdx.x - blocks0,
+                                         first ? blocks0 : blocks1);
+}
+
+hipError_t launch_quantize2_e4m3_delayed(const void *x0_bf16, int64_t rows0, int64_t cols0, void *state0, uint8_t *q0,
+                                         uint8_t *q0T, float *sc0, const void *x1_bf16, int64_t rows1, int64_t cols1,
+                                         void *state1, uint8_t *q1, uint8_t *q1T, float *sc1, int bootstrap,
+                                         hipStream_t s)
+{
+    if (bootstrap) {  // empty histories: each tensor's own amax first (once per state)
+        hipError_t e = launch_quantize_f8_delayed<false>(x0_bf16, rows0, cols0, state0, 1, q0, q0T, s, sc0);
+        if (e != hipSuccess)
+            return e;
+        return launch_quantize_f8_delayed<false>(x1_bf16, rows1, cols1, state1, 1, q1, q1T, s, sc1);
+    }
+    auto tiles = [](int64_t v) { return (v + kQuantBigTile - 1) / kQuantBigTile; };
+    float *st0 = (float *)state0, *st1 = (float *)state1;
+    QuantTensorDelayed t0{(const uint16_t *)x0_bf16, rows0, cols0, tiles(cols0), st0 + 17, q0, q0T, (uint32_t *)st0 + 16};
+    QuantTensorDelayed t1{(const uint16_t *)x1_bf16, rows1, cols1, tiles(cols1), st1 + 17, q1, q1T, (uint32_t *)st1 + 16};
+    // a bounded grid (its one atomic per workgroup stays a few hundred per tensor), shared out in
+    // proportion to the tile counts
+    const int64_t n0 = tiles(rows0) * tiles(cols0), n1 = tiles(rows1) * tiles(cols1);
+    int64_t b1 = (int64_t)(1024.0 * (double)n1 / (double)(n0 + n1) + 0.5);
+    b1 = b1 < 1 ? 1 : (b1 > n1 ? n1 : b1);
+    int64_t b0 = 1024 - b1;
+    b0 = b0 < 1 ? 1 : (b0 > n0 ? n0 : b0);
+    hipLaunchKernelGGL(quantize2_delayed_16x16_kernel, dim3((unsigned)(b0 + b1)), dim3(kQuantThreads), 0, s, t0, b0, t1, b1);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return e;
+    hipLaunchKernelGGL(delayed_state_update2_kernel, dim3(2), dim3(64), 0, s, (uint32_t *)state0, sc0, (uint32_t *)state1,
+                       sc1, 448.0f);
+    return hipGetLastError();
 }
 
 // LayerNorm -> per-tensor E4M3 cast (Sec. 4.3).  Launches: row statistics (2 B/element from
@@ -1089,7 +1184,7 @@ hipError_t launch_layernorm_quantize(const void *x_bf16, const void *res_bf16, c
     }
     if (bootstrap) {  // empty history: the tensor's own amax makes the scale
         hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 1, 448.0f,
-                           (const uint32_t *)partials, (int)bounded);
+                           (const uint32_t *)partials, (int)bounded, (float *)nullptr);
         if ((e = hipGetLastError()) != hipSuccess)
             return e;
     }
@@ -1108,7 +1203,7 @@ hipError_t launch_layernorm_quantize(const void *x_bf16, const void *res_bf16, c
         return e;
     if (!bootstrap)
         hipLaunchKernelGGL(delayed_state_update_kernel, dim3(1), dim3(64), 0, s, (uint32_t *)state, 0, 448.0f,
-                           (const uint32_t *)nullptr, 0);
+                           (const uint32_t *)nullptr, 0, (float *)nullptr);
     return hipGetLastError();
 }
 

@@ -41,11 +41,20 @@ hipError_t launch_quantize_e5m2(const void *x_bf16, int64_t rows, int64_t cols, 
                                 uint8_t *q, uint8_t *qT, float *scale_out, float *scale_inv_out,
                                 hipStream_t s);
 hipError_t launch_delayed_state_init(void *state, hipStream_t s);
+// sc_out (optional): three fp32 of the caller's - the tensor's amax, the scale its cast used, its inverse
 hipError_t launch_quantize_e4m3_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
-                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s);
+                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s,
+                                        float *sc_out = nullptr);
 // the same for a tensor cast to E5M2 (gradients of the HYBRID recipe): scale = 57344 / max(history)
 hipError_t launch_quantize_e5m2_delayed(const void *x_bf16, int64_t rows, int64_t cols, void *state,
-                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s);
+                                        int bootstrap, uint8_t *q, uint8_t *qT, hipStream_t s,
+                                        float *sc_out = nullptr);
+// two tensors (rows, cols multiples of 16; transposed copies required) on their two states: one
+// cast launch and one state-update launch
+hipError_t launch_quantize2_e4m3_delayed(const void *x0_bf16, int64_t rows0, int64_t cols0, void *state0, uint8_t *q0,
+                                         uint8_t *q0T, float *sc0, const void *x1_bf16, int64_t rows1, int64_t cols1,
+                                         void *state1, uint8_t *q1, uint8_t *q1T, float *sc1, int bootstrap,
+                                         hipStream_t s);
 // LayerNorm of x (or of h = bf16(x + res), stored to h_out) followed by the per-tensor E4M3 cast of
 // the normalised tensor; state == nullptr: current scaling (amax_out required), else delayed
 // scaling on that state.  stats: 2 doubles per row, partials: kAmaxPartialsMax words of scratch.

@@ -189,6 +189,32 @@ def test_layernorm_quantize_full_size(shape):
     assert np.array_equal(gqT[~flips.T], oqT[~flips.T])
 
 
+def test_layernorm_degenerate_rows():
+    # constant rows (variance 0: every normalised value is a zero whose sign the gain decides), an
+    # all-zero tensor and eps = 0 on a two-valued row
+    rows, cols = 16, 64
+    x = np.full((rows, cols), 5.5, np.float32)
+    x[1] = 0.0
+    x[2] = np.where(np.arange(cols) % 2 == 0, 3.0, -1.0)
+    gamma = np.where(np.arange(cols) % 3 == 0, -1.5, 0.75).astype(np.float32)
+    for beta in (None, np.linspace(-1, 1, cols).astype(np.float32)):
+        for eps in (np.float32(1e-5), np.float32(0.0)):
+            if eps == 0.0:
+                x[:] = x[2]   # eps = 0 needs a positive variance in every row
+            xb, gb = synth.f32_to_bf16_bits(x), synth.f32_to_bf16_bits(gamma)
+            bb = None if beta is None else synth.f32_to_bf16_bits(beta)
+            y64, yb = oracle.layernorm(xb, gb, bb, float(eps))
+            scale, _ = oracle.scale_from_amax(oracle.amax_bf16(yb))
+            oq, _ = oracle.quantize_e4m3(yb, scale, transpose=False)
+            q = torch.full((rows, cols), 0x55, dtype=torch.uint8, device=DEV)
+            y = torch.full((rows, cols), float("nan"), dtype=torch.bfloat16, device=DEV)
+            tw.tweo_layernorm_quantize_e4m3(to_dev_bf16(xb), to_dev_bf16(gb), q, ws_for(rows), eps=eps,
+                                            beta_bf16=None if bb is None else to_dev_bf16(bb), y_out_bf16=y)
+            torch.cuda.synchronize()
+            assert np.array_equal(bf16_bits(y), yb), (beta is None, eps)
+            assert np.array_equal(q.cpu().numpy(), oq), (beta is None, eps)
+
+
 def test_layernorm_error_paths():
     x = torch.zeros((16, 16), dtype=torch.bfloat16, device=DEV)
     g = torch.ones((16,), dtype=torch.bfloat16, device=DEV)
