@@ -465,7 +465,12 @@ tweo_status tweo_fp8_linear_bwd_bf16_inject(const void *dy_bf16, const void *a_b
  * K a multiple of 128 and at least 512, no residual, p in {0, 4}); it falls back
  * to variant 11 otherwise.  Variant 16 is the same kernel on 192x256 tiles (any
  * M, N a multiple of 256, K a multiple of 128 and at least 2048); it falls back
- * to variant 14 otherwise.
+ * to variant 14 otherwise.  Variant 17 (INT8 only, M <= 64, K % 64 == 0, K >= 1024,
+ * N % 4 == 0) is the weight-streaming kernel that stages X through LDS; elsewhere
+ * it means variant 4.  These three setters and tweo_profile_gemm_launches are test
+ * and measurement knobs: they change which kernel ANY caller's next launch takes
+ * and what tweo_workspace_bytes() returns, so set them before sizing workspaces,
+ * from one thread, and never in production code.
  */
 tweo_status tweo_set_gemm_tile(int variant);
 

@@ -1359,6 +1359,182 @@ __global__ __launch_bounds__(WAVES * 64) void w8a8_skinny_resident_kernel(const 
     }
 }
 
+// The same contraction with X staged through LDS.  In the MFMA operand layout a 16-lane group of
+// a load instruction touches 16 different rows, 16 bytes of each: the texture unit then moves 16
+// bytes per clock and CU, about 25 GB/s per CU, and at M = 64 a workgroup reads more bytes of X
+// (all of it, from the L2) than of its own weight rows (measured: time = (weights + CUs x X) /
+// 6.5 TB/s for every shape and M).  Here a chunk of X (all M rows x KCH bytes of K) is fetched by
+// direct-to-LDS loads in which a wave reads 1 KB of one row, i.e. whole 128-byte lines, once per
+// workgroup; the fragments then come out of LDS (rows padded by 16 bytes: conflict free).  The
+// weight rows are used once, so they still go straight to registers.  Per chunk: X of chunk c + 1
+// and the weights of chunk c + 2 are in flight while chunk c is multiplied; one barrier.
+template <int MB, int NB, int XC, bool VEC>
+__global__ __launch_bounds__(512) void w8a8_skinny_lds_kernel(const int8_t *__restrict__ X,
+                                                              const int8_t *__restrict__ W, int M, int N, int K,
+                                                              float alpha, StepVectors sv, uint16_t *__restrict__ Y)
+{
+    constexpr int WAVES = 8, STEP = 64, KCH = XC * WAVES * STEP, PITCH = KCH + 16, ROWS = MB * 16;
+    constexpr int BUF = ROWS * PITCH, PARTS = KCH / 1024, PPW = ROWS * PARTS / WAVES, WSET = XC * NB;
+    static_assert(KCH % 1024 == 0 && (ROWS * PARTS) % WAVES == 0, "whole 1 KB pieces, shared out evenly");
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // two X buffers; the reduction reuses them
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int r16 = lane & 15, kc = lane >> 4;
+    const int steps = K / STEP, blocks = (N + 15) / 16, grid = gridDim.x;
+    const int chunks = (K + KCH - 1) / KCH;
+    // workgroups walk the chunks in rotated orders (they all read the same X)
+    const int rot = (int)((blockIdx.x >> 3) % (unsigned)chunks);
+    auto chunk_at = [&](int c) { const int r = c + rot; return r < chunks ? r : r - chunks; };
+    // one wave instruction moves 1 KB of one row of X: lane l the 16 bytes at k = l * 16 of the piece.
+    // Pieces that reach past K (last chunk) read the row's first bytes instead: the steps they
+    // would feed are masked below.
+    auto dma_chunk = [&](int cc, int buf) {
+#pragma unroll
+        for (int i = 0; i < PPW; ++i) {
+            const int p = i * WAVES + wave, row = p / PARTS, part = p % PARTS;
+            const int m = row < M ? row : M - 1;
+            int k = cc * KCH + part * 1024 + lane * 16;
+            k = k + 16 <= K ? k : lane * 16 % K;
+            dma_load16(lds_base + buf * BUF + row * PITCH + part * 1024, (const uint8_t *)X + (int64_t)m * K, (uint32_t)k);
+        }
+    };
+    for (int first = blockIdx.x; first < blocks; first += NB * grid) {
+        const int8_t *wrow[NB];
+#pragma unroll
+        for (int a = 0; a < NB; ++a) {
+            int blk = first + a * grid;
+            blk = blk < blocks ? blk : blocks - 1;  // block slots past the end: duplicates, never stored
+            int n = blk * 16 + r16;
+            n = n < N ? n : N - 1;
+            wrow[a] = W + (int64_t)n * K + kc * 16;
+        }
+        v4i acc[NB][MB];
+#pragma unroll
+        for (int a = 0; a < NB; ++a)
+#pragma unroll
+            for (int b = 0; b < MB; ++b)
+                acc[a][b] = v4i{0, 0, 0, 0};
+        v4i wf[3][XC][NB];
+        // wave w owns the steps w * XC .. w * XC + XC - 1 of a chunk; steps past K read step 0 and are masked
+        // The weight loads are inline asm, like the X loads: the compiler then inserts no waits of
+        // its own for them (its bookkeeping of three rotating register sets across the loop's back
+        // edge made every third chunk wait for the loads it had just issued), and the one explicit
+        // wait per chunk below covers both.  A set is not touched between its loads and that wait.
+        auto load_w = [&](int cc, v4i(&wb)[XC][NB]) {
+#pragma unroll
+            for (int u = 0; u < XC; ++u) {
+                const int su = (cc * WAVES + wave) * XC + u;
+                const int koff = (su < steps ? su : 0) * STEP;
+#pragma unroll
+                for (int a = 0; a < NB; ++a)
+                    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(wb[u][a]) : "v"(wrow[a] + koff) : "memory");
+            }
+        };
+        auto multiply = [&](int cc, int buf, v4i(&wb)[XC][NB]) {
+            v4i xf[XC][MB];
+#pragma unroll
+            for (int u = 0; u < XC; ++u)
+#pragma unroll
+                for (int a = 0; a < NB; ++a)
+                    asm volatile("" : "+v"(wb[u][a]));  // used from here on, behind the wait and the barrier
+#pragma unroll
+            for (int u = 0; u < XC; ++u) {
+                const bool ok = (cc * WAVES + wave) * XC + u < steps;
+#pragma unroll
+                for (int b = 0; b < MB; ++b) {
+                    const v4i v = *(const v4i *)(smem + buf * BUF + (b * 16 + r16) * PITCH + (wave * XC + u) * STEP + kc * 16);
+                    xf[u][b] = ok ? v : v4i{0, 0, 0, 0};
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < XC; ++u)
+#pragma unroll
+                for (int a = 0; a < NB; ++a)
+#pragma unroll
+                    for (int b = 0; b < MB; ++b)
+                        // first operand -> register index (n), second -> lane%16 (m)
+                        acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wb[u][a], xf[u][b], acc[a][b], 0, 0, 0);
+        };
+        // iteration c: X of chunk c + 1 (direct to LDS) and then the weights of chunk c + 2 are
+        // requested, chunk c is multiplied, and the wait in front of the barrier leaves exactly
+        // the youngest weight set in flight
+        auto iteration = [&](int c, v4i(&w_cur)[XC][NB], v4i(&w_nxt2)[XC][NB]) {
+            if (c + 1 < chunks)
+                dma_chunk(chunk_at(c + 1), (c + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (c + 2 < chunks)
+                load_w(chunk_at(c + 2), w_nxt2);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(chunk_at(c), c & 1, w_cur);
+            __builtin_amdgcn_sched_barrier(0);
+            if (c + 2 < chunks)
+                wait_vmcnt<WSET>();
+            else
+                wait_vmcnt<0>();
+            block_barrier();
+        };
+        __syncthreads();  // the buffers are free (previous pass: reduction)
+        dma_chunk(chunk_at(0), 0);
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(chunk_at(0), wf[0]);
+        if (chunks > 1)
+            load_w(chunk_at(1), wf[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        wait_vmcnt<0>();
+        block_barrier();
+        for (int c = 0; c < chunks; c += 3) {
+            iteration(c, wf[0], wf[2]);
+            if (c + 1 < chunks)
+                iteration(c + 1, wf[1], wf[0]);
+            if (c + 2 < chunks)
+                iteration(c + 2, wf[2], wf[1]);
+        }
+        // acc[v] of lane l is C[n = 4*(l/16) + v, m = l%16] of its 16x16 block
+        v4i(*red)[MB][kWave] = (v4i(*)[MB][kWave])smem;
+#pragma unroll
+        for (int a = 0; a < NB; ++a) {
+            const int blk = first + a * grid;
+            if (a > 0)
+                __syncthreads();
+#pragma unroll
+            for (int b = 0; b < MB; ++b)
+                red[wave][b][lane] = acc[a][b];
+            __syncthreads();
+            if (blk >= blocks)
+                continue;  // uniform over the workgroup
+            for (int t = tid; t < MB * kWave; t += WAVES * kWave) {
+                const int b = t / kWave, l = t % kWave;
+                v4i sum = red[0][b][l];
+#pragma unroll
+                for (int w = 1; w < WAVES; ++w)
+                    sum += red[w][b][l];
+                const int m = b * 16 + (l & 15), n = blk * 16 + 4 * (l >> 4);
+                if (m < M && n < N) {
+                    float y[4];
+                    if constexpr (VEC) {
+                        const float rstep = sv.rs[(int64_t)m * sv.rs_stride];
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            y[v] = ((float)sum[v] * rstep) * sv.cs[(int64_t)(n + v) * sv.cs_stride];
+                        if (sv.out_i8) {
+                            *(uint32_t *)((uint8_t *)Y + (int64_t)m * N + n) =
+                                round_to_i8(y[0], sv.out_inv_step) | (round_to_i8(y[1], sv.out_inv_step) << 8) |
+                                (round_to_i8(y[2], sv.out_inv_step) << 16) | (round_to_i8(y[3], sv.out_inv_step) << 24);
+                            continue;
+                        }
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            y[v] = (float)sum[v] * alpha;
+                    }
+                    *(uint2 *)(Y + (int64_t)m * N + n) = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+                }
+            }
+        }
+    }
+}
+
 // Second half of a K split: out = bf16((*s0 * *s1) * (((p_0 + p_1) + p_2) + ...)), the runs added
 // in index order (the result does not depend on which workgroup finished first).
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partials, int splits,
@@ -1445,9 +1621,9 @@ size_t stream_k_workspace_bytes()
 // (K % 128 == 0): 256x256, 256x128, 128x128, 192x256.  15: deferred-epilogue persistent kernel
 // (256x256, four waves; M, N % 256 == 0, K % 128 == 0, K >= 512).  16: the same kernel on 192x256
 // tiles (any M, K >= 2048).
-constexpr int kNumVariants = 16;
-static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256, 256, 128, 256, 128, 256, 256, 128, 192, 256, 192};
-static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128, 256, 256, 256};
+constexpr int kNumVariants = 17;
+static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256, 256, 128, 256, 128, 256, 256, 128, 192, 256, 192, 64};
+static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128, 256, 256, 256, 64};
 int gemm_num_variants() { return kNumVariants; }
 
 static int num_cus();
@@ -1477,7 +1653,7 @@ static int defer_workgroups(int64_t M, int64_t N, int bm = 256)
 static int pick_variant(int64_t M, int64_t N, int64_t K)
 {
     auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-    int v = g_tile_override;
+    int v = g_tile_override >= 17 ? 4 : g_tile_override;
     if (v == 0) {
         if (M * N <= 128 * 128 * 16) {
             v = 4;
@@ -1950,8 +2126,67 @@ static hipError_t launch_skinny_resident(const GemmArgs &a, hipStream_t s, int w
     return hipGetLastError();
 }
 
+template <int MB, int NB, int XC>
+static hipError_t launch_skinny_lds(const GemmArgs &a, hipStream_t s)
+{
+    constexpr int KCH = XC * 8 * 64, BUF = MB * 16 * (KCH + 16);
+    constexpr int RED = 8 * MB * 64 * 16;
+    constexpr int LDS = 2 * BUF > RED ? 2 * BUF : RED;
+    static_assert(LDS <= 160 * 1024, "LDS capacity");
+    static bool attr_done[2] = {false, false};
+    const int vec = a.row_step != nullptr ? 1 : 0;
+    const void *kern = vec ? (const void *)w8a8_skinny_lds_kernel<MB, NB, XC, true>
+                           : (const void *)w8a8_skinny_lds_kernel<MB, NB, XC, false>;
+    if (!attr_done[vec]) {
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess)
+            return e;
+        attr_done[vec] = true;
+    }
+    const int blocks = (int)((a.N + 15) / 16);
+    int grid = num_cus();
+    if (grid > blocks)
+        grid = blocks;
+    const StepVectors sv{a.row_step, a.col_step, a.row_step_stride, a.col_step_stride, a.out_i8 ? 1 : 0, a.out_inv_step};
+    if (vec)
+        launch_gemm_kernel(w8a8_skinny_lds_kernel<MB, NB, XC, true>, dim3((unsigned)grid), dim3(512), LDS, s,
+                           (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
+                           (uint16_t *)a.out);
+    else
+        launch_gemm_kernel(w8a8_skinny_lds_kernel<MB, NB, XC, false>, dim3((unsigned)grid), dim3(512), LDS, s,
+                           (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
+                           (uint16_t *)a.out);
+    return hipGetLastError();
+}
+
+template <int MB, int XC>
+static hipError_t launch_skinny_lds_nb(const GemmArgs &a, hipStream_t s)
+{
+    const int64_t blocks = (a.N + 15) / 16, cus = num_cus();
+    const int64_t per = (blocks + cus - 1) / cus;
+    if (per <= 1)
+        return launch_skinny_lds<MB, 1, XC>(a, s);
+    if (per == 2)
+        return launch_skinny_lds<MB, 2, XC>(a, s);
+    if (per == 3)
+        return launch_skinny_lds<MB, 3, XC>(a, s);
+    return launch_skinny_lds<MB, 4, XC>(a, s);
+}
+
 hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s)
 {
+    // Small M with a lot of X per workgroup (M > 32, or a long K): X staged through LDS.  Measured
+    // cold at the 7B shapes (us, M = 16 / 32 / 64): 11008 -> 4096: 13.6 / 15.5 / 20.5 against 17.0 /
+    // 28.6 / 32.4 for the kernels below; 4096 -> 12288: 13.7 / 14.3 / 17.0 against 12.0 / 13.9 / 17.9.
+    const bool lds_x = a.M <= 64 && a.K % 64 == 0 && a.N % 4 == 0 && a.K >= 1024 &&
+                       (a.M > 32 || (a.M >= 4 && a.K > 64 * 8 * 8));
+    if ((g_tile_override == 0 && lds_x) || (g_tile_override == 17 && a.M <= 64 && a.K % 64 == 0 && a.N % 4 == 0 && a.K >= 1024)) {
+        if (a.M <= 16)
+            return launch_skinny_lds_nb<1, 4>(a, s);
+        if (a.M <= 32)
+            return launch_skinny_lds_nb<2, 2>(a, s);
+        return launch_skinny_lds_nb<4, 2>(a, s);
+    }
     // 4 <= M <= 64, K within what a workgroup's registers hold of X, several 16-row blocks of W per
     // workgroup to walk over.  Measured at K = 4096, N = 12288: 10.3 / 11.1 / 13.1 / 17.3 us for
     // M = 4 / 16 / 32 / 64 against 10.9 / 13.5 / 18.5 / 19.4 for the per-block kernel below, which

@@ -82,6 +82,32 @@ def test_w8a8_resident_activation_kernel_bit_exact(shape):
     assert np.array_equal(bf16_bits(y), oracle.w8a8_linear(oxq, owq, alpha))
 
 
+@pytest.mark.parametrize("shape", [(1, 1024, 24), (5, 1088, 48), (16, 4160, 4104), (17, 1024, 200), (33, 11008, 72),
+                                   (64, 11008, 4104), (64, 2048, 16384), (8, 1024, 20480), (40, 3072, 12288),
+                                   (64, 1024, 8), (32, 5120, 5000)])
+def test_w8a8_lds_staged_activation_kernel_bit_exact(shape):
+    # the weight-streaming kernel that stages X through LDS (forced: variant 17): every M block
+    # count, 1 to 4 weight blocks per workgroup and a second pass (20480 rows), K that ends inside
+    # a chunk (1088, 4160, 11008, 5120), ragged M and N
+    M, K, N = shape
+    say("w8a8 lds-staged M=%d K=%d N=%d" % (M, K, N))
+    x, w = synth.w8a8_inputs(0, M, K=K, N=N)
+    ax, aw = oracle.amax_bf16(x), oracle.amax_bf16(w)
+    inv_x, inv_w = np.float32(127.0) / ax, np.float32(127.0) / aw
+    alpha = (ax / np.float32(127.0)) * (aw / np.float32(127.0))
+    oxq, owq = oracle.quantize_i8(x, inv_x), oracle.quantize_i8(w, inv_w)
+    want = oracle.w8a8_linear(oxq, owq, alpha)
+    for rep in range(2):
+        y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)  # poisoned
+        tw.tweo_set_gemm_tile(17)
+        try:
+            tw.tweo_w8a8_linear(to_dev(oxq), to_dev(owq), alpha, y, workspace(tw.TWEO_OP_W8A8_LINEAR, M, N, K))
+            torch.cuda.synchronize()
+        finally:
+            tw.tweo_set_gemm_tile(0)
+        assert np.array_equal(bf16_bits(y), want)
+
+
 def test_w8a8_stream_k_bit_exact():
     # 64 tiles, long K, K-split switched on: int32 partial accumulators are added exactly, so the
     # result is the same bits as the plain schedule's and the oracle's

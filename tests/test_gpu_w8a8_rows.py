@@ -118,6 +118,26 @@ def test_scaled_linear_bit_exact(shape, gran):
     assert np.array_equal(got, oracle.w8a8_linear_scaled(xq, wq, sx, sw))
 
 
+@pytest.mark.parametrize("gran", ["KC", "TT"])
+@pytest.mark.parametrize("shape", [(5, 1088, 48), (33, 11008, 72), (64, 2048, 16384), (16, 4160, 4104)])
+def test_scaled_linear_lds_staged_kernel(shape, gran):
+    # the same through the weight-streaming kernel that stages X through LDS (variant 17), bf16 and INT8 outputs
+    M, K, N = shape
+    say("w8a8 scaled lds-staged M=%d K=%d N=%d %s" % (M, K, N, gran))
+    xq, wq, sx, sw = quantised(M, K, N, gran)
+    assert np.array_equal(run_scaled(xq, wq, sx, sw, tile=17), oracle.w8a8_linear_scaled(xq, wq, sx, sw))
+    inv_out = np.float32(127.0) / np.float32(1.5)
+    yq = torch.full((M, N), 99, dtype=torch.int8, device=DEV)
+    tw.tweo_set_gemm_tile(17)
+    try:
+        tw.tweo_w8a8_linear_scaled_i8out(to_dev(xq), to_dev(wq), to_dev(np.atleast_1d(sx).astype(np.float32)),
+                                         to_dev(np.atleast_1d(sw).astype(np.float32)), inv_out, yq)
+        torch.cuda.synchronize()
+    finally:
+        tw.tweo_set_gemm_tile(0)
+    assert np.array_equal(yq.cpu().numpy(), oracle.w8a8_linear_scaled_i8out(xq, wq, sx, sw, inv_out))
+
+
 @pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 8, 11, 12, 13, 14, 15, 16])
 @pytest.mark.parametrize("shape", [(200, 512, 392), (768, 2048, 512)])
 def test_scaled_linear_every_tiled_kernel(shape, tile):
