@@ -452,25 +452,24 @@ tweo_status tweo_fp8_linear_bwd_bf16_inject(const void *dy_bf16, const void *a_b
 
 /*
  * Tuning hook for benchmarks and tests: forces the GEMM kernel variant.
- * 0 = choose from the shape (the default).  1-4 = register-staged kernel, tiles
- * 256x256, 256x128, 128x128, 64x64 (any K % 16 == 0).  5-10 = DMA-pipelined
- * kernel with 64-byte stages (K % 64 == 0): 256x256 with 4 waves, with 8 waves,
- * 256x128, 128x128, and 256x128 / 128x256 at two workgroups per CU.  11-14 =
+ * 0 = choose from the shape (the default).  1, 3, 4 = register-staged kernel, tiles
+ * 256x256, 128x128, 64x64 (any K % 16 == 0).  6, 8 = DMA-pipelined kernel with
+ * 64-byte stages (K % 64 == 0): 256x256 with 8 waves, 128x128.  11, 13, 14 =
  * persistent streaming kernel with 128-byte stages (K % 128 == 0): 256x256,
- * 256x128, 128x128, 192x256.  A variant whose K requirement is not met falls
- * back to the nearest one that fits.  Process-wide, not thread safe.  Results
- * are identical up to the fp32 summation order.  Returns
- * TWEO_ERR_INVALID_ARG for an unknown variant.  Variant 15 is the
- * deferred-epilogue persistent kernel (256x256 tiles, M and N multiples of 256,
- * K a multiple of 128 and at least 512, no residual, p in {0, 4}); it falls back
- * to variant 11 otherwise.  Variant 16 is the same kernel on 192x256 tiles (any
- * M, N a multiple of 256, K a multiple of 128 and at least 2048); it falls back
- * to variant 14 otherwise.  Variant 17 (INT8 only, M <= 64, K % 64 == 0, K >= 1024,
- * N % 4 == 0) is the weight-streaming kernel that stages X through LDS; elsewhere
- * it means variant 4.  These three setters and tweo_profile_gemm_launches are test
- * and measurement knobs: they change which kernel ANY caller's next launch takes
- * and what tweo_workspace_bytes() returns, so set them before sizing workspaces,
- * from one thread, and never in production code.
+ * 128x128, 192x256.  15 = the deferred-epilogue persistent kernel (256x256 tiles, M
+ * and N multiples of 256, K a multiple of 128 and at least 512, no residual, p in
+ * {0, 4}); it falls back to variant 11 otherwise.  16 = the same kernel on 192x256
+ * tiles (any M, N a multiple of 256, K a multiple of 128 and at least 2048); it
+ * falls back to variant 14 otherwise.  17 (INT8 only, M <= 64, K % 64 == 0,
+ * K >= 1024, N % 4 == 0) = the weight-streaming kernel that stages X through LDS;
+ * elsewhere it means variant 4.  A variant whose K requirement is not met falls
+ * back to the nearest one that fits.  Results are identical up to the fp32
+ * summation order.  Returns TWEO_ERR_INVALID_ARG for an unknown (or retired:
+ * 2, 5, 7, 9, 10, 12) variant.
+ * This setter, tweo_set_stream_k and tweo_profile_gemm_launches are test and
+ * measurement knobs: process-wide, not thread safe; they change which kernel ANY
+ * caller's next launch takes and what tweo_workspace_bytes() returns, so set them
+ * before sizing workspaces, from one thread, and never in production code.
  */
 tweo_status tweo_set_gemm_tile(int variant);
 

@@ -74,7 +74,7 @@ tweo_status tweo_profile_gemm_launches(void *const *events, int pairs)
 
 tweo_status tweo_set_gemm_tile(int variant)
 {
-    if (variant < 0 || variant > gemm_num_variants())
+    if (!gemm_variant_exists(variant))
         return TWEO_ERR_INVALID_ARG;
     set_gemm_tile_override(variant);
     return TWEO_OK;

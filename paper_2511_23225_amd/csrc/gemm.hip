@@ -1558,17 +1558,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 // host side
 
 typedef Tile<256, 256, 2, 2> T256x256;
-typedef Tile<256, 128, 2, 2> T256x128;
 typedef Tile<128, 128, 2, 2> T128x128;
 typedef Tile<64, 64, 1, 1> T64x64;
-typedef TileD<256, 256, 2, 2, 4> D256x256w4;
 typedef TileD<256, 256, 2, 4, 4, 2> D256x256w8;
-typedef TileD<256, 128, 2, 2, 4> D256x128w4;
 typedef TileD<128, 128, 2, 2, 4, 2> D128x128w4;
-typedef TileD<256, 128, 2, 2, 3, 2> D256x128o2;  // two workgroups per CU
-typedef TileD<128, 256, 2, 2, 3, 2> D128x256o2;
 typedef TileS<256, 256, 2, 4, 2, 2> S256x256w8;  // persistent, 8 waves, one workgroup per CU
-typedef TileS<256, 128, 2, 2, 3, 1> S256x128w4;
 typedef TileS<128, 128, 2, 2, 2, 2> S128x128w4;  // two workgroups per CU
 typedef TileS<192, 256, 2, 4, 2, 2> S192x256w8;  // for tile counts that 256x256 quantises badly
 
@@ -1616,15 +1610,21 @@ size_t stream_k_workspace_bytes()
     return kStreamKCounterBytes + (size_t)2 * num_cus_public() * 256 * 256 * 4;
 }
 
-// Kernel variants.  1-4: register-staged kernel (any K % 16 == 0), tiles 256x256, 256x128,
-// 128x128, 64x64.  5-10: DMA-pipelined kernel (K % 64 == 0).  11-14: persistent streaming kernel
-// (K % 128 == 0): 256x256, 256x128, 128x128, 192x256.  15: deferred-epilogue persistent kernel
-// (256x256, four waves; M, N % 256 == 0, K % 128 == 0, K >= 512).  16: the same kernel on 192x256
-// tiles (any M, K >= 2048).
+// Kernel variants (the numbers are what tweo_set_gemm_tile takes; retired ones are refused).
+// 1, 3, 4: register-staged kernel (any K % 16 == 0), tiles 256x256, 128x128, 64x64.  6, 8:
+// DMA-pipelined kernel on 64-byte stages (K % 64 == 0), 256x256 with 8 waves and 128x128.  11, 13,
+// 14: persistent streaming kernel (K % 128 == 0): 256x256, 128x128, 192x256.  15: deferred-epilogue
+// persistent kernel (256x256, four waves; M, N % 256 == 0, K % 128 == 0, K >= 512).  16: the same
+// kernel on 192x256 tiles (any M, K >= 2048).  17: INT8 weight-streaming kernel with X staged
+// through LDS (M <= 64).
 constexpr int kNumVariants = 17;
 static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256, 256, 128, 256, 128, 256, 256, 128, 192, 256, 192, 64};
 static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128, 256, 256, 256, 64};
 int gemm_num_variants() { return kNumVariants; }
+bool gemm_variant_exists(int v)
+{
+    return v >= 0 && v <= kNumVariants && v != 2 && v != 5 && v != 7 && v != 9 && v != 10 && v != 12;
+}
 
 static int num_cus();
 int num_cus_public() { return num_cus(); }
@@ -1708,9 +1708,9 @@ static int pick_variant(int64_t M, int64_t N, int64_t K)
         }
     }
     if (v >= 11 && K % 128 != 0)  // the persistent kernels need whole 128-byte stages
-        v = (v == 11 || v >= 14) ? 6 : (v == 12 ? 7 : 8);
+        v = v == 13 ? 8 : 6;
     if (v >= 5 && K % 64 != 0)
-        v = (v == 5 || v == 6) ? 1 : ((v == 7 || v == 9) ? 2 : 3);
+        v = v == 6 ? 1 : 3;
     return v;
 }
 
@@ -1947,17 +1947,11 @@ static hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
     switch (resolve_variant(a)) {
     case 1: return launch_tile<T256x256, INT8, false>(a, s);
-    case 2: return launch_tile<T256x128, INT8, false>(a, s);
     case 3: return launch_tile<T128x128, INT8, false>(a, s);
     case 4: return launch_tile<T64x64, INT8, false>(a, s);
-    case 5: return launch_tile<D256x256w4, INT8, true>(a, s);
     case 6: return launch_tile<D256x256w8, INT8, true>(a, s);
-    case 7: return launch_tile<D256x128w4, INT8, true>(a, s);
     case 8: return launch_tile<D128x128w4, INT8, true>(a, s);
-    case 9: return launch_tile<D256x128o2, INT8, true>(a, s);
-    case 10: return launch_tile<D128x256o2, INT8, true>(a, s);
     case 11: return launch_stream<S256x256w8, INT8, 1>(a, s);
-    case 12: return launch_stream<S256x128w4, INT8, 1>(a, s);
     case 13: return launch_stream<S128x128w4, INT8, 2>(a, s);
     case 14: return launch_stream<S192x256w8, INT8, 1>(a, s);
     case 15: return launch_defer<INT8>(a, s);

@@ -125,5 +125,6 @@ bool set_profile_events(void *const *events, int pairs);
 // Tile-shape override for benchmarking sweeps: 0 = heuristic.
 void set_gemm_tile_override(int variant);
 int gemm_num_variants();
+bool gemm_variant_exists(int v);
 
 }  // namespace tweo

@@ -45,7 +45,7 @@ CASES = [  # (cfg, gemm, M, K, N): several tiles and ragged tails in M and N
 ]
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14])
+@pytest.mark.parametrize("tile", [0, 1, 3, 4, 6, 8, 11, 13, 14])
 @pytest.mark.parametrize("case", CASES)
 def test_fwd_with_penalty(case, tile):
     cfg, gi, M, K, N = case
@@ -247,7 +247,7 @@ def test_penalty_printed_regimes_through_the_gemm():
         assert abs(S / (M * N) - printed) <= 1e-6 * printed
 
 
-@pytest.mark.parametrize("tile", [0, 1, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15])
+@pytest.mark.parametrize("tile", [0, 1, 3, 4, 6, 8, 11, 13, 14, 15])
 @pytest.mark.parametrize("case", [(0, 0, 256, 512, 512), (1, 1, 208, 256, 144), (3, 0, 144, 640, 400),
                                   (3, 0, 1024, 512, 768)])
 def test_bwd(case, tile):

@@ -15,7 +15,7 @@ def say(*a):
     print(*a, flush=True)
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14])
+@pytest.mark.parametrize("tile", [0, 1, 3, 4, 6, 8, 11, 13, 14])
 @pytest.mark.parametrize("shape", [(1, 4096, 264), (16, 1024, 512), (64, 2048, 136), (200, 512, 392),
                                    (512, 768, 256), (33, 11008, 72), (17, 1024, 200), (32, 640, 136),
                                    (48, 4096, 520), (64, 11008, 264), (5, 192, 8)])

@@ -138,7 +138,7 @@ def test_scaled_linear_lds_staged_kernel(shape, gran):
     assert np.array_equal(yq.cpu().numpy(), oracle.w8a8_linear_scaled_i8out(xq, wq, sx, sw, inv_out))
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 8, 11, 12, 13, 14, 15, 16])
+@pytest.mark.parametrize("tile", [1, 3, 4, 6, 8, 11, 13, 14, 15, 16])
 @pytest.mark.parametrize("shape", [(200, 512, 392), (768, 2048, 512)])
 def test_scaled_linear_every_tiled_kernel(shape, tile):
     # forced variants; 15 and 16 (per-tensor only kernels) must fall back, not ignore the vectors

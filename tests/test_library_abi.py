@@ -97,6 +97,8 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
                                                     4096, None) == tw.TWEO_ERR_INVALID_ARG   # no state
     assert tw.tweo_workspace_bytes(tw.TWEO_OP_LAYERNORM_QUANTIZE, 16384, 1, 1) == 2304 + 16384 * 16
     assert lib.tweo_set_gemm_tile(99) == tw.TWEO_ERR_INVALID_ARG
+    assert lib.tweo_set_gemm_tile(12) == tw.TWEO_ERR_INVALID_ARG   # a retired variant
+    assert lib.tweo_set_gemm_tile(17) == tw.TWEO_OK
     assert lib.tweo_set_gemm_tile(0) == tw.TWEO_OK
 
 
