@@ -461,7 +461,7 @@ tweo_status tweo_fp8_linear_bwd_bf16_inject(const void *dy_bf16, const void *a_b
  * {0, 4}); it falls back to variant 11 otherwise.  16 = the same kernel on 192x256
  * tiles (any M, N a multiple of 256, K a multiple of 128 and at least 2048); it
  * falls back to variant 14 otherwise.  17 (INT8 only, M <= 64, K % 64 == 0,
- * K >= 1024, N % 4 == 0) = the weight-streaming kernel that stages X through LDS;
+ * N % 4 == 0) = the weight-streaming kernel (what such shapes get anyway);
  * elsewhere it means variant 4.  A variant whose K requirement is not met falls
  * back to the nearest one that fits.  Results are identical up to the fp32
  * summation order.  Returns TWEO_ERR_INVALID_ARG for an unknown (or retired:

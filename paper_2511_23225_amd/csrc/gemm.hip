@@ -1128,15 +1128,13 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
 }
 
 // ---------------------------------------------------------------------------
-// W8A8 linear for small M (decode-time batches, M <= 64): the product is bound
-// by streaming the N x K weight bytes from HBM once, so there is no LDS staging
-// and no tiling of K across workgroups.  A workgroup owns 16*NBLK weight rows;
-// its 8 waves split K into 8 contiguous slices, each wave multiplies its slice
-// with v_mfma_i32_16x16x64_i8 (operands loaded straight from global memory in
-// the MFMA lane layout: row = lane%16, 16 bytes at k = 16*(lane/16)), and the 8
-// partial int32 tiles are added through LDS - exact, so the result is the same
-// bits as any other summation order.  y = bf16(fp32(acc) * alpha) (Sec. 4.4), or with VEC
-// y = bf16((fp32(acc) * rs[m]) * cs[n]): dequantisation steps per token and per output channel.
+// W8A8 linear for small M (decode-time batches, M <= 64): the product is bound by streaming the
+// N x K weight bytes from HBM once.  One workgroup per CU owns up to NB blocks of 16 weight rows
+// (block ids b, b + grid, ...); its 8 waves split K; products come from v_mfma_i32_16x16x64_i8
+// (operand row = lane % 16, 16 bytes at k = 16 * (lane / 16)); the partial int32 tiles of the
+// waves are added through LDS - exact, so the result is the same bits as any other summation
+// order.  y = bf16(fp32(acc) * alpha) (Sec. 4.4), or with VEC y = bf16((fp32(acc) * rs[m]) * cs[n]):
+// dequantisation steps per token and per output channel.
 struct StepVectors {
     const float *rs, *cs;
     int rs_stride, cs_stride;
@@ -1144,84 +1142,145 @@ struct StepVectors {
     float out_inv_step;
 };
 
-template <int NBLK, int MB, int UNROLL, int WAVES, bool IL, bool VEC>
-__global__ __launch_bounds__(WAVES * 64) void w8a8_skinny_kernel(const int8_t *__restrict__ X,
-                                                          const int8_t *__restrict__ W, int M, int N,
-                                                          int K, float alpha, StepVectors sv,
-                                                          uint16_t *__restrict__ Y)
+// How the operands get to the MFMAs decides everything here.  Measured on MI355X: a load in the
+// MFMA operand layout (a 16-lane group touches 16 different rows, 16 bytes of each) moves 16 bytes
+// per clock and CU through the texture unit, about 25 GB/s per CU, and with every workgroup
+// reading all of X from the L2 the time of such kernels was (weights + CUs x X) / 6.5 TB/s for every
+// shape and M (11008 -> 4096 at M = 64: 32 us).  A direct-to-LDS load in which 16 neighbouring
+// lanes read 256 contiguous bytes moves 64 bytes per clock.  So both operands are staged through a
+// ring of LDS stages and
+// every byte, weights included, arrives by such loads: a stage is KCH = 64 * KSTEPS bytes of K for
+// the M rows of X and the workgroup's 16 * NB weight rows, S stages form a ring, S - 1 of them are
+// in flight while one is multiplied, one barrier per stage.  The 16-byte chunks of a row are
+// stored XOR-swizzled with the row's index in its block of 16 (the loading lane picks the global
+// chunk accordingly), so that the fragment reads of 16 rows at one k are conflict free.  Wave w
+// multiplies k step w % KSTEPS of every stage, for the M blocks of part w / KSTEPS; the partial
+// tiles meet in LDS at the end.  Stages past the end of K re-load the last one into slots nobody
+// reads any more, so that the count of loads in flight stays what the waits assume.
+template <int MB, int NB, int KSTEPS, int S, bool VEC>
+__global__ __launch_bounds__(512) void w8a8_skinny_ring_kernel(const int8_t *__restrict__ X,
+                                                               const int8_t *__restrict__ W, int M, int N, int K,
+                                                               float alpha, StepVectors sv, uint16_t *__restrict__ Y)
 {
-    constexpr int STEP = 64;
-    __shared__ v4i red[WAVES][MB][kWave];
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    constexpr int WAVES = 8, STEP = 64, KCH = KSTEPS * STEP, PARTS = WAVES / KSTEPS, MBW = MB / PARTS;
+    constexpr int ROWS_X = MB * 16, ROWS = ROWS_X + NB * 16, STAGE = ROWS * KCH;
+    constexpr int RPI = 1024 / KCH, NI = ROWS / RPI, PPW = (NI + WAVES - 1) / WAVES, CPR = KCH / 16, T = NB * MBW;
+    static_assert(MB % PARTS == 0 && 1024 % KCH == 0 && ROWS % RPI == 0, "shapes divide");
+    static_assert(S * STAGE <= 160 * 1024 && WAVES * T * 1024 <= S * STAGE, "LDS capacity");
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int r16 = lane & 15, kc = lane >> 4;
-    const int n0 = blockIdx.x * 16 * NBLK;
-    // K is cut in 64-byte steps; wave w takes a contiguous run of them (IL = false) or every
-    // WAVES-th step (IL = true: the waves of a workgroup then read adjacent 64-byte columns)
-    const int steps = K / STEP, per = (steps + WAVES - 1) / WAVES;
-    const int s_begin = IL ? wave : wave * per;
-    const int s_end = IL ? steps : (s_begin + per < steps ? s_begin + per : steps);
-    constexpr int S_INC = IL ? WAVES : 1;
-    const int8_t *wp[NBLK], *xp[MB];
+    const int step = wave % KSTEPS, part = wave / KSTEPS;
+    const int steps = K / STEP, blocks = (N + 15) / 16, grid = gridDim.x;
+    const int chunks = (K + KCH - 1) / KCH;
+    const bool ragged = K % KCH != 0;
+    // workgroups walk the chunks in rotated orders (they all read the same X)
+    const int rot = (int)((blockIdx.x >> 3) % (unsigned)chunks);
+    auto chunk_at = [&](int t) {
+        const int c = t < chunks ? t : chunks - 1;
+        const int r = c + rot;
+        return r < chunks ? r : r - chunks;
+    };
+    // fragment reads: row r16 of a block, chunk 4 * step + kc of the stage, swizzled
+    const uint32_t frag_col = (uint32_t)(((step * 4 + kc) ^ r16) * 16);
+    for (int first = blockIdx.x; first < blocks; first += NB * grid) {
+        // this wave's DMA instructions of a stage: instruction i covers the stage's rows i * RPI ..,
+        // lane l the LDS slot (row l / CPR, chunk l % CPR), which holds the global chunk slot ^ row
+        const uint8_t *src[PPW];
+        uint32_t voff[PPW], voff_last[PPW], dst[PPW];
 #pragma unroll
-    for (int b = 0; b < NBLK; ++b) {
-        int n = n0 + b * 16 + r16;
-        n = n < N ? n : N - 1;  // rows past N: duplicates, never stored
-        wp[b] = W + (int64_t)n * K + kc * 16;
-    }
-#pragma unroll
-    for (int b = 0; b < MB; ++b) {
-        int m = b * 16 + r16;
-        m = m < M ? m : M - 1;
-        xp[b] = X + (int64_t)m * K + kc * 16;
-    }
-    v4i acc[NBLK][MB];
-#pragma unroll
-    for (int a = 0; a < NBLK; ++a)
-#pragma unroll
-        for (int b = 0; b < MB; ++b)
-            acc[a][b] = v4i{0, 0, 0, 0};
-    for (int s = s_begin; s < s_end; s += UNROLL * S_INC) {
-        v4i wf[UNROLL][NBLK], xf[UNROLL][MB];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            // past the slice end: re-read this trip's first step (in bounds), its MFMA is skipped
-            const int su = s + u * S_INC;
-            const int64_t k = (int64_t)(su < s_end ? su : s) * STEP;
-#pragma unroll
-            for (int a = 0; a < NBLK; ++a)
-                wf[u][a] = *(const v4i *)(wp[a] + k);
-#pragma unroll
-            for (int b = 0; b < MB; ++b)
-                xf[u][b] = *(const v4i *)(xp[b] + k);
-        }
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u)
-            if (s + u * S_INC < s_end) {
-#pragma unroll
-                for (int a = 0; a < NBLK; ++a)
-#pragma unroll
-                    for (int b = 0; b < MB; ++b)
-                        // first operand -> register index (n), second -> lane%16 (m)
-                        acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[u][a], xf[u][b], acc[a][b],
-                                                                         0, 0, 0);
+        for (int j = 0; j < PPW; ++j) {
+            int i = j * WAVES + wave;
+            i = i < NI ? i : NI - 1;
+            const int rr = i * RPI + lane / CPR, R = rr & 15, c = (lane % CPR) ^ R;
+            uint32_t rowoff;
+            if (i * RPI < ROWS_X) {  // uniform: an instruction lies in X or in one weight block
+                const int m = rr < M ? rr : M - 1;
+                src[j] = (const uint8_t *)X;
+                rowoff = (uint32_t)m * (uint32_t)K;
+            } else {
+                const int a = (i * RPI - ROWS_X) / 16;
+                int blk = first + a * grid;
+                blk = blk < blocks ? blk : blocks - 1;  // block slots past the end: duplicates, never stored
+                const int n = blk * 16 + R < N ? R : N - 1 - blk * 16;
+                src[j] = (const uint8_t *)W + (int64_t)blk * 16 * K;
+                rowoff = (uint32_t)n * (uint32_t)K;
             }
-    }
-    // acc[v] of lane l is C[n = 4*(l/16) + v, m = l%16] of its 16x16 block
+            voff[j] = rowoff + (uint32_t)c * 16u;
+            // the last chunk of a K that ends inside it: chunks past K read the row's first bytes
+            // (they only ever meet zeroed X fragments); this offset is absolute in K
+            const int k_last = (chunks - 1) * KCH + c * 16;
+            voff_last[j] = rowoff + (uint32_t)(k_last + 16 <= K ? k_last : c * 16 % STEP);
+            dst[j] = (uint32_t)i * 1024u;
+        }
+        auto dma_stage = [&](int cc, int slot) {
+            const bool last = ragged && cc == chunks - 1;
 #pragma unroll
-    for (int a = 0; a < NBLK; ++a) {
-        if (a > 0)
-            __syncthreads();
+            for (int j = 0; j < PPW; ++j)
+                dma_load16(lds_base + slot * STAGE + dst[j], last ? src[j] : src[j] + (int64_t)cc * KCH,
+                           last ? voff_last[j] : voff[j]);
+        };
+        v4i acc[NB][MBW];
 #pragma unroll
-        for (int b = 0; b < MB; ++b)
-            red[wave][b][lane] = acc[a][b];
-        __syncthreads();
-        for (int t = tid; t < MB * kWave; t += WAVES * kWave) {
-            const int b = t / kWave, l = t % kWave;
-            v4i sum = red[0][b][l];
+        for (int a = 0; a < NB; ++a)
 #pragma unroll
-            for (int w = 1; w < WAVES; ++w)
-                sum += red[w][b][l];
-            const int m = b * 16 + (l & 15), n = n0 + a * 16 + 4 * (l >> 4);
+            for (int b = 0; b < MBW; ++b)
+                acc[a][b] = v4i{0, 0, 0, 0};
+        auto multiply = [&](int cc, int slot) {
+            const uint8_t *st = smem + slot * STAGE + frag_col;
+            const bool ok = cc * KSTEPS + step < steps;
+            v4i wfr[NB], xfr[MBW];
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+                wfr[a] = *(const v4i *)(st + (ROWS_X + a * 16 + r16) * KCH);
+#pragma unroll
+            for (int b = 0; b < MBW; ++b) {
+                const v4i v = *(const v4i *)(st + ((part * MBW + b) * 16 + r16) * KCH);
+                xfr[b] = ok ? v : v4i{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+#pragma unroll
+                for (int b = 0; b < MBW; ++b)
+                    // first operand -> register index (n), second -> lane%16 (m)
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wfr[a], xfr[b], acc[a][b], 0, 0, 0);
+        };
+        block_barrier();  // the ring is free (previous pass: reduction)
+#pragma unroll
+        for (int t = 0; t < S - 1; ++t)
+            dma_stage(chunk_at(t), t);
+        int slot = 0, fill = S - 1;  // slot of stage c; slot the next stage goes to
+        for (int c = 0; c < chunks; ++c) {
+            wait_vmcnt<(S - 2) * PPW>();  // this wave's loads of stage c have landed ...
+            block_barrier();              // ... everybody's have, and the slot of stage c - 1 is free
+            dma_stage(chunk_at(c + S - 1), fill);
+            multiply(chunk_at(c), slot);
+            slot = slot + 1 == S ? 0 : slot + 1;
+            fill = fill + 1 == S ? 0 : fill + 1;
+        }
+        wait_vmcnt<0>();  // the loads past the end have landed: the ring can be reused
+        block_barrier();
+        // acc[v] of lane l is C[n = 4*(l/16) + v, m = l%16] of its 16x16 block
+        v4i(*red)[T][kWave] = (v4i(*)[T][kWave])smem;
+#pragma unroll
+        for (int a = 0; a < NB; ++a)
+#pragma unroll
+            for (int b = 0; b < MBW; ++b)
+                red[wave][a * MBW + b][lane] = acc[a][b];
+        block_barrier();
+        for (int t = tid; t < NB * MB * kWave; t += WAVES * kWave) {
+            const int a = t / (MB * kWave), b = (t / kWave) % MB, l = t % kWave;
+            const int blk = first + a * grid;
+            if (blk >= blocks)
+                continue;
+            const int w0 = (b / MBW) * KSTEPS, tile = a * MBW + b % MBW;
+            v4i sum = red[w0][tile][l];
+#pragma unroll
+            for (int w = 1; w < KSTEPS; ++w)
+                sum += red[w0 + w][tile][l];
+            const int m = b * 16 + (l & 15), n = blk * 16 + 4 * (l >> 4);
             if (m < M && n < N) {
                 float y[4];
                 if constexpr (VEC) {
@@ -1240,296 +1299,7 @@ __global__ __launch_bounds__(WAVES * 64) void w8a8_skinny_kernel(const int8_t *_
                     for (int v = 0; v < 4; ++v)
                         y[v] = (float)sum[v] * alpha;
                 }
-                *(uint2 *)(Y + (int64_t)m * N + n) =
-                    make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
-            }
-        }
-    }
-}
-
-// The same contraction for K short enough that a workgroup can keep its whole share of X in
-// registers: wave w owns the 64-byte K steps w, w+WAVES, ... (at most XC of them) and loads
-// their X fragments once; the workgroup then walks over 16-row blocks of W (block ids
-// blockIdx.x, +gridDim.x, ...), so X crosses the L2 -> CU path once per workgroup instead of
-// once per 16 weight rows, and the next block's weights are in flight while this block's
-// partial tiles are added through LDS.  Same arithmetic, same bits.
-template <int MB, int WAVES, int XC, int DEPTH, bool VEC>
-__global__ __launch_bounds__(WAVES * 64) void w8a8_skinny_resident_kernel(const int8_t *__restrict__ X,
-                                                                   const int8_t *__restrict__ W, int M, int N,
-                                                                   int K, float alpha, StepVectors sv,
-                                                                   uint16_t *__restrict__ Y)
-{
-    constexpr int STEP = 64;
-    __shared__ v4i red[WAVES][MB][kWave];
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int r16 = lane & 15, kc = lane >> 4;
-    const int steps = K / STEP;  // <= XC * WAVES (checked by the host)
-    const int blocks = (N + 15) / 16;
-    // k offset of this wave's u-th step; steps past the end re-read step `wave % steps` with a
-    // zero X fragment, so their products vanish
-    // Workgroups start at different steps (rotation by workgroup index): they all read the same
-    // X, and in the same order they would all queue at the same L2 channel at the same time.
-    int koff[XC];
-    v4i xf[XC][MB];
-    const int rot = (int)(blockIdx.x % XC);
-#pragma unroll
-    for (int u = 0; u < XC; ++u) {
-        const int su = wave + ((u + rot) % XC) * WAVES;
-        const bool ok = su < steps;
-        koff[u] = (ok ? su : wave % steps) * STEP + kc * 16;
-#pragma unroll
-        for (int b = 0; b < MB; ++b) {
-            int m = b * 16 + r16;
-            m = m < M ? m : M - 1;
-            const v4i v = *(const v4i *)(X + (int64_t)m * K + koff[u]);
-            xf[u][b] = ok ? v : v4i{0, 0, 0, 0};
-        }
-    }
-    auto load_w = [&](int blk, v4i(&wf)[XC]) {
-        int n = blk * 16 + r16;
-        n = n < N ? n : N - 1;  // rows past N: duplicates, never stored
-        const int8_t *wp = W + (int64_t)n * K;
-#pragma unroll
-        for (int u = 0; u < XC; ++u)
-            wf[u] = *(const v4i *)(wp + koff[u]);
-    };
-    // DEPTH blocks of weights in flight: block i+DEPTH-1 is requested before block i is multiplied
-    v4i wf[DEPTH][XC];
-    const int grid = gridDim.x;
-    int blk = blockIdx.x;
-#pragma unroll
-    for (int d = 0; d < DEPTH - 1; ++d)
-        if (blk + d * grid < blocks)
-            load_w(blk + d * grid, wf[d]);
-    while (blk < blocks) {
-#pragma unroll
-        for (int d = 0; d < DEPTH; ++d) {
-            if (blk >= blocks)
-                break;
-            const int ahead = blk + (DEPTH - 1) * grid;
-            if (ahead < blocks)
-                load_w(ahead, wf[(d + DEPTH - 1) % DEPTH]);
-            v4i acc[MB];
-#pragma unroll
-            for (int b = 0; b < MB; ++b)
-                acc[b] = v4i{0, 0, 0, 0};
-#pragma unroll
-            for (int u = 0; u < XC; ++u)
-#pragma unroll
-                for (int b = 0; b < MB; ++b)
-                    // first operand -> register index (n), second -> lane%16 (m)
-                    acc[b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[d][u], xf[u][b], acc[b], 0, 0, 0);
-#pragma unroll
-            for (int b = 0; b < MB; ++b)
-                red[wave][b][lane] = acc[b];
-            __syncthreads();
-            // acc[v] of lane l is C[n = 4*(l/16) + v, m = l%16] of its 16x16 block
-            for (int t = tid; t < MB * kWave; t += WAVES * kWave) {
-                const int b = t / kWave, l = t % kWave;
-                v4i sum = red[0][b][l];
-#pragma unroll
-                for (int w = 1; w < WAVES; ++w)
-                    sum += red[w][b][l];
-                const int m = b * 16 + (l & 15), n = blk * 16 + 4 * (l >> 4);
-                if (m < M && n < N) {
-                    float y[4];
-                    if constexpr (VEC) {
-                        const float rstep = sv.rs[(int64_t)m * sv.rs_stride];
-#pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            y[v] = ((float)sum[v] * rstep) * sv.cs[(int64_t)(n + v) * sv.cs_stride];
-                        if (sv.out_i8) {
-                            *(uint32_t *)((uint8_t *)Y + (int64_t)m * N + n) =
-                                round_to_i8(y[0], sv.out_inv_step) | (round_to_i8(y[1], sv.out_inv_step) << 8) |
-                                (round_to_i8(y[2], sv.out_inv_step) << 16) | (round_to_i8(y[3], sv.out_inv_step) << 24);
-                            continue;
-                        }
-                    } else {
-#pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            y[v] = (float)sum[v] * alpha;
-                    }
-                    *(uint2 *)(Y + (int64_t)m * N + n) =
-                        make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
-                }
-            }
-            __syncthreads();  // red is rewritten by the next block
-            blk += grid;
-        }
-    }
-}
-
-// The same contraction with X staged through LDS.  In the MFMA operand layout a 16-lane group of
-// a load instruction touches 16 different rows, 16 bytes of each: the texture unit then moves 16
-// bytes per clock and CU, about 25 GB/s per CU, and at M = 64 a workgroup reads more bytes of X
-// (all of it, from the L2) than of its own weight rows (measured: time = (weights + CUs x X) /
-// 6.5 TB/s for every shape and M).  Here a chunk of X (all M rows x KCH bytes of K) is fetched by
-// direct-to-LDS loads in which a wave reads 1 KB of one row, i.e. whole 128-byte lines, once per
-// workgroup; the fragments then come out of LDS (rows padded by 16 bytes: conflict free).  The
-// weight rows are used once, so they still go straight to registers.  Per chunk: X of chunk c + 1
-// and the weights of chunk c + 2 are in flight while chunk c is multiplied; one barrier.
-template <int MB, int NB, int XC, bool VEC>
-__global__ __launch_bounds__(512) void w8a8_skinny_lds_kernel(const int8_t *__restrict__ X,
-                                                              const int8_t *__restrict__ W, int M, int N, int K,
-                                                              float alpha, StepVectors sv, uint16_t *__restrict__ Y)
-{
-    constexpr int WAVES = 8, STEP = 64, KCH = XC * WAVES * STEP, PITCH = KCH + 16, ROWS = MB * 16;
-    constexpr int BUF = ROWS * PITCH, PARTS = KCH / 1024, PPW = ROWS * PARTS / WAVES, WSET = XC * NB;
-    static_assert(KCH % 1024 == 0 && (ROWS * PARTS) % WAVES == 0, "whole 1 KB pieces, shared out evenly");
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // two X buffers; the reduction reuses them
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int r16 = lane & 15, kc = lane >> 4;
-    const int steps = K / STEP, blocks = (N + 15) / 16, grid = gridDim.x;
-    const int chunks = (K + KCH - 1) / KCH;
-    // workgroups walk the chunks in rotated orders (they all read the same X)
-    const int rot = (int)((blockIdx.x >> 3) % (unsigned)chunks);
-    auto chunk_at = [&](int c) { const int r = c + rot; return r < chunks ? r : r - chunks; };
-    // one wave instruction moves 1 KB of one row of X: lane l the 16 bytes at k = l * 16 of the piece.
-    // Pieces that reach past K (last chunk) read the row's first bytes instead: the steps they
-    // would feed are masked below.
-    auto dma_chunk = [&](int cc, int buf) {
-#pragma unroll
-        for (int i = 0; i < PPW; ++i) {
-            const int p = i * WAVES + wave, row = p / PARTS, part = p % PARTS;
-            const int m = row < M ? row : M - 1;
-            int k = cc * KCH + part * 1024 + lane * 16;
-            k = k + 16 <= K ? k : lane * 16 % K;
-            dma_load16(lds_base + buf * BUF + row * PITCH + part * 1024, (const uint8_t *)X + (int64_t)m * K, (uint32_t)k);
-        }
-    };
-    for (int first = blockIdx.x; first < blocks; first += NB * grid) {
-        const int8_t *wrow[NB];
-#pragma unroll
-        for (int a = 0; a < NB; ++a) {
-            int blk = first + a * grid;
-            blk = blk < blocks ? blk : blocks - 1;  // block slots past the end: duplicates, never stored
-            int n = blk * 16 + r16;
-            n = n < N ? n : N - 1;
-            wrow[a] = W + (int64_t)n * K + kc * 16;
-        }
-        v4i acc[NB][MB];
-#pragma unroll
-        for (int a = 0; a < NB; ++a)
-#pragma unroll
-            for (int b = 0; b < MB; ++b)
-                acc[a][b] = v4i{0, 0, 0, 0};
-        v4i wf[3][XC][NB];
-        // wave w owns the steps w * XC .. w * XC + XC - 1 of a chunk; steps past K read step 0 and are masked
-        // The weight loads are inline asm, like the X loads: the compiler then inserts no waits of
-        // its own for them (its bookkeeping of three rotating register sets across the loop's back
-        // edge made every third chunk wait for the loads it had just issued), and the one explicit
-        // wait per chunk below covers both.  A set is not touched between its loads and that wait.
-        auto load_w = [&](int cc, v4i(&wb)[XC][NB]) {
-#pragma unroll
-            for (int u = 0; u < XC; ++u) {
-                const int su = (cc * WAVES + wave) * XC + u;
-                const int koff = (su < steps ? su : 0) * STEP;
-#pragma unroll
-                for (int a = 0; a < NB; ++a)
-                    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(wb[u][a]) : "v"(wrow[a] + koff) : "memory");
-            }
-        };
-        auto multiply = [&](int cc, int buf, v4i(&wb)[XC][NB]) {
-            v4i xf[XC][MB];
-#pragma unroll
-            for (int u = 0; u < XC; ++u)
-#pragma unroll
-                for (int a = 0; a < NB; ++a)
-                    asm volatile("" : "+v"(wb[u][a]));  // used from here on, behind the wait and the barrier
-#pragma unroll
-            for (int u = 0; u < XC; ++u) {
-                const bool ok = (cc * WAVES + wave) * XC + u < steps;
-#pragma unroll
-                for (int b = 0; b < MB; ++b) {
-                    const v4i v = *(const v4i *)(smem + buf * BUF + (b * 16 + r16) * PITCH + (wave * XC + u) * STEP + kc * 16);
-                    xf[u][b] = ok ? v : v4i{0, 0, 0, 0};
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < XC; ++u)
-#pragma unroll
-                for (int a = 0; a < NB; ++a)
-#pragma unroll
-                    for (int b = 0; b < MB; ++b)
-                        // first operand -> register index (n), second -> lane%16 (m)
-                        acc[a][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wb[u][a], xf[u][b], acc[a][b], 0, 0, 0);
-        };
-        // iteration c: X of chunk c + 1 (direct to LDS) and then the weights of chunk c + 2 are
-        // requested, chunk c is multiplied, and the wait in front of the barrier leaves exactly
-        // the youngest weight set in flight
-        auto iteration = [&](int c, v4i(&w_cur)[XC][NB], v4i(&w_nxt2)[XC][NB]) {
-            if (c + 1 < chunks)
-                dma_chunk(chunk_at(c + 1), (c + 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
-            if (c + 2 < chunks)
-                load_w(chunk_at(c + 2), w_nxt2);
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(chunk_at(c), c & 1, w_cur);
-            __builtin_amdgcn_sched_barrier(0);
-            if (c + 2 < chunks)
-                wait_vmcnt<WSET>();
-            else
-                wait_vmcnt<0>();
-            block_barrier();
-        };
-        __syncthreads();  // the buffers are free (previous pass: reduction)
-        dma_chunk(chunk_at(0), 0);
-        __builtin_amdgcn_sched_barrier(0);
-        load_w(chunk_at(0), wf[0]);
-        if (chunks > 1)
-            load_w(chunk_at(1), wf[1]);
-        __builtin_amdgcn_sched_barrier(0);
-        wait_vmcnt<0>();
-        block_barrier();
-        for (int c = 0; c < chunks; c += 3) {
-            iteration(c, wf[0], wf[2]);
-            if (c + 1 < chunks)
-                iteration(c + 1, wf[1], wf[0]);
-            if (c + 2 < chunks)
-                iteration(c + 2, wf[2], wf[1]);
-        }
-        // acc[v] of lane l is C[n = 4*(l/16) + v, m = l%16] of its 16x16 block
-        v4i(*red)[MB][kWave] = (v4i(*)[MB][kWave])smem;
-#pragma unroll
-        for (int a = 0; a < NB; ++a) {
-            const int blk = first + a * grid;
-            if (a > 0)
-                __syncthreads();
-#pragma unroll
-            for (int b = 0; b < MB; ++b)
-                red[wave][b][lane] = acc[a][b];
-            __syncthreads();
-            if (blk >= blocks)
-                continue;  // uniform over the workgroup
-            for (int t = tid; t < MB * kWave; t += WAVES * kWave) {
-                const int b = t / kWave, l = t % kWave;
-                v4i sum = red[0][b][l];
-#pragma unroll
-                for (int w = 1; w < WAVES; ++w)
-                    sum += red[w][b][l];
-                const int m = b * 16 + (l & 15), n = blk * 16 + 4 * (l >> 4);
-                if (m < M && n < N) {
-                    float y[4];
-                    if constexpr (VEC) {
-                        const float rstep = sv.rs[(int64_t)m * sv.rs_stride];
-#pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            y[v] = ((float)sum[v] * rstep) * sv.cs[(int64_t)(n + v) * sv.cs_stride];
-                        if (sv.out_i8) {
-                            *(uint32_t *)((uint8_t *)Y + (int64_t)m * N + n) =
-                                round_to_i8(y[0], sv.out_inv_step) | (round_to_i8(y[1], sv.out_inv_step) << 8) |
-                                (round_to_i8(y[2], sv.out_inv_step) << 16) | (round_to_i8(y[3], sv.out_inv_step) << 24);
-                            continue;
-                        }
-                    } else {
-#pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            y[v] = (float)sum[v] * alpha;
-                    }
-                    *(uint2 *)(Y + (int64_t)m * N + n) = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
-                }
+                *(uint2 *)(Y + (int64_t)m * N + n) = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
             }
         }
     }
@@ -1615,8 +1385,7 @@ size_t stream_k_workspace_bytes()
 // DMA-pipelined kernel on 64-byte stages (K % 64 == 0), 256x256 with 8 waves and 128x128.  11, 13,
 // 14: persistent streaming kernel (K % 128 == 0): 256x256, 128x128, 192x256.  15: deferred-epilogue
 // persistent kernel (256x256, four waves; M, N % 256 == 0, K % 128 == 0, K >= 512).  16: the same
-// kernel on 192x256 tiles (any M, K >= 2048).  17: INT8 weight-streaming kernel with X staged
-// through LDS (M <= 64).
+// kernel on 192x256 tiles (any M, K >= 2048).  17: the INT8 weight-streaming kernel (M <= 64).
 constexpr int kNumVariants = 17;
 static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256, 256, 128, 256, 128, 256, 256, 128, 192, 256, 192, 64};
 static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128, 256, 256, 256, 64};
@@ -2084,53 +1853,14 @@ hipError_t launch_fp8_gemm(const GemmArgs &a, hipStream_t s)
     }
     return a.a_e5m2 ? launch_fp8_gemm_e5m2(a, s) : launch_gemm<false>(a, s);
 }
-template <int NBLK, int MB, int UNROLL, int WAVES, bool IL>
-static hipError_t launch_skinny(const GemmArgs &a, hipStream_t s)
+template <int MB, int NB, int KSTEPS, int S>
+static hipError_t launch_skinny_ring(const GemmArgs &a, hipStream_t s)
 {
-    const unsigned grid = (unsigned)((a.N + 16 * NBLK - 1) / (16 * NBLK));
-    const StepVectors sv{a.row_step, a.col_step, a.row_step_stride, a.col_step_stride, a.out_i8 ? 1 : 0, a.out_inv_step};
-    if (a.row_step != nullptr)
-        launch_gemm_kernel(w8a8_skinny_kernel<NBLK, MB, UNROLL, WAVES, IL, true>, dim3(grid), dim3(WAVES * 64), 0, s,
-                           (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
-                           (uint16_t *)a.out);
-    else
-        launch_gemm_kernel(w8a8_skinny_kernel<NBLK, MB, UNROLL, WAVES, IL, false>, dim3(grid), dim3(WAVES * 64), 0, s,
-                           (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
-                           (uint16_t *)a.out);
-    return hipGetLastError();
-}
-
-
-template <int MB, int WAVES, int XC, int DEPTH>
-static hipError_t launch_skinny_resident(const GemmArgs &a, hipStream_t s, int wg_per_cu)
-{
-    const int blocks = (int)((a.N + 15) / 16);
-    int grid = num_cus() * wg_per_cu;
-    if (grid > blocks)
-        grid = blocks;
-    const StepVectors sv{a.row_step, a.col_step, a.row_step_stride, a.col_step_stride, a.out_i8 ? 1 : 0, a.out_inv_step};
-    if (a.row_step != nullptr)
-        launch_gemm_kernel(w8a8_skinny_resident_kernel<MB, WAVES, XC, DEPTH, true>, dim3((unsigned)grid), dim3(WAVES * 64), 0,
-                           s, (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
-                           (uint16_t *)a.out);
-    else
-        launch_gemm_kernel(w8a8_skinny_resident_kernel<MB, WAVES, XC, DEPTH, false>, dim3((unsigned)grid), dim3(WAVES * 64), 0,
-                           s, (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
-                           (uint16_t *)a.out);
-    return hipGetLastError();
-}
-
-template <int MB, int NB, int XC>
-static hipError_t launch_skinny_lds(const GemmArgs &a, hipStream_t s)
-{
-    constexpr int KCH = XC * 8 * 64, BUF = MB * 16 * (KCH + 16);
-    constexpr int RED = 8 * MB * 64 * 16;
-    constexpr int LDS = 2 * BUF > RED ? 2 * BUF : RED;
-    static_assert(LDS <= 160 * 1024, "LDS capacity");
+    constexpr int LDS = S * (MB * 16 + NB * 16) * KSTEPS * 64;
     static bool attr_done[2] = {false, false};
     const int vec = a.row_step != nullptr ? 1 : 0;
-    const void *kern = vec ? (const void *)w8a8_skinny_lds_kernel<MB, NB, XC, true>
-                           : (const void *)w8a8_skinny_lds_kernel<MB, NB, XC, false>;
+    const void *kern = vec ? (const void *)w8a8_skinny_ring_kernel<MB, NB, KSTEPS, S, true>
+                           : (const void *)w8a8_skinny_ring_kernel<MB, NB, KSTEPS, S, false>;
     if (!attr_done[vec]) {
         hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         if (e != hipSuccess)
@@ -2143,68 +1873,57 @@ static hipError_t launch_skinny_lds(const GemmArgs &a, hipStream_t s)
         grid = blocks;
     const StepVectors sv{a.row_step, a.col_step, a.row_step_stride, a.col_step_stride, a.out_i8 ? 1 : 0, a.out_inv_step};
     if (vec)
-        launch_gemm_kernel(w8a8_skinny_lds_kernel<MB, NB, XC, true>, dim3((unsigned)grid), dim3(512), LDS, s,
+        launch_gemm_kernel(w8a8_skinny_ring_kernel<MB, NB, KSTEPS, S, true>, dim3((unsigned)grid), dim3(512), LDS, s,
                            (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
                            (uint16_t *)a.out);
     else
-        launch_gemm_kernel(w8a8_skinny_lds_kernel<MB, NB, XC, false>, dim3((unsigned)grid), dim3(512), LDS, s,
+        launch_gemm_kernel(w8a8_skinny_ring_kernel<MB, NB, KSTEPS, S, false>, dim3((unsigned)grid), dim3(512), LDS, s,
                            (const int8_t *)a.A, (const int8_t *)a.B, (int)a.M, (int)a.N, (int)a.K, a.alpha, sv,
                            (uint16_t *)a.out);
     return hipGetLastError();
 }
 
-template <int MB, int XC>
-static hipError_t launch_skinny_lds_nb(const GemmArgs &a, hipStream_t s)
+// stage shapes: M <= 16: 512 bytes of K a stage (eight k steps, one per wave); above: 256 bytes (four
+// k steps x two parts of the M blocks); ring depth what 160 KB of LDS allow
+static hipError_t launch_skinny_ring_any(const GemmArgs &a, hipStream_t s)
 {
     const int64_t blocks = (a.N + 15) / 16, cus = num_cus();
     const int64_t per = (blocks + cus - 1) / cus;
+    if (a.M <= 16) {
+        if (per <= 1)
+            return launch_skinny_ring<1, 1, 8, 6>(a, s);
+        if (per == 2)
+            return launch_skinny_ring<1, 2, 8, 5>(a, s);
+        if (per == 3)
+            return launch_skinny_ring<1, 3, 8, 4>(a, s);
+        return launch_skinny_ring<1, 4, 8, 3>(a, s);
+    }
+    if (a.M <= 32) {
+        if (per <= 1)
+            return launch_skinny_ring<2, 1, 4, 8>(a, s);
+        if (per == 2)
+            return launch_skinny_ring<2, 2, 4, 8>(a, s);
+        if (per == 3)
+            return launch_skinny_ring<2, 3, 4, 6>(a, s);
+        return launch_skinny_ring<2, 4, 4, 6>(a, s);
+    }
     if (per <= 1)
-        return launch_skinny_lds<MB, 1, XC>(a, s);
+        return launch_skinny_ring<4, 1, 4, 6>(a, s);
     if (per == 2)
-        return launch_skinny_lds<MB, 2, XC>(a, s);
+        return launch_skinny_ring<4, 2, 4, 6>(a, s);
     if (per == 3)
-        return launch_skinny_lds<MB, 3, XC>(a, s);
-    return launch_skinny_lds<MB, 4, XC>(a, s);
+        return launch_skinny_ring<4, 3, 4, 5>(a, s);
+    return launch_skinny_ring<4, 4, 4, 4>(a, s);
 }
 
 hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s)
 {
-    // Small M with a lot of X per workgroup (M > 32, or a long K): X staged through LDS.  Measured
-    // cold at the 7B shapes (us, M = 16 / 32 / 64): 11008 -> 4096: 13.6 / 15.5 / 20.5 against 17.0 /
-    // 28.6 / 32.4 for the kernels below; 4096 -> 12288: 13.7 / 14.3 / 17.0 against 12.0 / 13.9 / 17.9.
-    const bool lds_x = a.M <= 64 && a.K % 64 == 0 && a.N % 4 == 0 && a.K >= 1024 &&
-                       (a.M > 32 || (a.M >= 4 && a.K > 64 * 8 * 8));
-    if ((g_tile_override == 0 && lds_x) || (g_tile_override == 17 && a.M <= 64 && a.K % 64 == 0 && a.N % 4 == 0 && a.K >= 1024)) {
-        if (a.M <= 16)
-            return launch_skinny_lds_nb<1, 4>(a, s);
-        if (a.M <= 32)
-            return launch_skinny_lds_nb<2, 2>(a, s);
-        return launch_skinny_lds_nb<4, 2>(a, s);
-    }
-    // 4 <= M <= 64, K within what a workgroup's registers hold of X, several 16-row blocks of W per
-    // workgroup to walk over.  Measured at K = 4096, N = 12288: 10.3 / 11.1 / 13.1 / 17.3 us for
-    // M = 4 / 16 / 32 / 64 against 10.9 / 13.5 / 18.5 / 19.4 for the per-block kernel below, which
-    // stays ahead for M = 1 (9.4 against 10.0: a single row of X costs nothing to re-read).  More
-    // waves, a second workgroup per CU or a third block in flight were all slower.
-    if (g_tile_override == 0 && a.M >= 4 && a.M <= 64 && a.K % 64 == 0 && a.K <= 64 * 8 * 8 && a.N % 4 == 0 &&
-        a.N >= 16 * 2 * num_cus()) {
-        if (a.M <= 16)
-            return launch_skinny_resident<1, 8, 8, 2>(a, s, 1);
-        if (a.M <= 32)
-            return launch_skinny_resident<2, 8, 8, 2>(a, s, 1);
-        return launch_skinny_resident<4, 8, 8, 2>(a, s, 1);
-    }
-    // small M: weight-streaming kernel (forced variants keep the tiled kernels, for tests)
-    if (g_tile_override == 0 && a.M <= 64 && a.K % 64 == 0 && a.N % 4 == 0) {
-        // measured on the 7B shapes: enough workgroups to cover the CUs matters more than the
-        // re-reads of X from L2, so few weight rows per workgroup when N is small
-        const bool wide = a.N >= 8192;
-        if (a.M <= 16)
-            return wide ? launch_skinny<1, 1, 8, 8, true>(a, s) : launch_skinny<1, 1, 4, 16, true>(a, s);
-        if (a.M <= 32)
-            return launch_skinny<2, 2, 8, 8, false>(a, s);
-        return wide ? launch_skinny<4, 4, 4, 8, true>(a, s) : launch_skinny<1, 4, 4, 16, true>(a, s);
-    }
+    // small M: the weight-streaming kernel (forced tiled variants keep the tiled kernels, for
+    // tests; 17 forces this one).  Measured cold at the 7B shapes, kernel time in us for M = 1 /
+    // 16 / 32 / 64: 4096 -> 12288: 10.7 / 11.3 / 13.0 / 15.6, 11008 -> 4096: 10.2 / 10.8 / 14.1 / 18.0
+    // (a plain read of the 45-50 MB of weights by one kernel takes 10.2-11.1).
+    if ((g_tile_override == 0 || g_tile_override == 17) && a.M <= 64 && a.K % 64 == 0 && a.N % 4 == 0)
+        return launch_skinny_ring_any(a, s);
     return launch_gemm<true>(a, s);
 }
 

@@ -66,11 +66,11 @@ def test_w8a8_deferred_epilogue_kernel_bit_exact(shape):
 
 @pytest.mark.parametrize("shape", [(4, 4096, 8192), (16, 1024, 8200), (17, 2048, 8192), (33, 4096, 12288),
                                    (64, 64, 8192), (48, 640, 16384), (64, 4096, 8192), (5, 192, 8200)])
-def test_w8a8_resident_activation_kernel_bit_exact(shape):
-    # 4 <= M <= 64, K <= 4096, N >= 8192: the weight-streaming kernel that keeps X in registers and
-    # walks over blocks of weight rows; ragged M and N, K steps fewer than / not a multiple of the waves
+def test_w8a8_weight_streaming_kernel_wide_outputs_bit_exact(shape):
+    # M <= 64 with many blocks of weight rows per workgroup (two to four, and a second pass); ragged M
+    # and N, K shorter than a stage and K that ends inside one
     M, K, N = shape
-    say("w8a8 resident M=%d K=%d N=%d" % (M, K, N))
+    say("w8a8 weight streaming, wide M=%d K=%d N=%d" % (M, K, N))
     x, w = synth.w8a8_inputs(0, M, K=K, N=N)
     ax, aw = oracle.amax_bf16(x), oracle.amax_bf16(w)
     inv_x, inv_w = np.float32(127.0) / ax, np.float32(127.0) / aw
@@ -84,13 +84,13 @@ def test_w8a8_resident_activation_kernel_bit_exact(shape):
 
 @pytest.mark.parametrize("shape", [(1, 1024, 24), (5, 1088, 48), (16, 4160, 4104), (17, 1024, 200), (33, 11008, 72),
                                    (64, 11008, 4104), (64, 2048, 16384), (8, 1024, 20480), (40, 3072, 12288),
-                                   (64, 1024, 8), (32, 5120, 5000)])
-def test_w8a8_lds_staged_activation_kernel_bit_exact(shape):
-    # the weight-streaming kernel that stages X through LDS (forced: variant 17): every M block
-    # count, 1 to 4 weight blocks per workgroup and a second pass (20480 rows), K that ends inside
-    # a chunk (1088, 4160, 11008, 5120), ragged M and N
+                                   (64, 1024, 8), (32, 5120, 5000), (64, 64, 8192), (3, 192, 40), (48, 320, 264)])
+def test_w8a8_weight_streaming_kernel_forced_bit_exact(shape):
+    # the weight-streaming kernel (forced: variant 17): every M block count, 1 to 4 weight blocks per
+    # workgroup and a second pass (20480 rows), K that ends inside a stage (1088, 4160, 11008,
+    # 5120), ragged M and N; twice, the second call finding the first one's LDS and outputs
     M, K, N = shape
-    say("w8a8 lds-staged M=%d K=%d N=%d" % (M, K, N))
+    say("w8a8 weight streaming, forced M=%d K=%d N=%d" % (M, K, N))
     x, w = synth.w8a8_inputs(0, M, K=K, N=N)
     ax, aw = oracle.amax_bf16(x), oracle.amax_bf16(w)
     inv_x, inv_w = np.float32(127.0) / ax, np.float32(127.0) / aw

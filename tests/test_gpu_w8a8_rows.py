@@ -120,10 +120,10 @@ def test_scaled_linear_bit_exact(shape, gran):
 
 @pytest.mark.parametrize("gran", ["KC", "TT"])
 @pytest.mark.parametrize("shape", [(5, 1088, 48), (33, 11008, 72), (64, 2048, 16384), (16, 4160, 4104)])
-def test_scaled_linear_lds_staged_kernel(shape, gran):
-    # the same through the weight-streaming kernel that stages X through LDS (variant 17), bf16 and INT8 outputs
+def test_scaled_linear_weight_streaming_kernel_forced(shape, gran):
+    # the same with the weight-streaming kernel forced (variant 17), bf16 and INT8 outputs
     M, K, N = shape
-    say("w8a8 scaled lds-staged M=%d K=%d N=%d %s" % (M, K, N, gran))
+    say("w8a8 scaled, weight streaming forced M=%d K=%d N=%d %s" % (M, K, N, gran))
     xq, wq, sx, sw = quantised(M, K, N, gran)
     assert np.array_equal(run_scaled(xq, wq, sx, sw, tile=17), oracle.w8a8_linear_scaled(xq, wq, sx, sw))
     inv_out = np.float32(127.0) / np.float32(1.5)
@@ -183,8 +183,8 @@ def test_error_paths():
         tw.tweo_w8a8_linear_scaled(q, q, st[:3], st, y)
 
 
-# INT8 output for a quantised residual stream: the weight-streaming kernels (per-block and
-# resident-X), the tiled kernels on ragged and whole-tile shapes; steps that leave most values in
+# INT8 output for a quantised residual stream: the weight-streaming kernel (one and several
+# weight blocks per workgroup), the tiled kernels on ragged and whole-tile shapes; steps that leave most values in
 # range, and one that saturates
 @pytest.mark.parametrize("gran", ["KC", "TT"])
 @pytest.mark.parametrize("shape", [(1, 4096, 264), (17, 1024, 200), (64, 2048, 136), (64, 4096, 8192), (8, 4096, 8192),
