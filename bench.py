@@ -149,6 +149,20 @@ def time_elementwise(tw, torch, L, peers, iters=20):
             res[mode] = {"GB/s": round(n * bytes_per_elt / ms / 1e6, 1), "us": round(ms * 1e3, 2),
                          "frac_of_hbm_peak": round(n * bytes_per_elt / ms / 1e6 / HBM_PEAK_GBS, 3)}
         out[name] = res
+    # the reduction kernel alone (its own start-to-end events, no clearing launch in front): a pure
+    # read of the tensor, i.e. what one kernel can stream from HBM on this machine
+    ev = GemmEvents(torch, tw)
+    d = []
+    for lo in range(0, 16, 8):
+        ev = GemmEvents(torch, tw)
+        ev.arm(8, 0.0)
+        for k in range(8):
+            tw.tweo_amax(xs[(lo + k) % len(xs)], am[0:1])
+        torch.cuda.synchronize()
+        d += ev.durations_ms()
+    us = sorted(d)[len(d) // 2] * 1e3
+    out["amax"]["cold_kernel_only"] = {"us": round(us, 2), "GB/s": round(2.0 * n / us / 1e3, 1),
+                                       "frac_of_hbm_peak": round(2.0 * n / us / 1e3 / HBM_PEAK_GBS, 3)}
     out["note"] = "cold = rotation over %d distinct %.0f MB tensors (HBM); warm = one tensor (memory-side cache)" % (
         len(xs), n * 2 / 1e6)
     return out
@@ -285,6 +299,13 @@ def time_w8a8(tw, torch, synth, dev, iters=20, copies=8):
             if wqs is None:
                 wq, step_w = quant(up(w))
                 wqs = [wq] + [torch.roll(wq, 16 * 37 * (c + 1), 0) for c in range(copies - 1)]
+            if "plain_read_of_the_weights_cold" not in shape:
+                # what ONE kernel needs to read these bytes cold, doing nothing else: the amax
+                # reduction kernel (its own events) over the same rotating copies
+                am = torch.zeros(4, dtype=torch.float32, device=dev)
+                reads = [(lambda c: (lambda: tw.tweo_amax(wqs[c].view(torch.bfloat16), am[0:1])))(c) for c in range(copies)]
+                us_r = kernel_us(reads + reads)
+                shape["plain_read_of_the_weights_cold"] = {"us": round(us_r, 2), "GB/s": round(N * K / us_r / 1e3, 1)}
             xq, step_x = quant(up(x))
             ys = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in range(copies if M <= 64 else 1)]
             ws = torch.empty(tw.tweo_workspace_bytes(tw.TWEO_OP_W8A8_LINEAR, M, N, K), dtype=torch.uint8, device=dev)

@@ -474,8 +474,8 @@ tweo_status tweo_fp8_linear_bwd_bf16_inject(const void *dy_bf16, const void *a_b
 tweo_status tweo_set_gemm_tile(int variant);
 
 /*
- * Measurement hook for benchmarks: the next `pairs` GEMM kernels that the
- * library launches (FP8 or INT8, any entry point) record events[2i] when the
+ * Measurement hook for benchmarks: the next `pairs` GEMM kernels (FP8 or INT8, any
+ * entry point) or reduction kernels of tweo_amax that the library launches record events[2i] when the
  * kernel starts and events[2i + 1] when it ends, i.e. the kernel's own duration
  * (events recorded on the stream around a call also time the gap that recording
  * them opens in front of the kernel).  `events`: host array of 2 * pairs

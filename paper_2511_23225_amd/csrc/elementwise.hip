@@ -1,6 +1,7 @@
 // HBM-bound passes of the per-tensor FP8 / INT8 recipes: amax reduction, E4M3
 // quantize-cast (with a transposed copy), static INT8 quantize, and the small
 // fill / finish kernels around them.  gfx950 only.
+#include <hip/hip_ext.h>
 #include "kernels.h"
 #include "device_utils.h"
 
@@ -280,10 +281,19 @@ static hipError_t launch_amax_impl(const void *x_bf16, int64_t n, float *amax_ze
         hipLaunchKernelGGL(amax_kernel<true>, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, s,
                            (const uint4 *)x_bf16, n_vec, per_block, (const uint16_t *)x_bf16 + n_vec * 8, n_tail,
                            (uint32_t *)amax_zeroed);
-    else
-        hipLaunchKernelGGL(amax_kernel<false>, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, s,
-                           (const uint4 *)x_bf16, n_vec, per_block, (const uint16_t *)x_bf16 + n_vec * 8, n_tail,
-                           (uint32_t *)amax_zeroed);
+    else {
+        // the stand-alone reduction is also a measurement kernel (a pure read of n elements): it
+        // takes an armed pair of profile events like the GEMM kernels do
+        hipEvent_t e0, e1;
+        if (take_profile_events(&e0, &e1))
+            hipExtLaunchKernelGGL(amax_kernel<false>, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, s, e0, e1, 0,
+                                  (const uint4 *)x_bf16, n_vec, per_block, (const uint16_t *)x_bf16 + n_vec * 8, n_tail,
+                                  (uint32_t *)amax_zeroed);
+        else
+            hipLaunchKernelGGL(amax_kernel<false>, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, s,
+                               (const uint4 *)x_bf16, n_vec, per_block, (const uint16_t *)x_bf16 + n_vec * 8, n_tail,
+                               (uint32_t *)amax_zeroed);
+    }
     if (blocks_out)
         *blocks_out = (int)blocks;
     return hipGetLastError();

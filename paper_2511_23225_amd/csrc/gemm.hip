@@ -1352,12 +1352,20 @@ bool set_profile_events(void *const *events, int pairs)
     g_prof_next = 0;
     return true;
 }
+bool take_profile_events(hipEvent_t *e0, hipEvent_t *e1)
+{
+    if (g_prof_next >= g_prof_count)
+        return false;
+    *e0 = g_prof_events[2 * g_prof_next];
+    *e1 = g_prof_events[2 * g_prof_next + 1];
+    ++g_prof_next;
+    return true;
+}
 template <typename KERNEL, typename... ARGS>
 static void launch_gemm_kernel(KERNEL kernel, dim3 grid, dim3 block, size_t lds, hipStream_t s, ARGS... args)
 {
-    if (g_prof_next < g_prof_count) {
-        hipEvent_t e0 = g_prof_events[2 * g_prof_next], e1 = g_prof_events[2 * g_prof_next + 1];
-        ++g_prof_next;
+    hipEvent_t e0, e1;
+    if (take_profile_events(&e0, &e1)) {
         hipExtLaunchKernelGGL(kernel, grid, block, lds, s, e0, e1, 0, args...);
     } else {
         hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);

@@ -121,6 +121,8 @@ bool stream_k_enabled();
 // Measurement hook: the next `pairs` GEMM kernel launches record events[2i] at their start and
 // events[2i+1] at their end (hipEvent_t handles); false if pairs is out of range.
 bool set_profile_events(void *const *events, int pairs);
+// the next armed pair, if any (consumed): a launch that takes one records them at its start and end
+bool take_profile_events(hipEvent_t *e0, hipEvent_t *e1);
 
 // Tile-shape override for benchmarking sweeps: 0 = heuristic.
 void set_gemm_tile_override(int variant);
