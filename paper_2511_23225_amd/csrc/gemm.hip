@@ -1324,6 +1324,65 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
                                      pack_bf16x2(hi[0] * alpha, hi[1] * alpha), pack_bf16x2(hi[2] * alpha, hi[3] * alpha));
 }
 
+// Second half of a K split on the deferred-epilogue kernel's tiles: the runs sit in the
+// workspace in the order the GEMM's lanes held them ([unit = split * tiles + tile][wave][block]
+// [quarter][lane] float4: rows lane % 32 of the block, columns 8 * quarter + 4 * (lane / 32) .. +3).
+// A wave of this kernel takes one pair of neighbouring blocks of one tile (64 columns x 32 rows),
+// adds the runs in index order, scales, rounds and regroups the lanes' values into whole 128-byte
+// lines of the output as the GEMM's own write-out does.
+__global__ __launch_bounds__(256) void splitk_reduce_defer_kernel(const float4 *__restrict__ partials, int splits,
+                                                                  int tiles_m, int tiles_n, int N,
+                                                                  const float *__restrict__ s0,
+                                                                  const float *__restrict__ s1, uint16_t *__restrict__ out)
+{
+    using T = DeferTile<4>;
+    const float alpha = (*s0) * (*s1);
+    const int lane = threadIdx.x & (kWave - 1), l31 = lane & 31, lh = lane >> 5;
+    const int task = blockIdx.x * 4 + (threadIdx.x >> 6);  // (tile, wave, band i, block pair jp)
+    const int n_tiles = tiles_m * tiles_n;
+    const int tile = task >> 5, wave = (task >> 3) & 3, i = (task >> 1) & 3, jp = task & 1;
+    if (tile >= n_tiles)
+        return;
+    const int wm = wave >> 1, wn = wave & 1;
+    v4f sum[2][4];
+    const int64_t unit_stride = (int64_t)T::NWAVES * T::NB * 4 * kWave;
+    const float4 *src = partials + ((int64_t)tile * T::NWAVES + wave) * (T::NB * 4 * kWave) +
+                        (int64_t)((i * 4 + 2 * jp) * 4) * kWave + lane;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 v = src[(b * 4 + q) * kWave];
+            sum[b][q] = v4f{v.x, v.y, v.z, v.w};
+        }
+    for (int sp = 1; sp < splits; ++sp) {
+        src += (int64_t)n_tiles * unit_stride;
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = src[(b * 4 + q) * kWave];
+                sum[b][q] += v4f{v.x, v.y, v.z, v.w};
+            }
+    }
+    uint32_t A[8], B[8];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            A[2 * q + h] = pack_bf16x2(sum[0][q][2 * h] * alpha, sum[0][q][2 * h + 1] * alpha);
+            B[2 * q + h] = pack_bf16x2(sum[1][q][2 * h] * alpha, sum[1][q][2 * h + 1] * alpha);
+        }
+    block_pair_to_lines(A, B, lane);
+    int tm, tn;
+    tile_from_id(tile, tiles_m, tiles_n, tm, tn);
+    const int64_t row0 = (int64_t)tm * T::BM + wm * 128 + i * 32 + (l31 & ~3);
+    const int64_t col0 = (int64_t)tn * T::BN + wn * 128 + jp * 64 + lh * 32 + (l31 & 3) * 8;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        *(uint4 *)(out + (row0 + u) * N + col0) = make_uint4(A[2 * u], A[2 * u + 1], B[2 * u], B[2 * u + 1]);
+}
+
 // ---------------------------------------------------------------------------
 // host side
 
@@ -1742,10 +1801,35 @@ static hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 // Measured: 349 -> 117 us for that shape, 104 -> 94 us for 2048x2048 over 16384 (64 tiles, the
 // limit taken); at a contraction of 8192 the scratch traffic and the second launch eat the gain
 // (40 -> 46 us), hence the 16384 floor.
+// The same on the deferred-epilogue kernel (whole 256x256 tiles, K in whole 128-byte stages), one
+// unit per CU at most and at least 16 stages per unit (with 8 the fp32 runs' traffic grows faster
+// than the units shrink).  Measured in the blocks' steps: 2304x768 over 50432 tokens 117 -> 88 us,
+// 3072x768 143 -> 111 us, 2048x2048 over 16384 91 -> 71 us; over 8192 tokens 2304x768 49 -> 35 us,
+// 768x768 48 -> 30 us, 3072x768 51 -> 39 us; a contraction of 4096 loses (14 -> 20 us), and so do
+// 64 tiles over 8192 (40 -> 46 us).
+constexpr int kKsplitDeferMinStages = 16, kKsplitDeferMinKt = 64;
+static int defer_ksplit(int64_t M, int64_t N, int64_t K)
+{
+    if (g_tile_override != 0 || M % 256 != 0 || N % 256 != 0 || K % 128 != 0 || N > ((int64_t)1 << 22))
+        return 1;
+    const int64_t tiles = (M / 256) * (N / 256), kt = K / 128, cus = num_cus();
+    if (kt < kKsplitDeferMinKt || tiles * (kt >= 128 ? 4 : 6) > cus)
+        return 1;
+    int64_t splits = cus / tiles;
+    if (splits > kt / kKsplitDeferMinStages)
+        splits = kt / kKsplitDeferMinStages;
+    if (splits > 32)
+        splits = 32;
+    return splits >= 2 ? (int)splits : 1;
+}
+
 int fp8_gemm_ksplit(int64_t M, int64_t N, int64_t K)
 {
     if (g_tile_override != 0)
         return 1;
+    const int ds = defer_ksplit(M, N, K);
+    if (ds > 1)
+        return ds;
     const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256), k_tiles = (K + kBK - 1) / kBK;
     const int64_t cus = num_cus();
     if (tiles * 4 > cus || k_tiles < 128)
@@ -1825,6 +1909,49 @@ static hipError_t launch_ksplit(const GemmArgs &a, hipStream_t s, int splits)
     return hipGetLastError();
 }
 
+template <bool A_E5M2>
+static hipError_t launch_ksplit_defer(const GemmArgs &a, hipStream_t s, int splits)
+{
+    using T = DeferTile<4>;
+    const void *kern = (const void *)gemm_nt_defer_kernel<false, 0, 3, 4, A_E5M2, true, true>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+        if (e != hipSuccess)
+            return e;
+        attr_done = true;
+    }
+    GemmDev g{};
+    g.A = a.A;
+    g.B = a.B;
+    g.M = (int)a.M;
+    g.N = (int)a.N;
+    g.K = (int)a.K;
+    g.s0 = a.s0;
+    g.s1 = a.s1;
+    g.out = (uint16_t *)a.out;
+    g.tiles_m = (int)(a.M / T::BM);
+    g.tiles_n = (int)(a.N / T::BN);
+    g.ksplit = splits;
+    g.ksplit_out = (float *)a.sk_workspace;
+    const int n_tiles = g.tiles_m * g.tiles_n;
+    const dim3 grid((unsigned)(n_tiles * splits)), block(T::THREADS), rgrid((unsigned)(n_tiles * 8));
+    hipEvent_t e0 = nullptr, e1 = nullptr;  // a profiled launch brackets both kernels
+    take_profile_events(&e0, &e1);
+    if (e0 != nullptr)
+        hipExtLaunchKernelGGL((gemm_nt_defer_kernel<false, 0, 3, 4, A_E5M2, true, true>), grid, block, T::LDS_BYTES, s, e0,
+                              nullptr, 0, g);
+    else
+        hipLaunchKernelGGL((gemm_nt_defer_kernel<false, 0, 3, 4, A_E5M2, true, true>), grid, block, T::LDS_BYTES, s, g);
+    if (e1 != nullptr)
+        hipExtLaunchKernelGGL(splitk_reduce_defer_kernel, rgrid, dim3(256), 0, s, nullptr, e1, 0,
+                              (const float4 *)g.ksplit_out, splits, g.tiles_m, g.tiles_n, g.N, a.s0, a.s1, (uint16_t *)a.out);
+    else
+        hipLaunchKernelGGL(splitk_reduce_defer_kernel, rgrid, dim3(256), 0, s, (const float4 *)g.ksplit_out, splits,
+                           g.tiles_m, g.tiles_n, g.N, a.s0, a.s1, (uint16_t *)a.out);
+    return hipGetLastError();
+}
+
 // E5M2 A operand (gradient GEMMs of the HYBRID recipe; no penalty, no residual): the deferred
 // kernel where it applies, else the register-staged kernel.
 static hipError_t launch_fp8_gemm_e5m2(const GemmArgs &a, hipStream_t s)
@@ -1854,6 +1981,8 @@ hipError_t launch_fp8_gemm(const GemmArgs &a, hipStream_t s)
         if (splits > 1 && a.sk_workspace != nullptr && ((uintptr_t)a.sk_workspace & 15u) == 0 &&
             a.sk_workspace_bytes >= (size_t)splits * (size_t)a.M * (size_t)a.N * sizeof(float))
         {
+            if (defer_ksplit(a.M, a.N, a.K) > 1)
+                return a.a_e5m2 ? launch_ksplit_defer<true>(a, s, splits) : launch_ksplit_defer<false>(a, s, splits);
             if (a.a_e5m2)
                 return launch_ksplit<true, false>(a, s, splits);
             return a.K % 64 == 0 ? launch_ksplit<false, true>(a, s, splits) : launch_ksplit<false, false>(a, s, splits);

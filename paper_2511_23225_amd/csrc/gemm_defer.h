@@ -100,7 +100,12 @@ __device__ __forceinline__ void for_each_constant(std::integer_sequence<int, Is.
 // 64 (whole 128-byte lines, 8 rows per instruction); otherwise a lane stores 16 bytes of its own
 // row (32 rows per instruction: 2.25 times the time in the store path, measured on stores that
 // hit in L2).
-template <bool INT8, int PMODE, int D, int MT, bool A_E5M2 = false, bool LINES = true>
+// KSPLIT: g.ksplit workgroups share a tile; workgroup id = split * tiles + tile multiplies its run
+// of K stages (at least two) and leaves the fp32 sums in g.ksplit_out in the order the lanes hold
+// them (unit, wave, block, quarter, lane: every store instruction writes 1 KB contiguously);
+// splitk_reduce_defer_kernel adds the runs in index order, rounds and writes the output.  One
+// unit per workgroup, so nothing is deferred.
+template <bool INT8, int PMODE, int D, int MT, bool A_E5M2 = false, bool LINES = true, bool KSPLIT = false>
 __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
 {
     using T = DeferTile<MT>;
@@ -109,15 +114,21 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int wm = wave >> 1, wn = wave & 1;
     const int l31 = lane & 31, lh = lane >> 5;
-    const int total = g.tiles_m * g.tiles_n;
+    const int n_tiles = g.tiles_m * g.tiles_n;
+    const int total = KSPLIT ? n_tiles * g.ksplit : n_tiles;
     // persistent schedule: round r hands tile ids [r*G, (r+1)*G) to the G workgroups; inside a
     // round each XCD (workgroup index mod 8) gets a contiguous run of ids
     const int G = gridDim.x;
     const int xcd = blockIdx.x & 7, per_xcd = G >> 3, rem_xcd = G & 7;
     const int slot = xcd * per_xcd + (xcd < rem_xcd ? xcd : rem_xcd) + (blockIdx.x >> 3);
-    const int kt = g.K / T::BK;
     if (slot >= total)
         return;
+    int kt = g.K / T::BK, k_first = 0;
+    if constexpr (KSPLIT) {
+        const int split = slot / n_tiles, base = kt / g.ksplit, rem = kt % g.ksplit;
+        k_first = split * base + (split < rem ? split : rem);
+        kt = base + (split < rem ? 1 : 0);
+    }
 
     float alpha;
     if constexpr (INT8)
@@ -149,8 +160,8 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
     Stream sa, sb;
     auto stream_set = [&](Stream &st, bool is_b) {
         int tm, tn;
-        tile_from_id(st.id, g.tiles_m, g.tiles_n, tm, tn);
-        st.ptr = is_b ? g.B + (int64_t)tn * T::BN * g.K : g.A + (int64_t)tm * T::BM * g.K;
+        tile_from_id(KSPLIT ? st.id % n_tiles : st.id, g.tiles_m, g.tiles_n, tm, tn);
+        st.ptr = (is_b ? g.B + (int64_t)tn * T::BN * g.K : g.A + (int64_t)tm * T::BM * g.K) + (int64_t)k_first * T::BK;
         st.s = 0;
         if constexpr (T::EDGE) {
             if (!is_b) {
@@ -170,7 +181,7 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
         if (st.s + 1 < kt) {
             ++st.s;
             st.ptr += T::BK;
-        } else if (st.id + G < total) {
+        } else if (!KSPLIT && st.id + G < total) {
             st.id += G;
             stream_set(st, is_b);
         }
@@ -369,17 +380,8 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
     //             which piece register u of lane a holds piece a of row 4*(row/4) + u.
     //  r = 12..15 store u = r-12: a quad writes 64 contiguous bytes of row 4*(row/4) + u, the two
     //             half-waves the two halves of the line.
-    const bool quad_b0 = (lane & 1) != 0, quad_b1 = (lane & 2) != 0;
     const uint32_t out_quad = (uint32_t)(l31 & ~3) * (uint32_t)g.N * 2u + (uint32_t)lh * 64u + (uint32_t)(l31 & 3) * 16u;
     const int64_t row_bytes = (int64_t)g.N * 2;
-    auto quad_exchange = [&](uint32_t &r0, uint32_t &r1, bool hi, auto ctrl_c) {
-        // lanes with the bit clear: r1 <- partner's r0; lanes with it set: r0 <- partner's r1
-        constexpr int CTRL = decltype(ctrl_c)::value;
-        const uint32_t from0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)r0, CTRL, 0xf, 0xf, true);
-        const uint32_t from1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)r1, CTRL, 0xf, 0xf, true);
-        r0 = hi ? from1 : r0;
-        r1 = hi ? r1 : from0;
-    };
     auto drain_step_lines = [&](int q) {
         const int c = q / 16, r = q % 16, i = c >> 1, jp = c & 1;
         uint32_t *A = packed[i][2 * jp], *B = packed[i][2 * jp + 1];
@@ -393,11 +395,7 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
         } else if (r < 12) {
             const int d = r - 8;
             uint32_t *src = (d & 2) ? B : A;
-            uint32_t &p0 = src[(d & 1)], &p1 = src[2 + (d & 1)], &p2 = src[4 + (d & 1)], &p3 = src[6 + (d & 1)];
-            quad_exchange(p0, p1, quad_b0, std::integral_constant<int, 0xB1>{});  // partner lane ^ 1
-            quad_exchange(p2, p3, quad_b0, std::integral_constant<int, 0xB1>{});
-            quad_exchange(p0, p2, quad_b1, std::integral_constant<int, 0x4E>{});  // partner lane ^ 2
-            quad_exchange(p1, p3, quad_b1, std::integral_constant<int, 0x4E>{});
+            quad_transpose(src[(d & 1)], src[2 + (d & 1)], src[4 + (d & 1)], src[6 + (d & 1)], lane);
         } else {
             const int u = r - 12;
             if (!T::EDGE || i * 32 + (l31 & ~3) + u < prow_left) {
@@ -545,6 +543,34 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
     for (int j = 0; j < 4; ++j)
         load_b(fb[j], 0, j);
 
+    if constexpr (KSPLIT) {
+        stage(no_drain{}, integral_constant<int, 1>{}, false_type{});
+        for (int s = 1; s < kt; ++s)
+            stage(no_drain{}, mid{}, false_type{});
+        // the last MFMAs are still in the pipe (the hardware does not interlock an accumulator
+        // read written as asm against them): a few hundred cycles
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7\n\ts_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+        wait_vmcnt<0>();
+        float4 *dst = (float4 *)g.ksplit_out + ((int64_t)slot * T::NWAVES + wave) * (T::NB * 4 * kWave) + lane;
+#pragma unroll
+        for (int b = 0; b < T::NB; ++b)
+#pragma unroll
+            for (int hq = 0; hq < 2; ++hq) {
+                float t[8];
+                asm volatile("v_accvgpr_read_b32 %0, %8\n\tv_accvgpr_read_b32 %1, %9\n\t"
+                             "v_accvgpr_read_b32 %2, %10\n\tv_accvgpr_read_b32 %3, %11\n\t"
+                             "v_accvgpr_read_b32 %4, %12\n\tv_accvgpr_read_b32 %5, %13\n\t"
+                             "v_accvgpr_read_b32 %6, %14\n\tv_accvgpr_read_b32 %7, %15"
+                             : "=v"(t[0]), "=v"(t[1]), "=v"(t[2]), "=v"(t[3]), "=v"(t[4]), "=v"(t[5]), "=v"(t[6]), "=v"(t[7])
+                             : "a"(acc[b >> 2][b & 3][8 * hq + 0]), "a"(acc[b >> 2][b & 3][8 * hq + 1]),
+                               "a"(acc[b >> 2][b & 3][8 * hq + 2]), "a"(acc[b >> 2][b & 3][8 * hq + 3]),
+                               "a"(acc[b >> 2][b & 3][8 * hq + 4]), "a"(acc[b >> 2][b & 3][8 * hq + 5]),
+                               "a"(acc[b >> 2][b & 3][8 * hq + 6]), "a"(acc[b >> 2][b & 3][8 * hq + 7]));
+                dst[(b * 4 + 2 * hq) * kWave] = make_float4(t[0], t[1], t[2], t[3]);
+                dst[(b * 4 + 2 * hq + 1) * kWave] = make_float4(t[4], t[5], t[6], t[7]);
+            }
+        return;
+    }
     // first tile: nothing to write out yet
     int id = slot;
     {

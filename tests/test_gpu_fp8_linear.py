@@ -275,8 +275,11 @@ def test_bwd(case, tile):
 
 # outputs of a few 256x256 tiles under a very long contraction: the K split (several workgroups per
 # tile, fp32 runs added in order by a second kernel).  wgrad over 16384 tokens of a 768-wide layer
-# (8 runs), a ragged one whose last K stage is partial, a dgrad over a long N; each run twice.
-@pytest.mark.parametrize("case", [(1, 1, 16384, 768, 768), (3, 0, 16400, 264, 528), (0, 0, 256, 512, 16384)])
+# (8 runs on the deferred-epilogue kernel), a ragged one whose last K stage is partial (the
+# register-staged kernel), a dgrad over a long N, a wgrad over 8192 tokens (4 runs of 16 stages) and
+# one whose stages do not divide evenly over the runs (67 stages, 4 runs); each run twice.
+@pytest.mark.parametrize("case", [(1, 1, 16384, 768, 768), (3, 0, 16400, 264, 528), (0, 0, 256, 512, 16384),
+                                  (1, 0, 8192, 768, 2304), (1, 2, 8576, 512, 768)])
 def test_bwd_k_split(case):
     cfg, gi, M, K, N = case
     say("bwd K split cfg=%d M=%d K=%d N=%d" % (cfg, M, K, N))

@@ -87,6 +87,7 @@ HYBRID_CASES = [
     (3, 2, 2304, 512, 4608, 15),
     (1, 1, 2048, 768, 2304, 16),
     (3, 0, 16400, 264, 528, 0),  # few tiles, long contraction: the K split with an E5M2 operand
+    (1, 1, 16384, 768, 768, 0),  # the same on whole 256x256 tiles: the deferred-epilogue kernel's K split
 ]
 
 

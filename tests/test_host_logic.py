@@ -30,9 +30,12 @@ def test_k_split_scratch_is_in_the_backward_workspace():
     M, N, K = 50432, 2304, 768
     bwd = tw.tweo_workspace_bytes(tw.TWEO_OP_FP8_LINEAR_BWD, M, N, K)
     assert bwd == 256 + 9 * N * K * 4
-    # the LLaMA output projection: 64 tiles, 4 runs; a contraction of 8192 is not split
+    # the LLaMA output projection: 64 tiles, 4 runs; a contraction of 8192 gives 4 runs of 16 stages
+    # for up to 42 tiles and none for 64; one of 4096 is not split
     assert tw.tweo_workspace_bytes(tw.TWEO_OP_FP8_LINEAR_BWD, 16384, 2048, 2048) == 256 + 4 * 2048 * 2048 * 4
-    assert tw.tweo_workspace_bytes(tw.TWEO_OP_FP8_LINEAR_BWD, 8192, 2304, 768) == 512
+    assert tw.tweo_workspace_bytes(tw.TWEO_OP_FP8_LINEAR_BWD, 8192, 2304, 768) == 256 + 4 * 2304 * 768 * 4
+    assert tw.tweo_workspace_bytes(tw.TWEO_OP_FP8_LINEAR_BWD, 8192, 4096, 1024) == 512
+    assert tw.tweo_workspace_bytes(tw.TWEO_OP_FP8_LINEAR_BWD, 4096, 768, 768) == 512
     # many tiles: nothing beyond the fixed part
     assert tw.tweo_workspace_bytes(tw.TWEO_OP_FP8_LINEAR_BWD, 16384, 6144, 2048) == 512
 
