@@ -1373,7 +1373,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_defer_kernel(const float4 *
             A[2 * q + h] = pack_bf16x2(sum[0][q][2 * h] * alpha, sum[0][q][2 * h + 1] * alpha);
             B[2 * q + h] = pack_bf16x2(sum[1][q][2 * h] * alpha, sum[1][q][2 * h + 1] * alpha);
         }
-    block_pair_to_lines(A, B, lane);
+    block_pair_to_lines(A, B);
     int tm, tn;
     tile_from_id(tile, tiles_m, tiles_n, tm, tn);
     const int64_t row0 = (int64_t)tm * T::BM + wm * 128 + i * 32 + (l31 & ~3);
@@ -1759,16 +1759,20 @@ static hipError_t launch_defer_inst(const GemmArgs &a, hipStream_t s)
 template <bool INT8>
 static hipError_t launch_defer(const GemmArgs &a, hipStream_t s)
 {
-    // a tile is written out over the first 15, 7 or 3 stages of the next one (never its last)
+    // a tile is written out over the first 15, 7, 5 or 3 stages of the next one (never its last)
     const int64_t kt = a.K / 128;
     if (a.p == 4) {
         if (kt >= 16)
             return launch_defer_inst<INT8, 4, 15, 4>(a, s);
-        return kt >= 8 ? launch_defer_inst<INT8, 4, 7, 4>(a, s) : launch_defer_inst<INT8, 4, 3, 4>(a, s);
+        if (kt >= 8)
+            return launch_defer_inst<INT8, 4, 7, 4>(a, s);
+        return kt >= 6 ? launch_defer_inst<INT8, 4, 5, 4>(a, s) : launch_defer_inst<INT8, 4, 3, 4>(a, s);
     }
     if (kt >= 16)
         return launch_defer_inst<INT8, 0, 15, 4>(a, s);
-    return kt >= 8 ? launch_defer_inst<INT8, 0, 7, 4>(a, s) : launch_defer_inst<INT8, 0, 3, 4>(a, s);
+    if (kt >= 8)
+        return launch_defer_inst<INT8, 0, 7, 4>(a, s);
+    return kt >= 6 ? launch_defer_inst<INT8, 0, 5, 4>(a, s) : launch_defer_inst<INT8, 0, 3, 4>(a, s);
 }
 
 // 192x256 tiles: long contractions only (K >= 2048)
@@ -1963,7 +1967,9 @@ static hipError_t launch_fp8_gemm_e5m2(const GemmArgs &a, hipStream_t s)
         const int64_t kt = a.K / 128;
         if (kt >= 16)
             return launch_defer_inst<false, 0, 15, 4, true>(a, s);
-        return kt >= 8 ? launch_defer_inst<false, 0, 7, 4, true>(a, s) : launch_defer_inst<false, 0, 3, 4, true>(a, s);
+        if (kt >= 8)
+            return launch_defer_inst<false, 0, 7, 4, true>(a, s);
+        return kt >= 6 ? launch_defer_inst<false, 0, 5, 4, true>(a, s) : launch_defer_inst<false, 0, 3, 4, true>(a, s);
     }
     if (v == 16)
         return launch_defer_inst<false, 0, 15, 3, true>(a, s);

@@ -83,8 +83,64 @@ struct DeferTile {
     }
 };
 
+// Where the write-out of a tile happens inside the first D stages of the next one (LINES).  Per
+// pair of neighbouring blocks there are 20 arithmetic micro-steps (penalty terms, lane exchanges)
+// and 4 stores.  The arithmetic is dealt evenly over all slots from slot 2 on; a store goes to the
+// first slot without an operand load (the two share the address unit) after its pair's arithmetic,
+// one store per slot.  alu_lo/alu_hi: the arithmetic steps of slot s; store: the store of slot s or -1.
+template <typename T, int D>
+struct DrainPlan {
+    static constexpr int NSLOT = D * T::SLOTS, PAIRS = T::NB / 2, ALU = PAIRS * 20, STORES = PAIRS * 4;
+    int alu_lo[NSLOT], alu_hi[NSLOT], store[NSLOT];
+    bool ok;
+};
+template <typename T, int D>
+constexpr DrainPlan<T, D> make_drain_plan()
+{
+    using P = DrainPlan<T, D>;
+    constexpr int FIRST = 2;
+    // the arithmetic ends as late as still leaves store slots for the last pairs (the last slots
+    // of a stage carry loads)
+    for (int end = P::NSLOT - 8; end > P::NSLOT / 2; --end) {
+        P p{};
+        int at[P::ALU] = {};
+        for (int a = 0; a < P::ALU; ++a)
+            at[a] = FIRST + (int)((long long)a * (end - FIRST) / P::ALU);
+        for (int s = 0, a = 0; s < P::NSLOT; ++s) {
+            p.alu_lo[s] = a;
+            while (a < P::ALU && at[a] == s)
+                ++a;
+            p.alu_hi[s] = a;
+            p.store[s] = -1;
+        }
+        int s = 0;
+        p.ok = true;
+        for (int st = 0; st < P::STORES && p.ok; ++st) {
+            const int ready = at[(st / 4) * 20 + 19] + 1;  // the slot after the pair's last exchange
+            if (s < ready)
+                s = ready;
+            while (s < P::NSLOT && T::load_slot(s % T::SLOTS))
+                ++s;
+            if (s >= P::NSLOT)
+                p.ok = false;
+            else
+                p.store[s++] = st;
+        }
+        if (p.ok)
+            return p;
+    }
+    P bad{};
+    bad.ok = false;
+    return bad;
+}
+
+template <typename T, int D>
+struct DrainPlanOf {  // evaluated once per tile shape and D, not once per slot body
+    static constexpr DrainPlan<T, D> value = make_drain_plan<T, D>();
+};
+
 // PMODE: 4 = TWEO penalty with p = 4 (the paper's setting), 0 = none.  D: number of stages of
-// the next tile over which the write-out of a tile is spread (3, 7 or 15; needs K >= 128 * (D + 1):
+// the next tile over which the write-out of a tile is spread (3, 5, 7 or 15; needs K >= 128 * (D + 1):
 // the tile's last stage, which converts its own blocks, takes no part in it).
 // calls f(integral_constant<int, 0>), f(integral_constant<int, 1>), ... in order
 template <typename F, int... Is>
@@ -154,24 +210,64 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
     uint32_t voffs_a[T::EDGE ? T::NA : 1];
     struct Stream {
         const uint8_t *ptr;  // first row of the tile's panel, at the stage to load next
-        int s, id;           // that stage and its tile id
+        int s;               // that stage
         uint32_t bufoff;     // LDS buffer it goes to: 0 or STAGE_STRIDE
     };
     Stream sa, sb;
-    auto stream_set = [&](Stream &st, bool is_b) {
-        int tm, tn;
-        tile_from_id(KSPLIT ? st.id % n_tiles : st.id, g.tiles_m, g.tiles_n, tm, tn);
-        st.ptr = (is_b ? g.B + (int64_t)tn * T::BN * g.K : g.A + (int64_t)tm * T::BM * g.K) + (int64_t)k_first * T::BK;
-        st.s = 0;
+    // Where this workgroup's tiles lie, 64 of them at a time: lane r holds the operand offsets of
+    // its tile number vec_r0 + r (id = slot + number * G), worked out by the vector unit once; at a
+    // tile boundary the scalar side fetches one lane's values instead of dividing (the divisions
+    // of the id raster cost both streams about 250 cycles per tile when done in scalar code).
+    uint32_t ta_lo = 0, ta_hi = 0, tb_lo = 0, tb_hi = 0;
+    int tvalid = 0, tmv = 0, tnv = 0, vec_r0 = 0;
+    auto tiles_fill = [&](int r0) {
+        const int id_l = KSPLIT ? slot % n_tiles : slot + (r0 + lane) * G;
+        int tm = 0, tn = 0;
+        if (id_l < (KSPLIT ? n_tiles : total))
+            tile_from_id(id_l, g.tiles_m, g.tiles_n, tm, tn);
+        const uint64_t oa = (uint64_t)tm * T::BM * (uint64_t)g.K, ob = (uint64_t)tn * T::BN * (uint64_t)g.K;
+        ta_lo = (uint32_t)oa;
+        ta_hi = (uint32_t)(oa >> 32);
+        tb_lo = (uint32_t)ob;
+        tb_hi = (uint32_t)(ob >> 32);
+        tvalid = g.M - tm * T::BM;
+        tmv = tm;
+        tnv = tn;
+        vec_r0 = r0;
+    };
+    auto tile_a = [&](int r) {
+        const int l = r - vec_r0;
+        return g.A + (((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)ta_hi, l) << 32) |
+                      (uint32_t)__builtin_amdgcn_readlane((int)ta_lo, l)) + (int64_t)k_first * T::BK;
+    };
+    auto tile_b = [&](int r) {
+        const int l = r - vec_r0;
+        return g.B + (((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)tb_hi, l) << 32) |
+                      (uint32_t)__builtin_amdgcn_readlane((int)tb_lo, l)) + (int64_t)k_first * T::BK;
+    };
+    auto set_voffs_a = [&](int valid) {  // EDGE: rows past the matrix load the last valid one
         if constexpr (T::EDGE) {
-            if (!is_b) {
-                const int valid = g.M - tm * T::BM;  // >= 1
 #pragma unroll
-                for (int p8 = 0; p8 < T::NA; ++p8) {
-                    const int r = p8 * 32 + wave * 8 + dma_row;
-                    voffs_a[p8] = (uint32_t)(r < valid ? r : valid - 1) * (uint32_t)g.K + dma_chunk;
-                }
+            for (int p8 = 0; p8 < T::NA; ++p8) {
+                const int r = p8 * 32 + wave * 8 + dma_row;
+                voffs_a[p8] = (uint32_t)(r < valid ? r : valid - 1) * (uint32_t)g.K + dma_chunk;
             }
+        }
+    };
+    // the tile the streams move on to while tile number r - 1 is multiplied
+    const uint8_t *next_a = nullptr, *next_b = nullptr;
+    int next_valid = 0, next_tm = 0, next_tn = 0;
+    bool has_next = false;
+    auto plan_next = [&](int r) {
+        has_next = !KSPLIT && slot + r * G < total;
+        if (has_next) {
+            if (r - vec_r0 >= kWave)
+                tiles_fill(r);
+            next_a = tile_a(r);
+            next_b = tile_b(r);
+            next_valid = __builtin_amdgcn_readlane(tvalid, r - vec_r0);
+            next_tm = __builtin_amdgcn_readlane(tmv, r - vec_r0);
+            next_tn = __builtin_amdgcn_readlane(tnv, r - vec_r0);
         }
     };
     // Past the workgroup's last stage a stream keeps re-reading that stage (in bounds) into
@@ -181,9 +277,11 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
         if (st.s + 1 < kt) {
             ++st.s;
             st.ptr += T::BK;
-        } else if (!KSPLIT && st.id + G < total) {
-            st.id += G;
-            stream_set(st, is_b);
+        } else if (has_next) {
+            st.ptr = is_b ? next_b : next_a;
+            st.s = 0;
+            if (!is_b)
+                set_voffs_a(next_valid);
         }
     };
     auto dma_piece_a = [&](int p8) {
@@ -337,7 +435,7 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
     // of a half exchanges words between lane and lane + 32 (word 4P+2 of the lower lanes <-> word
     // 4P of the upper ones, likewise 4P+3 <-> 4P+1), after which the four words of a lane are
     // eight consecutive columns; steps 1 and 2 add the penalty terms; step 3 stores.
-    auto drain_step_rows = [&](int q) {
+    auto drain_step = [&](int q) {
         const int b = q / T::STEPS_PER_BLOCK, i = b >> 2, j = b & 3;
         const int P = (q % T::STEPS_PER_BLOCK) >> 2, k = q & 3;
         uint32_t *w = &packed[i][j][4 * P];
@@ -369,52 +467,51 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
         if (k == 3 && j == 3 && P == 1)
             sp += rows32;
     };
-    // LINES.  Micro-step q works on the pair of neighbouring blocks q / 16 (blocks 2c, 2c+1 of band
-    // i: 64 columns = one 128-byte line per row), r = q % 16:
-    //  r = 0..7   word r of both blocks: penalty terms, then the word of block 2c+1 in the lower
-    //             half-wave is exchanged with the word of block 2c in the upper one.  After the
-    //             eight exchanges lane (row, lh) holds all 32 columns of its row in block 2c+lh:
-    //             16-byte piece u = words {A[2u], A[2u+1], B[2u], B[2u+1]} (A, B: the register
-    //             arrays of blocks 2c and 2c+1).
-    //  r = 8..11  dword r-8 of the four pieces: 4x4 transposition over the lanes of a quad, after
+    // LINES.  Arithmetic step a works on the pair of neighbouring blocks c = a / 20 (blocks 2c,
+    // 2c+1 of band i: 64 columns = one 128-byte line per row), r = a % 20, with A, B the register
+    // arrays of blocks 2c and 2c+1:
+    //  r = 0..15  word w = r/2: penalty terms of A[w] (even r) / of B[w] (odd r), after which B[w]
+    //             of the lower half-wave is exchanged with A[w] of the upper one.  After the eight
+    //             exchanges lane (row, lh) holds all 32 columns of its row in block 2c+lh: 16-byte
+    //             piece u = words {A[2u], A[2u+1], B[2u], B[2u+1]}.
+    //  r = 16..19 dword r-16 of the four pieces: 4x4 transposition over the lanes of a quad, after
     //             which piece register u of lane a holds piece a of row 4*(row/4) + u.
-    //  r = 12..15 store u = r-12: a quad writes 64 contiguous bytes of row 4*(row/4) + u, the two
-    //             half-waves the two halves of the line.
+    // Store step st: pair st / 4, u = st % 4: a quad writes 64 contiguous bytes of row
+    // 4*(row/4) + u, the two half-waves the two halves of the line.
     const uint32_t out_quad = (uint32_t)(l31 & ~3) * (uint32_t)g.N * 2u + (uint32_t)lh * 64u + (uint32_t)(l31 & 3) * 16u;
     const int64_t row_bytes = (int64_t)g.N * 2;
-    auto drain_step_lines = [&](int q) {
-        const int c = q / 16, r = q % 16, i = c >> 1, jp = c & 1;
+    const QuadMasks qmasks = quad_masks();
+    auto drain_alu = [&](int a) {
+        const int c = a / 20, r = a % 20, i = c >> 1, jp = c & 1;
         uint32_t *A = packed[i][2 * jp], *B = packed[i][2 * jp + 1];
-        if (r < 8) {
-            if (PMODE != 0 && (!T::EDGE || i * 32 + l31 < prow_left)) {
-                pen_word(A[r]);
-                pen_word(B[r]);
-            }
+        if (r < 16) {
+            const int w = r >> 1;
+            if (PMODE != 0 && (!T::EDGE || i * 32 + l31 < prow_left))
+                pen_word((r & 1) ? B[w] : A[w]);
             // the swap reads its operands early, and what follows may read its results early
-            asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(A[r]), "+v"(B[r]));
-        } else if (r < 12) {
-            const int d = r - 8;
-            uint32_t *src = (d & 2) ? B : A;
-            quad_transpose(src[(d & 1)], src[2 + (d & 1)], src[4 + (d & 1)], src[6 + (d & 1)], lane);
+            if (r & 1)
+                asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(A[w]), "+v"(B[w]));
         } else {
-            const int u = r - 12;
-            if (!T::EDGE || i * 32 + (l31 & ~3) + u < prow_left) {
-                const v4i v = {(int)A[2 * u], (int)A[2 * u + 1], (int)B[2 * u], (int)B[2 * u + 1]};
-                const uint8_t *spu = sp + u * row_bytes;
-                asm volatile("global_store_dwordx4 %0, %1, %2 offset:%3\n\ts_nop 1"
-                             :
-                             : "v"(out_quad), "v"(v), "s"(spu), "n"(jp * 128)
-                             : "memory");
-            }
-            if (u == 3 && jp == 1)
-                sp += rows32;
+            const int d = r - 16;
+            uint32_t *src = (d & 2) ? B : A;
+            quad_transpose(src[(d & 1)], src[2 + (d & 1)], src[4 + (d & 1)], src[6 + (d & 1)], qmasks);
         }
     };
-    auto drain_step = [&](int q) {
-        if constexpr (LINES)
-            drain_step_lines(q);
-        else
-            drain_step_rows(q);
+    auto drain_store = [&](int st) {
+        const int c = st / 4, u = st % 4, i = c >> 1, jp = c & 1;
+        uint32_t *A = packed[i][2 * jp], *B = packed[i][2 * jp + 1];
+        if (!T::EDGE || i * 32 + (l31 & ~3) + u < prow_left) {
+            const v4i v = {(int)A[2 * u], (int)A[2 * u + 1], (int)B[2 * u], (int)B[2 * u + 1]};
+            const uint8_t *spu = sp + u * row_bytes;
+            // a store of more than 8 bytes reads its data late: nothing may write those
+            // registers in the next wait states (the compiler does not know this is a store)
+            asm volatile("global_store_dwordx4 %0, %1, %2 offset:%3\n\ts_nop 1"
+                         :
+                         : "v"(out_quad), "v"(v), "s"(spu), "n"(jp * 128)
+                         : "memory");
+        }
+        if (u == 3 && jp == 1)
+            sp += rows32;
     };
 
     // The penalty terms are summed per lane over every tile of the workgroup (a few thousand
@@ -494,7 +591,21 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
                         if ((LAST && T::convert_slot(h) == t) || (FIRST == 2 && T::convert_slot(h) == t + T::SLOTS))
                             convert_half(h);
                     // write-out of the previous tile
-                    if constexpr (DR >= 0 && !T::load_slot(t)) {
+                    if constexpr (DR >= 0 && LINES) {
+                        using Plan = DrainPlanOf<T, D>;
+                        static_assert(Plan::value.ok, "the write-out fits the first D stages");
+                        constexpr int ds = DR * T::SLOTS + t;
+                        constexpr int a_lo = Plan::value.alu_lo[ds], a_hi = Plan::value.alu_hi[ds], st = Plan::value.store[ds];
+                        static_assert(a_hi - a_lo <= 3, "at most three arithmetic steps per slot");
+                        if constexpr (a_lo < a_hi)
+                            drain_alu(a_lo);
+                        if constexpr (a_lo + 1 < a_hi)
+                            drain_alu(a_lo + 1);
+                        if constexpr (a_lo + 2 < a_hi)
+                            drain_alu(a_lo + 2);
+                        if constexpr (st >= 0)
+                            drain_store(st);
+                    } else if constexpr (DR >= 0 && !T::load_slot(t)) {
                         constexpr int w = DR * T::FREE + T::free_index(t);
                         constexpr int q_lo = (w * T::DRAIN_STEPS + W - 1) / W;
                         constexpr int q_hi = ((w + 1) * T::DRAIN_STEPS + W - 1) / W;
@@ -518,10 +629,14 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
     typedef integral_constant<int, 0> mid;
 
     // ---- prologue: stage 0 whole, B of stage 1, the first half of the A pieces of stage 1 ----
-    sa.id = sb.id = slot;
+    tiles_fill(0);
     sa.bufoff = sb.bufoff = 0;
-    stream_set(sa, false);
-    stream_set(sb, true);
+    sa.s = sb.s = 0;
+    sa.ptr = tile_a(0);
+    sb.ptr = tile_b(0);
+    set_voffs_a(__builtin_amdgcn_readlane(tvalid, 0));
+    const int first_tm = __builtin_amdgcn_readlane(tmv, 0), first_tn = __builtin_amdgcn_readlane(tnv, 0);
+    plan_next(1);
 #pragma unroll
     for (int p8 = 0; p8 < T::NA; ++p8)
         dma_piece_a(p8);
@@ -574,8 +689,7 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
     // first tile: nothing to write out yet
     int id = slot;
     {
-        int tm, tn;
-        tile_from_id(id, g.tiles_m, g.tiles_n, tm, tn);
+        const int tm = first_tm, tn = first_tn;
         stage(no_drain{}, integral_constant<int, 1>{}, false_type{});
         for (int s = 1; s < kt - 1; ++s)
             stage(no_drain{}, mid{}, false_type{});
@@ -583,15 +697,19 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
         store_begin(tm, tn);
     }
     // every further tile writes its predecessor out during its first D stages
+    int round = 0;
     for (id += G; id < total; id += G) {
-        int tm, tn;
-        tile_from_id(id, g.tiles_m, g.tiles_n, tm, tn);
+        const int tm = next_tm, tn = next_tn;  // what the last plan_next fetched: this tile
+        ++round;
+        plan_next(round + 1);
         stage(integral_constant<int, 0>{}, integral_constant<int, 2>{}, false_type{});
         stage(integral_constant<int, 1>{}, mid{}, false_type{});
         stage(integral_constant<int, 2>{}, mid{}, false_type{});
-        if constexpr (D >= 7) {
+        if constexpr (D >= 5) {
             stage(integral_constant<int, 3>{}, mid{}, false_type{});
             stage(integral_constant<int, 4>{}, mid{}, false_type{});
+        }
+        if constexpr (D >= 7) {
             stage(integral_constant<int, 5>{}, mid{}, false_type{});
             stage(integral_constant<int, 6>{}, mid{}, false_type{});
         }
