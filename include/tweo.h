@@ -451,6 +451,26 @@ tweo_status tweo_fp8_linear_bwd_bf16_inject(const void *dy_bf16, const void *a_b
                                             void *stream);
 
 /*
+ * Sec. 4.3, current scaling.  The bf16 entry points (tweo_fp8_linear_fwd_bf16,
+ * tweo_fp8_linear_bwd_bf16 and its hybrid form) take the amax and cast their
+ * tensors in ONE launch that holds the data in registers between the two steps
+ * (4 instead of 6 bytes of traffic per element for what fits the chip).  That
+ * kernel waits inside for all of its workgroups, one per CU, so all of them must be
+ * able to run at the same time.  One stream, or several streams that do not run two
+ * of these entry points at the same moment, need nothing.  A caller that lets them
+ * overlap on one device (each launch could hold a part of the CUs and wait for the
+ * rest) calls tweo_set_fused_cast(0) first: the entry points then use one amax and
+ * one cast launch as before, with identical results.  Process-wide, not thread
+ * safe, default 1.  Under stream capture the two-launch form is always used.
+ * The wait is bounded (about 0.1 s): a launch that gives up makes the amax and the
+ * scales it returns NaN and counts itself; tweo_fused_cast_timeouts copies that
+ * per-device count to *count (host pointer; synchronises with the device; 0 in
+ * any correct run).
+ */
+tweo_status tweo_set_fused_cast(int on);
+tweo_status tweo_fused_cast_timeouts(unsigned *count);
+
+/*
  * Tuning hook for benchmarks and tests: forces the GEMM kernel variant.
  * 0 = choose from the shape (the default).  1, 3, 4 = register-staged kernel, tiles
  * 256x256, 128x128, 64x64 (any K % 16 == 0).  6, 8 = DMA-pipelined kernel with

@@ -19,7 +19,8 @@ TWEO_OK, TWEO_ERR_INVALID_ARG, TWEO_ERR_UNSUPPORTED, TWEO_ERR_WORKSPACE, TWEO_ER
 EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quantize_e4m3",
            "tweo_fp8_linear_fwd", "tweo_fp8_linear_bwd", "tweo_quantize_i8", "tweo_w8a8_linear",
            "tweo_fp8_linear_fwd_bf16", "tweo_fp8_linear_bwd_bf16", "tweo_set_gemm_tile",
-           "tweo_set_stream_k", "tweo_penalty_grad_inject", "tweo_delayed_state_bytes",
+           "tweo_set_stream_k", "tweo_set_fused_cast", "tweo_fused_cast_timeouts",
+           "tweo_penalty_grad_inject", "tweo_delayed_state_bytes",
            "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed", "tweo_profile_gemm_launches",
            "tweo_quantize_e5m2", "tweo_fp8_linear_bwd_hybrid", "tweo_fp8_linear_bwd_bf16_hybrid",
            "tweo_quantize_i8_rows", "tweo_w8a8_linear_scaled", "tweo_w8a8_linear_scaled_i8out",
@@ -94,6 +95,8 @@ def load():
                                                   ctypes.POINTER(Fp8Saved), i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     L.tweo_set_gemm_tile.argtypes = [ctypes.c_int]
     L.tweo_set_stream_k.argtypes = [ctypes.c_int]
+    L.tweo_set_fused_cast.argtypes = [ctypes.c_int]
+    L.tweo_fused_cast_timeouts.argtypes = [ctypes.POINTER(ctypes.c_uint)]
     L.tweo_profile_gemm_launches.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
     L.tweo_delayed_state_bytes.argtypes = []
     L.tweo_delayed_state_bytes.restype = ctypes.c_size_t
@@ -150,6 +153,16 @@ def tweo_set_gemm_tile(variant):
 
 def tweo_set_stream_k(on):
     _check(load().tweo_set_stream_k(1 if on else 0), "tweo_set_stream_k")
+
+
+def tweo_set_fused_cast(on):
+    _check(load().tweo_set_fused_cast(1 if on else 0), "tweo_set_fused_cast")
+
+
+def tweo_fused_cast_timeouts():
+    c = ctypes.c_uint(0)
+    _check(load().tweo_fused_cast_timeouts(ctypes.byref(c)), "tweo_fused_cast_timeouts")
+    return int(c.value)
 
 
 def tweo_profile_gemm_launches(events):

@@ -72,6 +72,23 @@ tweo_status tweo_profile_gemm_launches(void *const *events, int pairs)
     return set_profile_events(events, pairs) ? TWEO_OK : TWEO_ERR_UNSUPPORTED;
 }
 
+tweo_status tweo_set_fused_cast(int on)
+{
+    set_fused_cast(on != 0);
+    return TWEO_OK;
+}
+
+tweo_status tweo_fused_cast_timeouts(unsigned *count)
+{
+    if (!count)
+        return TWEO_ERR_INVALID_ARG;
+    uint32_t c = 0;
+    if (fused_cast_timeouts(&c) != hipSuccess)
+        return TWEO_ERR_HIP;
+    *count = c;
+    return TWEO_OK;
+}
+
 tweo_status tweo_set_gemm_tile(int variant)
 {
     if (!gemm_variant_exists(variant))
@@ -555,12 +572,19 @@ tweo_status tweo_fp8_linear_fwd_bf16(const void *x_bf16, const void *w_bf16,
     // activation and weight share one amax launch and one cast launch (a kernel of its own for
     // the small weight tensor is mostly launch and tail latency); the amax launch leaves one
     // maximum per workgroup, the cast launch reduces them: nothing to clear, no atomics
-    uint32_t *px = (uint32_t *)workspace, *pw = px + kAmaxPartialsMax;
-    int nx = 0, nw = 0;
-    hipError_t e = launch_amax2_partials(x_bf16, M * K, px, &nx, w_bf16, N * K, pw, &nw, s);
-    if (e == hipSuccess)
-        e = launch_quantize2_e4m3(x_bf16, M, K, sc + 0, saved->xq, saved->xqT, sc + 1, sc + 2, w_bf16, N, K,
-                                  sc + 3, saved->wq, saved->wqT, sc + 4, sc + 5, s, px, nx, pw, nw);
+    // (or, where it applies, one launch for both steps that keeps the tensors on chip in between)
+    hipError_t e;
+    if (fused_cast_applies(M, K, N, K, s)) {
+        e = launch_amax_cast_fused(x_bf16, M, K, sc + 0, saved->xq, saved->xqT, sc + 1, sc + 2, w_bf16, N, K, sc + 3,
+                                   saved->wq, saved->wqT, sc + 4, sc + 5, false, workspace, s);
+    } else {
+        uint32_t *px = (uint32_t *)workspace, *pw = px + kAmaxPartialsMax;
+        int nx = 0, nw = 0;
+        e = launch_amax2_partials(x_bf16, M * K, px, &nx, w_bf16, N * K, pw, &nw, s);
+        if (e == hipSuccess)
+            e = launch_quantize2_e4m3(x_bf16, M, K, sc + 0, saved->xq, saved->xqT, sc + 1, sc + 2, w_bf16, N, K,
+                                      sc + 3, saved->wq, saved->wqT, sc + 4, sc + 5, s, px, nx, pw, nw);
+    }
     if (e != hipSuccess)
         return TWEO_ERR_HIP;
     return tweo_fp8_linear_fwd(saved->xq, sc + 2, saved->wq, sc + 5, residual_bf16, M, N, K, y_bf16,
@@ -582,11 +606,17 @@ static tweo_status fp8_linear_bwd_bf16_impl(const void *dy_bf16, const tweo_fp8_
         return TWEO_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     float *sc = saved->scalars;
-    uint32_t *pdy = (uint32_t *)workspace;
-    int ndy = 0;
-    hipError_t e = launch_amax_partials(dy_bf16, M * N, pdy, &ndy, s);
-    if (e == hipSuccess)
-        e = launch_quantize_f8_from_partials(dy_bf16, M, N, pdy, ndy, dy_e5m2, sc + 6, dyq, dyqT, sc + 7, sc + 8, s);
+    hipError_t e;
+    if (fused_cast_applies(M, N, 0, 0, s)) {
+        e = launch_amax_cast_fused(dy_bf16, M, N, sc + 6, dyq, dyqT, sc + 7, sc + 8, nullptr, 0, 0, nullptr, nullptr,
+                                   nullptr, nullptr, nullptr, dy_e5m2, workspace, s);
+    } else {
+        uint32_t *pdy = (uint32_t *)workspace;
+        int ndy = 0;
+        e = launch_amax_partials(dy_bf16, M * N, pdy, &ndy, s);
+        if (e == hipSuccess)
+            e = launch_quantize_f8_from_partials(dy_bf16, M, N, pdy, ndy, dy_e5m2, sc + 6, dyq, dyqT, sc + 7, sc + 8, s);
+    }
     if (e != hipSuccess)
         return TWEO_ERR_HIP;
     return fp8_linear_bwd_impl(dyq, dyqT, sc + 8, saved->wqT, sc + 5, saved->xqT, sc + 2, M, N, K,

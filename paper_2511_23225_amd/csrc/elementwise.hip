@@ -2,6 +2,8 @@
 // quantize-cast (with a transposed copy), static INT8 quantize, and the small
 // fill / finish kernels around them.  gfx950 only.
 #include <hip/hip_ext.h>
+#include <atomic>
+#include <chrono>
 #include "kernels.h"
 #include "device_utils.h"
 
@@ -965,6 +967,341 @@ hipError_t launch_amax_quantize_inject(const void *dy_bf16, const void *a_bf16, 
         else
             launch(quantize_inject_16x16_kernel<false, 1>);
     }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// amax and cast in ONE launch (current scaling, Sec. 4.3), the tensor held on chip in between.
+// Two passes over a tensor move 6 bytes per element (2 read for the amax, 2 read again and 2
+// written by the cast), and the second read costs nearly what the first did even when the
+// memory-side cache serves it.  Here one workgroup per CU (8 waves, up to 256 registers a lane)
+// reads its share of the tensor(s) once, keeps the last 16x16 block of every lane in registers
+// (one block per lane = 256 KB per CU: a 16384x2048 activation fits the chip whole), publishes its
+// maxima, waits until every workgroup has, and casts: what it kept straight from registers, the
+// rest after reading it again, newest first.  Reads and writes also fall into separate phases.
+//
+// The wait is a barrier over the grid, so every workgroup must be resident: the grid is at most one
+// workgroup per CU and the kernel needs a CU's registers whole.  Two such launches running at the
+// same time on one device (two streams) could each hold a part of the CUs and wait for the rest:
+// callers that overlap bf16 entry points on one device switch this path off
+// (set_fused_cast(false)).  The wait is bounded: a workgroup that gives up counts itself in
+// g_fused_cast_timeouts, publishes a NaN amax (the scalars the caller reads are then NaN, not
+// plausibly wrong) and finishes.
+//
+// Barrier without read-modify-write atomics, fences or cleared memory: workgroup b writes slot b of
+// `slots` (16 bytes each, in the caller's workspace) as two 64-bit words, each one of its maxima
+// under one half of the call's 64-bit token; lane i of every workgroup polls slot i until both
+// words carry this call's token.  A word is stored and loaded whole, at device scope, past the
+// XCD-private L2, and carries its own validity, so no release or acquire is needed - either would
+// write back or invalidate a whole L2 (measured: 15 us per barrier).  Tokens come from a
+// process-wide counter, so whatever an earlier call (or nobody) left in the slots is never
+// mistaken for this call's.
+__device__ uint32_t g_fused_cast_timeouts;
+
+struct FusedTensor {
+    const uint16_t *x;
+    int64_t rows, cols, tiles_x;  // tiles_x: 256-column tiles per row of tiles
+    uint8_t *q, *qT;
+    float *amax_store, *scale_out, *scale_inv_out;
+};
+
+constexpr int kFusedThreads = 512, kFusedWaves = kFusedThreads / kWave;
+constexpr int kFusedSpinLimit = 1 << 18;  // polls of ~0.25 us each
+
+struct FusedSlot {
+    uint64_t w0, w1;  // token half << 32 | magnitude pattern << 16 (as the amax partials elsewhere)
+};
+
+// lane's 16x16 block of wave tile `wt` (a 128x128 quadrant of a 256x256 tile): false if outside
+__device__ __forceinline__ bool fused_locate(const FusedTensor &t, int64_t wt, int lane, int64_t &r0, int64_t &c0)
+{
+    const int64_t big = wt >> 2, by = big / t.tiles_x, bx = big - by * t.tiles_x;
+    const int quad = (int)(wt & 3);
+    r0 = by * kQuantBigTile + (quad >> 1) * 128 + (lane >> 3) * 16;
+    c0 = bx * kQuantBigTile + (quad & 1) * 128 + (lane & 7) * 16;
+    return r0 < t.rows && c0 < t.cols;
+}
+
+// rows 8*half .. +7 of a lane's block: codes into qd and out to q (16 bytes a row)
+template <bool E5M2>
+__device__ __forceinline__ void cast_rows8(const uint4 (&in)[8][2], int half, float scale, uint32_t (&qd)[16][4],
+                                           uint8_t *__restrict__ q, int64_t r0, int64_t c0, int64_t cols)
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = half * 8 + i;
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            const uint4 v = in[i][w];
+            qd[r][2 * w] = cvt4_f8<E5M2>(bf16lo_to_f32(v.x) * scale, bf16hi_to_f32(v.x) * scale,
+                                     bf16lo_to_f32(v.y) * scale, bf16hi_to_f32(v.y) * scale);
+            qd[r][2 * w + 1] = cvt4_f8<E5M2>(bf16lo_to_f32(v.z) * scale, bf16hi_to_f32(v.z) * scale,
+                                         bf16lo_to_f32(v.w) * scale, bf16hi_to_f32(v.w) * scale);
+        }
+        *(uint4 *)(q + (r0 + r) * cols + c0) = make_uint4(qd[r][0], qd[r][1], qd[r][2], qd[r][3]);
+    }
+}
+
+// the block's codes transposed: column c0 + j of the block is 16 bytes of row c0 + j of qT
+__device__ __forceinline__ void store_block_transposed(const uint32_t (&qd)[16][4], uint8_t *__restrict__ qT,
+                                                       int64_t rows, int64_t r0, int64_t c0)
+{
+#pragma unroll
+    for (int C = 0; C < 4; ++C) {
+        uint32_t t[4][4];  // t[R][k]: column 4C+k, rows 4R..4R+3
+#pragma unroll
+        for (int R = 0; R < 4; ++R)
+            transpose4x4_bytes(qd[4 * R][C], qd[4 * R + 1][C], qd[4 * R + 2][C], qd[4 * R + 3][C], t[R][0], t[R][1],
+                               t[R][2], t[R][3]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            *(uint4 *)(qT + (c0 + 4 * C + k) * rows + r0) = make_uint4(t[0][k], t[1][k], t[2][k], t[3][k]);
+    }
+}
+
+template <bool E5M2>
+__global__ __launch_bounds__(kFusedThreads, 1) void amax_cast_fused_kernel(FusedTensor t0, FusedTensor t1, int64_t wt0,
+                                                                           int64_t wt_total, int rounds,
+                                                                           FusedSlot *slots, uint64_t token)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int G = gridDim.x;
+    auto tile_of = [&](int k) { return ((int64_t)k * G + blockIdx.x) * kFusedWaves + wave; };
+
+    // this wave's tiles are k = 0 .. mine-1 (the last round of the grid may not reach it)
+    const int mine = tile_of(rounds - 1) < wt_total ? rounds : rounds - 1;
+
+    // ---- phase 1: maxima; the block of the wave's last tile stays in `keep` ---------------------
+    uint32_t mx0 = 0, mx1 = 0;
+    for (int k = 0; k < mine - 1; ++k) {
+        const int64_t wt = tile_of(k);
+        const bool first = wt < wt0;
+        const FusedTensor &t = first ? t0 : t1;
+        int64_t r0, c0;
+        if (!fused_locate(t, first ? wt : wt - wt0, lane, r0, c0))
+            continue;
+        uint32_t m = 0;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            uint4 in[8][2];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint4 *src = (const uint4 *)(t.x + (r0 + half * 8 + i) * t.cols + c0);
+                in[i][0] = src[0];
+                in[i][1] = src[1];
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                m = pk_absmax4(pk_absmax4(m, in[i][0]), in[i][1]);
+        }
+        if (first)
+            mx0 = pk_absmax4(mx0, make_uint4(m, 0u, 0u, 0u));
+        else
+            mx1 = pk_absmax4(mx1, make_uint4(m, 0u, 0u, 0u));
+    }
+    uint4 keep[16][2];
+    bool kept = false, kept_first = false;
+    int64_t kr0 = 0, kc0 = 0;
+    {
+        if (mine > 0) {
+            const int64_t wt = tile_of(mine - 1);
+            kept_first = wt < wt0;
+            const FusedTensor &t = kept_first ? t0 : t1;
+            kept = fused_locate(t, kept_first ? wt : wt - wt0, lane, kr0, kc0);
+            if (kept) {
+                uint32_t m = 0;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const uint4 *src = (const uint4 *)(t.x + (kr0 + i) * t.cols + kc0);
+                    keep[i][0] = src[0];
+                    keep[i][1] = src[1];
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    m = pk_absmax4(pk_absmax4(m, keep[i][0]), keep[i][1]);
+                if (kept_first)
+                    mx0 = pk_absmax4(mx0, make_uint4(m, 0u, 0u, 0u));
+                else
+                    mx1 = pk_absmax4(mx1, make_uint4(m, 0u, 0u, 0u));
+            }
+        }
+    }
+
+    // ---- the workgroup's maxima, published; everybody's, collected ---------------------------
+    __shared__ uint32_t red[2][kFusedWaves];
+    __shared__ uint32_t all[2];
+    auto fold = [](uint32_t m) { return (m & 0xFFFFu) > (m >> 16) ? (m & 0xFFFFu) : (m >> 16); };
+    {
+        const uint32_t a = wave_reduce_max_u32(fold(mx0)), b = wave_reduce_max_u32(fold(mx1));
+        if (lane == 0) {
+            red[0][wave] = a;
+            red[1][wave] = b;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t a = red[0][0], b = red[1][0];
+#pragma unroll
+        for (int w = 1; w < kFusedWaves; ++w) {
+            a = red[0][w] > a ? red[0][w] : a;
+            b = red[1][w] > b ? red[1][w] : b;
+        }
+        FusedSlot *mine = slots + blockIdx.x;
+        __hip_atomic_store(&mine->w0, (token << 32) | (uint64_t)(a << 16), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&mine->w1, (token & 0xFFFFFFFF00000000ull) | (uint64_t)(b << 16), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+    uint32_t a = 0, b = 0;
+    if ((int)threadIdx.x < G) {
+        const FusedSlot *theirs = slots + threadIdx.x;
+        int spins = 0;
+        uint64_t w0, w1;
+        for (;;) {
+            w0 = __hip_atomic_load(&theirs->w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            w1 = __hip_atomic_load(&theirs->w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (((w0 >> 32) == (token & 0xFFFFFFFFull) && (w1 >> 32) == (token >> 32)) || ++spins > kFusedSpinLimit)
+                break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        if (spins > kFusedSpinLimit) {
+            atomicAdd(&g_fused_cast_timeouts, 1u);
+            a = b = 0x7FC00000u;  // NaN: above every magnitude pattern
+        } else {
+            a = (uint32_t)w0;
+            b = (uint32_t)w1;
+        }
+    }
+    a = wave_reduce_max_u32(a);
+    b = wave_reduce_max_u32(b);
+    __syncthreads();  // red[] has been read by thread 0
+    if (lane == 0) {
+        red[0][wave] = a;
+        red[1][wave] = b;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kFusedWaves; ++w) {
+            a = red[0][w] > a ? red[0][w] : a;
+            b = red[1][w] > b ? red[1][w] : b;
+        }
+        all[0] = a;
+        all[1] = b;
+    }
+    __syncthreads();
+    const float amax0 = __uint_as_float(all[0]), amax1 = __uint_as_float(all[1]);
+    const float scale0 = scale_f8<E5M2>(amax0), scale1 = scale_f8<E5M2>(amax1);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *t0.amax_store = amax0;
+        *t0.scale_out = scale0;
+        *t0.scale_inv_out = 1.0f / scale0;
+        if (wt_total > wt0) {
+            *t1.amax_store = amax1;
+            *t1.scale_out = scale1;
+            *t1.scale_inv_out = 1.0f / scale1;
+        }
+    }
+
+    // ---- phase 2: the cast, newest data first --------------------------------------------------
+    uint32_t qd[16][4];
+    if (kept) {
+        const FusedTensor &t = kept_first ? t0 : t1;
+        const float scale = kept_first ? scale0 : scale1;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            uint4 in[8][2];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                in[i][0] = keep[half * 8 + i][0];
+                in[i][1] = keep[half * 8 + i][1];
+            }
+            cast_rows8<E5M2>(in, half, scale, qd, t.q, kr0, kc0, t.cols);
+        }
+        store_block_transposed(qd, t.qT, t.rows, kr0, kc0);
+    }
+    for (int k = mine - 2; k >= 0; --k) {
+        const int64_t wt = tile_of(k);
+        const bool first = wt < wt0;
+        const FusedTensor &t = first ? t0 : t1;
+        const float scale = first ? scale0 : scale1;
+        int64_t r0, c0;
+        if (!fused_locate(t, first ? wt : wt - wt0, lane, r0, c0))
+            continue;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            uint4 in[8][2];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint4 *src = (const uint4 *)(t.x + (r0 + half * 8 + i) * t.cols + c0);
+                in[i][0] = src[0];
+                in[i][1] = src[1];
+            }
+            cast_rows8<E5M2>(in, half, scale, qd, t.q, r0, c0, t.cols);
+        }
+        store_block_transposed(qd, t.qT, t.rows, r0, c0);
+    }
+}
+
+static bool g_fused_cast_on = true;
+void set_fused_cast(bool on) { g_fused_cast_on = on; }
+bool fused_cast_enabled() { return g_fused_cast_on; }
+
+hipError_t fused_cast_timeouts(uint32_t *count)
+{
+    return hipMemcpyFromSymbol(count, HIP_SYMBOL(g_fused_cast_timeouts), sizeof(uint32_t));
+}
+
+// Tokens start from the clock so that two processes that share a workspace allocation one after
+// the other (the allocator hands memory round) do not start from the same number either.
+static uint64_t next_fused_token()
+{
+    static std::atomic<uint64_t> counter{(uint64_t)std::chrono::steady_clock::now().time_since_epoch().count() << 20 | 1u};
+    return counter.fetch_add(1, std::memory_order_relaxed);
+}
+
+// Whether the fused launch applies: whole 16x16 blocks, enough work to pay for the wait, not under
+// stream capture (a replayed graph would replay the token).
+bool fused_cast_applies(int64_t rows0, int64_t cols0, int64_t rows1, int64_t cols1, hipStream_t s)
+{
+    if (!g_fused_cast_on || rows0 % 16 != 0 || cols0 % 16 != 0 || rows1 % 16 != 0 || cols1 % 16 != 0)
+        return false;
+    // small tensors: two short launches are as fast (measured: no gain below ~16M elements)
+    if (rows0 * cols0 + rows1 * cols1 < ((int64_t)1 << 24))
+        return false;
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess || st != hipStreamCaptureStatusNone)
+        return false;
+    return true;
+}
+
+// x1 may be nullptr (one tensor).  slots: 16 bytes per workgroup, at most kFusedMaxWorkgroups of
+// them, no initial contents assumed.
+hipError_t launch_amax_cast_fused(const void *x0_bf16, int64_t rows0, int64_t cols0, float *amax0, uint8_t *q0,
+                                  uint8_t *q0T, float *scale0, float *scale0_inv, const void *x1_bf16,
+                                  int64_t rows1, int64_t cols1, float *amax1, uint8_t *q1, uint8_t *q1T,
+                                  float *scale1, float *scale1_inv, bool e5m2, void *slots, hipStream_t s)
+{
+    auto tiles = [](int64_t v) { return (v + kQuantBigTile - 1) / kQuantBigTile; };
+    const FusedTensor t0{(const uint16_t *)x0_bf16, rows0, cols0, tiles(cols0), q0, q0T, amax0, scale0, scale0_inv};
+    FusedTensor t1 = t0;
+    int64_t wt1 = 0;
+    if (x1_bf16 != nullptr) {
+        t1 = FusedTensor{(const uint16_t *)x1_bf16, rows1, cols1, tiles(cols1), q1, q1T, amax1, scale1, scale1_inv};
+        wt1 = 4 * tiles(rows1) * tiles(cols1);
+    }
+    const int64_t wt0 = 4 * tiles(rows0) * tiles(cols0), wt_total = wt0 + wt1;
+    int64_t grid = (wt_total + kFusedWaves - 1) / kFusedWaves;
+    const int64_t cap = amax_cus() < kFusedMaxWorkgroups ? amax_cus() : kFusedMaxWorkgroups;
+    if (grid > cap)
+        grid = cap;
+    const int rounds = (int)((wt_total + grid * kFusedWaves - 1) / (grid * kFusedWaves));
+    const uint64_t token = next_fused_token();
+    if (e5m2)
+        hipLaunchKernelGGL(amax_cast_fused_kernel<true>, dim3((unsigned)grid), dim3(kFusedThreads), 0, s, t0, t1, wt0,
+                           wt_total, rounds, (FusedSlot *)slots, token);
+    else
+        hipLaunchKernelGGL(amax_cast_fused_kernel<false>, dim3((unsigned)grid), dim3(kFusedThreads), 0, s, t0, t1, wt0,
+                           wt_total, rounds, (FusedSlot *)slots, token);
     return hipGetLastError();
 }
 
