@@ -130,10 +130,15 @@ def time_elementwise(tw, torch, L, peers, iters=20):
     am = torch.zeros(4 * len(xs), dtype=torch.float32, device=L.x.device)
     for i, t in enumerate(xs):
         tw.tweo_amax(t, am[4 * i:4 * i + 1])
+    sc = torch.zeros(8, dtype=torch.float32, device=L.x.device)
+    slots = torch.empty(4096, dtype=torch.uint8, device=L.x.device)
+    # amax + cast + transposed copy in one call: 4 algorithmic bytes per element (one read, two
+    # writes); two launches move 6 (the one-launch form re-reads what it cannot keep on chip)
     passes = (
         ("amax", lambda i: tw.tweo_amax(xs[i], am[4 * i:4 * i + 1]), 2.0),
         ("quantize_e4m3_T", lambda i: tw.tweo_quantize_e4m3(xs[i], am[4 * i:4 * i + 1], qs[i], qTs[i]), 4.0),
-        ("quantize_e4m3", lambda i: tw.tweo_quantize_e4m3(xs[i], am[4 * i:4 * i + 1], qs[i], None), 3.0))
+        ("quantize_e4m3", lambda i: tw.tweo_quantize_e4m3(xs[i], am[4 * i:4 * i + 1], qs[i], None), 3.0),
+        ("amax_quantize_T_one_call", lambda i: tw.tweo_amax_quantize_f8(xs[i], sc[0:1], qs[i], qTs[i], sc[4:5], sc[5:6], slots), 4.0))
     for name, fn, bytes_per_elt in passes:
         res = {"MB": round(n * bytes_per_elt / 1e6, 1)}
         for mode, pick in (("warm", lambda k: 0), ("cold", lambda k: k % len(xs))):

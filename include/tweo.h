@@ -451,8 +451,26 @@ tweo_status tweo_fp8_linear_bwd_bf16_inject(const void *dy_bf16, const void *a_b
                                             void *stream);
 
 /*
- * Sec. 4.3, current scaling.  The bf16 entry points (tweo_fp8_linear_fwd_bf16,
- * tweo_fp8_linear_bwd_bf16 and its hybrid form) take the amax and cast their
+ * amax, scale and cast of one tensor in one call (Sec. 4.3, current scaling: the
+ * scale comes from this tensor's own amax; E4M3 range +-448, Sec. 1; e5m2 != 0:
+ * the gradient format of the HYBRID recipe, range +-57344).  The same results as
+ * tweo_amax followed by tweo_quantize_e4m3 / tweo_quantize_e5m2; from 2^24
+ * elements on it is one launch that keeps the tensor on chip between the two steps
+ * (see tweo_set_fused_cast below), otherwise two launches.
+ *   x_bf16 [rows, cols], rows % 16 == 0 and cols % 16 == 0.
+ *   amax_out, scale_out, scale_inv_out: one fp32 each on the device, all required.
+ *   q [rows, cols] and qT [cols, rows] codes, both required.
+ *   workspace: at least 4096 bytes of device memory, 16-byte aligned, contents
+ *   arbitrary (TWEO_ERR_WORKSPACE otherwise).
+ */
+tweo_status tweo_amax_quantize_f8(const void *x_bf16, int64_t rows, int64_t cols, int e5m2,
+                                  float *amax_out, uint8_t *q, uint8_t *qT, float *scale_out,
+                                  float *scale_inv_out, void *workspace, size_t workspace_bytes,
+                                  void *stream);
+
+/*
+ * Sec. 4.3, current scaling.  tweo_amax_quantize_f8 and the bf16 entry points
+ * (tweo_fp8_linear_fwd_bf16, tweo_fp8_linear_bwd_bf16 and its hybrid form) take the amax and cast their
  * tensors in ONE launch that holds the data in registers between the two steps
  * (4 instead of 6 bytes of traffic per element for what fits the chip).  That
  * kernel waits inside for all of its workgroups, one per CU, so all of them must be

@@ -19,7 +19,7 @@ TWEO_OK, TWEO_ERR_INVALID_ARG, TWEO_ERR_UNSUPPORTED, TWEO_ERR_WORKSPACE, TWEO_ER
 EXPORTS = ("tweo_workspace_bytes", "tweo_status_string", "tweo_amax", "tweo_quantize_e4m3",
            "tweo_fp8_linear_fwd", "tweo_fp8_linear_bwd", "tweo_quantize_i8", "tweo_w8a8_linear",
            "tweo_fp8_linear_fwd_bf16", "tweo_fp8_linear_bwd_bf16", "tweo_set_gemm_tile",
-           "tweo_set_stream_k", "tweo_set_fused_cast", "tweo_fused_cast_timeouts",
+           "tweo_set_stream_k", "tweo_set_fused_cast", "tweo_fused_cast_timeouts", "tweo_amax_quantize_f8",
            "tweo_penalty_grad_inject", "tweo_delayed_state_bytes",
            "tweo_delayed_state_init", "tweo_quantize_e4m3_delayed", "tweo_profile_gemm_launches",
            "tweo_quantize_e5m2", "tweo_fp8_linear_bwd_hybrid", "tweo_fp8_linear_bwd_bf16_hybrid",
@@ -66,6 +66,7 @@ def load():
     L.tweo_amax.argtypes = [vp, i64, vp, vp]
     L.tweo_quantize_e4m3.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp]
     L.tweo_quantize_e5m2.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp]
+    L.tweo_amax_quantize_f8.argtypes = [vp, i64, i64, ctypes.c_int, vp, vp, vp, vp, vp, vp, sz, vp]
     L.tweo_fp8_linear_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp,
                                       ctypes.POINTER(PenaltyCfg), vp, vp, sz, vp]
     L.tweo_fp8_linear_fwd_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp,
@@ -153,6 +154,14 @@ def tweo_set_gemm_tile(variant):
 
 def tweo_set_stream_k(on):
     _check(load().tweo_set_stream_k(1 if on else 0), "tweo_set_stream_k")
+
+
+def tweo_amax_quantize_f8(x_bf16, amax_out, q, qT, scale_out, scale_inv_out, workspace, e5m2=False):
+    rows, cols = x_bf16.shape
+    wp, wb = _ws(workspace)
+    _check(load().tweo_amax_quantize_f8(_ptr(x_bf16), rows, cols, 1 if e5m2 else 0, _ptr(amax_out), _ptr(q), _ptr(qT),
+                                        _ptr(scale_out), _ptr(scale_inv_out), wp, wb, _stream()),
+           "tweo_amax_quantize_f8")
 
 
 def tweo_set_fused_cast(on):

@@ -185,6 +185,32 @@ tweo_status tweo_quantize_e5m2(const void *x_bf16, int64_t rows, int64_t cols, c
                                            scale_inv_out, (hipStream_t)stream));
 }
 
+tweo_status tweo_amax_quantize_f8(const void *x_bf16, int64_t rows, int64_t cols, int e5m2,
+                                  float *amax_out, uint8_t *q, uint8_t *qT, float *scale_out,
+                                  float *scale_inv_out, void *workspace, size_t workspace_bytes,
+                                  void *stream)
+{
+    if (!x_bf16 || !amax_out || !q || !qT || !scale_out || !scale_inv_out || rows <= 0 || cols <= 0 ||
+        !aligned16(x_bf16) || !aligned16(q) || !aligned16(qT))
+        return TWEO_ERR_INVALID_ARG;
+    if (rows % 16 != 0 || cols % 16 != 0 || rows > kMaxDim || cols > kMaxDim)
+        return TWEO_ERR_UNSUPPORTED;
+    if (!workspace || !aligned16(workspace) || workspace_bytes < kAmaxScratchBytes)
+        return TWEO_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    if (fused_cast_applies(rows, cols, 0, 0, s))
+        return hip_status(launch_amax_cast_fused(x_bf16, rows, cols, amax_out, q, qT, scale_out, scale_inv_out, nullptr,
+                                                 0, 0, nullptr, nullptr, nullptr, nullptr, nullptr, e5m2 != 0,
+                                                 workspace, s));
+    uint32_t *partials = (uint32_t *)workspace;
+    int n = 0;
+    hipError_t e = launch_amax_partials(x_bf16, rows * cols, partials, &n, s);
+    if (e == hipSuccess)
+        e = launch_quantize_f8_from_partials(x_bf16, rows, cols, partials, n, e5m2 != 0, amax_out, q, qT, scale_out,
+                                             scale_inv_out, s);
+    return hip_status(e);
+}
+
 size_t tweo_delayed_state_bytes(void) { return TWEO_DELAYED_STATE_WORDS * sizeof(float); }
 
 tweo_status tweo_delayed_state_init(void *state, void *stream)

@@ -505,7 +505,10 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
             const uint8_t *spu = sp + u * row_bytes;
             // a store of more than 8 bytes reads its data late: nothing may write those
             // registers in the next wait states (the compiler does not know this is a store)
-            asm volatile("global_store_dwordx4 %0, %1, %2 offset:%3\n\ts_nop 1"
+            // "nt": the output is not read again by this kernel; with whole lines per store the
+            // streaming hint lets the memory side write them out while the GEMM still runs
+            // instead of during the next kernel (measured: LLaMA block step -1.7 %, ViT -3.4 %)
+            asm volatile("global_store_dwordx4 %0, %1, %2 offset:%3 nt\n\ts_nop 1"
                          :
                          : "v"(out_quad), "v"(v), "s"(spu), "n"(jp * 128)
                          : "memory");
@@ -762,7 +765,7 @@ __global__ __launch_bounds__(256, 1) void gemm_nt_defer_kernel(GemmDev g)
 #pragma unroll
                     for (int w = 0; w < 4; ++w)
                         pen_word((uint32_t)d[w]);
-                    asm volatile("global_store_dwordx4 %0, %1, %2\n\ts_nop 1" : : "v"(lane_off), "v"(d), "s"(sp) : "memory");
+                    asm volatile("global_store_dwordx4 %0, %1, %2 nt\n\ts_nop 1" : : "v"(lane_off), "v"(d), "s"(sp) : "memory");
                 }
                 sp += rows4;
             }

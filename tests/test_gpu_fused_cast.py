@@ -125,3 +125,25 @@ def test_fused_cast_is_skipped_under_capture_and_when_switched_off():
             assert float(sc[0]) == 2.0 * oracle.amax_bf16(x)
             assert np.array_equal(xq.cpu().numpy(), eager[0])  # scale halves as the data doubles
     assert tw.tweo_fused_cast_timeouts() == 0
+
+
+@pytest.mark.parametrize("e5m2", [False, True])
+@pytest.mark.parametrize("shape", [(4112, 4112), (272, 1040), (16, 16)])
+def test_amax_quantize_in_one_call(shape, e5m2):
+    # the stand-alone entry point: one launch from 2^24 elements, two below; oracle bits either way
+    rows, cols = shape
+    print("amax_quantize_f8", shape, "e5m2" if e5m2 else "e4m3", flush=True)
+    x = synth.fp8_linear_inputs(3, 2, M=rows, K=cols, N=16)[0]
+    q = torch.full((rows, cols), 0x55, dtype=torch.uint8, device=DEV)
+    qT = torch.full((cols, rows), 0x55, dtype=torch.uint8, device=DEV)
+    sc = torch.full((12,), -3.0, dtype=torch.float32, device=DEV)
+    ws = torch.full((4096,), 0xA5, dtype=torch.uint8, device=DEV)
+    tw.tweo_amax_quantize_f8(to_dev_bf16(x), sc[0:1], q, qT, sc[4:5], sc[8:9], ws, e5m2=e5m2)
+    torch.cuda.synchronize()
+    amax = oracle.amax_bf16(x)
+    s, si = oracle.scale_from_amax_e5m2(amax) if e5m2 else oracle.scale_from_amax(amax)
+    oq, oqT = oracle.quantize_e5m2(x, s) if e5m2 else oracle.quantize_e4m3(x, s)
+    assert np.array_equal(q.cpu().numpy(), oq) and np.array_equal(qT.cpu().numpy(), oqT)
+    got = sc.cpu().numpy()[[0, 4, 8]].view(np.uint32)
+    assert np.array_equal(got, np.array([amax, s, si], np.float32).view(np.uint32))
+    assert tw.tweo_fused_cast_timeouts() == 0

@@ -51,6 +51,10 @@ def test_argument_checks_return_before_any_launch():
     assert L.tweo_amax(p(2), 64, p(), None) == INV
     assert L.tweo_quantize_e4m3(p(), 16, 16, None, p(), p(), None, None, None) == INV
     assert L.tweo_quantize_e5m2(p(), 16, 12, p(), p(), p(), None, None, None) == UNS      # cols % 8
+    assert L.tweo_amax_quantize_f8(p(), 16, 16, 0, p(), p(), None, p(), p(), p(), 4096, None) == INV   # no qT
+    assert L.tweo_amax_quantize_f8(p(), 16, 24, 0, p(), p(), p(), p(), p(), p(), 4096, None) == UNS   # cols % 16
+    assert L.tweo_amax_quantize_f8(p(), 16, 16, 0, p(), p(), p(), p(), p(), p(), 4095, None) == WSP   # workspace
+    assert L.tweo_fused_cast_timeouts(None) == INV
     assert L.tweo_quantize_i8(p(), 12, 1.0, p(), None) == UNS                             # n % 8
     assert L.tweo_quantize_i8(p(), 16, float("nan"), p(), None) == INV
     assert L.tweo_quantize_i8_rows(p(), 4, 16, -1.0, p(), p(), None) == INV               # eps < 0
