@@ -201,7 +201,7 @@ tweo_status tweo_amax_quantize_f8(const void *x_bf16, int64_t rows, int64_t cols
     if (fused_cast_applies(rows, cols, 0, 0, s))
         return hip_status(launch_amax_cast_fused(x_bf16, rows, cols, amax_out, q, qT, scale_out, scale_inv_out, nullptr,
                                                  0, 0, nullptr, nullptr, nullptr, nullptr, nullptr, e5m2 != 0,
-                                                 workspace, s));
+                                                 false, workspace, s));
     uint32_t *partials = (uint32_t *)workspace;
     int n = 0;
     hipError_t e = launch_amax_partials(x_bf16, rows * cols, partials, &n, s);
@@ -602,7 +602,7 @@ tweo_status tweo_fp8_linear_fwd_bf16(const void *x_bf16, const void *w_bf16,
     hipError_t e;
     if (fused_cast_applies(M, K, N, K, s)) {
         e = launch_amax_cast_fused(x_bf16, M, K, sc + 0, saved->xq, saved->xqT, sc + 1, sc + 2, w_bf16, N, K, sc + 3,
-                                   saved->wq, saved->wqT, sc + 4, sc + 5, false, workspace, s);
+                                   saved->wq, saved->wqT, sc + 4, sc + 5, false, true, workspace, s);
     } else {
         uint32_t *px = (uint32_t *)workspace, *pw = px + kAmaxPartialsMax;
         int nx = 0, nw = 0;
@@ -635,7 +635,7 @@ static tweo_status fp8_linear_bwd_bf16_impl(const void *dy_bf16, const tweo_fp8_
     hipError_t e;
     if (fused_cast_applies(M, N, 0, 0, s)) {
         e = launch_amax_cast_fused(dy_bf16, M, N, sc + 6, dyq, dyqT, sc + 7, sc + 8, nullptr, 0, 0, nullptr, nullptr,
-                                   nullptr, nullptr, nullptr, dy_e5m2, workspace, s);
+                                   nullptr, nullptr, nullptr, dy_e5m2, false, workspace, s);
     } else {
         uint32_t *pdy = (uint32_t *)workspace;
         int ndy = 0;

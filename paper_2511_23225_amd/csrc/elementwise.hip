@@ -1043,6 +1043,10 @@ __device__ __forceinline__ void cast_rows8(const uint4 (&in)[8][2], int half, fl
 }
 
 // the block's codes transposed: column c0 + j of the block is 16 bytes of row c0 + j of qT
+// LATER: nobody reads this copy soon (the transposed codes of a forward cast wait for the backward
+// pass): the stores carry the streaming hint, the lines leave for memory without displacing what
+// the next GEMM reads
+template <bool LATER = false>
 __device__ __forceinline__ void store_block_transposed(const uint32_t (&qd)[16][4], uint8_t *__restrict__ qT,
                                                        int64_t rows, int64_t r0, int64_t c0)
 {
@@ -1054,12 +1058,19 @@ __device__ __forceinline__ void store_block_transposed(const uint32_t (&qd)[16][
             transpose4x4_bytes(qd[4 * R][C], qd[4 * R + 1][C], qd[4 * R + 2][C], qd[4 * R + 3][C], t[R][0], t[R][1],
                                t[R][2], t[R][3]);
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
-            *(uint4 *)(qT + (c0 + 4 * C + k) * rows + r0) = make_uint4(t[0][k], t[1][k], t[2][k], t[3][k]);
+        for (int k = 0; k < 4; ++k) {
+            typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+            v4u *dst = (v4u *)(qT + (c0 + 4 * C + k) * rows + r0);
+            const v4u v = {t[0][k], t[1][k], t[2][k], t[3][k]};
+            if constexpr (LATER)
+                __builtin_nontemporal_store(v, dst);
+            else
+                *dst = v;
+        }
     }
 }
 
-template <bool E5M2>
+template <bool E5M2, bool T_LATER>
 __global__ __launch_bounds__(kFusedThreads, 1) void amax_cast_fused_kernel(FusedTensor t0, FusedTensor t1, int64_t wt0,
                                                                            int64_t wt_total, int rounds,
                                                                            FusedSlot *slots, uint64_t token)
@@ -1217,7 +1228,7 @@ __global__ __launch_bounds__(kFusedThreads, 1) void amax_cast_fused_kernel(Fused
             }
             cast_rows8<E5M2>(in, half, scale, qd, t.q, kr0, kc0, t.cols);
         }
-        store_block_transposed(qd, t.qT, t.rows, kr0, kc0);
+        store_block_transposed<T_LATER>(qd, t.qT, t.rows, kr0, kc0);
     }
     for (int k = mine - 2; k >= 0; --k) {
         const int64_t wt = tile_of(k);
@@ -1238,7 +1249,7 @@ __global__ __launch_bounds__(kFusedThreads, 1) void amax_cast_fused_kernel(Fused
             }
             cast_rows8<E5M2>(in, half, scale, qd, t.q, r0, c0, t.cols);
         }
-        store_block_transposed(qd, t.qT, t.rows, r0, c0);
+        store_block_transposed<T_LATER>(qd, t.qT, t.rows, r0, c0);
     }
 }
 
@@ -1279,7 +1290,8 @@ bool fused_cast_applies(int64_t rows0, int64_t cols0, int64_t rows1, int64_t col
 hipError_t launch_amax_cast_fused(const void *x0_bf16, int64_t rows0, int64_t cols0, float *amax0, uint8_t *q0,
                                   uint8_t *q0T, float *scale0, float *scale0_inv, const void *x1_bf16,
                                   int64_t rows1, int64_t cols1, float *amax1, uint8_t *q1, uint8_t *q1T,
-                                  float *scale1, float *scale1_inv, bool e5m2, void *slots, hipStream_t s)
+                                  float *scale1, float *scale1_inv, bool e5m2, bool transposed_later, void *slots,
+                                  hipStream_t s)
 {
     auto tiles = [](int64_t v) { return (v + kQuantBigTile - 1) / kQuantBigTile; };
     const FusedTensor t0{(const uint16_t *)x0_bf16, rows0, cols0, tiles(cols0), q0, q0T, amax0, scale0, scale0_inv};
@@ -1296,12 +1308,16 @@ hipError_t launch_amax_cast_fused(const void *x0_bf16, int64_t rows0, int64_t co
         grid = cap;
     const int rounds = (int)((wt_total + grid * kFusedWaves - 1) / (grid * kFusedWaves));
     const uint64_t token = next_fused_token();
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kFusedThreads), 0, s, t0, t1, wt0, wt_total, rounds,
+                           (FusedSlot *)slots, token);
+    };
     if (e5m2)
-        hipLaunchKernelGGL(amax_cast_fused_kernel<true>, dim3((unsigned)grid), dim3(kFusedThreads), 0, s, t0, t1, wt0,
-                           wt_total, rounds, (FusedSlot *)slots, token);
+        launch(amax_cast_fused_kernel<true, false>);  // gradients: both copies are read at once
+    else if (transposed_later)
+        launch(amax_cast_fused_kernel<false, true>);
     else
-        hipLaunchKernelGGL(amax_cast_fused_kernel<false>, dim3((unsigned)grid), dim3(kFusedThreads), 0, s, t0, t1, wt0,
-                           wt_total, rounds, (FusedSlot *)slots, token);
+        launch(amax_cast_fused_kernel<false, false>);
     return hipGetLastError();
 }
 

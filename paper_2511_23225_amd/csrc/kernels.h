@@ -31,13 +31,14 @@ hipError_t launch_amax2_partials(const void *x0_bf16, int64_t n0, uint32_t *part
 // the cast that consumes them (rows, cols multiples of 16); stores the maximum to *amax_out
 // amax and cast of one or two tensors (x1 may be nullptr) in one launch that keeps the data on
 // chip between the two; fused_cast_applies says whether a call can take it (shapes, capture, the
-// switch); slots: kFusedMaxWorkgroups * 16 bytes of the caller's workspace, contents arbitrary.
+// switch); transposed_later: the transposed codes are not read before a later call (streaming stores); slots: kFusedMaxWorkgroups * 16 bytes of the caller's workspace, contents arbitrary.
 constexpr int kFusedMaxWorkgroups = 256;
 bool fused_cast_applies(int64_t rows0, int64_t cols0, int64_t rows1, int64_t cols1, hipStream_t s);
 hipError_t launch_amax_cast_fused(const void *x0_bf16, int64_t rows0, int64_t cols0, float *amax0, uint8_t *q0,
                                   uint8_t *q0T, float *scale0, float *scale0_inv, const void *x1_bf16,
                                   int64_t rows1, int64_t cols1, float *amax1, uint8_t *q1, uint8_t *q1T,
-                                  float *scale1, float *scale1_inv, bool e5m2, void *slots, hipStream_t s);
+                                  float *scale1, float *scale1_inv, bool e5m2, bool transposed_later, void *slots,
+                                  hipStream_t s);
 void set_fused_cast(bool on);
 bool fused_cast_enabled();
 hipError_t fused_cast_timeouts(uint32_t *count);
