@@ -639,7 +639,10 @@ constexpr int kQuantBigTile = 256;
 // LN: the tensor that is cast is the LayerNorm of x (statistics precomputed per row).  AMAX_ONLY
 // (with DELAYED's bounded grid and tile loop): nothing is stored, workgroup b leaves the maximum
 // magnitude pattern of what it would have cast in amax_acc[b].
-template <bool WITH_T, bool DELAYED, bool E5M2 = false, int INJECT = 0, bool LN = false, bool AMAX_ONLY = false>
+// T_LATER: the transposed codes are not read before a later call (a forward cast's, which wait for
+// the backward pass): streaming stores.
+template <bool WITH_T, bool DELAYED, bool E5M2 = false, int INJECT = 0, bool LN = false, bool AMAX_ONLY = false,
+          bool T_LATER = false>
 __device__ __forceinline__ void quantize_e4m3_16x16_body(
     const uint16_t *__restrict__ x, int64_t rows, int64_t cols, int64_t tiles_x,
     const float *__restrict__ amax, uint8_t *__restrict__ q, uint8_t *__restrict__ qT,
@@ -766,9 +769,15 @@ __device__ __forceinline__ void quantize_e4m3_16x16_body(
                 transpose4x4_bytes(qd[4 * R][C], qd[4 * R + 1][C], qd[4 * R + 2][C], qd[4 * R + 3][C],
                                    t[R][0], t[R][1], t[R][2], t[R][3]);
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                *(uint4 *)(qT + (c0 + 4 * C + k) * rows + r0) =
-                    make_uint4(t[0][k], t[1][k], t[2][k], t[3][k]);
+            for (int k = 0; k < 4; ++k) {
+                typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+                v4u *dst = (v4u *)(qT + (c0 + 4 * C + k) * rows + r0);
+                const v4u v = {t[0][k], t[1][k], t[2][k], t[3][k]};
+                if constexpr (T_LATER)
+                    __builtin_nontemporal_store(v, dst);
+                else
+                    *dst = v;
+            }
         }
     }
     }
@@ -836,7 +845,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize2_e4m3_16x16_kernel(Qua
 {
     const bool first = (int64_t)blockIdx.x < blocks0;
     const QuantTensor &t = first ? t0 : t1;
-    quantize_e4m3_16x16_body<true, false>(t.x, t.rows, t.cols, t.tiles_x, t.amax, t.q, t.qT, t.scale_out,
+    quantize_e4m3_16x16_body<true, false, false, 0, false, false, true>(t.x, t.rows, t.cols, t.tiles_x, t.amax, t.q, t.qT, t.scale_out,
                                           t.scale_inv_out, nullptr,
                                           first ? (int64_t)blockIdx.x : (int64_t)blockIdx.x - blocks0, 1,
                                           t.amax_partials, t.n_partials, t.amax_store);
@@ -1456,7 +1465,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize2_delayed_16x16_kernel(
 {
     const bool first = (int64_t)blockIdx.x < blocks0;
     const QuantTensorDelayed &t = first ? t0 : t1;
-    quantize_e4m3_16x16_body<true, true>(t.x, t.rows, t.cols, t.tiles_x, t.scale, t.q, t.qT, nullptr, nullptr, t.amax_acc,
+    quantize_e4m3_16x16_body<true, true, false, 0, false, false, true>(t.x, t.rows, t.cols, t.tiles_x, t.scale, t.q, t.qT, nullptr, nullptr, t.amax_acc,
                                          first ? (int64_t)blockIdx.x : (int64_t)blockIdx.x - blocks0,
                                          first ? blocks0 : blocks1);
 }
