@@ -984,10 +984,12 @@ hipError_t launch_amax_quantize_inject(const void *dy_bf16, const void *a_bf16, 
 // Two passes over a tensor move 6 bytes per element (2 read for the amax, 2 read again and 2
 // written by the cast), and the second read costs nearly what the first did even when the
 // memory-side cache serves it.  Here one workgroup per CU (8 waves, up to 256 registers a lane)
-// reads its share of the tensor(s) once, keeps the last 16x16 block of every lane in registers
-// (one block per lane = 256 KB per CU: a 16384x2048 activation fits the chip whole), publishes its
-// maxima, waits until every workgroup has, and casts: what it kept straight from registers, the
-// rest after reading it again, newest first.  Reads and writes also fall into separate phases.
+// reads its share of the tensor(s) once, keeps the last two 16x16 blocks of every lane on chip
+// (the last one and the lower half of the one before it in registers, the upper half of that one
+// in LDS: 512 KB per CU, 128 MB over the chip - a 16384x2048 activation with its weight fits whole,
+// a 16384x6144 gradient to two thirds), publishes its maxima, waits until every workgroup has, and
+// casts: what it kept straight from registers and LDS, the rest after reading it again, newest
+// first.  Reads and writes also fall into separate phases.
 //
 // The wait is a barrier over the grid, so every workgroup must be resident: the grid is at most one
 // workgroup per CU and the kernel needs a CU's registers whole.  Two such launches running at the
@@ -1016,6 +1018,7 @@ struct FusedTensor {
 
 constexpr int kFusedThreads = 512, kFusedWaves = kFusedThreads / kWave;
 constexpr int kFusedSpinLimit = 1 << 18;  // polls of ~0.25 us each
+constexpr int kFusedLdsBytes = 8 * 2 * kFusedThreads * 16;  // eight rows of 32 bytes per lane
 
 struct FusedSlot {
     uint64_t w0, w1;  // token half << 32 | magnitude pattern << 16 (as the amax partials elsewhere)
@@ -1091,7 +1094,14 @@ __global__ __launch_bounds__(kFusedThreads, 1) void amax_cast_fused_kernel(Fused
     // this wave's tiles are k = 0 .. mine-1 (the last round of the grid may not reach it)
     const int mine = tile_of(rounds - 1) < wt_total ? rounds : rounds - 1;
 
-    // ---- phase 1: maxima; the block of the wave's last tile stays in `keep` ---------------------
+    // ---- phase 1: maxima; the block of the wave's last tile stays in `keep`, the upper half (rows
+    // 0..7 of every lane's block) of the tile before it in LDS (lane-private slots, 16-byte pieces of
+    // neighbouring lanes side by side: 128 KB per CU) ------------------------------------------------
+    extern __shared__ __attribute__((aligned(16))) uint4 lds_keep[];  // [8 rows][2 pieces][kFusedThreads]
+    uint4 keep2[8][2];  // the lower half of that tile: the registers that are left
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        keep2[i][0] = keep2[i][1] = make_uint4(0u, 0u, 0u, 0u);
     uint32_t mx0 = 0, mx1 = 0;
     for (int k = 0; k < mine - 1; ++k) {
         const int64_t wt = tile_of(k);
@@ -1113,6 +1123,21 @@ __global__ __launch_bounds__(kFusedThreads, 1) void amax_cast_fused_kernel(Fused
 #pragma unroll
             for (int i = 0; i < 8; ++i)
                 m = pk_absmax4(pk_absmax4(m, in[i][0]), in[i][1]);
+            if (k == mine - 2) {
+                if (half == 0) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        lds_keep[(i * 2 + 0) * kFusedThreads + threadIdx.x] = in[i][0];
+                        lds_keep[(i * 2 + 1) * kFusedThreads + threadIdx.x] = in[i][1];
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        keep2[i][0] = in[i][0];
+                        keep2[i][1] = in[i][1];
+                    }
+                }
+            }
         }
         if (first)
             mx0 = pk_absmax4(mx0, make_uint4(m, 0u, 0u, 0u));
@@ -1250,11 +1275,25 @@ __global__ __launch_bounds__(kFusedThreads, 1) void amax_cast_fused_kernel(Fused
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             uint4 in[8][2];
+            if (half == 0 && k == mine - 2) {  // what this lane left in LDS in phase 1
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint4 *src = (const uint4 *)(t.x + (r0 + half * 8 + i) * t.cols + c0);
-                in[i][0] = src[0];
-                in[i][1] = src[1];
+                for (int i = 0; i < 8; ++i) {
+                    in[i][0] = lds_keep[(i * 2 + 0) * kFusedThreads + threadIdx.x];
+                    in[i][1] = lds_keep[(i * 2 + 1) * kFusedThreads + threadIdx.x];
+                }
+            } else if (k == mine - 2) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    in[i][0] = keep2[i][0];
+                    in[i][1] = keep2[i][1];
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint4 *src = (const uint4 *)(t.x + (r0 + half * 8 + i) * t.cols + c0);
+                    in[i][0] = src[0];
+                    in[i][1] = src[1];
+                }
             }
             cast_rows8<E5M2>(in, half, scale, qd, t.q, r0, c0, t.cols);
         }
@@ -1317,17 +1356,26 @@ hipError_t launch_amax_cast_fused(const void *x0_bf16, int64_t rows0, int64_t co
         grid = cap;
     const int rounds = (int)((wt_total + grid * kFusedWaves - 1) / (grid * kFusedWaves));
     const uint64_t token = next_fused_token();
-    auto launch = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kFusedThreads), 0, s, t0, t1, wt0, wt_total, rounds,
-                           (FusedSlot *)slots, token);
+    hipError_t err = hipSuccess;
+    auto launch = [&](auto kernel, bool &attr_done) {
+        if (!attr_done) {  // more dynamic LDS than a kernel gets without asking
+            err = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLdsBytes);
+            if (err != hipSuccess)
+                return;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kFusedThreads), kFusedLdsBytes, s, t0, t1, wt0, wt_total,
+                           rounds, (FusedSlot *)slots, token);
+        err = hipGetLastError();
     };
+    static bool done[3] = {false, false, false};
     if (e5m2)
-        launch(amax_cast_fused_kernel<true, false>);  // gradients: both copies are read at once
+        launch(amax_cast_fused_kernel<true, false>, done[0]);  // gradients: both copies are read at once
     else if (transposed_later)
-        launch(amax_cast_fused_kernel<false, true>);
+        launch(amax_cast_fused_kernel<false, true>, done[1]);
     else
-        launch(amax_cast_fused_kernel<false, false>);
-    return hipGetLastError();
+        launch(amax_cast_fused_kernel<false, false>, done[2]);
+    return err;
 }
 
 // ---------------------------------------------------------------------------
