@@ -1001,8 +1001,8 @@ hipError_t launch_amax_quantize_inject(const void *dy_bf16, const void *a_bf16, 
 //
 // Barrier without read-modify-write atomics, fences or cleared memory: workgroup b writes slot b of
 // `slots` (16 bytes each, in the caller's workspace) as two 64-bit words, each one of its maxima
-// under one half of the call's 64-bit token; lane i of every workgroup polls slot i until both
-// words carry this call's token.  A word is stored and loaded whole, at device scope, past the
+// under a 32-bit tag derived from the call's 64-bit token, both tags new in every call; lane i of
+// every workgroup polls slot i until both words carry this call's tags.  A word is stored and loaded whole, at device scope, past the
 // XCD-private L2, and carries its own validity, so no release or acquire is needed - either would
 // write back or invalidate a whole L2 (measured: 15 us per barrier).  Tokens come from a
 // process-wide counter, so whatever an earlier call (or nobody) left in the slots is never
@@ -1023,6 +1023,86 @@ constexpr int kFusedLdsBytes = 8 * 2 * kFusedThreads * 16;  // eight rows of 32 
 struct FusedSlot {
     uint64_t w0, w1;  // token half << 32 | magnitude pattern << 16 (as the amax partials elsewhere)
 };
+
+// The grid-wide exchange of the two maxima (packed pairs of bf16 magnitude patterns per lane in, the
+// tensors' fp32 amax patterns out): see the comment above for the scheme.  WAVES = waves per
+// workgroup; the grid has at most WAVES * 64 workgroups (lane i polls slot i).  Every lane of the
+// workgroup calls it.
+template <int WAVES>
+__device__ __forceinline__ void fused_grid_max(uint32_t mx0, uint32_t mx1, FusedSlot *slots, uint64_t token,
+                                               uint32_t &all0, uint32_t &all1)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int G = gridDim.x;
+    // BOTH words carry a tag that changes with every call (the token's low half, and the high half of
+    // its product with an odd constant): a reader that finds this call's first word next to the
+    // second word of the call before must not take that one for new.  (Tags that shared the token's
+    // high half - the same in every call of a process - let exactly that happen: rarely, a
+    // workgroup cast the second tensor with the maximum of an earlier call.)
+    const uint64_t tag0 = token & 0xFFFFFFFFull, tag1 = (token * 0x9E3779B97F4A7C15ull) >> 32;
+    __shared__ uint32_t red[2][WAVES];
+    __shared__ uint32_t all[2];
+    auto fold = [](uint32_t m) { return (m & 0xFFFFu) > (m >> 16) ? (m & 0xFFFFu) : (m >> 16); };
+    {
+        const uint32_t a = wave_reduce_max_u32(fold(mx0)), b = wave_reduce_max_u32(fold(mx1));
+        if (lane == 0) {
+            red[0][wave] = a;
+            red[1][wave] = b;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t a = red[0][0], b = red[1][0];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) {
+            a = red[0][w] > a ? red[0][w] : a;
+            b = red[1][w] > b ? red[1][w] : b;
+        }
+        FusedSlot *mine = slots + blockIdx.x;
+        __hip_atomic_store(&mine->w0, (tag0 << 32) | (uint64_t)(a << 16), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&mine->w1, (tag1 << 32) | (uint64_t)(b << 16), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    uint32_t a = 0, b = 0;
+    if ((int)threadIdx.x < G) {
+        const FusedSlot *theirs = slots + threadIdx.x;
+        int spins = 0;
+        uint64_t w0, w1;
+        for (;;) {
+            w0 = __hip_atomic_load(&theirs->w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            w1 = __hip_atomic_load(&theirs->w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (((w0 >> 32) == tag0 && (w1 >> 32) == tag1) || ++spins > kFusedSpinLimit)
+                break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        if (spins > kFusedSpinLimit) {
+            atomicAdd(&g_fused_cast_timeouts, 1u);
+            a = b = 0x7FC00000u;  // NaN: above every magnitude pattern
+        } else {
+            a = (uint32_t)w0;
+            b = (uint32_t)w1;
+        }
+    }
+    a = wave_reduce_max_u32(a);
+    b = wave_reduce_max_u32(b);
+    __syncthreads();  // red[] has been read by thread 0
+    if (lane == 0) {
+        red[0][wave] = a;
+        red[1][wave] = b;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) {
+            a = red[0][w] > a ? red[0][w] : a;
+            b = red[1][w] > b ? red[1][w] : b;
+        }
+        all[0] = a;
+        all[1] = b;
+    }
+    __syncthreads();
+    all0 = all[0];
+    all1 = all[1];
+}
 
 // lane's 16x16 block of wave tile `wt` (a 128x128 quadrant of a 256x256 tile): false if outside
 __device__ __forceinline__ bool fused_locate(const FusedTensor &t, int64_t wt, int lane, int64_t &r0, int64_t &c0)
@@ -1173,68 +1253,9 @@ __global__ __launch_bounds__(kFusedThreads, 1) void amax_cast_fused_kernel(Fused
     }
 
     // ---- the workgroup's maxima, published; everybody's, collected ---------------------------
-    __shared__ uint32_t red[2][kFusedWaves];
-    __shared__ uint32_t all[2];
-    auto fold = [](uint32_t m) { return (m & 0xFFFFu) > (m >> 16) ? (m & 0xFFFFu) : (m >> 16); };
-    {
-        const uint32_t a = wave_reduce_max_u32(fold(mx0)), b = wave_reduce_max_u32(fold(mx1));
-        if (lane == 0) {
-            red[0][wave] = a;
-            red[1][wave] = b;
-        }
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t a = red[0][0], b = red[1][0];
-#pragma unroll
-        for (int w = 1; w < kFusedWaves; ++w) {
-            a = red[0][w] > a ? red[0][w] : a;
-            b = red[1][w] > b ? red[1][w] : b;
-        }
-        FusedSlot *mine = slots + blockIdx.x;
-        __hip_atomic_store(&mine->w0, (token << 32) | (uint64_t)(a << 16), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&mine->w1, (token & 0xFFFFFFFF00000000ull) | (uint64_t)(b << 16), __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
-    }
-    uint32_t a = 0, b = 0;
-    if ((int)threadIdx.x < G) {
-        const FusedSlot *theirs = slots + threadIdx.x;
-        int spins = 0;
-        uint64_t w0, w1;
-        for (;;) {
-            w0 = __hip_atomic_load(&theirs->w0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            w1 = __hip_atomic_load(&theirs->w1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (((w0 >> 32) == (token & 0xFFFFFFFFull) && (w1 >> 32) == (token >> 32)) || ++spins > kFusedSpinLimit)
-                break;
-            __builtin_amdgcn_s_sleep(8);
-        }
-        if (spins > kFusedSpinLimit) {
-            atomicAdd(&g_fused_cast_timeouts, 1u);
-            a = b = 0x7FC00000u;  // NaN: above every magnitude pattern
-        } else {
-            a = (uint32_t)w0;
-            b = (uint32_t)w1;
-        }
-    }
-    a = wave_reduce_max_u32(a);
-    b = wave_reduce_max_u32(b);
-    __syncthreads();  // red[] has been read by thread 0
-    if (lane == 0) {
-        red[0][wave] = a;
-        red[1][wave] = b;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-#pragma unroll
-        for (int w = 1; w < kFusedWaves; ++w) {
-            a = red[0][w] > a ? red[0][w] : a;
-            b = red[1][w] > b ? red[1][w] : b;
-        }
-        all[0] = a;
-        all[1] = b;
-    }
-    __syncthreads();
-    const float amax0 = __uint_as_float(all[0]), amax1 = __uint_as_float(all[1]);
+    uint32_t all0, all1;
+    fused_grid_max<kFusedWaves>(mx0, mx1, slots, token, all0, all1);
+    const float amax0 = __uint_as_float(all0), amax1 = __uint_as_float(all1);
     const float scale0 = scale_f8<E5M2>(amax0), scale1 = scale_f8<E5M2>(amax1);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         *t0.amax_store = amax0;
@@ -1324,7 +1345,9 @@ bool fused_cast_applies(int64_t rows0, int64_t cols0, int64_t rows1, int64_t col
 {
     if (!g_fused_cast_on || rows0 % 16 != 0 || cols0 % 16 != 0 || rows1 % 16 != 0 || cols1 % 16 != 0)
         return false;
-    // small tensors: two short launches are as fast (measured: no gain below ~16M elements)
+    // small tensors: two short launches are as fast (measured: no gain below ~16M elements, also not
+    // with a form of this kernel in which every lane keeps one 8x8 block and nothing is read twice:
+    // GPT-2 block step 0.563 -> 0.561 ms)
     if (rows0 * cols0 + rows1 * cols1 < ((int64_t)1 << 24))
         return false;
     hipStreamCaptureStatus st = hipStreamCaptureStatusNone;

@@ -147,3 +147,51 @@ def test_amax_quantize_in_one_call(shape, e5m2):
     got = sc.cpu().numpy()[[0, 4, 8]].view(np.uint32)
     assert np.array_equal(got, np.array([amax, s, si], np.float32).view(np.uint32))
     assert tw.tweo_fused_cast_timeouts() == 0
+
+
+def test_every_call_takes_its_own_maxima():
+    # Calls in a row on one workspace whose second tensor's maximum changes from call to call
+    # (forwards with weights w and 4 w in turn; the gradient of this shape is small and takes the
+    # two-launch form, whose workgroup maxima land in the same words in between).  The workgroups exchange their maxima through words that earlier calls also wrote:
+    # a word of an earlier call taken for this call's would cast a part of the weight with another
+    # call's scale.  Codes and scalars of every call against the two-launch form (itself checked
+    # against the oracle).
+    M, K, N = 8192, 2048, 256   # 2^24 activation elements: the one-launch form; a small weight and gradient
+    x, w, dy = synth.fp8_linear_inputs(3, 0, M=M, K=K, N=N)
+    w4 = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(w) * np.float32(4.0))
+    xd, dyd = to_dev_bf16(x), to_dev_bf16(dy)
+    wds = [to_dev_bf16(w), to_dev_bf16(w4)]
+    u8 = lambda *s: torch.full(s, 0x55, dtype=torch.uint8, device=DEV)
+    xq, xqT, wq, wqT, dyq, dyqT = u8(M, K), u8(K, M), u8(N, K), u8(K, N), u8(M, N), u8(N, M)
+    sc = torch.zeros(16, dtype=torch.float32, device=DEV)
+    saved = tw.make_saved(xq, xqT, wq, wqT, sc)
+    y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    dx = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
+    dw = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+    ws = workspace(tw.TWEO_OP_FP8_LINEAR_FWD_BF16, M, N, K)
+    wsb = workspace(tw.TWEO_OP_FP8_LINEAR_BWD_BF16, M, N, K)
+    ws = ws if ws.numel() >= wsb.numel() else wsb   # one workspace for both calls
+
+    def step(wd):
+        tw.tweo_fp8_linear_fwd_bf16(xd, wd, y, saved, workspace=ws)
+        tw.tweo_fp8_linear_bwd_bf16(dyd, saved, K, dyq, dyqT, dx, dw, ws)
+
+    want = []
+    tw.tweo_set_fused_cast(False)
+    try:
+        for i, wd in enumerate(wds):
+            step(wd)
+            torch.cuda.synchronize()
+            want.append([t.clone() for t in (wq, wqT, xq, dyq, sc)])
+            amax = oracle.amax_bf16(w if i == 0 else w4)
+            s, _ = oracle.scale_from_amax(amax)
+            assert np.array_equal(wq.cpu().numpy(), oracle.quantize_e4m3(w if i == 0 else w4, s)[0])
+    finally:
+        tw.tweo_set_fused_cast(True)
+    bad = torch.zeros((), dtype=torch.int64, device=DEV)
+    for it in range(300):
+        step(wds[it & 1])
+        for got, ref in zip((wq, wqT, xq, dyq, sc), want[it & 1]):
+            bad += (got != ref).any()
+    assert int(bad) == 0, "%d tensors of 1500 differ from the two-launch form" % int(bad)
+    assert tw.tweo_fused_cast_timeouts() == 0

@@ -70,8 +70,9 @@ def test_fp8_linear_step_in_a_graph():
             torch.cuda.synchronize()
             graph.replay()
             got = outputs()
-            for a, b in zip(got, eager[i]):
-                assert torch.equal(a, b), "replay %d of dataset %d differs from the eager result" % (rep, i)
+            for name, a, b in zip(("y", "dx", "dw", "S", "scalars", "dyq"), got, eager[i]):
+                assert torch.equal(a, b), "replay %d of dataset %d: %s differs from the eager result in %d of %d" % (
+                    rep, i, name, int((a != b).sum()), a.numel())
 
 
 def test_w8a8_decode_step_in_a_graph():
