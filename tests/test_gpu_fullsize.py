@@ -209,3 +209,48 @@ def test_full_size_w8a8_finer_granularities(gi, M):
     assert np.array_equal(bf16_bits(y[sel]), want)
     assert np.array_equal(yq[sel].cpu().numpy(), want_q)
     assert 0 < np.mean(np.abs(want_q) == 127) < 0.5  # some saturate, most do not
+
+
+# qkv (one-launch casts, six rounds of 256x256 tiles, 192x256 weight-gradient tiles), the output
+# projection (K-split weight gradient), ViT fc2 at a token count that is no multiple of a tile
+# height (partial last round, ragged last band)
+@pytest.mark.parametrize("shape", [(16384, 2048, 6144), (16384, 2048, 2048), (18912, 3072, 768)])
+def test_full_size_step_is_deterministic_whatever_the_workspace_held(shape):
+    # "Same inputs, byte-identical outputs" at the sizes bench.py times: every kernel of the step
+    # that hands data from one workgroup to another (the casts' grid-wide exchange of maxima, the
+    # K-split runs and their reduction, the penalty partials) does so through the workspace.  The
+    # step repeated over workspaces filled with different bytes must leave the same bits in every
+    # output - a word of an earlier call taken for this call's would show here.
+    M, K, N = shape
+    say("determinism", shape)
+    x, w, dy = synth.fp8_linear_inputs(3, 0, M=M, K=K, N=N)
+    xd, wd, dyd = to_dev_bf16(x), to_dev_bf16(w), to_dev_bf16(dy)
+    u8 = lambda *s: torch.empty(s, dtype=torch.uint8, device=DEV)
+    bf = lambda *s: torch.empty(s, dtype=torch.bfloat16, device=DEV)
+    xq, xqT, wq, wqT, dyq, dyqT = u8(M, K), u8(K, M), u8(N, K), u8(K, N), u8(M, N), u8(N, M)
+    y, dx, dw = bf(M, N), bf(M, K), bf(N, K)
+    sc = torch.zeros(16, dtype=torch.float32, device=DEV)
+    S = torch.zeros(2, dtype=torch.float64, device=DEV)
+    saved = tw.make_saved(xq, xqT, wq, wqT, sc)
+    ws = torch.empty(max(tw.tweo_workspace_bytes(op, M, N, K) for op in
+                         (tw.TWEO_OP_FP8_LINEAR_FWD_BF16, tw.TWEO_OP_FP8_LINEAR_BWD_BF16)),
+                     dtype=torch.uint8, device=DEV)
+    outs = (xq, xqT, wq, wqT, dyq, dyqT, y.view(torch.int16), dx.view(torch.int16), dw.view(torch.int16), sc, S)
+    names = ("xq", "xqT", "wq", "wqT", "dyq", "dyqT", "y", "dx", "dw", "scalars", "penalty")
+    first = None
+    for rep, fill in enumerate((0x00, 0xFF, 0xA5, None, None, 0x7F, None, None)):
+        if fill is not None:
+            ws.fill_(fill)           # None: whatever the call before left
+        for t in (xq, xqT, wq, wqT, dyq, dyqT):
+            t.fill_(0x55)
+        for t in (y, dx, dw):
+            t.fill_(float("nan"))
+        tw.tweo_fp8_linear_fwd_bf16(xd, wd, y, saved, pen=PEN, penalty_sum=S, workspace=ws)
+        tw.tweo_fp8_linear_bwd_bf16(dyd, saved, K, dyq, dyqT, dx, dw, ws)
+        torch.cuda.synchronize()
+        if first is None:
+            first = [t.clone() for t in outs]
+            continue
+        for name, a, b in zip(names, outs, first):
+            assert torch.equal(a, b), "repetition %d: %s differs in %d elements" % (rep, name, int((a != b).sum()))
+    assert tw.tweo_fused_cast_timeouts() == 0
