@@ -138,7 +138,9 @@ def time_elementwise(tw, torch, L, peers, iters=20):
         ("amax", lambda i: tw.tweo_amax(xs[i], am[4 * i:4 * i + 1]), 2.0),
         ("quantize_e4m3_T", lambda i: tw.tweo_quantize_e4m3(xs[i], am[4 * i:4 * i + 1], qs[i], qTs[i]), 4.0),
         ("quantize_e4m3", lambda i: tw.tweo_quantize_e4m3(xs[i], am[4 * i:4 * i + 1], qs[i], None), 3.0),
-        ("amax_quantize_T_one_call", lambda i: tw.tweo_amax_quantize_f8(xs[i], sc[0:1], qs[i], qTs[i], sc[4:5], sc[5:6], slots), 4.0))
+        ("amax_quantize_T_one_call", lambda i: tw.tweo_amax_quantize_f8(xs[i], sc[0:1], qs[i], qTs[i], sc[4:5], sc[5:6], slots), 4.0),
+        # static INT8 quantisation (Eq. 4 with a precomputed step): 2 read + 1 written
+        ("quantize_i8_static", lambda i: tw.tweo_quantize_i8(xs[i], 127.0 / 20.0, qs[i].view(torch.int8)), 3.0))
     for name, fn, bytes_per_elt in passes:
         res = {"MB": round(n * bytes_per_elt / 1e6, 1)}
         for mode, pick in (("warm", lambda k: 0), ("cold", lambda k: k % len(xs))):

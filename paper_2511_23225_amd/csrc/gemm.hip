@@ -2027,7 +2027,8 @@ static hipError_t launch_skinny_ring(const GemmArgs &a, hipStream_t s)
 }
 
 // stage shapes: M <= 16: 512 bytes of K a stage (eight k steps, one per wave); above: 256 bytes (four
-// k steps x two parts of the M blocks); ring depth what 160 KB of LDS allow
+// k steps x two parts of the M blocks; 512 where a workgroup has one block of weight rows); ring depth
+// what 160 KB of LDS allow (the depth hardly matters: two stages measured like five)
 static hipError_t launch_skinny_ring_any(const GemmArgs &a, hipStream_t s)
 {
     const int64_t blocks = (a.N + 15) / 16, cus = num_cus();
@@ -2050,8 +2051,8 @@ static hipError_t launch_skinny_ring_any(const GemmArgs &a, hipStream_t s)
             return launch_skinny_ring<2, 3, 4, 6>(a, s);
         return launch_skinny_ring<2, 4, 4, 6>(a, s);
     }
-    if (per <= 1)
-        return launch_skinny_ring<4, 1, 4, 6>(a, s);
+    if (per <= 1)  // 512-byte stages: half as many barriers (11008 -> 4096 at M = 64: 18.0 -> 16.7 us)
+        return launch_skinny_ring<4, 1, 8, 3>(a, s);
     if (per == 2)
         return launch_skinny_ring<4, 2, 4, 6>(a, s);
     if (per == 3)
