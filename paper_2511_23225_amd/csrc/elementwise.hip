@@ -572,7 +572,7 @@ __device__ __forceinline__ double sumsq8_f64(uint4 v, double mean)
 // Row statistics: one wave per row, the first kLnCached 16-byte pieces of every lane stay in
 // registers between the mean and the variance, so rows of up to 4096 elements are read from memory
 // once (2 B/element).  RESIDUAL: the row is h = bf16(x + r), stored to h_out on the way.
-constexpr int kLnThreads = 1024;
+constexpr int kLnThreads = 256;
 constexpr int kLnCached = 8;
 
 template <bool RESIDUAL>
@@ -1587,8 +1587,12 @@ hipError_t launch_layernorm_quantize(const void *x_bf16, const void *res_bf16, c
     const int vec = (int)(cols / 8);
     constexpr int WAVES = kLnThreads / kWave;
     int64_t sgrid = (rows + WAVES - 1) / WAVES;
-    if (sgrid > 2 * amax_cus())
-        sgrid = 2 * amax_cus();
+    // small workgroups, as many as fit a CU at once (70 / 80 registers a lane: seven / six waves per
+    // SIMD): the pass is a chain of latencies per row (loads, two wave-wide fp64 reductions), so what
+    // counts is how many rows are in flight
+    const int64_t resident = (res_bf16 != nullptr ? 6 : 7) * (int64_t)amax_cus();
+    if (sgrid > resident)
+        sgrid = resident;
     if (res_bf16 != nullptr)
         hipLaunchKernelGGL(ln_stats_kernel<true>, dim3((unsigned)sgrid), dim3(kLnThreads), 0, s, (const uint4 *)x_bf16,
                            (const uint4 *)res_bf16, (uint4 *)h_out, rows, vec, eps, stats);
