@@ -218,6 +218,49 @@ def time_layernorm(tw, torch, dev, rows=16384, cols=2048, copies=6, iters=24):
     return out
 
 
+def vendor_library_context(torch, layers, reps=6):
+    """Context, not a product path: the FP8 GEMM of the vendor's library (hipBLASLt behind
+    torch._scaled_mm) on the same 15 GEMMs, fed with the codes the step above left in the layers'
+    buffers, each launch timed by its own pair of events.  Shows what fraction of the datasheet
+    peak a tuned library kernel reaches on this machine under the same operand statistics."""
+    try:
+        f8 = torch.float8_e4m3fn
+        one = torch.ones((), dtype=torch.float32, device=layers[0].xq.device)
+        calls = []
+        for L in layers:
+            fl = 2.0 * L.M * L.N * L.K
+            calls += [("%s fwd" % L.name, L.xq, L.wq, fl), ("%s dgrad" % L.name, L.dyq, L.wqT, fl),
+                      ("%s wgrad" % L.name, L.dyqT, L.xqT, fl)]
+        mm = lambda a, b: torch._scaled_mm(a.view(f8), b.view(f8).t(), scale_a=one, scale_b=one,
+                                           out_dtype=torch.bfloat16)
+        for _ in range(2):
+            for _, a, b, _ in calls:
+                mm(a, b)
+        torch.cuda.synchronize()
+        evs = []
+        for _ in range(reps):
+            for _, a, b, _ in calls:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                mm(a, b)
+                e1.record()
+                evs.append((e0, e1))
+        torch.cuda.synchronize()
+        us = [1e3 * e0.elapsed_time(e1) for e0, e1 in evs]
+        per = {}
+        for i, (name, _, _, fl) in enumerate(calls):
+            d = sorted(us[i::len(calls)])[reps // 2]
+            per[name] = {"us": round(d, 1), "TFLOP/s": round(fl / d / 1e6, 1)}
+        tot_us = sum(v["us"] for v in per.values())
+        tot_fl = sum(c[3] for c in calls)
+        return {"what": "torch._scaled_mm (vendor FP8 GEMM library) on the same 15 GEMMs and operand codes; "
+                        "medians of %d event-timed calls each, events around the call" % reps,
+                "TFLOP/s": round(tot_fl / tot_us / 1e6, 1),
+                "frac_of_fp8_peak": round(tot_fl / tot_us / 1e6 / FP8_PEAK_TFLOPS, 4), "per_gemm": per}
+    except Exception as e:  # a context figure: its absence must not fail the bench
+        return {"error": "%s: %s" % (type(e).__name__, str(e)[:200])}
+
+
 def time_penalty_cost(tw, torch, L, reps=24):
     """What the fused penalty (Sec. 3.3) costs on one layer's forward GEMM, operands already
     quantised, with and without, alternating, medians.  Two clocks: the GEMM kernel's own
@@ -615,6 +658,8 @@ def main():
         ms_h = (time.perf_counter() - t0) * 1e3 / a.steps
         out["delayed_scaling_hybrid_e5m2_gradients"] = {"ms_per_step": round(ms_h, 4),
                                                         "TFLOP/s": round(step_flops / (ms_h * 1e-3) / 1e12, 2)}
+        if a.workload == "llama":
+            out["vendor_library_context"] = vendor_library_context(torch, layers)
         big = max(layers, key=lambda L: L.M * L.K)
         peers = [L.y for L in layers if L is not big and L.y.numel() == big.x.numel()]
         while len(peers) < 3:
