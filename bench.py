@@ -379,6 +379,14 @@ def time_w8a8(tw, torch, synth, dev, iters=20, copies=8):
                 r["us"] = round(us, 2)
                 r["TOP/s"] = round(2.0 * M * N * K / us / 1e6, 2)
                 r["frac_of_int8_peak"] = round(2.0 * M * N * K / us / 1e6 / INT8_PEAK_TOPS, 3)
+                try:
+                    # context, not a path of this library: the vendor library's INT8 GEMM on the same
+                    # codes (int32 output, no dequantisation), timed the same way
+                    wt = wqs[0].t()
+                    us_v = stream_us([lambda: torch._int_mm(xq, wt)], 100)
+                    r["vendor_int_mm_context"] = {"us": round(us_v, 2), "TOP/s": round(2.0 * M * N * K / us_v / 1e6, 2)}
+                except Exception as ex:
+                    r["vendor_int_mm_context"] = {"error": "%s: %s" % (type(ex).__name__, str(ex)[:120])}
             shape["M=%d" % M] = r
             if gi == 0:
                 # the finer granularities of Sec. 4.4 on the same codes: per-token steps found on the
