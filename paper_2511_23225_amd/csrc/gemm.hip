@@ -1128,7 +1128,7 @@ __global__ __launch_bounds__(T::THREADS, T::WPE) void gemm_nt_stream_kernel(Gemm
 }
 
 // ---------------------------------------------------------------------------
-// W8A8 linear for small M (decode-time batches, M <= 64): the product is bound by streaming the
+// W8A8 linear for small M (decode-time batches, M <= 128): the product is bound by streaming the
 // N x K weight bytes from HBM once.  One workgroup per CU owns up to NB blocks of 16 weight rows
 // (block ids b, b + grid, ...); its 8 waves split K; products come from v_mfma_i32_16x16x64_i8
 // (operand row = lane % 16, 16 bytes at k = 16 * (lane / 16)); the partial int32 tiles of the
@@ -1452,7 +1452,7 @@ size_t stream_k_workspace_bytes()
 // DMA-pipelined kernel on 64-byte stages (K % 64 == 0), 256x256 with 8 waves and 128x128.  11, 13,
 // 14: persistent streaming kernel (K % 128 == 0): 256x256, 128x128, 192x256.  15: deferred-epilogue
 // persistent kernel (256x256, four waves; M, N % 256 == 0, K % 128 == 0, K >= 512).  16: the same
-// kernel on 192x256 tiles (any M, K >= 2048).  17: the INT8 weight-streaming kernel (M <= 64).
+// kernel on 192x256 tiles (any M, K >= 2048).  17: the INT8 weight-streaming kernel (M <= 128).
 constexpr int kNumVariants = 17;
 static const int kVariantBM[kNumVariants + 1] = {0, 256, 256, 128, 64, 256, 256, 256, 128, 256, 128, 256, 256, 128, 192, 256, 192, 64};
 static const int kVariantBN[kNumVariants + 1] = {0, 256, 128, 128, 64, 256, 256, 128, 128, 128, 256, 256, 128, 128, 256, 256, 256, 64};
@@ -2029,6 +2029,7 @@ static hipError_t launch_skinny_ring(const GemmArgs &a, hipStream_t s)
 // stage shapes: M <= 16: 512 bytes of K a stage (eight k steps, one per wave); above: 256 bytes (four
 // k steps x two parts of the M blocks; 512 where a workgroup has one block of weight rows); ring depth
 // what 160 KB of LDS allow (the depth hardly matters: two stages measured like five)
+constexpr int64_t kSkinnyMaxM = 128;  // rows of X the weight-streaming kernel takes
 static hipError_t launch_skinny_ring_any(const GemmArgs &a, hipStream_t s)
 {
     const int64_t blocks = (a.N + 15) / 16, cus = num_cus();
@@ -2051,22 +2052,33 @@ static hipError_t launch_skinny_ring_any(const GemmArgs &a, hipStream_t s)
             return launch_skinny_ring<2, 3, 4, 6>(a, s);
         return launch_skinny_ring<2, 4, 4, 6>(a, s);
     }
-    if (per <= 1)  // 512-byte stages: half as many barriers (11008 -> 4096 at M = 64: 18.0 -> 16.7 us)
-        return launch_skinny_ring<4, 1, 8, 3>(a, s);
+    if (a.M <= 64) {
+        if (per <= 1)  // 512-byte stages: half as many barriers (11008 -> 4096 at M = 64: 18.0 -> 16.7 us)
+            return launch_skinny_ring<4, 1, 8, 3>(a, s);
+        if (per == 2)
+            return launch_skinny_ring<4, 2, 4, 6>(a, s);
+        if (per == 3)
+            return launch_skinny_ring<4, 3, 4, 5>(a, s);
+        return launch_skinny_ring<4, 4, 4, 4>(a, s);
+    }
+    // 64 < M <= 128: eight blocks of 16 rows of X beside the weight rows, 256-byte stages
+    if (per <= 1)
+        return launch_skinny_ring<8, 1, 4, 4>(a, s);
     if (per == 2)
-        return launch_skinny_ring<4, 2, 4, 6>(a, s);
+        return launch_skinny_ring<8, 2, 4, 4>(a, s);
     if (per == 3)
-        return launch_skinny_ring<4, 3, 4, 5>(a, s);
-    return launch_skinny_ring<4, 4, 4, 4>(a, s);
+        return launch_skinny_ring<8, 3, 4, 3>(a, s);
+    return launch_skinny_ring<8, 4, 4, 3>(a, s);
 }
 
 hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s)
 {
     // small M: the weight-streaming kernel (forced tiled variants keep the tiled kernels, for
     // tests; 17 forces this one).  Measured cold at the 7B shapes, kernel time in us for M = 1 /
-    // 16 / 32 / 64: 4096 -> 12288: 10.7 / 11.3 / 13.0 / 15.6, 11008 -> 4096: 10.2 / 10.8 / 14.1 / 18.0
-    // (a plain read of the 45-50 MB of weights by one kernel takes 10.2-11.1).
-    if ((g_tile_override == 0 || g_tile_override == 17) && a.M <= 64 && a.K % 64 == 0 && a.N % 4 == 0)
+    // 16 / 32 / 64 / 128: 4096 -> 12288: 10.7 / 11.3 / 13.0 / 15.6 / 19.6, 11008 -> 4096: 10.2 / 10.8 /
+    // 14.1 / 16.8 / 27.0 (a plain read of the 45-50 MB of weights by one kernel takes 10.2-11.1; the
+    // tiled kernels at M = 128: 27 and 66).
+    if ((g_tile_override == 0 || g_tile_override == 17) && a.M <= kSkinnyMaxM && a.K % 64 == 0 && a.N % 4 == 0)
         return launch_skinny_ring_any(a, s);
     return launch_gemm<true>(a, s);
 }

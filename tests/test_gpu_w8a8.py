@@ -140,3 +140,28 @@ def test_w8a8_extreme_accumulators():
     y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)  # poisoned
     tw.tweo_w8a8_linear(to_dev(xq), to_dev(wq), 1.0, y, workspace(tw.TWEO_OP_W8A8_LINEAR, M, N, K))
     assert np.array_equal(bf16_bits(y), oracle.w8a8_linear(xq, wq, 1.0))
+
+
+@pytest.mark.parametrize("tile", [0, 17])
+@pytest.mark.parametrize("shape", [(65, 1024, 72), (96, 2048, 136), (100, 11008, 264), (128, 4096, 520),
+                                   (128, 640, 4104), (80, 192, 8), (128, 4096, 12288), (128, 11008, 4096),
+                                   (112, 4096, 11008)])
+def test_w8a8_weight_streaming_up_to_128_rows(shape, tile):
+    # 64 < M <= 128 on the weight-streaming kernel (eight blocks of 16 rows of X): one to four blocks
+    # of weight rows per workgroup, ragged M, N and K (K a multiple of 64 only), the 7B shapes
+    M, K, N = shape
+    say("w8a8 streaming M=%d K=%d N=%d tile=%d" % (M, K, N, tile))
+    x, w = synth.w8a8_inputs(1, M, K=K, N=N)
+    ax, aw = oracle.amax_bf16(x), oracle.amax_bf16(w)
+    inv_x, inv_w = np.float32(127.0) / ax, np.float32(127.0) / aw
+    alpha = (ax / np.float32(127.0)) * (aw / np.float32(127.0))
+    oxq, owq = oracle.quantize_i8(x, inv_x), oracle.quantize_i8(w, inv_w)
+    y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)  # poisoned
+    tw.tweo_set_gemm_tile(tile)
+    try:
+        tw.tweo_w8a8_linear(to_dev(oxq), to_dev(owq), alpha, y, workspace(tw.TWEO_OP_W8A8_LINEAR, M, N, K))
+        torch.cuda.synchronize()
+    finally:
+        tw.tweo_set_gemm_tile(0)
+    want = oracle.w8a8_linear(oxq, owq, alpha)
+    assert np.array_equal(bf16_bits(y), want)
