@@ -126,7 +126,8 @@ size_t tweo_workspace_bytes(int op, int64_t M, int64_t N, int64_t K)
     case TWEO_OP_FP8_LINEAR_BWD_BF16:
         return kAmaxScratchBytes + tweo_workspace_bytes(TWEO_OP_FP8_LINEAR_BWD, M, N, K);
     case TWEO_OP_W8A8_LINEAR:
-        return 256 + (stream_k_candidate(M, N, K) ? stream_k_workspace_bytes() : 0);
+        return 256 + round256(std::max(stream_k_candidate(M, N, K) ? stream_k_workspace_bytes() : (size_t)0,
+                                       fp8_gemm_ksplit_bytes(M, N, K)));
     case TWEO_OP_LAYERNORM_QUANTIZE:  // M rows (N, K unused)
         return kAmaxPartialsMax * sizeof(uint32_t) + 256 + round256((size_t)M * 2 * sizeof(double));
     default:

@@ -1330,13 +1330,16 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 // A wave of this kernel takes one pair of neighbouring blocks of one tile (64 columns x 32 rows),
 // adds the runs in index order, scales, rounds and regroups the lanes' values into whole 128-byte
 // lines of the output as the GEMM's own write-out does.
+// INT8: the runs are int32 sums (added exactly, then y = bf16(fp32(sum) * alpha_i8), Sec. 4.4 Eq. 4).
+template <bool INT8>
 __global__ __launch_bounds__(256) void splitk_reduce_defer_kernel(const float4 *__restrict__ partials, int splits,
                                                                   int tiles_m, int tiles_n, int N,
                                                                   const float *__restrict__ s0,
-                                                                  const float *__restrict__ s1, uint16_t *__restrict__ out)
+                                                                  const float *__restrict__ s1, float alpha_i8,
+                                                                  uint16_t *__restrict__ out)
 {
     using T = DeferTile<4>;
-    const float alpha = (*s0) * (*s1);
+    const float alpha = INT8 ? alpha_i8 : (*s0) * (*s1);
     const int lane = threadIdx.x & (kWave - 1), l31 = lane & 31, lh = lane >> 5;
     const int task = blockIdx.x * 4 + (threadIdx.x >> 6);  // (tile, wave, band i, block pair jp)
     const int n_tiles = tiles_m * tiles_n;
@@ -1344,7 +1347,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_defer_kernel(const float4 *
     if (tile >= n_tiles)
         return;
     const int wm = wave >> 1, wn = wave & 1;
-    v4f sum[2][4];
+    typedef typename std::conditional<INT8, v4i, v4f>::type sum_t;
+    sum_t sum[2][4];
     const int64_t unit_stride = (int64_t)T::NWAVES * T::NB * 4 * kWave;
     const float4 *src = partials + ((int64_t)tile * T::NWAVES + wave) * (T::NB * 4 * kWave) +
                         (int64_t)((i * 4 + 2 * jp) * 4) * kWave + lane;
@@ -1353,7 +1357,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_defer_kernel(const float4 *
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const float4 v = src[(b * 4 + q) * kWave];
-            sum[b][q] = v4f{v.x, v.y, v.z, v.w};
+            sum[b][q] = __builtin_bit_cast(sum_t, v);
         }
     for (int sp = 1; sp < splits; ++sp) {
         src += (int64_t)n_tiles * unit_stride;
@@ -1362,7 +1366,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_defer_kernel(const float4 *
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const float4 v = src[(b * 4 + q) * kWave];
-                sum[b][q] += v4f{v.x, v.y, v.z, v.w};
+                sum[b][q] += __builtin_bit_cast(sum_t, v);
             }
     }
     uint32_t A[8], B[8];
@@ -1370,8 +1374,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_defer_kernel(const float4 *
     for (int q = 0; q < 4; ++q)
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            A[2 * q + h] = pack_bf16x2(sum[0][q][2 * h] * alpha, sum[0][q][2 * h + 1] * alpha);
-            B[2 * q + h] = pack_bf16x2(sum[1][q][2 * h] * alpha, sum[1][q][2 * h + 1] * alpha);
+            A[2 * q + h] = pack_bf16x2((float)sum[0][q][2 * h] * alpha, (float)sum[0][q][2 * h + 1] * alpha);
+            B[2 * q + h] = pack_bf16x2((float)sum[1][q][2 * h] * alpha, (float)sum[1][q][2 * h + 1] * alpha);
         }
     block_pair_to_lines(A, B);
     int tm, tn;
@@ -1810,14 +1814,16 @@ static hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 // than the units shrink).  Measured in the blocks' steps: 2304x768 over 50432 tokens 117 -> 88 us,
 // 3072x768 143 -> 111 us, 2048x2048 over 16384 91 -> 71 us; over 8192 tokens 2304x768 49 -> 35 us,
 // 768x768 48 -> 30 us, 3072x768 51 -> 39 us; a contraction of 4096 loses (14 -> 20 us), and so do
-// 64 tiles over 8192 (40 -> 46 us).
+// 64 tiles over 8192 (40 -> 46 us).  From 80 stages on, up to half as many tiles as CUs are split
+// (INT8, 4096 wide over 11008: 64 tiles 67 -> 60 us, 80 tiles 106 -> 68 us): the INT8 flavour of the
+// same kernel leaves int32 runs, which the reduce kernel adds exactly.
 constexpr int kKsplitDeferMinStages = 16, kKsplitDeferMinKt = 64;
 static int defer_ksplit(int64_t M, int64_t N, int64_t K)
 {
     if (g_tile_override != 0 || M % 256 != 0 || N % 256 != 0 || K % 128 != 0 || N > ((int64_t)1 << 22))
         return 1;
     const int64_t tiles = (M / 256) * (N / 256), kt = K / 128, cus = num_cus();
-    if (kt < kKsplitDeferMinKt || tiles * (kt >= 128 ? 4 : 6) > cus)
+    if (kt < kKsplitDeferMinKt || tiles * (kt >= 80 ? 2 : 6) > cus)
         return 1;
     int64_t splits = cus / tiles;
     if (splits > kt / kKsplitDeferMinStages)
@@ -1913,11 +1919,11 @@ static hipError_t launch_ksplit(const GemmArgs &a, hipStream_t s, int splits)
     return hipGetLastError();
 }
 
-template <bool A_E5M2>
+template <bool A_E5M2, bool INT8 = false>
 static hipError_t launch_ksplit_defer(const GemmArgs &a, hipStream_t s, int splits)
 {
     using T = DeferTile<4>;
-    const void *kern = (const void *)gemm_nt_defer_kernel<false, 0, 3, 4, A_E5M2, true, true>;
+    const void *kern = (const void *)gemm_nt_defer_kernel<INT8, 0, 3, 4, A_E5M2, true, true>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
@@ -1943,16 +1949,17 @@ static hipError_t launch_ksplit_defer(const GemmArgs &a, hipStream_t s, int spli
     hipEvent_t e0 = nullptr, e1 = nullptr;  // a profiled launch brackets both kernels
     take_profile_events(&e0, &e1);
     if (e0 != nullptr)
-        hipExtLaunchKernelGGL((gemm_nt_defer_kernel<false, 0, 3, 4, A_E5M2, true, true>), grid, block, T::LDS_BYTES, s, e0,
+        hipExtLaunchKernelGGL((gemm_nt_defer_kernel<INT8, 0, 3, 4, A_E5M2, true, true>), grid, block, T::LDS_BYTES, s, e0,
                               nullptr, 0, g);
     else
-        hipLaunchKernelGGL((gemm_nt_defer_kernel<false, 0, 3, 4, A_E5M2, true, true>), grid, block, T::LDS_BYTES, s, g);
+        hipLaunchKernelGGL((gemm_nt_defer_kernel<INT8, 0, 3, 4, A_E5M2, true, true>), grid, block, T::LDS_BYTES, s, g);
     if (e1 != nullptr)
-        hipExtLaunchKernelGGL(splitk_reduce_defer_kernel, rgrid, dim3(256), 0, s, nullptr, e1, 0,
-                              (const float4 *)g.ksplit_out, splits, g.tiles_m, g.tiles_n, g.N, a.s0, a.s1, (uint16_t *)a.out);
+        hipExtLaunchKernelGGL(splitk_reduce_defer_kernel<INT8>, rgrid, dim3(256), 0, s, nullptr, e1, 0,
+                              (const float4 *)g.ksplit_out, splits, g.tiles_m, g.tiles_n, g.N, a.s0, a.s1, a.alpha,
+                              (uint16_t *)a.out);
     else
-        hipLaunchKernelGGL(splitk_reduce_defer_kernel, rgrid, dim3(256), 0, s, (const float4 *)g.ksplit_out, splits,
-                           g.tiles_m, g.tiles_n, g.N, a.s0, a.s1, (uint16_t *)a.out);
+        hipLaunchKernelGGL(splitk_reduce_defer_kernel<INT8>, rgrid, dim3(256), 0, s, (const float4 *)g.ksplit_out, splits,
+                           g.tiles_m, g.tiles_n, g.N, a.s0, a.s1, a.alpha, (uint16_t *)a.out);
     return hipGetLastError();
 }
 
@@ -2080,6 +2087,14 @@ hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s)
     // tiled kernels at M = 128: 27 and 66).
     if ((g_tile_override == 0 || g_tile_override == 17) && a.M <= kSkinnyMaxM && a.K % 64 == 0 && a.N % 4 == 0)
         return launch_skinny_ring_any(a, s);
+    // few whole 256x256 tiles under a long contraction (prefill chunks of a few hundred tokens into
+    // a narrow projection): the K split of the deferred-epilogue kernel, int32 runs added exactly
+    if (a.row_step == nullptr && !a.out_i8) {
+        const int splits = defer_ksplit(a.M, a.N, a.K);
+        if (splits > 1 && a.sk_workspace != nullptr && ((uintptr_t)a.sk_workspace & 15u) == 0 &&
+            a.sk_workspace_bytes >= (size_t)splits * (size_t)a.M * (size_t)a.N * sizeof(int32_t))
+            return launch_ksplit_defer<false, true>(a, s, splits);
+    }
     return launch_gemm<true>(a, s);
 }
 

@@ -277,9 +277,10 @@ def test_bwd(case, tile):
 # tile, fp32 runs added in order by a second kernel).  wgrad over 16384 tokens of a 768-wide layer
 # (8 runs on the deferred-epilogue kernel), a ragged one whose last K stage is partial (the
 # register-staged kernel), a dgrad over a long N, a wgrad over 8192 tokens (4 runs of 16 stages) and
-# one whose stages do not divide evenly over the runs (67 stages, 4 runs); each run twice.
+# one whose stages do not divide evenly over the runs (67 stages, 4 runs), and one with 48 tiles
+# under 80 stages (5 runs: from 80 stages on, up to half as many tiles as CUs are split); each run twice.
 @pytest.mark.parametrize("case", [(1, 1, 16384, 768, 768), (3, 0, 16400, 264, 528), (0, 0, 256, 512, 16384),
-                                  (1, 0, 8192, 768, 2304), (1, 2, 8576, 512, 768)])
+                                  (1, 0, 8192, 768, 2304), (1, 2, 8576, 512, 768), (3, 0, 10240, 2048, 1536)])
 def test_bwd_k_split(case):
     cfg, gi, M, K, N = case
     say("bwd K split cfg=%d M=%d K=%d N=%d" % (cfg, M, K, N))

@@ -165,3 +165,27 @@ def test_w8a8_weight_streaming_up_to_128_rows(shape, tile):
         tw.tweo_set_gemm_tile(0)
     want = oracle.w8a8_linear(oxq, owq, alpha)
     assert np.array_equal(bf16_bits(y), want)
+
+
+@pytest.mark.parametrize("shape", [(256, 11008, 4096), (512, 8192, 256), (256, 16384, 512), (512, 11008, 4096),
+                                   (1024, 10240, 2816)])
+def test_w8a8_k_split_of_whole_tiles(shape):
+    # few whole 256x256 tiles under a contraction of 8192 and more: workgroups share a tile's K, the
+    # int32 runs are added exactly by a second kernel (with the workspace tweo_workspace_bytes asks
+    # for); without a workspace the tiled kernels run - both must give the oracle's bits
+    M, K, N = shape
+    say("w8a8 k-split tiles M=%d K=%d N=%d" % (M, K, N))
+    assert tw.tweo_workspace_bytes(tw.TWEO_OP_W8A8_LINEAR, M, N, K) >= 2 * M * N * 4
+    x, w = synth.w8a8_inputs(0, M, K=K, N=N)
+    ax, aw = oracle.amax_bf16(x), oracle.amax_bf16(w)
+    inv_x, inv_w = np.float32(127.0) / ax, np.float32(127.0) / aw
+    alpha = (ax / np.float32(127.0)) * (aw / np.float32(127.0))
+    oxq, owq = oracle.quantize_i8(x, inv_x), oracle.quantize_i8(w, inv_w)
+    want = oracle.w8a8_linear(oxq, owq, alpha)
+    xd, wd = to_dev(oxq), to_dev(owq)
+    ws = torch.full((tw.tweo_workspace_bytes(tw.TWEO_OP_W8A8_LINEAR, M, N, K),), 0xEE, dtype=torch.uint8, device=DEV)
+    for w_arg in (ws, ws, None):
+        y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)  # poisoned
+        tw.tweo_w8a8_linear(xd, wd, alpha, y, w_arg)
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_bits(y), want)
