@@ -344,7 +344,7 @@ def time_w8a8(tw, torch, synth, dev, iters=20, copies=8):
         K, N = g.K, g.N
         shape = {}
         wqs = None
-        for M in (1, 16, 64, 4096):
+        for M in (1, 16, 64, 128, 512, 4096):  # 128 and 512: between the sizes the workload names
             x, w = synth.w8a8_inputs(gi, M, with_w=wqs is None)
             if wqs is None:
                 wq, step_w = quant(up(w))
@@ -357,12 +357,12 @@ def time_w8a8(tw, torch, synth, dev, iters=20, copies=8):
                 us_r = kernel_us(reads + reads)
                 shape["plain_read_of_the_weights_cold"] = {"us": round(us_r, 2), "GB/s": round(N * K / us_r / 1e3, 1)}
             xq, step_x = quant(up(x))
-            ys = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in range(copies if M <= 64 else 1)]
+            ys = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in range(copies if M <= 128 else 1)]
             ws = torch.empty(tw.tweo_workspace_bytes(tw.TWEO_OP_W8A8_LINEAR, M, N, K), dtype=torch.uint8, device=dev)
             bytes_ = M * K + N * K + 2 * M * N
             call = lambda c: (lambda: tw.tweo_w8a8_linear(xq, wqs[c], step_x * step_w, ys[c % len(ys)], ws))
             r = {}
-            if M <= 64:
+            if M <= 128:  # the weight-streaming kernel
                 warm, cold = [call(0)] * 8, [call(c) for c in range(copies)]
                 stream_us(cold, copies)
                 r["cold_kernel_us"] = round(kernel_us(cold + cold), 2)
@@ -375,7 +375,7 @@ def time_w8a8(tw, torch, synth, dev, iters=20, copies=8):
             else:
                 # the compute-bound shape is timed at the clock the chip settles at under load: it
                 # takes some 20 ms of work to get there from the idle state the small shapes leave
-                us = stream_us([call(0)], 100)
+                us = stream_us([call(c) for c in range(copies)] if M < 4096 else [call(0)], 100)  # weights cold below 4096
                 r["us"] = round(us, 2)
                 r["TOP/s"] = round(2.0 * M * N * K / us / 1e6, 2)
                 r["frac_of_int8_peak"] = round(2.0 * M * N * K / us / 1e6 / INT8_PEAK_TOPS, 3)
@@ -388,7 +388,7 @@ def time_w8a8(tw, torch, synth, dev, iters=20, copies=8):
                 except Exception as ex:
                     r["vendor_int_mm_context"] = {"error": "%s: %s" % (type(ex).__name__, str(ex)[:120])}
             shape["M=%d" % M] = r
-            if gi == 0:
+            if gi == 0 and M in (1, 16, 64, 4096):
                 # the finer granularities of Sec. 4.4 on the same codes: per-token steps found on the
                 # fly (quantise kernel timed with the GEMM), per-channel weight steps
                 xb = up(x)
