@@ -1512,7 +1512,7 @@ static int pick_variant(int64_t M, int64_t N, int64_t K)
             // their own barriers) where the shape allows it: ahead of the 8-wave kernel by 15 %
             // when a tile's write-out has 15 stages to hide under, by nothing at 6 stages.
             const int64_t kt = K / 128;
-            const bool e15 = M % 256 == 0 && N % 256 == 0 && K % 128 == 0 && K >= 512 && tiles(256, 256) >= (int64_t)cus;
+            const bool e15 = M % 256 == 0 && N % 256 == 0 && K % 128 == 0 && K >= 512 && 2 * tiles(256, 256) >= (int64_t)cus;
             const bool e16 = N % 256 == 0 && K % 128 == 0 && K >= 2048;
             const double gain = kt >= 16 ? 1.15 : (kt >= 8 ? 1.08 : 1.0);
             const double c15 = e15 ? cost(256, 256, cus, gain) : 1e300;
@@ -1541,9 +1541,11 @@ static int pick_variant(int64_t M, int64_t N, int64_t K)
             // more than the model's rounds say (8192x2304, K = 768: 26 us against 31 us measured)
             if (v == 14 && K < 1024 && c13 < 1.2 * c14)
                 v = 13;
-            // a single round of 128x128 tiles under a long contraction: the non-persistent
-            // kernel with its four-stage ring is 10-15 % ahead (weight gradients of narrow layers)
-            if (v == 13 && K >= 4096 && K % 64 == 0 && tiles(128, 128) <= (int64_t)(2 * cus))
+            // at most one 128x128 tile per CU under a long contraction: the non-persistent
+            // kernel with its four-stage ring is 10-15 % ahead (weight gradients of narrow layers);
+            // with more tiles than CUs it falls behind (INT8, 12288 wide over 4096 at M = 384 / 512:
+            // 39 / 47 us against 32 / 37)
+            if (v == 13 && K >= 4096 && K % 64 == 0 && tiles(128, 128) <= (int64_t)cus)
                 v = 8;
         }
     }
