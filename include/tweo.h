@@ -499,7 +499,8 @@ tweo_status tweo_fused_cast_timeouts(unsigned *count);
  * {0, 4}); it falls back to variant 11 otherwise.  16 = the same kernel on 192x256
  * tiles (any M, N a multiple of 256, K a multiple of 128 and at least 2048); it
  * falls back to variant 14 otherwise.  17 (INT8 only, M <= 128, K % 64 == 0,
- * N % 4 == 0) = the weight-streaming kernel (what such shapes get anyway);
+ * N % 4 == 0; M <= 256 when K >= 8192 and N <= 16 x the CU count) = the
+ * weight-streaming kernel (what such shapes get anyway);
  * elsewhere it means variant 4.  A variant whose K requirement is not met falls
  * back to the nearest one that fits.  Results are identical up to the fp32
  * summation order.  Returns TWEO_ERR_INVALID_ARG for an unknown (or retired:

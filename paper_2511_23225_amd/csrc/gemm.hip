@@ -1164,9 +1164,11 @@ __global__ __launch_bounds__(512) void w8a8_skinny_ring_kernel(const int8_t *__r
 {
     constexpr int WAVES = 8, STEP = 64, KCH = KSTEPS * STEP, PARTS = WAVES / KSTEPS, MBW = MB / PARTS;
     constexpr int ROWS_X = MB * 16, ROWS = ROWS_X + NB * 16, STAGE = ROWS * KCH;
-    constexpr int RPI = 1024 / KCH, NI = ROWS / RPI, PPW = (NI + WAVES - 1) / WAVES, CPR = KCH / 16, T = NB * MBW;
+    constexpr int RPI = 1024 / KCH, NI = ROWS / RPI, PPW = (NI + WAVES - 1) / WAVES, CPR = KCH / 16;
+    // the waves' partial tiles meet in the ring's memory, RB blocks of weight rows at a time
+    constexpr int RB_FIT = (S * STAGE) / (WAVES * MBW * 1024), RB = RB_FIT < NB ? RB_FIT : NB, T = RB * MBW;
     static_assert(MB % PARTS == 0 && 1024 % KCH == 0 && ROWS % RPI == 0, "shapes divide");
-    static_assert(S * STAGE <= 160 * 1024 && WAVES * T * 1024 <= S * STAGE, "LDS capacity");
+    static_assert(S * STAGE <= 160 * 1024 && RB >= 1, "LDS capacity");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
@@ -1261,45 +1263,48 @@ __global__ __launch_bounds__(512) void w8a8_skinny_ring_kernel(const int8_t *__r
             fill = fill + 1 == S ? 0 : fill + 1;
         }
         wait_vmcnt<0>();  // the loads past the end have landed: the ring can be reused
-        block_barrier();
         // acc[v] of lane l is C[n = 4*(l/16) + v, m = l%16] of its 16x16 block
         v4i(*red)[T][kWave] = (v4i(*)[T][kWave])smem;
 #pragma unroll
-        for (int a = 0; a < NB; ++a)
+        for (int a0 = 0; a0 < NB; a0 += RB) {
+            block_barrier();  // the ring, or the sums of the blocks before, have been read
 #pragma unroll
-            for (int b = 0; b < MBW; ++b)
-                red[wave][a * MBW + b][lane] = acc[a][b];
-        block_barrier();
-        for (int t = tid; t < NB * MB * kWave; t += WAVES * kWave) {
-            const int a = t / (MB * kWave), b = (t / kWave) % MB, l = t % kWave;
-            const int blk = first + a * grid;
-            if (blk >= blocks)
-                continue;
-            const int w0 = (b / MBW) * KSTEPS, tile = a * MBW + b % MBW;
-            v4i sum = red[w0][tile][l];
+            for (int a = a0; a < a0 + RB && a < NB; ++a)
 #pragma unroll
-            for (int w = 1; w < KSTEPS; ++w)
-                sum += red[w0 + w][tile][l];
-            const int m = b * 16 + (l & 15), n = blk * 16 + 4 * (l >> 4);
-            if (m < M && n < N) {
-                float y[4];
-                if constexpr (VEC) {
-                    const float rstep = sv.rs[(int64_t)m * sv.rs_stride];
+                for (int b = 0; b < MBW; ++b)
+                    red[wave][(a - a0) * MBW + b][lane] = acc[a][b];
+            block_barrier();
+            for (int t = tid; t < RB * MB * kWave; t += WAVES * kWave) {
+                const int a = a0 + t / (MB * kWave), b = (t / kWave) % MB, l = t % kWave;
+                const int blk = first + a * grid;
+                if (a >= NB || blk >= blocks)
+                    continue;
+                const int w0 = (b / MBW) * KSTEPS, tile = (a - a0) * MBW + b % MBW;
+                v4i sum = red[w0][tile][l];
 #pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        y[v] = ((float)sum[v] * rstep) * sv.cs[(int64_t)(n + v) * sv.cs_stride];
-                    if (sv.out_i8) {
-                        *(uint32_t *)((uint8_t *)Y + (int64_t)m * N + n) =
-                            round_to_i8(y[0], sv.out_inv_step) | (round_to_i8(y[1], sv.out_inv_step) << 8) |
-                            (round_to_i8(y[2], sv.out_inv_step) << 16) | (round_to_i8(y[3], sv.out_inv_step) << 24);
-                        continue;
+                for (int w = 1; w < KSTEPS; ++w)
+                    sum += red[w0 + w][tile][l];
+                const int m = b * 16 + (l & 15), n = blk * 16 + 4 * (l >> 4);
+                if (m < M && n < N) {
+                    float y[4];
+                    if constexpr (VEC) {
+                        const float rstep = sv.rs[(int64_t)m * sv.rs_stride];
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            y[v] = ((float)sum[v] * rstep) * sv.cs[(int64_t)(n + v) * sv.cs_stride];
+                        if (sv.out_i8) {
+                            *(uint32_t *)((uint8_t *)Y + (int64_t)m * N + n) =
+                                round_to_i8(y[0], sv.out_inv_step) | (round_to_i8(y[1], sv.out_inv_step) << 8) |
+                                (round_to_i8(y[2], sv.out_inv_step) << 16) | (round_to_i8(y[3], sv.out_inv_step) << 24);
+                            continue;
+                        }
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            y[v] = (float)sum[v] * alpha;
                     }
-                } else {
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        y[v] = (float)sum[v] * alpha;
+                    *(uint2 *)(Y + (int64_t)m * N + n) = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
                 }
-                *(uint2 *)(Y + (int64_t)m * N + n) = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
             }
         }
     }
@@ -2070,6 +2075,8 @@ static hipError_t launch_skinny_ring_any(const GemmArgs &a, hipStream_t s)
             return launch_skinny_ring<4, 3, 4, 5>(a, s);
         return launch_skinny_ring<4, 4, 4, 4>(a, s);
     }
+    if (a.M > 128)  // up to 256 rows for one block of weight rows per workgroup (see launch_i8_gemm)
+        return a.M <= 192 ? launch_skinny_ring<12, 1, 4, 3>(a, s) : launch_skinny_ring<16, 1, 4, 2>(a, s);
     // 64 < M <= 128: eight blocks of 16 rows of X beside the weight rows, 256-byte stages
     if (per <= 1)
         return launch_skinny_ring<8, 1, 4, 4>(a, s);
@@ -2088,6 +2095,14 @@ hipError_t launch_i8_gemm(const GemmArgs &a, hipStream_t s)
     // 14.1 / 16.8 / 27.0 (a plain read of the 45-50 MB of weights by one kernel takes 10.2-11.1; the
     // tiled kernels at M = 128: 27 and 66).
     if ((g_tile_override == 0 || g_tile_override == 17) && a.M <= kSkinnyMaxM && a.K % 64 == 0 && a.N % 4 == 0)
+        return launch_skinny_ring_any(a, s);
+    // up to 256 rows into a projection of at most one block of 16 weight rows per CU under a long
+    // contraction (11008 -> 4096: 16 tiles of 256x256): still the weight stream, unless the K split
+    // below applies (M = 256 with a workspace)
+    if ((g_tile_override == 0 || g_tile_override == 17) && a.M <= 256 && a.K % 64 == 0 && a.N % 4 == 0 &&
+        a.K >= 8192 && (a.N + 15) / 16 <= num_cus() &&
+        !(a.row_step == nullptr && !a.out_i8 && defer_ksplit(a.M, a.N, a.K) > 1 && a.sk_workspace != nullptr &&
+          a.sk_workspace_bytes >= (size_t)defer_ksplit(a.M, a.N, a.K) * (size_t)a.M * (size_t)a.N * sizeof(int32_t)))
         return launch_skinny_ring_any(a, s);
     // few whole 256x256 tiles under a long contraction (prefill chunks of a few hundred tokens into
     // a narrow projection): the K split of the deferred-epilogue kernel, int32 runs added exactly

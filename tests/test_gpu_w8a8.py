@@ -189,3 +189,33 @@ def test_w8a8_k_split_of_whole_tiles(shape):
         tw.tweo_w8a8_linear(xd, wd, alpha, y, w_arg)
         torch.cuda.synchronize()
         assert np.array_equal(bf16_bits(y), want)
+
+
+@pytest.mark.parametrize("shape", [(192, 11008, 4096), (256, 8192, 2048), (160, 8192, 520), (200, 16384, 264),
+                                   (129, 8192, 8), (256, 11008, 4096)])
+def test_w8a8_weight_streaming_up_to_256_rows_into_a_narrow_projection(shape):
+    # 128 < M <= 256, K >= 8192, at most one block of 16 weight rows per CU: twelve or sixteen blocks
+    # of rows of X beside the weight rows.  With a workspace, M = 256 on whole tiles takes the K split
+    # of the tiled kernel instead; without one the weight-streaming kernel: the same bits either way.
+    M, K, N = shape
+    say("w8a8 streaming (narrow) M=%d K=%d N=%d" % (M, K, N))
+    x, w = synth.w8a8_inputs(2, M, K=K, N=N)
+    ax, aw = oracle.amax_bf16(x), oracle.amax_bf16(w)
+    inv_x, inv_w = np.float32(127.0) / ax, np.float32(127.0) / aw
+    alpha = (ax / np.float32(127.0)) * (aw / np.float32(127.0))
+    oxq, owq = oracle.quantize_i8(x, inv_x), oracle.quantize_i8(w, inv_w)
+    want = oracle.w8a8_linear(oxq, owq, alpha)
+    xd, wd = to_dev(oxq), to_dev(owq)
+    for w_arg in (workspace(tw.TWEO_OP_W8A8_LINEAR, M, N, K), None):
+        y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)  # poisoned
+        tw.tweo_w8a8_linear(xd, wd, alpha, y, w_arg)
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_bits(y), want)
+    # per-token and per-channel steps take the same kernel
+    sx = torch.full((M,), float(ax / np.float32(127.0)), dtype=torch.float32, device=DEV)
+    sw = torch.full((N,), float(aw / np.float32(127.0)), dtype=torch.float32, device=DEV)
+    y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)
+    tw.tweo_w8a8_linear_scaled(xd, wd, sx, sw, y)
+    torch.cuda.synchronize()
+    want_v = oracle.w8a8_linear_scaled(oxq, owq, sx.cpu().numpy(), sw.cpu().numpy())
+    assert np.array_equal(bf16_bits(y), want_v)
