@@ -165,6 +165,14 @@ def test_w8a8_weight_streaming_up_to_128_rows(shape, tile):
         tw.tweo_set_gemm_tile(0)
     want = oracle.w8a8_linear(oxq, owq, alpha)
     assert np.array_equal(bf16_bits(y), want)
+    if tile == 0:
+        # per-token and per-channel steps take the same kernel
+        sx = torch.full((M,), float(ax / np.float32(127.0)), dtype=torch.float32, device=DEV)
+        sw = torch.full((N,), float(aw / np.float32(127.0)), dtype=torch.float32, device=DEV)
+        y = torch.full((M, N), float('nan'), dtype=torch.bfloat16, device=DEV)
+        tw.tweo_w8a8_linear_scaled(to_dev(oxq), to_dev(owq), sx, sw, y)
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_bits(y), oracle.w8a8_linear_scaled(oxq, owq, sx.cpu().numpy(), sw.cpu().numpy()))
 
 
 @pytest.mark.parametrize("shape", [(256, 11008, 4096), (512, 8192, 256), (256, 16384, 512), (512, 11008, 4096),
